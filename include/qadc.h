@@ -1,0 +1,190 @@
+/*
+ * qadc.h -- C ABI of the MI355X (gfx950) asymmetric-distance scan over
+ * product-quantized codes with quantized distance tables.
+ *
+ * The calls follow the paper's statement of the search problem (Section 2.1.3:
+ * query z, codebooks, short codes, R -> the R nearest codes) and its distance
+ * quantizer (Section 3.4) and scan loop (Section 3.5).
+ *
+ * General conventions
+ *   - Pointers marked [dev] are device pointers owned by the caller (hipMalloc /
+ *     PyTorch); pointers marked [host] are ordinary host memory.  The library
+ *     never frees or keeps caller memory beyond a call, except that an index
+ *     handle keeps the codebook pointer it was given (the caller keeps that
+ *     buffer alive for the life of the handle).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Every call only enqueues work on that stream; it never synchronises and
+ *     never allocates device memory (pq_index_create excepted).
+ *   - Return value: PQ_OK (0) or a negative code; pq_last_error() then gives a
+ *     thread-local description.  Nothing throws or aborts.
+ *   - Row-major, densely packed arrays throughout.  Inputs are assumed finite
+ *     (no NaN / Inf in queries, codebooks or tables).
+ *   - Sub-code layout (Section 3.3, packing paragraph): a code is a
+ *     little-endian bit stream of code_size = ceil(sum(nbits)/8) bytes;
+ *     sub-code j occupies bits [off_j, off_j + nbits[j]), off_j = sum of the
+ *     earlier widths, bit 0 = least significant bit of byte 0.  For m x 4
+ *     layouts byte i holds sub-code 2i in its low nibble and 2i+1 in its high
+ *     nibble.
+ *   - Results are sorted ascending by (key, id); ties go to the lowest id.
+ *     When fewer than R codes exist the tail is padded with id = -1,
+ *     key = q_max, dist = +inf.
+ */
+#ifndef QADC_H
+#define QADC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PQ_OK 0
+#define PQ_EINVAL (-1) /* bad argument: null pointer, bad shape, unsupported size, misalignment */
+#define PQ_ENOMEM (-2) /* caller-supplied workspace too small */
+#define PQ_EHIP (-3)   /* a HIP runtime call failed (message holds hipGetErrorString) */
+
+/* limits of this build */
+#define PQ_MAX_M 64           /* sub-quantizers per code */
+#define PQ_MAX_TABLE_LEN 4096 /* sum_j 2^nbits[j] */
+#define PQ_MAX_R 2048         /* results per query */
+#define PQ_MAX_T_EFF 8192     /* calibration codes: max(t, 4R) must not exceed this */
+#define PQ_MAX_DIM 4096
+
+/* Immutable description of a product quantizer; opaque. */
+typedef struct pq_index pq_index_t;
+
+/*
+ * Per-query state of the distance quantizer (Section 3.4).  One per query for
+ * the exhaustive calls.  24 bytes, no padding.
+ *   d_min     sum over sub-quantizers of the smallest table entry (fp64 sum)
+ *   delta     bin width (d_max - d_min)/q_max; 0 when d_max <= d_min or when
+ *             there was no code to calibrate on (all table entries are then 0)
+ *   d_max     R-th smallest float ADC among the first t_eff codes
+ *   key_bound R-th smallest *quantized* key among the calibration codes: an
+ *             inclusive upper bound on the R-th best key of any superset.
+ *             Only a pruning hint; set it to q_max if unknown.
+ */
+typedef struct pq_qparams {
+    double d_min;
+    double delta;
+    float d_max;
+    uint32_t key_bound;
+} pq_qparams_t;
+
+/*
+ * Create an index handle.  Section 2.1.2 (product quantizer = m codebooks) and
+ * Section 3.1 (irregular product quantizers: sub-quantizers of different widths
+ * over sub-vectors of different dimension).
+ *   d          vector dimension, 1..PQ_MAX_DIM
+ *   m          number of sub-quantizers, 1..PQ_MAX_M
+ *   nbits      [host][m] bits of each sub-quantizer, each 1..8
+ *   dsub       [host][m] dimensions of each sub-vector, each >= 1, sum == d
+ *   codebooks  [dev] concatenation over j of [2^nbits[j]][dsub[j]] float32
+ *   acc_bits   8 or 16: width of quantized table entries and of the
+ *              saturating accumulator (q_max = 2^acc_bits - 1)
+ * Allocates a few KB of device memory for the layout description on the
+ * current device.  Returns PQ_EINVAL for bad shapes.
+ */
+int pq_index_create(pq_index_t **out, int d, int m, const int32_t *nbits, const int32_t *dsub,
+                    const float *codebooks, int acc_bits);
+void pq_index_destroy(pq_index_t *idx);
+
+size_t pq_code_size(const pq_index_t *idx); /* bytes per code */
+size_t pq_table_len(const pq_index_t *idx); /* T = sum_j 2^nbits[j] */
+
+/* Bytes of workspace pq_adc_scan_topk needs for (nq queries, n codes, R). */
+size_t pq_workspace_bytes(const pq_index_t *idx, int nq, int64_t n, int R);
+/* Bytes of workspace ivf_adc_scan_topk needs for (nq queries, nprobe probes, R). */
+size_t ivf_workspace_bytes(const pq_index_t *idx, int nq, int nprobe, int R);
+
+/*
+ * Distance tables, eq. (1): tables[q][toff_j + i] = || z_q^j - C^j[i] ||^2.
+ * fp32, dimensions accumulated in ascending order with separate subtract,
+ * multiply and add (no fused multiply-add), so the result is reproducible bit
+ * for bit.
+ *   queries [dev][nq][d] float32      tables [dev][nq][T] float32 (out)
+ * nq == 0 is a no-op.
+ */
+int pq_compute_tables(const pq_index_t *idx, const float *queries, int nq, float *tables,
+                      void *stream);
+
+/*
+ * Distance quantizer, Section 3.4.  For every query:
+ *   t_eff = min(n, max(t, 4R)); d_max = min(R,t_eff)-th smallest float ADC
+ *   (eq. (2), fp32, sub-quantizers in ascending order) among codes 0..t_eff-1;
+ *   p_min(j) = smallest entry of table j; d_min = sum_j p_min(j) (fp64);
+ *   delta = (d_max - d_min)/q_max (fp64);
+ *   q = min(q_max, floor((p - p_min(j))/delta)) (fp64), all 0 if delta is not a
+ *   positive finite number (delta is then stored as 0).
+ *   tables  [dev][nq][T] float32       codes [dev][n][code_size] uint8
+ *   qtables [dev][nq][T] uint8 (acc_bits 8) or uint16 (acc_bits 16)   (out)
+ *   qparams [dev][nq]                                                   (out)
+ * Requires 1 <= R <= PQ_MAX_R, t >= 1, max(t,4R) <= PQ_MAX_T_EFF, n >= 0.
+ */
+int pq_quantize_tables(const pq_index_t *idx, const float *tables, int nq, const uint8_t *codes,
+                       int64_t n, int t, int R, void *qtables, pq_qparams_t *qparams,
+                       void *stream);
+
+/*
+ * Scan, eq. (2) with quantized tables and saturating unsigned sums at the
+ * accumulator width (Section 3.4 last paragraph, Section 3.5), then the R
+ * smallest (key, id) per query, id = position of the code in `codes`.
+ *   qtables, qparams  as written by pq_quantize_tables (or by the caller)
+ *   codes     [dev][n][code_size], n < 2^31; must be 16-byte aligned
+ *   out_ids   [dev][nq][R] int32       out_keys [dev][nq][R] uint16
+ *   out_dist  [dev][nq][R] float32 = fmaf(key, (float)delta, (float)d_min)
+ *   workspace [dev] >= pq_workspace_bytes(idx, nq, n, R) bytes, 256-byte
+ *             aligned, any content; private to this call until the stream has
+ *             finished it (concurrent calls need distinct workspaces)
+ * nq == 0 is a no-op; n == 0 writes padding only.
+ */
+int pq_adc_scan_topk(const pq_index_t *idx, const void *qtables, const pq_qparams_t *qparams,
+                     int nq, const uint8_t *codes, int64_t n, int R, int32_t *out_ids,
+                     uint16_t *out_keys, float *out_dist, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/*
+ * Inverted-list search (Section 2.1.1: residuals are what is encoded;
+ * Section 2.1.3: one table set per probed cell from z' = z - centroid).
+ * For every query: d_max from the float ADC of the first t_eff probed codes
+ * (probe order, list order, each with its own cell's tables); per probed list
+ * its own p_min / d_min / delta from that shared d_max; lists whose d_min
+ * exceeds d_max are skipped; every code of the other probed lists gets
+ * dist = fmaf(key, (float)delta_l, (float)d_min_l); the R smallest
+ * (dist, stored id) are returned.
+ *   coarse       [dev][K][d] float32 cell centroids
+ *   list_offsets [dev][K+1] int64, list l = codes [off[l], off[l+1])
+ *   list_codes   [dev][off[K]][code_size]; 16-byte aligned base
+ *   list_ids     [dev][off[K]] int32 stored ids
+ *   queries      [dev][nq][d]
+ *   probe_ids    [dev][nq][nprobe] int32, nearest cell first, distinct;
+ *                negative entries are ignored
+ *   out_ids      [dev][nq][R] int32     out_dist [dev][nq][R] float32
+ *   workspace    >= ivf_workspace_bytes(idx, nq, nprobe, R), 256-byte aligned
+ * Requires 1 <= nprobe <= 1024 and the limits of pq_quantize_tables.
+ */
+int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_centroids, int K,
+                      const int64_t *list_offsets, const uint8_t *list_codes,
+                      const int32_t *list_ids, const float *queries, int nq,
+                      const int32_t *probe_ids, int nprobe, int t, int R, int32_t *out_ids,
+                      float *out_dist, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Timing hook for benchmarks: while enabled, the library brackets every launch
+ * of the scan kernels (the dominant kernels of pq_adc_scan_topk and
+ * ivf_adc_scan_topk) with HIP events on the caller's stream.
+ * pq_profile_read synchronises those events, returns the number of launches
+ * seen since the last read and their summed duration in milliseconds, and
+ * clears the record.  Not thread-safe; off by default.
+ */
+void pq_profile_enable(int on);
+int pq_profile_read(double *total_ms);
+
+/* Description of the last error on this thread ("" if none). */
+const char *pq_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QADC_H */

@@ -1,0 +1,231 @@
+"""Thin ctypes binding of libqadc.so: argument marshalling only.
+
+Every function here has the name of the C entry point it forwards to (see
+``include/qadc.h``).  PyTorch supplies device memory (``tensor.data_ptr()``) and
+the stream; no step of the search path runs in Python or in PyTorch ops.  There
+is no CPU fallback: if the library is missing or a call fails, an exception is
+raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqadc.so")
+_lib = None
+
+PQ_OK, PQ_EINVAL, PQ_ENOMEM, PQ_EHIP = 0, -1, -2, -3
+QPARAMS_BYTES = 24
+
+EXPORTS = [
+    "pq_index_create", "pq_index_destroy", "pq_code_size", "pq_table_len", "pq_workspace_bytes",
+    "ivf_workspace_bytes", "pq_compute_tables", "pq_quantize_tables", "pq_adc_scan_topk",
+    "ivf_adc_scan_topk", "pq_profile_enable", "pq_profile_read", "pq_last_error",
+]
+
+
+class QadcError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libqadc error {code}: {msg}")
+        self.code = code
+
+
+def load() -> ctypes.CDLL:
+    """Load libqadc.so, building it first only if it was never built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+    lib.pq_index_create.argtypes = [ctypes.POINTER(vp), i32, i32, vp, vp, vp, i32]
+    lib.pq_index_create.restype = i32
+    lib.pq_index_destroy.argtypes = [vp]
+    lib.pq_index_destroy.restype = None
+    lib.pq_code_size.argtypes = [vp]
+    lib.pq_code_size.restype = sz
+    lib.pq_table_len.argtypes = [vp]
+    lib.pq_table_len.restype = sz
+    lib.pq_workspace_bytes.argtypes = [vp, i32, i64, i32]
+    lib.pq_workspace_bytes.restype = sz
+    lib.ivf_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    lib.ivf_workspace_bytes.restype = sz
+    lib.pq_compute_tables.argtypes = [vp, vp, i32, vp, vp]
+    lib.pq_compute_tables.restype = i32
+    lib.pq_quantize_tables.argtypes = [vp, vp, i32, vp, i64, i32, i32, vp, vp, vp]
+    lib.pq_quantize_tables.restype = i32
+    lib.pq_adc_scan_topk.argtypes = [vp, vp, vp, i32, vp, i64, i32, vp, vp, vp, vp, sz, vp]
+    lib.pq_adc_scan_topk.restype = i32
+    lib.ivf_adc_scan_topk.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, vp, i32, i32, i32, vp, vp,
+                                      vp, sz, vp]
+    lib.ivf_adc_scan_topk.restype = i32
+    lib.pq_profile_enable.argtypes = [i32]
+    lib.pq_profile_enable.restype = None
+    lib.pq_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double)]
+    lib.pq_profile_read.restype = i32
+    lib.pq_last_error.argtypes = []
+    lib.pq_last_error.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int) -> None:
+    if rc != PQ_OK:
+        raise QadcError(rc, load().pq_last_error().decode("utf-8", "replace"))
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous(), "libqadc needs contiguous tensors"
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _dev(t: torch.Tensor, dtype) -> None:
+    assert t.is_cuda and t.dtype == dtype, (t.device, t.dtype, dtype)
+
+
+class PqIndex:
+    """Owner of a ``pq_index_t*`` (pq_index_create / pq_index_destroy)."""
+
+    def __init__(self, d: int, nbits: Sequence[int], dsub: Sequence[int], codebooks: torch.Tensor,
+                 acc_bits: int):
+        lib = load()
+        _dev(codebooks, torch.float32)
+        self.codebooks = codebooks.contiguous()  # the handle keeps this pointer
+        nb = (ctypes.c_int32 * len(nbits))(*nbits)
+        ds = (ctypes.c_int32 * len(dsub))(*dsub)
+        h = ctypes.c_void_p()
+        with torch.cuda.device(codebooks.device):
+            _check(lib.pq_index_create(ctypes.byref(h), d, len(nbits), ctypes.cast(nb, ctypes.c_void_p),
+                                       ctypes.cast(ds, ctypes.c_void_p), self.codebooks.data_ptr(),
+                                       acc_bits))
+        self.handle = h
+        self.d, self.m, self.acc_bits = d, len(nbits), acc_bits
+        self.nbits, self.dsub = list(nbits), list(dsub)
+        self.code_size = int(lib.pq_code_size(h))
+        self.table_len = int(lib.pq_table_len(h))
+        self.q_max = (1 << acc_bits) - 1
+        self.qdtype = torch.uint8 if acc_bits == 8 else torch.uint16
+        self.device = codebooks.device
+
+    def close(self) -> None:
+        if getattr(self, "handle", None):
+            load().pq_index_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def pq_workspace_bytes(idx: PqIndex, nq: int, n: int, R: int) -> int:
+    return int(load().pq_workspace_bytes(idx.handle, nq, n, R))
+
+
+def ivf_workspace_bytes(idx: PqIndex, nq: int, nprobe: int, R: int) -> int:
+    return int(load().ivf_workspace_bytes(idx.handle, nq, nprobe, R))
+
+
+def pq_compute_tables(idx: PqIndex, queries: torch.Tensor, tables: Optional[torch.Tensor] = None,
+                      stream=None) -> torch.Tensor:
+    _dev(queries, torch.float32)
+    nq = queries.shape[0]
+    if tables is None:
+        tables = torch.empty((nq, idx.table_len), dtype=torch.float32, device=queries.device)
+    _check(load().pq_compute_tables(idx.handle, _ptr(queries), nq, _ptr(tables), _stream(stream)))
+    return tables
+
+
+def pq_quantize_tables(idx: PqIndex, tables: torch.Tensor, codes: torch.Tensor, t: int, R: int,
+                       qtables: Optional[torch.Tensor] = None,
+                       qparams: Optional[torch.Tensor] = None, stream=None
+                       ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """qparams is a [nq, 24] uint8 tensor holding pq_qparams_t records."""
+    _dev(tables, torch.float32)
+    _dev(codes, torch.uint8)
+    nq = tables.shape[0]
+    if qtables is None:
+        qtables = torch.empty((nq, idx.table_len), dtype=idx.qdtype, device=tables.device)
+    if qparams is None:
+        qparams = torch.empty((nq, QPARAMS_BYTES), dtype=torch.uint8, device=tables.device)
+    _check(load().pq_quantize_tables(idx.handle, _ptr(tables), nq, _ptr(codes), codes.shape[0], t, R,
+                                     _ptr(qtables), _ptr(qparams), _stream(stream)))
+    return qtables, qparams
+
+
+def pq_adc_scan_topk(idx: PqIndex, qtables: torch.Tensor, qparams: torch.Tensor,
+                     codes: torch.Tensor, R: int, workspace: Optional[torch.Tensor] = None,
+                     out=None, stream=None):
+    _dev(codes, torch.uint8)
+    nq, n = qtables.shape[0], codes.shape[0]
+    dev = codes.device
+    if workspace is None:
+        workspace = torch.empty(pq_workspace_bytes(idx, nq, n, R), dtype=torch.uint8, device=dev)
+    if out is None:
+        out = (torch.empty((nq, R), dtype=torch.int32, device=dev),
+               torch.empty((nq, R), dtype=torch.uint16, device=dev),
+               torch.empty((nq, R), dtype=torch.float32, device=dev))
+    ids, keys, dist = out
+    _check(load().pq_adc_scan_topk(idx.handle, _ptr(qtables), _ptr(qparams), nq, _ptr(codes), n, R,
+                                   _ptr(ids), _ptr(keys), _ptr(dist), _ptr(workspace),
+                                   workspace.numel(), _stream(stream)))
+    return ids, keys, dist
+
+
+def ivf_adc_scan_topk(idx: PqIndex, coarse: torch.Tensor, list_offsets: torch.Tensor,
+                      list_codes: torch.Tensor, list_ids: torch.Tensor, queries: torch.Tensor,
+                      probe_ids: torch.Tensor, t: int, R: int,
+                      workspace: Optional[torch.Tensor] = None, out=None, stream=None):
+    _dev(coarse, torch.float32)
+    _dev(list_offsets, torch.int64)
+    _dev(list_codes, torch.uint8)
+    _dev(list_ids, torch.int32)
+    _dev(queries, torch.float32)
+    _dev(probe_ids, torch.int32)
+    nq, nprobe = probe_ids.shape
+    dev = queries.device
+    if workspace is None:
+        workspace = torch.empty(ivf_workspace_bytes(idx, nq, nprobe, R), dtype=torch.uint8,
+                                device=dev)
+    if out is None:
+        out = (torch.empty((nq, R), dtype=torch.int32, device=dev),
+               torch.empty((nq, R), dtype=torch.float32, device=dev))
+    ids, dist = out
+    _check(load().ivf_adc_scan_topk(idx.handle, _ptr(coarse), coarse.shape[0], _ptr(list_offsets),
+                                    _ptr(list_codes), _ptr(list_ids), _ptr(queries), nq,
+                                    _ptr(probe_ids), nprobe, t, R, _ptr(ids), _ptr(dist),
+                                    _ptr(workspace), workspace.numel(), _stream(stream)))
+    return ids, dist
+
+
+def pq_profile_enable(on: bool) -> None:
+    load().pq_profile_enable(1 if on else 0)
+
+
+def pq_profile_read() -> Tuple[int, float]:
+    ms = ctypes.c_double(0.0)
+    cnt = load().pq_profile_read(ctypes.byref(ms))
+    return int(cnt), float(ms.value)
+
+
+def unpack_qparams(qparams: torch.Tensor):
+    """[nq,24] uint8 -> dict of numpy arrays (d_min, delta, d_max, key_bound)."""
+    import numpy as np
+    raw = qparams.detach().cpu().numpy()
+    rec = np.dtype([("d_min", "<f8"), ("delta", "<f8"), ("d_max", "<f4"), ("key_bound", "<u4")])
+    return raw.view(rec).reshape(-1)

@@ -1,0 +1,235 @@
+// Index handle, layout planning, error reporting and the timing hook.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "qadc_internal.h"
+
+static thread_local char g_err[512] = "";
+
+void qadc_set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char *pq_last_error(void) { return g_err; }
+
+// Partition the sub-quantizers into consecutive groups of at most gmax bits.
+static void plan_groups(DevLayout &L, int gmax) {
+    L.ng = 0;
+    L.gtab_len = 0;
+    int j = 0;
+    while (j < L.m) {
+        int g = L.ng++;
+        L.gfirst[g] = (uint8_t)j;
+        L.goff[g] = L.bitoff[j];
+        int w = L.nbits[j];
+        int cnt = 1;
+        while (j + cnt < L.m && w + L.nbits[j + cnt] <= gmax) {
+            w += L.nbits[j + cnt];
+            ++cnt;
+        }
+        L.gw[g] = (uint8_t)w;
+        L.gcount[g] = (uint8_t)cnt;
+        L.gbase[g] = (uint32_t)L.gtab_len;
+        L.gtab_len += 1 << w;
+        j += cnt;
+    }
+}
+
+extern "C" int pq_index_create(pq_index_t **out, int d, int m, const int32_t *nbits,
+                               const int32_t *dsub, const float *codebooks, int acc_bits) {
+    if (!out || !nbits || !dsub || !codebooks) {
+        qadc_set_error("pq_index_create: null argument");
+        return PQ_EINVAL;
+    }
+    *out = nullptr;
+    if (d < 1 || d > PQ_MAX_DIM || m < 1 || m > PQ_MAX_M || (acc_bits != 8 && acc_bits != 16)) {
+        qadc_set_error("pq_index_create: need 1<=d<=%d, 1<=m<=%d, acc_bits in {8,16} (got d=%d m=%d acc_bits=%d)",
+                       PQ_MAX_DIM, PQ_MAX_M, d, m, acc_bits);
+        return PQ_EINVAL;
+    }
+    DevLayout L;
+    memset(&L, 0, sizeof(L));
+    L.d = d;
+    L.m = m;
+    L.acc_bits = acc_bits;
+    L.qmax = (1 << acc_bits) - 1;
+    int bit = 0, t = 0, dim = 0;
+    size_t cb = 0;
+    for (int j = 0; j < m; ++j) {
+        if (nbits[j] < 1 || nbits[j] > 8 || dsub[j] < 1) {
+            qadc_set_error("pq_index_create: nbits[%d]=%d (1..8) dsub[%d]=%d (>=1)", j, nbits[j], j, dsub[j]);
+            return PQ_EINVAL;
+        }
+        L.nbits[j] = (uint8_t)nbits[j];
+        L.bitoff[j] = (uint16_t)bit;
+        L.toff[j] = (uint16_t)t;
+        L.dimoff[j] = (uint16_t)dim;
+        L.dsub[j] = (uint16_t)dsub[j];
+        L.cboff[j] = (uint32_t)cb;
+        bit += nbits[j];
+        t += 1 << nbits[j];
+        dim += dsub[j];
+        cb += ((size_t)1 << nbits[j]) * (size_t)dsub[j];
+        if (dim > d) break;
+    }
+    if (dim != d) {
+        qadc_set_error("pq_index_create: sum(dsub)=%d differs from d=%d", dim, d);
+        return PQ_EINVAL;
+    }
+    if (t > PQ_MAX_TABLE_LEN) {
+        qadc_set_error("pq_index_create: table length %d exceeds %d", t, PQ_MAX_TABLE_LEN);
+        return PQ_EINVAL;
+    }
+    L.T = t;
+    L.code_bits = bit;
+    L.cs = (bit + 7) / 8;
+
+    // group plan: widest groups whose tables stay within 16 KB of LDS
+    const int esz = acc_bits == 8 ? 1 : 2;
+    bool all4 = true;
+    for (int j = 0; j < m; ++j) all4 = all4 && nbits[j] == 4;
+    if (all4 && m % 2 == 0) {
+        plan_groups(L, 8);
+    } else {
+        int gmax = 11;
+        for (; gmax >= 8; --gmax) {
+            plan_groups(L, gmax);
+            if ((size_t)L.gtab_len * esz <= 16384) break;
+        }
+        if (gmax < 8) plan_groups(L, 1);  // every sub-quantizer alone: T entries
+    }
+    L.kind = SCAN_GENERIC;
+    if (all4 && m == 16) L.kind = SCAN_NIB8;
+    if (all4 && m == 32) L.kind = SCAN_NIB16;
+
+    pq_index *idx = new pq_index;
+    idx->h = L;
+    idx->codebooks = codebooks;
+    idx->dev = nullptr;
+    hipError_t e = hipGetDevice(&idx->device);
+    if (e == hipSuccess) e = hipMalloc((void **)&idx->dev, sizeof(DevLayout));
+    if (e == hipSuccess) e = hipMemcpy(idx->dev, &L, sizeof(DevLayout), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        qadc_set_error("pq_index_create: %s", hipGetErrorString(e));
+        if (idx->dev) (void)hipFree(idx->dev);
+        delete idx;
+        return PQ_EHIP;
+    }
+    *out = idx;
+    return PQ_OK;
+}
+
+extern "C" void pq_index_destroy(pq_index_t *idx) {
+    if (!idx) return;
+    if (idx->dev) (void)hipFree(idx->dev);
+    delete idx;
+}
+
+extern "C" size_t pq_code_size(const pq_index_t *idx) { return idx ? (size_t)idx->h.cs : 0; }
+extern "C" size_t pq_table_len(const pq_index_t *idx) { return idx ? (size_t)idx->h.T : 0; }
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R) {
+    (void)idx;
+    ScanPlan p;
+    const int64_t tile_codes = 1024;
+    int64_t tiles = (n + tile_codes - 1) / tile_codes;
+    int64_t gmax = 2048 / (nq > 0 ? nq : 1);
+    if (gmax < 64) gmax = 64;
+    if (gmax > 2048) gmax = 2048;
+    int64_t G = tiles < 1 ? 1 : (tiles > gmax ? gmax : tiles);
+    p.G = (int)G;
+    p.cap_b = R <= 256 ? 512 : 2048;
+    int64_t pc = 32 * (int64_t)R;
+    if (pc < 16384) pc = 16384;
+    p.pilot_codes = n < pc ? n : pc;
+    p.state_off = 0;
+    p.counts_off = align_up(sizeof(ScanState), 256);
+    p.slots_off = p.counts_off + align_up((size_t)p.G * sizeof(uint32_t), 256);
+    p.per_query = p.slots_off + (size_t)p.G * (size_t)p.cap_b * sizeof(uint64_t);
+    p.per_query = align_up(p.per_query, 256);
+    p.total = p.per_query * (size_t)(nq > 0 ? nq : 0);
+    return p;
+}
+
+IvfPlan qadc_ivf_plan(const pq_index *idx, int nq, int nprobe, int R) {
+    (void)idx;
+    IvfPlan p;
+    p.cap_b = R <= 256 ? 1024 : 4096;
+    p.counts_off = align_up(sizeof(IvfState), 256);
+    p.slots_off = p.counts_off + align_up((size_t)nprobe * sizeof(uint32_t), 256);
+    p.per_query = align_up(p.slots_off + (size_t)nprobe * (size_t)p.cap_b * sizeof(uint64_t), 256);
+    p.total = p.per_query * (size_t)(nq > 0 ? nq : 0);
+    return p;
+}
+
+extern "C" size_t ivf_workspace_bytes(const pq_index_t *idx, int nq, int nprobe, int R) {
+    if (!idx || nq < 0 || nprobe < 1 || R < 1) return 0;
+    size_t t = qadc_ivf_plan(idx, nq, nprobe, R).total;
+    return t ? t : 256;
+}
+
+extern "C" size_t pq_workspace_bytes(const pq_index_t *idx, int nq, int64_t n, int R) {
+    if (!idx || nq < 0 || n < 0 || R < 1) return 0;
+    size_t t = qadc_scan_plan(idx, nq, n, R).total;
+    return t ? t : 256;
+}
+
+// ---------------------------------------------------------------- profiling --
+static bool g_prof_on = false;
+static std::vector<hipEvent_t> g_prof_ev;   // begin/end pairs
+static std::vector<hipEvent_t> g_prof_pool;
+
+static hipEvent_t prof_get_event() {
+    hipEvent_t e = nullptr;
+    if (!g_prof_pool.empty()) {
+        e = g_prof_pool.back();
+        g_prof_pool.pop_back();
+    } else if (hipEventCreate(&e) != hipSuccess) {
+        e = nullptr;
+    }
+    return e;
+}
+
+void qadc_prof_begin(hipStream_t s) {
+    if (!g_prof_on) return;
+    hipEvent_t e = prof_get_event();
+    if (e) (void)hipEventRecord(e, s);
+    g_prof_ev.push_back(e);
+}
+
+void qadc_prof_end(hipStream_t s) {
+    if (!g_prof_on) return;
+    hipEvent_t e = prof_get_event();
+    if (e) (void)hipEventRecord(e, s);
+    g_prof_ev.push_back(e);
+}
+
+extern "C" void pq_profile_enable(int on) { g_prof_on = on != 0; }
+
+extern "C" int pq_profile_read(double *total_ms) {
+    double tot = 0.0;
+    int cnt = 0;
+    for (size_t i = 0; i + 1 < g_prof_ev.size(); i += 2) {
+        hipEvent_t a = g_prof_ev[i], b = g_prof_ev[i + 1];
+        if (a && b && hipEventSynchronize(b) == hipSuccess) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, a, b) == hipSuccess) {
+                tot += ms;
+                ++cnt;
+            }
+        }
+    }
+    for (hipEvent_t e : g_prof_ev)
+        if (e) g_prof_pool.push_back(e);
+    g_prof_ev.clear();
+    if (total_ms) *total_ms = tot;
+    return cnt;
+}

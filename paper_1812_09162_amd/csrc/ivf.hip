@@ -1,0 +1,530 @@
+// ivf_adc_scan_topk: ADC over the inverted lists of the probed cells.
+// Section 2.1.1 (residuals are encoded), Section 2.1.3 (one table set per probed
+// cell from z' = z - centroid), Section 3.4 (distance quantizer).
+//
+//   k_ivf_calib  one block per query: float ADC of the first t_eff probed codes
+//                (each with its own cell's tables) -> d_max; then the quantized
+//                distances of the same codes -> a first bound thr0 on the R-th
+//                best distance and the binning (lo, scale) used for pruning.
+//   k_ivf_scan   one block per (query, probed cell): residual tables, the
+//                cell's p_min / d_min / delta from the shared d_max, quantized
+//                group tables in LDS, scan of the list; candidates are
+//                (distance, stored id) packed into a sortable 64-bit word.
+//   k_ivf_final  one block per query: rank the surviving candidates; exact
+//                multi-pass selection over all probed codes if a slot overflowed.
+#include "scan_device.h"
+
+struct IvfLds {
+    float *zres;   // [d]
+    float *tab;    // [T]
+    float *pmin;   // [PQ_MAX_M]
+    uint16_t *qt;  // [T]
+    void *gtab;    // [gtab_len] of QT
+    double *sc;    // {d_min, delta}
+    int *flag;     // skip flag
+};
+
+__device__ inline size_t ivf_lds_bytes_dev(const DevLayout *L, size_t esz) {
+    return (size_t)L->d * 4 + (size_t)L->T * 4 + PQ_MAX_M * 4 + (size_t)L->T * 2 +
+           (((size_t)L->gtab_len * esz + 15) & ~(size_t)15) + 32;
+}
+static size_t ivf_lds_bytes(const DevLayout &L, size_t esz) {
+    return (size_t)L.d * 4 + (size_t)L.T * 4 + PQ_MAX_M * 4 + (size_t)L.T * 2 +
+           (((size_t)L.gtab_len * esz + 15) & ~(size_t)15) + 32;
+}
+
+// carve the per-list LDS arrays out of `base` (16-byte aligned)
+__device__ inline unsigned char *ivf_carve(const DevLayout *L, unsigned char *base, size_t esz,
+                                           IvfLds &l) {
+    unsigned char *p = base;
+    l.sc = (double *)p;      p += 16;
+    l.flag = (int *)p;       p += 16;
+    l.zres = (float *)p;     p += (size_t)L->d * 4;
+    l.tab = (float *)p;      p += (size_t)L->T * 4;
+    l.pmin = (float *)p;     p += PQ_MAX_M * 4;
+    l.gtab = (void *)p;      p += (((size_t)L->gtab_len * esz + 15) & ~(size_t)15);
+    l.qt = (uint16_t *)p;    p += (size_t)L->T * 2;
+    return p;
+}
+
+// Block-wide: residual, float tables (eq. (1)), p_min, d_min; with `quantize`
+// also delta from dmax, the quantized table and (with `groups`) the group
+// tables.  Returns false when the list is skipped (d_min > d_max).
+template <typename QT>
+__device__ inline bool ivf_setup(const DevLayout *L, const float *__restrict__ cb,
+                                 const float *__restrict__ z, const float *__restrict__ cen,
+                                 float dmax, bool quantize, bool groups, const IvfLds &l) {
+    const int d = L->d, m = L->m, T = L->T, qmax = L->qmax;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) l.zres[i] = __fsub_rn(z[i], cen[i]);
+    __syncthreads();
+    for (int e = threadIdx.x; e < T; e += blockDim.x) {
+        int j = 0;
+        while (j + 1 < m && (int)L->toff[j + 1] <= e) ++j;
+        const int i = e - L->toff[j];
+        const int ds = L->dsub[j];
+        const float *c = cb + L->cboff[j] + (size_t)i * ds;
+        const float *zz = l.zres + L->dimoff[j];
+        float acc = 0.0f;
+        for (int k = 0; k < ds; ++k) {
+            float diff = __fsub_rn(zz[k], c[k]);
+            acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+        }
+        l.tab[e] = acc;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < m) {
+        const int j = threadIdx.x;
+        const int kj = 1 << L->nbits[j];
+        const float *tj = l.tab + L->toff[j];
+        float mn = tj[0];
+        for (int i = 1; i < kj; ++i) mn = tj[i] < mn ? tj[i] : mn;
+        l.pmin[j] = mn;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double dm = 0.0;
+        for (int j = 0; j < m; ++j) dm = dm + (double)l.pmin[j];
+        l.sc[0] = dm;
+        int skip = 0;
+        double delta = 0.0;
+        if (quantize) {
+            skip = dm > (double)dmax;
+            delta = ((double)dmax - dm) / (double)qmax;
+            if (!((delta > 0.0) && isfinite(delta))) delta = 0.0;
+        }
+        l.sc[1] = delta;
+        *l.flag = skip;
+    }
+    __syncthreads();
+    if (!quantize) return true;
+    if (*l.flag) return false;
+    const double delta = l.sc[1];
+    for (int e = threadIdx.x; e < T; e += blockDim.x) {
+        int j = 0;
+        while (j + 1 < m && (int)L->toff[j + 1] <= e) ++j;
+        uint32_t qv = 0;
+        if (delta > 0.0) {
+            double x = floor(((double)l.tab[e] - (double)l.pmin[j]) / delta);
+            qv = (x >= (double)qmax) ? (uint32_t)qmax : (uint32_t)x;
+        }
+        l.qt[e] = (uint16_t)qv;
+    }
+    __syncthreads();
+    if (groups) build_gtab<QT, uint16_t>(L, l.qt, (QT *)l.gtab);
+    return true;
+}
+
+__device__ __forceinline__ uint32_t dist_bin(float dist, float lo, float scale) {
+    float x = (dist - lo) * scale;
+    return x <= 0.0f ? 0u : (x >= 255.0f ? 255u : (uint32_t)x);
+}
+
+// ------------------------------------------------------------ k_ivf_calib ---
+__global__ void __launch_bounds__(256)
+k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
+            const float *__restrict__ coarse, const int64_t *__restrict__ list_offsets,
+            const uint8_t *__restrict__ list_codes, const float *__restrict__ queries,
+            const int32_t *__restrict__ probe_ids, int nprobe, int want, int R,
+            char *__restrict__ ws, size_t per_query) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sel[2];
+    __shared__ long long s_np;
+    IvfLds l;
+    unsigned char *rest = ivf_carve(L, smem, 2, l);
+    uint32_t *ord = (uint32_t *)rest;  // [want]
+    const size_t q = blockIdx.x;
+    IvfState *st = (IvfState *)(ws + q * per_query);
+    const int32_t *probes = probe_ids + q * nprobe;
+    const float *z = queries + q * L->d;
+    const int m = L->m, cs = L->cs, qmax = L->qmax;
+
+    if (threadIdx.x == 0) {
+        long long np = 0;
+        for (int a = 0; a < nprobe; ++a) {
+            int c = probes[a];
+            if (c >= 0) np += list_offsets[c + 1] - list_offsets[c];
+        }
+        s_np = np;
+    }
+    for (int i = threadIdx.x; i < 256; i += blockDim.x) st->hist[i] = 0;
+    __syncthreads();
+    const int t_eff = (int)(s_np < (long long)want ? s_np : (long long)want);
+    const int k = R < t_eff ? R : t_eff;
+    if (t_eff == 0) {
+        if (threadIdx.x == 0) {
+            st->thr = 255u;
+            st->overflow = 0u;
+            st->dmax = INFINITY;
+            st->thr0 = INFINITY;
+            st->lo = 0.f;
+            st->scale = 0.f;
+        }
+        return;
+    }
+    // pass 1: float ADC of the calibration codes
+    int seen = 0;
+    for (int a = 0; a < nprobe && seen < t_eff; ++a) {
+        const int c = probes[a];
+        if (c < 0) continue;
+        const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
+        if (hi == lo) continue;
+        ivf_setup<uint16_t>(L, cb, z, coarse + (size_t)c * L->d, 0.f, false, false, l);
+        const int take = (int)((hi - lo) < (int64_t)(t_eff - seen) ? (hi - lo) : (int64_t)(t_eff - seen));
+        for (int p = threadIdx.x; p < take; p += blockDim.x) {
+            const uint8_t *code = list_codes + (size_t)(lo + p) * cs;
+            float s = 0.0f;
+            for (int j = 0; j < m; ++j)
+                s = __fadd_rn(s, l.tab[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])]);
+            ord[seen + p] = qadc_f2ord(s);
+        }
+        seen += take;
+        __syncthreads();
+    }
+    const float dmax = qadc_ord2f(qadc_block_kth_u32(ord, t_eff, k, 4, hist, sel));
+    // pass 2: quantized distances of the same codes -> thr0 and the binning
+    seen = 0;
+    for (int a = 0; a < nprobe && seen < t_eff; ++a) {
+        const int c = probes[a];
+        if (c < 0) continue;
+        const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
+        if (hi == lo) continue;
+        const bool ok = ivf_setup<uint16_t>(L, cb, z, coarse + (size_t)c * L->d, dmax, true, false, l);
+        const int take = (int)((hi - lo) < (int64_t)(t_eff - seen) ? (hi - lo) : (int64_t)(t_eff - seen));
+        const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
+        for (int p = threadIdx.x; p < take; p += blockDim.x) {
+            uint32_t o = 0xffffffffu;
+            if (ok) {
+                const uint8_t *code = list_codes + (size_t)(lo + p) * cs;
+                uint32_t acc = 0;
+                for (int j = 0; j < m; ++j)
+                    acc += l.qt[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])];
+                if (acc > (uint32_t)qmax) acc = (uint32_t)qmax;
+                o = qadc_f2ord(fmaf((float)acc, fdelta, fdmin));
+            }
+            ord[seen + p] = o;
+        }
+        seen += take;
+        __syncthreads();
+    }
+    const uint32_t inf_o = qadc_f2ord(INFINITY);
+    uint32_t t0 = qadc_block_kth_u32(ord, t_eff, k, 4, hist, sel);
+    uint32_t l0 = qadc_block_kth_u32(ord, t_eff, 1, 4, hist, sel);
+    if (threadIdx.x == 0) {
+        const float thr0 = t0 > inf_o ? INFINITY : qadc_ord2f(t0);
+        const float lo = l0 > inf_o ? 0.f : qadc_ord2f(l0);
+        const float span = thr0 - lo;
+        st->thr = 255u;
+        st->overflow = 0u;
+        st->dmax = dmax;
+        st->thr0 = thr0;
+        st->lo = lo;
+        st->scale = (span > 0.f && isfinite(span)) ? 256.0f / span : 0.f;
+    }
+}
+
+// ------------------------------------------------------------- k_ivf_scan ---
+template <int KIND, typename QT>
+__global__ void __launch_bounds__(256)
+k_ivf_scan(const DevLayout *__restrict__ L, const float *__restrict__ cb,
+           const float *__restrict__ coarse, const int64_t *__restrict__ list_offsets,
+           const uint8_t *__restrict__ list_codes, const int32_t *__restrict__ list_ids,
+           const float *__restrict__ queries, const int32_t *__restrict__ probe_ids, int nprobe,
+           int R, char *__restrict__ ws, size_t per_query, size_t counts_off, size_t slots_off,
+           int cap_b) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ uint32_t s_count;
+    IvfLds l;
+    ivf_carve(L, smem, sizeof(QT), l);
+    const size_t q = blockIdx.y;
+    const int a = blockIdx.x;
+    char *wq = ws + q * per_query;
+    IvfState *st = (IvfState *)wq;
+    uint32_t *counts = (uint32_t *)(wq + counts_off);
+    const int c = probe_ids[q * nprobe + a];
+    int64_t lo = 0, hi = 0;
+    if (c >= 0) {
+        lo = list_offsets[c];
+        hi = list_offsets[c + 1];
+    }
+    if (hi == lo) {
+        if (threadIdx.x == 0) counts[a] = 0;
+        return;
+    }
+    const float dmax = st->dmax, thr0 = st->thr0, blo = st->lo, bscale = st->scale;
+    if (threadIdx.x == 0) s_count = 0;
+    const bool ok = ivf_setup<QT>(L, cb, queries + q * L->d, coarse + (size_t)c * L->d, dmax, true,
+                                  true, l);
+    if (!ok) {
+        if (threadIdx.x == 0) counts[a] = 0;
+        return;
+    }
+    const QT *gtab = (const QT *)l.gtab;
+    const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
+    SlotRef ref;
+    ref.slot = (uint64_t *)(wq + slots_off) + (size_t)a * cap_b;
+    ref.cap = (uint32_t)cap_b;
+    ref.lds_count = &s_count;
+    ref.st = (ScanState *)st;
+    for (int64_t base = lo; base < hi; base += 1024) {
+        const uint32_t thr = __hip_atomic_load(&st->thr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        float dist[4];
+        uint32_t bin[4];
+        bool pass[4], any = false;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t p = base + u * 256 + threadIdx.x;
+            const bool valid = p < hi;
+            const uint32_t key = valid ? key_at<KIND, QT>(L, gtab, list_codes, p) : 0u;
+            dist[u] = fmaf((float)key, fdelta, fdmin);
+            bin[u] = dist_bin(dist[u], blo, bscale);
+            pass[u] = valid && dist[u] <= thr0 && bin[u] <= thr;
+            any = any || pass[u];
+        }
+        if (__ballot(any) != 0) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t p = base + u * 256 + threadIdx.x;
+                const uint32_t id = pass[u] ? (uint32_t)list_ids[p] : 0u;
+                wave_append(pass[u], qadc_f2ord(dist[u]), id, bin[u], ref);
+            }
+            uint32_t nb = wave_bound_from_hist(st->hist, (uint32_t)R);
+            if (__lane_id() == 0 && nb < thr) atomicMin(&st->thr, nb);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) counts[a] = s_count < (uint32_t)cap_b ? s_count : (uint32_t)cap_b;
+}
+
+// ------------------------------------------------------------ k_ivf_final ---
+// Rank candidates (ordered-float distance << 32 | id) and write the first R.
+__device__ inline void ivf_rank_and_write(const uint64_t *A, int na, int R, int32_t *ids,
+                                          float *dist) {
+    for (int i = threadIdx.x; i < na; i += blockDim.x) {
+        const uint64_t mine = A[i];
+        int rank = 0;
+        for (int j = 0; j < na; ++j) rank += (A[j] < mine) ? 1 : 0;
+        if (rank < R) {
+            ids[rank] = (int32_t)(uint32_t)mine;
+            dist[rank] = qadc_ord2f((uint32_t)(mine >> 32));
+        }
+    }
+    for (int r = (na < R ? na : R) + threadIdx.x; r < R; r += blockDim.x) {
+        ids[r] = -1;
+        dist[r] = INFINITY;
+    }
+}
+
+// Exact selection by one block over every code of the probed, unskipped lists:
+// byte-wise radix selection of the R-th smallest 64-bit (distance, id) word,
+// regenerating the stream once per byte, then one collecting pass.
+template <int KIND, typename QT>
+__device__ inline int ivf_exact_select(const DevLayout *L, const float *cb, const float *coarse,
+                                       const int64_t *list_offsets, const uint8_t *list_codes,
+                                       const int32_t *list_ids, const float *z,
+                                       const int32_t *probes, int nprobe, float dmax, int R,
+                                       const IvfLds &l, uint64_t *A, uint32_t *hist, uint32_t *sh) {
+    uint64_t prefix = 0, mask = 0;
+    uint32_t kk = 0;
+    // pass 8 counts the stream, passes 7..0 select a byte each, pass -1 collects
+    for (int pass = 8; pass >= -1; --pass) {
+        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+        if (threadIdx.x == 0) sh[2] = 0;
+        __syncthreads();
+        for (int a = 0; a < nprobe; ++a) {
+            const int c = probes[a];
+            if (c < 0) continue;
+            const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
+            if (hi == lo) continue;
+            if (!ivf_setup<QT>(L, cb, z, coarse + (size_t)c * L->d, dmax, true, true, l)) continue;
+            const QT *gtab = (const QT *)l.gtab;
+            const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
+            for (int64_t p = lo + threadIdx.x; p < hi; p += blockDim.x) {
+                const uint32_t key = key_at<KIND, QT>(L, gtab, list_codes, p);
+                const uint64_t item = ((uint64_t)qadc_f2ord(fmaf((float)key, fdelta, fdmin)) << 32) |
+                                      (uint64_t)(uint32_t)list_ids[p];
+                if (pass == 8) {
+                    atomicAdd(&hist[0], 1u);
+                } else if (pass >= 0) {
+                    if ((item & mask) == prefix) atomicAdd(&hist[(item >> (8 * pass)) & 255u], 1u);
+                } else if (item <= prefix) {
+                    uint32_t pos = atomicAdd(&sh[2], 1u);
+                    if (pos < (uint32_t)R) A[pos] = item;
+                }
+            }
+            __syncthreads();
+        }
+        __syncthreads();
+        if (pass == 8) {
+            const uint32_t total = hist[0];
+            kk = total < (uint32_t)R ? total : (uint32_t)R;
+            if (kk == 0) return 0;
+        } else if (pass >= 0) {
+            if (threadIdx.x == 0) {
+                uint32_t run = 0;
+                int b = 0;
+                for (; b < 255; ++b) {
+                    if (run + hist[b] >= kk) break;
+                    run += hist[b];
+                }
+                sh[0] = (uint32_t)b;
+                sh[1] = kk - run;
+            }
+            __syncthreads();
+            prefix |= (uint64_t)sh[0] << (8 * pass);
+            mask |= (uint64_t)255u << (8 * pass);
+            kk = sh[1];
+        }
+        __syncthreads();
+    }
+    const uint32_t got = sh[2];
+    return (int)(got < (uint32_t)R ? got : (uint32_t)R);
+}
+
+template <int KIND, typename QT>
+__global__ void __launch_bounds__(1024)
+k_ivf_final(const DevLayout *__restrict__ L, const float *__restrict__ cb,
+            const float *__restrict__ coarse, const int64_t *__restrict__ list_offsets,
+            const uint8_t *__restrict__ list_codes, const int32_t *__restrict__ list_ids,
+            const float *__restrict__ queries, const int32_t *__restrict__ probe_ids, int nprobe,
+            int R, char *__restrict__ ws, size_t per_query, size_t counts_off, size_t slots_off,
+            int cap_b, int32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t sh[8];
+    uint64_t *A = (uint64_t *)smem;  // FINAL_CAP entries
+    const size_t q = blockIdx.x;
+    char *wq = ws + q * per_query;
+    IvfState *st = (IvfState *)wq;
+    const uint32_t *counts = (const uint32_t *)(wq + counts_off);
+    const uint64_t *slots = (const uint64_t *)(wq + slots_off);
+    if (threadIdx.x == 0) {
+        sh[0] = 0;
+        sh[1] = st->overflow;
+    }
+    __syncthreads();
+    const uint32_t thr = st->thr;
+    const float blo = st->lo, bscale = st->scale;
+    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
+    const int nwaves = blockDim.x / QADC_WAVE;
+    for (int a = wave; a < nprobe; a += nwaves) {
+        const uint32_t cnt = counts[a];
+        for (uint32_t i = lane; i < cnt; i += QADC_WAVE) {
+            const uint64_t c = slots[(size_t)a * cap_b + i];
+            if (dist_bin(qadc_ord2f((uint32_t)(c >> 32)), blo, bscale) <= thr) {
+                uint32_t pos = atomicAdd(&sh[0], 1u);
+                if (pos < FINAL_CAP)
+                    A[pos] = c;
+                else
+                    sh[1] = 1u;
+            }
+        }
+    }
+    __syncthreads();
+    int na = (int)sh[0];
+    const bool slow = sh[1] != 0;
+    __syncthreads();
+    if (slow) {
+        IvfLds l;
+        ivf_carve(L, smem + FINAL_CAP * 8, sizeof(QT), l);
+        na = ivf_exact_select<KIND, QT>(L, cb, coarse, list_offsets, list_codes, list_ids,
+                                        queries + q * L->d, probe_ids + q * nprobe, nprobe,
+                                        st->dmax, R, l, A, hist, sh);
+        __syncthreads();
+    }
+    ivf_rank_and_write(A, na, R, out_ids + q * R, out_dist + q * R);
+}
+
+// ------------------------------------------------------------------ host ---
+template <typename K>
+static int allow_lds(K kernel, size_t bytes) {
+    if (bytes <= 48 * 1024) return PQ_OK;
+    QADC_HIP_TRY(hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)bytes));
+    return PQ_OK;
+}
+
+template <int KIND, typename QT>
+static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *list_offsets,
+                      const uint8_t *list_codes, const int32_t *list_ids, const float *queries,
+                      int nq, const int32_t *probe_ids, int nprobe, int want, int R,
+                      int32_t *out_ids, float *out_dist, char *ws, const IvfPlan &p, hipStream_t s) {
+    const size_t lds_calib = ivf_lds_bytes(idx->h, 2) + (size_t)want * 4;
+    const size_t lds_scan = ivf_lds_bytes(idx->h, sizeof(QT));
+    const size_t lds_final = FINAL_CAP * 8 + lds_scan;
+    int rc;
+    if ((rc = allow_lds(k_ivf_calib, lds_calib)) != PQ_OK) return rc;
+    if ((rc = allow_lds(k_ivf_scan<KIND, QT>, lds_scan)) != PQ_OK) return rc;
+    if ((rc = allow_lds(k_ivf_final<KIND, QT>, lds_final)) != PQ_OK) return rc;
+    hipLaunchKernelGGL(k_ivf_calib, dim3(nq), dim3(256), lds_calib, s, idx->dev, idx->codebooks,
+                       coarse, list_offsets, list_codes, queries, probe_ids, nprobe, want, R, ws,
+                       p.per_query);
+    QADC_LAUNCH_CHECK("k_ivf_calib");
+    qadc_prof_begin(s);
+    hipLaunchKernelGGL((k_ivf_scan<KIND, QT>), dim3(nprobe, nq), dim3(256), lds_scan, s, idx->dev,
+                       idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,
+                       probe_ids, nprobe, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b);
+    qadc_prof_end(s);
+    QADC_LAUNCH_CHECK("k_ivf_scan");
+    hipLaunchKernelGGL((k_ivf_final<KIND, QT>), dim3(nq), dim3(1024), lds_final, s, idx->dev,
+                       idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,
+                       probe_ids, nprobe, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b,
+                       out_ids, out_dist);
+    QADC_LAUNCH_CHECK("k_ivf_final");
+    return PQ_OK;
+}
+
+extern "C" int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_centroids, int K,
+                                 const int64_t *list_offsets, const uint8_t *list_codes,
+                                 const int32_t *list_ids, const float *queries, int nq,
+                                 const int32_t *probe_ids, int nprobe, int t, int R,
+                                 int32_t *out_ids, float *out_dist, void *workspace,
+                                 size_t workspace_bytes, void *stream) {
+    if (!idx || nq < 0 || K < 1 || nprobe < 1 || nprobe > 1024) {
+        qadc_set_error("ivf_adc_scan_topk: bad handle, nq, K or nprobe (1..1024)");
+        return PQ_EINVAL;
+    }
+    if (R < 1 || R > PQ_MAX_R || t < 1) {
+        qadc_set_error("ivf_adc_scan_topk: need 1<=R<=%d and t>=1 (got R=%d t=%d)", PQ_MAX_R, R, t);
+        return PQ_EINVAL;
+    }
+    const int64_t want = t > 4 * (int64_t)R ? t : 4 * (int64_t)R;
+    if (want > PQ_MAX_T_EFF) {
+        qadc_set_error("ivf_adc_scan_topk: max(t,4R)=%lld exceeds %d", (long long)want, PQ_MAX_T_EFF);
+        return PQ_EINVAL;
+    }
+    if (nq == 0) return PQ_OK;
+    if (nq > 65535) {
+        qadc_set_error("ivf_adc_scan_topk: at most 65535 queries per call (got %d)", nq);
+        return PQ_EINVAL;
+    }
+    if (!coarse_centroids || !list_offsets || !list_codes || !list_ids || !queries || !probe_ids ||
+        !out_ids || !out_dist || !workspace) {
+        qadc_set_error("ivf_adc_scan_topk: null pointer");
+        return PQ_EINVAL;
+    }
+    if (((uintptr_t)list_codes & 15u) != 0 || ((uintptr_t)workspace & 255u) != 0) {
+        qadc_set_error("ivf_adc_scan_topk: list_codes must be 16-byte and workspace 256-byte aligned");
+        return PQ_EINVAL;
+    }
+    const IvfPlan p = qadc_ivf_plan(idx, nq, nprobe, R);
+    if (workspace_bytes < p.total) {
+        qadc_set_error("ivf_adc_scan_topk: workspace of %zu bytes, need %zu", workspace_bytes, p.total);
+        return PQ_ENOMEM;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const bool u8 = idx->h.acc_bits == 8;
+#define QADC_GO(KIND, QT)                                                                          \
+    return launch_ivf<KIND, QT>(idx, coarse_centroids, list_offsets, list_codes, list_ids, queries, \
+                                nq, probe_ids, nprobe, (int)want, R, out_ids, out_dist, ws, p, s)
+    switch (idx->h.kind) {
+        case SCAN_NIB8:
+            if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);
+        case SCAN_NIB16:
+            if (u8) QADC_GO(SCAN_NIB16, uint8_t); else QADC_GO(SCAN_NIB16, uint16_t);
+        default:
+            if (u8) QADC_GO(SCAN_GENERIC, uint8_t); else QADC_GO(SCAN_GENERIC, uint16_t);
+    }
+#undef QADC_GO
+}

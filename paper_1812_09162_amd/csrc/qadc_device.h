@@ -1,0 +1,94 @@
+// Device-side helpers shared by the kernels of libqadc (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qadc_internal.h"
+
+#define QADC_WAVE 64
+
+// Sub-code extraction from a little-endian bit stream (Section 3.3): `b` bits
+// starting at bit `off`; b <= 8, so at most two bytes are touched and the
+// second one is only read when the field really reaches into it.
+__device__ __forceinline__ uint32_t qadc_extract_sub(const uint8_t *code, int off, int b) {
+    int byte = off >> 3, sh = off & 7;
+    uint32_t v = (uint32_t)code[byte] >> sh;
+    if (sh + b > 8) v |= (uint32_t)code[byte + 1] << (8 - sh);
+    return v & ((1u << b) - 1u);
+}
+
+// Group field extraction: `w` <= 12 bits starting at bit `off` of a code of
+// `cs` bytes; touches at most three bytes, never past the end of the code.
+__device__ __forceinline__ uint32_t qadc_extract_group(const uint8_t *code, int cs, int off, int w) {
+    int byte = off >> 3, sh = off & 7;
+    uint32_t v = code[byte];
+    if (byte + 1 < cs) v |= (uint32_t)code[byte + 1] << 8;
+    if (byte + 2 < cs) v |= (uint32_t)code[byte + 2] << 16;
+    return (v >> sh) & ((1u << w) - 1u);
+}
+
+// Order-preserving map float -> uint32 (and back) for radix selection.
+__device__ __forceinline__ uint32_t qadc_f2ord(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float qadc_ord2f(uint32_t o) {
+    uint32_t u = (o & 0x80000000u) ? (o & 0x7fffffffu) : ~o;
+    return __uint_as_float(u);
+}
+
+// k-th smallest (k >= 1) of cnt uint32 values in LDS by most-significant-byte
+// radix selection over the bytes [0, nbytes).  All threads of the block call
+// it; `hist` is 256 words of LDS, `sel` two words.  Returns the value to every
+// thread.
+__device__ inline uint32_t qadc_block_kth_u32(const uint32_t *vals, int cnt, int k, int nbytes,
+                                              uint32_t *hist, uint32_t *sel) {
+    uint32_t prefix = 0, mask = 0;
+    int kk = k;
+    for (int pass = nbytes - 1; pass >= 0; --pass) {
+        int shift = pass * 8;
+        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < cnt; i += blockDim.x) {
+            uint32_t v = vals[i];
+            if ((v & mask) == prefix) atomicAdd(&hist[(v >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t run = 0;
+            int b = 0;
+            for (; b < 255; ++b) {
+                if (run + hist[b] >= (uint32_t)kk) break;
+                run += hist[b];
+            }
+            sel[0] = (uint32_t)b;
+            sel[1] = (uint32_t)kk - run;
+        }
+        __syncthreads();
+        prefix |= sel[0] << shift;
+        mask |= 255u << shift;
+        kk = (int)sel[1];
+        __syncthreads();
+    }
+    return prefix;
+}
+
+// Wave-wide inclusive prefix sum (wave64).
+__device__ __forceinline__ uint32_t qadc_wave_incl_scan(uint32_t v) {
+    int lane = __lane_id();
+#pragma unroll
+    for (int d = 1; d < QADC_WAVE; d <<= 1) {
+        uint32_t o = __shfl_up(v, d, QADC_WAVE);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+__device__ __forceinline__ uint32_t qadc_wave_min(uint32_t v) {
+#pragma unroll
+    for (int d = QADC_WAVE / 2; d >= 1; d >>= 1) {
+        uint32_t o = __shfl_xor(v, d, QADC_WAVE);
+        v = o < v ? o : v;
+    }
+    return v;
+}

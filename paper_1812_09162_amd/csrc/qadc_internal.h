@@ -1,0 +1,103 @@
+// Internal declarations shared by the translation units of libqadc.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qadc.h"
+
+// Layout of a product quantizer as the kernels see it.  A copy lives in device
+// memory; kernels read it through uniform (scalar) loads.
+//
+// Sub-quantizers are additionally partitioned into consecutive *groups* of at
+// most 12 code bits.  The scan looks up one pre-summed, pre-saturated entry per
+// group instead of one entry per sub-quantizer: because every addend is
+// non-negative, min(q_max, a+b+c+...) equals the saturating chain of Section
+// 3.4 no matter how the addends are bracketed.  For m x 4 layouts a group is
+// one code byte (two nibbles, 256 entries).
+struct DevLayout {
+    int32_t d, m, T, cs, acc_bits, qmax, code_bits;
+    int32_t ng;        // number of groups
+    int32_t gtab_len;  // total group-table entries
+    int32_t kind;      // SCAN_* below
+    uint8_t nbits[PQ_MAX_M];
+    uint16_t bitoff[PQ_MAX_M];  // first code bit of sub-quantizer j
+    uint16_t toff[PQ_MAX_M];    // first table entry of sub-quantizer j
+    uint16_t dimoff[PQ_MAX_M];  // first vector dimension of sub-quantizer j
+    uint16_t dsub[PQ_MAX_M];
+    uint32_t cboff[PQ_MAX_M];   // first codebook float of sub-quantizer j
+    uint8_t gw[PQ_MAX_M];       // bits of group g
+    uint16_t goff[PQ_MAX_M];    // first code bit of group g
+    uint8_t gfirst[PQ_MAX_M];   // first sub-quantizer of group g
+    uint8_t gcount[PQ_MAX_M];   // sub-quantizers in group g
+    uint32_t gbase[PQ_MAX_M];   // first group-table entry of group g
+};
+
+enum { SCAN_GENERIC = 0, SCAN_NIB8 = 1, SCAN_NIB16 = 2, SCAN_C5 = 3 };
+
+struct pq_index {
+    DevLayout h;          // host copy
+    DevLayout *dev;       // device copy
+    const float *codebooks;
+    int device;
+};
+
+// Per-query scratch state at the head of the scan workspace.
+struct ScanState {
+    uint32_t hist[256];  // candidates appended so far, per coarse key bin
+    uint32_t thr;        // current inclusive bin threshold
+    uint32_t overflow;   // a candidate slot overflowed: take the exact slow path
+    uint32_t pad[2];
+};
+
+// Per-query state of the inverted-list search; its head is laid out like ScanState.
+struct IvfState {
+    uint32_t hist[256];  // candidates appended so far, per bin of the unquantized distance
+    uint32_t thr;        // current inclusive bin threshold
+    uint32_t overflow;
+    float dmax;          // calibration bound (Section 3.4) shared by the probed lists
+    float thr0;          // static bound on a result's distance from the calibration codes
+    float lo, scale;     // bin(dist) = min(255, (dist - lo) * scale), 0 below lo
+    uint32_t pad[2];
+};
+
+struct IvfPlan {
+    int cap_b;         // candidate slots per (query, probe)
+    size_t per_query;  // bytes per query
+    size_t counts_off, slots_off;
+    size_t total;
+};
+IvfPlan qadc_ivf_plan(const pq_index *idx, int nq, int nprobe, int R);
+
+struct ScanPlan {
+    int G;        // blocks per query in the scan kernel
+    int cap_b;    // candidate slots per block
+    int64_t pilot_codes;
+    size_t per_query;  // bytes per query
+    size_t state_off, counts_off, slots_off;
+    size_t total;
+};
+
+void qadc_set_error(const char *fmt, ...);
+ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R);
+
+// profiling hook (scan kernels only)
+void qadc_prof_begin(hipStream_t s);
+void qadc_prof_end(hipStream_t s);
+
+#define QADC_HIP_TRY(expr)                                                        \
+    do {                                                                          \
+        hipError_t e__ = (expr);                                                  \
+        if (e__ != hipSuccess) {                                                  \
+            qadc_set_error("%s failed: %s", #expr, hipGetErrorString(e__));       \
+            return PQ_EHIP;                                                       \
+        }                                                                         \
+    } while (0)
+
+#define QADC_LAUNCH_CHECK(what)                                                   \
+    do {                                                                          \
+        hipError_t e__ = hipGetLastError();                                       \
+        if (e__ != hipSuccess) {                                                  \
+            qadc_set_error("launch of %s failed: %s", what, hipGetErrorString(e__)); \
+            return PQ_EHIP;                                                       \
+        }                                                                         \
+    } while (0)

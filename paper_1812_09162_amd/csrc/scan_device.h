@@ -1,0 +1,117 @@
+// Device code shared by the exhaustive and the inverted-list scan kernels.
+#pragma once
+#include <math.h>
+
+#include "qadc_device.h"
+
+#define FINAL_CAP 5120  // candidates a final kernel can rank in LDS
+
+// ------------------------------------------------------------ group tables --
+// gtab[gbase[g] + e] = min(q_max, sum of the quantized entries of the
+// sub-quantizers of group g selected by the bits of e).
+template <typename QT, typename ST = QT>
+__device__ inline void build_gtab(const DevLayout *L, const ST *__restrict__ qtab, QT *gtab) {
+    const uint32_t qmax = (uint32_t)L->qmax;
+    const int ng = L->ng;
+    for (int g = 0; g < ng; ++g) {
+        const int entries = 1 << L->gw[g];
+        const int first = L->gfirst[g], cnt = L->gcount[g];
+        const uint32_t base = L->gbase[g];
+        for (int e = threadIdx.x; e < entries; e += blockDim.x) {
+            uint32_t rem = (uint32_t)e, s = 0;
+            for (int c = 0; c < cnt; ++c) {
+                const int j = first + c, b = L->nbits[j];
+                s += qtab[L->toff[j] + (rem & ((1u << b) - 1u))];
+                rem >>= b;
+            }
+            gtab[base + e] = (QT)(s > qmax ? qmax : s);
+        }
+    }
+    __syncthreads();
+}
+
+// eight byte-indexed lookups for the two words of a 64-bit m x 4 code slice
+template <typename QT>
+__device__ __forceinline__ uint32_t sum8(const QT *t, uint32_t lo, uint32_t hi) {
+    return (uint32_t)t[lo & 255u] + (uint32_t)t[256 + ((lo >> 8) & 255u)] +
+           (uint32_t)t[512 + ((lo >> 16) & 255u)] + (uint32_t)t[768 + (lo >> 24)] +
+           (uint32_t)t[1024 + (hi & 255u)] + (uint32_t)t[1280 + ((hi >> 8) & 255u)] +
+           (uint32_t)t[1536 + ((hi >> 16) & 255u)] + (uint32_t)t[1792 + (hi >> 24)];
+}
+
+template <typename QT>
+__device__ __forceinline__ uint32_t key_generic(const DevLayout *L, const QT *gtab,
+                                                const uint8_t *code) {
+    const int ng = L->ng, cs = L->cs;
+    uint32_t s = 0;
+    for (int g = 0; g < ng; ++g)
+        s += gtab[L->gbase[g] + qadc_extract_group(code, cs, L->goff[g], L->gw[g])];
+    const uint32_t qmax = (uint32_t)L->qmax;
+    return s > qmax ? qmax : s;
+}
+
+// key of the code at position id (simple per-code loads; used off the hot loop)
+template <int KIND, typename QT>
+__device__ __forceinline__ uint32_t key_at(const DevLayout *L, const QT *gtab,
+                                           const uint8_t *__restrict__ codes, int64_t id) {
+    const uint32_t qmax = (uint32_t)L->qmax;
+    if (KIND == SCAN_NIB8) {
+        uint2 w = *(const uint2 *)(codes + id * 8);
+        uint32_t s = sum8(gtab, w.x, w.y);
+        return s > qmax ? qmax : s;
+    } else if (KIND == SCAN_NIB16) {
+        uint4 w = *(const uint4 *)(codes + id * 16);
+        uint32_t s = sum8(gtab, w.x, w.y) + sum8(gtab + 2048, w.z, w.w);
+        return s > qmax ? qmax : s;
+    } else {
+        return key_generic(L, gtab, codes + id * L->cs);
+    }
+}
+
+// -------------------------------------------------------------- threshold --
+// Smallest bin x with hist[0..x] summing to >= R, or 0xffffffff.  One wave.
+__device__ inline uint32_t wave_bound_from_hist(const uint32_t *hist, uint32_t R) {
+    const int lane = __lane_id();
+    uint32_t h[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        h[i] = __hip_atomic_load(&hist[4 * lane + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t s = h[0] + h[1] + h[2] + h[3];
+    uint32_t run = qadc_wave_incl_scan(s) - s;
+    uint32_t mine = 0xffffffffu;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        run += h[i];
+        if (run >= R && mine == 0xffffffffu) mine = (uint32_t)(4 * lane + i);
+    }
+    return qadc_wave_min(mine);
+}
+
+struct SlotRef {
+    uint64_t *slot;
+    uint32_t cap;
+    uint32_t *lds_count;
+    ScanState *st;
+};
+
+// Append the lanes with `pass` set.  Wave-uniform call.
+__device__ __forceinline__ void wave_append(bool pass, uint32_t key, uint32_t id, uint32_t bin,
+                                            const SlotRef &r) {
+    const uint64_t mask = __ballot(pass);
+    if (mask == 0) return;
+    const int lane = __lane_id();
+    const int leader = __ffsll((unsigned long long)mask) - 1;
+    uint32_t base = 0;
+    if (lane == leader) base = atomicAdd(r.lds_count, (uint32_t)__popcll(mask));
+    base = __shfl(base, leader, QADC_WAVE);
+    if (pass) {
+        uint32_t pos = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+        if (pos < r.cap) {
+            r.slot[pos] = ((uint64_t)key << 32) | (uint64_t)id;
+            atomicAdd(&r.st->hist[bin], 1u);
+        } else {
+            r.st->overflow = 1u;
+        }
+    }
+}
+

@@ -133,6 +133,7 @@ def make_layout(d: int, nbits: Sequence[int], acc_bits: int = 8) -> Layout:
 # --------------------------------------------------------------------------
 def _assign(x: torch.Tensor, c: torch.Tensor, chunk: int = 1 << 16) -> torch.Tensor:
     """index of the nearest row of c for every row of x (ties -> lowest index)."""
+    chunk = max(1, min(chunk, (1 << 28) // max(1, c.shape[0])))  # distance block <= 1 GiB
     out = torch.empty(x.shape[0], dtype=torch.int64, device=x.device)
     cn = (c * c).sum(1)
     for lo in range(0, x.shape[0], chunk):
@@ -191,9 +192,9 @@ def pack_codes(sub: torch.Tensor, lay: Layout) -> torch.Tensor:
     j in bits [off_j, off_j+nbits[j]), bit 0 = least significant bit of byte 0."""
     n = sub.shape[0]
     cs = lay.code_size
-    out = torch.zeros((n, cs), dtype=torch.uint8, device=sub.device)
     if all(b == 4 for b in lay.nbits) and lay.m % 2 == 0:
         return (sub[:, 0::2] | (sub[:, 1::2] << 4)).contiguous()
+    out = torch.empty((n, cs), dtype=torch.uint8, device=sub.device)
     step = 1 << 18
     for lo in range(0, n, step):
         blk = sub[lo:lo + step].to(torch.int32)
