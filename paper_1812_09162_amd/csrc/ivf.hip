@@ -124,7 +124,7 @@ __global__ void __launch_bounds__(256)
 k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
             const float *__restrict__ coarse, const int64_t *__restrict__ list_offsets,
             const uint8_t *__restrict__ list_codes, const float *__restrict__ queries,
-            const int32_t *__restrict__ probe_ids, int nprobe, int want, int R,
+            const int32_t *__restrict__ probe_ids, int nprobe, int K, int want, int R,
             char *__restrict__ ws, size_t per_query) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t hist[256];
@@ -143,7 +143,7 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         long long np = 0;
         for (int a = 0; a < nprobe; ++a) {
             int c = probes[a];
-            if (c >= 0) np += list_offsets[c + 1] - list_offsets[c];
+            if (c >= 0 && c < K) np += list_offsets[c + 1] - list_offsets[c];
         }
         s_np = np;
     }
@@ -166,7 +166,7 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     int seen = 0;
     for (int a = 0; a < nprobe && seen < t_eff; ++a) {
         const int c = probes[a];
-        if (c < 0) continue;
+        if (c < 0 || c >= K) continue;
         const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
         if (hi == lo) continue;
         ivf_setup<uint16_t>(L, cb, z, coarse + (size_t)c * L->d, 0.f, false, false, l);
@@ -186,7 +186,7 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     seen = 0;
     for (int a = 0; a < nprobe && seen < t_eff; ++a) {
         const int c = probes[a];
-        if (c < 0) continue;
+        if (c < 0 || c >= K) continue;
         const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
         if (hi == lo) continue;
         const bool ok = ivf_setup<uint16_t>(L, cb, z, coarse + (size_t)c * L->d, dmax, true, false, l);
@@ -230,7 +230,7 @@ k_ivf_scan(const DevLayout *__restrict__ L, const float *__restrict__ cb,
            const float *__restrict__ coarse, const int64_t *__restrict__ list_offsets,
            const uint8_t *__restrict__ list_codes, const int32_t *__restrict__ list_ids,
            const float *__restrict__ queries, const int32_t *__restrict__ probe_ids, int nprobe,
-           int R, char *__restrict__ ws, size_t per_query, size_t counts_off, size_t slots_off,
+           int K, int R, char *__restrict__ ws, size_t per_query, size_t counts_off, size_t slots_off,
            int cap_b) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t s_count;
@@ -243,7 +243,7 @@ k_ivf_scan(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     uint32_t *counts = (uint32_t *)(wq + counts_off);
     const int c = probe_ids[q * nprobe + a];
     int64_t lo = 0, hi = 0;
-    if (c >= 0) {
+    if (c >= 0 && c < K) {
         lo = list_offsets[c];
         hi = list_offsets[c + 1];
     }
@@ -322,7 +322,7 @@ template <int KIND, typename QT>
 __device__ inline int ivf_exact_select(const DevLayout *L, const float *cb, const float *coarse,
                                        const int64_t *list_offsets, const uint8_t *list_codes,
                                        const int32_t *list_ids, const float *z,
-                                       const int32_t *probes, int nprobe, float dmax, int R,
+                                       const int32_t *probes, int nprobe, int K, float dmax, int R,
                                        const IvfLds &l, uint64_t *A, uint32_t *hist, uint32_t *sh) {
     uint64_t prefix = 0, mask = 0;
     uint32_t kk = 0;
@@ -333,7 +333,7 @@ __device__ inline int ivf_exact_select(const DevLayout *L, const float *cb, cons
         __syncthreads();
         for (int a = 0; a < nprobe; ++a) {
             const int c = probes[a];
-            if (c < 0) continue;
+            if (c < 0 || c >= K) continue;
             const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
             if (hi == lo) continue;
             if (!ivf_setup<QT>(L, cb, z, coarse + (size_t)c * L->d, dmax, true, true, l)) continue;
@@ -387,7 +387,7 @@ k_ivf_final(const DevLayout *__restrict__ L, const float *__restrict__ cb,
             const float *__restrict__ coarse, const int64_t *__restrict__ list_offsets,
             const uint8_t *__restrict__ list_codes, const int32_t *__restrict__ list_ids,
             const float *__restrict__ queries, const int32_t *__restrict__ probe_ids, int nprobe,
-            int R, char *__restrict__ ws, size_t per_query, size_t counts_off, size_t slots_off,
+            int K, int R, char *__restrict__ ws, size_t per_query, size_t counts_off, size_t slots_off,
             int cap_b, int32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t hist[256];
@@ -428,7 +428,7 @@ k_ivf_final(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         IvfLds l;
         ivf_carve(L, smem + FINAL_CAP * 8, sizeof(QT), l);
         na = ivf_exact_select<KIND, QT>(L, cb, coarse, list_offsets, list_codes, list_ids,
-                                        queries + q * L->d, probe_ids + q * nprobe, nprobe,
+                                        queries + q * L->d, probe_ids + q * nprobe, nprobe, K,
                                         st->dmax, R, l, A, hist, sh);
         __syncthreads();
     }
@@ -447,7 +447,7 @@ static int allow_lds(K kernel, size_t bytes) {
 template <int KIND, typename QT>
 static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *list_offsets,
                       const uint8_t *list_codes, const int32_t *list_ids, const float *queries,
-                      int nq, const int32_t *probe_ids, int nprobe, int want, int R,
+                      int nq, const int32_t *probe_ids, int nprobe, int K, int want, int R,
                       int32_t *out_ids, float *out_dist, char *ws, const IvfPlan &p, hipStream_t s) {
     const size_t lds_calib = ivf_lds_bytes(idx->h, 2) + (size_t)want * 4;
     const size_t lds_scan = ivf_lds_bytes(idx->h, sizeof(QT));
@@ -457,18 +457,18 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     if ((rc = allow_lds(k_ivf_scan<KIND, QT>, lds_scan)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_final<KIND, QT>, lds_final)) != PQ_OK) return rc;
     hipLaunchKernelGGL(k_ivf_calib, dim3(nq), dim3(256), lds_calib, s, idx->dev, idx->codebooks,
-                       coarse, list_offsets, list_codes, queries, probe_ids, nprobe, want, R, ws,
+                       coarse, list_offsets, list_codes, queries, probe_ids, nprobe, K, want, R, ws,
                        p.per_query);
     QADC_LAUNCH_CHECK("k_ivf_calib");
     qadc_prof_begin(s);
     hipLaunchKernelGGL((k_ivf_scan<KIND, QT>), dim3(nprobe, nq), dim3(256), lds_scan, s, idx->dev,
                        idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,
-                       probe_ids, nprobe, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b);
+                       probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b);
     qadc_prof_end(s);
     QADC_LAUNCH_CHECK("k_ivf_scan");
     hipLaunchKernelGGL((k_ivf_final<KIND, QT>), dim3(nq), dim3(1024), lds_final, s, idx->dev,
                        idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,
-                       probe_ids, nprobe, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b,
+                       probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b,
                        out_ids, out_dist);
     QADC_LAUNCH_CHECK("k_ivf_final");
     return PQ_OK;
@@ -517,7 +517,7 @@ extern "C" int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_cent
     const bool u8 = idx->h.acc_bits == 8;
 #define QADC_GO(KIND, QT)                                                                          \
     return launch_ivf<KIND, QT>(idx, coarse_centroids, list_offsets, list_codes, list_ids, queries, \
-                                nq, probe_ids, nprobe, (int)want, R, out_ids, out_dist, ws, p, s)
+                                nq, probe_ids, nprobe, K, (int)want, R, out_ids, out_dist, ws, p, s)
     switch (idx->h.kind) {
         case SCAN_NIB8:
             if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);
