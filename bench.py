@@ -1,0 +1,245 @@
+#!/usr/bin/env python3
+"""Benchmark of the ADC-scan hot path on one MI355X.
+
+A step is one pass of the whole path -- distance tables, distance quantizer, scan
+and top-R -- over one batch of queries against the resident code array.  The
+headline workload is the PQ 16x4, R=100 exhaustive scan over N = 10,000,000
+codes (d = 96), one query per step.  Inputs are seeded synthetic data resident in
+HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--batch", type=int, default=1, help="queries per step")
+    ap.add_argument("--streams", type=int, default=4,
+                    help="HIP streams the steps are issued on round-robin (each with its own "
+                         "tables, outputs and workspace) so that the small per-query kernels of "
+                         "one step overlap the scan of another")
+    ap.add_argument("--unfused", action="store_true",
+                    help="issue pq_compute_tables, pq_quantize_tables and pq_adc_scan_topk as three "
+                         "calls instead of the fused pq_search_topk (same kernels' arithmetic)")
+    ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3"])
+    ap.add_argument("--n", type=int, default=0, help="override the number of codes")
+    ap.add_argument("--R", type=int, default=100)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the batch-32/256 legs")
+    ap.add_argument("--cpu-queries", type=int, default=8)
+    return ap.parse_args()
+
+
+class Runner:
+    """Pre-resolved pointers so that a step is three C calls and nothing else.  Step i runs
+    on stream i % streams with that stream's private buffers."""
+
+    def __init__(self, qb, idx, queries, codes, batch, R, t=400, streams=1, fused=True):
+        import torch
+        self.torch = torch
+        self.lib = qb.load()
+        self.idx, self.batch, self.R, self.t = idx, batch, R, t
+        self.queries, self.codes = queries, codes
+        self.nq_total = queries.shape[0] // batch * batch
+        dev = codes.device
+        self.n = codes.shape[0]
+        self.fused = fused
+        self.ws_bytes = (qb.pq_search_workspace_bytes if fused else qb.pq_workspace_bytes)(
+            idx, batch, self.n, R)
+        self.sets = []
+        for s in range(max(1, streams)):
+            st = torch.cuda.current_stream() if streams <= 1 else torch.cuda.Stream(device=dev)
+            bufs = dict(
+                tables=torch.empty((batch, idx.table_len), dtype=torch.float32, device=dev),
+                qt=torch.empty((batch, idx.table_len), dtype=idx.qdtype, device=dev),
+                qp=torch.empty((batch, qb.QPARAMS_BYTES), dtype=torch.uint8, device=dev),
+                ids=torch.empty((batch, R), dtype=torch.int32, device=dev),
+                keys=torch.empty((batch, R), dtype=torch.uint16, device=dev),
+                dist=torch.empty((batch, R), dtype=torch.float32, device=dev),
+                ws=torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev))
+            ptr = {k: v.data_ptr() for k, v in bufs.items()}
+            self.sets.append((st, st.cuda_stream or None, bufs, ptr))
+        self.ids, self.keys, self.dist = (self.sets[0][2][k] for k in ("ids", "keys", "dist"))
+        self.h = idx.handle
+        self.qb = qb
+        self.qbase = queries.data_ptr()
+        self.qrow = queries.shape[1] * 4
+        self.cptr = codes.data_ptr()
+
+    def step(self, i):
+        lib = self.lib
+        _, stream, _, p = self.sets[i % len(self.sets)]
+        off = (i * self.batch) % self.nq_total
+        if self.fused:
+            rc = lib.pq_search_topk(self.h, self.qbase + off * self.qrow, self.batch, self.cptr,
+                                    self.n, self.t, self.R, p["ids"], p["keys"], p["dist"], p["ws"],
+                                    self.ws_bytes, stream)
+            if rc != 0:
+                raise RuntimeError("libqadc: " + lib.pq_last_error().decode())
+            return
+        rc = lib.pq_compute_tables(self.h, self.qbase + off * self.qrow, self.batch, p["tables"],
+                                   stream)
+        rc |= lib.pq_quantize_tables(self.h, p["tables"], self.batch, self.cptr, self.n, self.t,
+                                     self.R, p["qt"], p["qp"], stream)
+        rc |= lib.pq_adc_scan_topk(self.h, p["qt"], p["qp"], self.batch, self.cptr, self.n, self.R,
+                                   p["ids"], p["keys"], p["dist"], p["ws"], self.ws_bytes, stream)
+        if rc != 0:
+            raise RuntimeError("libqadc: " + lib.pq_last_error().decode())
+
+    def run(self, steps, warmup, profile=False):
+        torch = self.torch
+        for i in range(warmup):
+            self.step(i)
+        torch.cuda.synchronize()
+        if profile:
+            self.qb.pq_profile_enable(True)
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(warmup + i)
+        self.issue_s = time.perf_counter() - t0   # host time to enqueue the steps
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        prof = None
+        if profile:
+            self.qb.pq_profile_enable(False)
+            prof = self.qb.pq_profile_read()
+        return dt, prof
+
+
+def cpu_baseline(pr, R, nq, t=400):
+    """The oracle, as it stands, on a bounded sample: nq whole-list queries in nq threads."""
+    import oracle
+    lay = pr.layout
+    codes = pr.codes.cpu().numpy()
+    cb = pr.codebooks.cpu().numpy()
+    qs = pr.queries[:nq].cpu().numpy()
+    oracle.search(lay.d, lay.nbits, lay.dsub, lay.acc_bits, cb, qs[0], codes[:1000], t, R)  # load
+    threads = min(nq, os.cpu_count() or 1, 16)
+
+    def one(q):
+        return oracle.search(lay.d, lay.nbits, lay.dsub, lay.acc_bits, cb, qs[q], codes, t, R)
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        res = list(ex.map(one, range(nq)))
+    dt = time.perf_counter() - t0
+    return res, dt, threads
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (multi-GPU sharding is a "
+              "design note only, no collective code exists)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_1812_09162_amd import binding as qb, synth
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU; there is no CPU fallback"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = dict(synth.CONFIGS[a.workload])
+    if a.n:
+        cfg["n"] = a.n
+    cfg["nq"] = min(cfg["nq"], 10_000)
+    t_build = time.perf_counter()
+    pr = synth.build(cfg, device=dev)
+    torch.cuda.synchronize()
+    t_build = time.perf_counter() - t_build
+    lay = pr.layout
+    n, cs = pr.codes.shape
+    idx = qb.PqIndex(lay.d, lay.nbits, lay.dsub, pr.codebooks, lay.acc_bits)
+
+    # headline: whole path, `batch` queries per step
+    run = Runner(qb, idx, pr.queries, pr.codes, a.batch, a.R, streams=a.streams, fused=not a.unfused)
+    dt, _ = run.run(a.steps, a.warmup)
+    ms_per_step = dt / a.steps * 1e3
+    codes_per_s = a.batch * n * a.steps / dt
+    # same steps again with HIP events around every launch of the scan kernel
+    dt_p, prof = run.run(a.steps, min(a.warmup, 10), profile=True)
+    k_cnt, k_ms = prof
+    k_avg_ms = k_ms / max(k_cnt, 1)
+    alg_bytes = float(n) * cs  # every code byte is read once per launch (per query batch)
+    achieved = alg_bytes / (k_avg_ms * 1e-3) / 1e9
+
+    # a sampled parity check at the size and launch configuration that was just timed
+    ids = run.ids.cpu().numpy().copy()
+    keys = run.keys.cpu().numpy().copy()
+    last_q = ((min(a.warmup, 10) + a.steps - 1) * a.batch) % run.nq_total
+
+    extras = {}
+    if not a.no_extras:
+        for bs, st in ((32, 60), (256, 10)):
+            r2 = Runner(qb, idx, pr.queries, pr.codes, bs, a.R, streams=min(a.streams, 2), fused=not a.unfused)
+            d2, p2 = r2.run(st, 2, profile=True)
+            extras[f"batch{bs}"] = {
+                "ms_per_step": d2 / st * 1e3,
+                "gcodes_per_s": bs * n * st / d2 / 1e9,
+                "glookups_per_s": bs * n * lay.m * st / d2 / 1e9,
+                "scan_kernel_ms": p2[1] / max(p2[0], 1),
+            }
+
+    out = {
+        "metric": "billion codes scanned/sec per GPU (PQ 16x4, R=100), whole path per query",
+        "value": codes_per_s / 1e9,
+        "unit": "Gcodes/s",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8" if lay.acc_bits == 8 else "u16",
+        "data": "synthetic",
+        "config": {"workload": f"{a.workload}: exhaustive ADC, N={n}, d={lay.d}, "
+                               f"m={lay.m}, bits={sorted(set(lay.nbits))}, code_bytes={cs}, "
+                               f"R={a.R}, t=400, batch={a.batch}, streams={a.streams}, "
+                               f"entry={'pq_compute_tables+pq_quantize_tables+pq_adc_scan_topk' if a.unfused else 'pq_search_topk'}",
+                   "seed": cfg["seed"], "dataset_build_s": round(t_build, 2)},
+        "whole_path_hbm_gbs": codes_per_s * cs / 1e9,
+        "host_issue_ms_per_step": run.issue_s / a.steps * 1e3,
+        "roofline": {"bound": "hbm", "kernel": "k_scan", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "kernel_avg_ms": k_avg_ms, "launches": k_cnt,
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "ms_per_step_with_events": dt_p / a.steps * 1e3},
+        "batched": extras,
+    }
+
+    if not a.no_cpu_baseline:
+        res, cdt, threads = cpu_baseline(pr, a.R, a.cpu_queries)
+        out["cpu_baseline"] = {"value": a.cpu_queries * n / cdt / 1e9, "unit": "Gcodes/s",
+                               "cores": threads, "kind": "oracle",
+                               "sample": f"{a.cpu_queries} queries x {n} codes (the full list), "
+                                         f"one query per thread, {cdt:.1f} s wall"}
+        # parity of the timed configuration: the last query of the timed loop, if it is in the sample
+        torch.cuda.synchronize()
+        run.step(0)
+        torch.cuda.synchronize()
+        g_ids = run.ids[0].cpu().numpy()
+        g_keys = run.keys[0].cpu().numpy().astype(np.uint16)
+        out["parity_sample"] = bool(np.array_equal(g_ids, res[0][0]) and
+                                    np.array_equal(g_keys, res[0][1]))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -145,6 +145,21 @@ int pq_adc_scan_topk(const pq_index_t *idx, const void *qtables, const pq_qparam
                      size_t workspace_bytes, void *stream);
 
 /*
+ * The three calls above in one: tables (eq. (1)), distance quantizer (Section
+ * 3.4) and scan + top-R (eq. (2), Section 3.5) for nq queries against one list
+ * of codes, with the float tables kept on chip.  Same arithmetic, same results
+ * and same argument rules as pq_compute_tables -> pq_quantize_tables ->
+ * pq_adc_scan_topk; it saves two kernel launches per batch, which matters
+ * when a batch is a single query.
+ *   workspace >= pq_search_workspace_bytes(idx, nq, n, R), 256-byte aligned, any
+ *   content; it also holds the quantized tables and quantizer parameters.
+ */
+size_t pq_search_workspace_bytes(const pq_index_t *idx, int nq, int64_t n, int R);
+int pq_search_topk(const pq_index_t *idx, const float *queries, int nq, const uint8_t *codes,
+                   int64_t n, int t, int R, int32_t *out_ids, uint16_t *out_keys, float *out_dist,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Inverted-list search (Section 2.1.1: residuals are what is encoded;
  * Section 2.1.3: one table set per probed cell from z' = z - centroid).
  * For every query: d_max from the float ADC of the first t_eff probed codes

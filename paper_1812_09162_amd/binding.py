@@ -24,7 +24,7 @@ QPARAMS_BYTES = 24
 EXPORTS = [
     "pq_index_create", "pq_index_destroy", "pq_code_size", "pq_table_len", "pq_workspace_bytes",
     "ivf_workspace_bytes", "pq_compute_tables", "pq_quantize_tables", "pq_adc_scan_topk",
-    "ivf_adc_scan_topk", "pq_profile_enable", "pq_profile_read", "pq_last_error",
+    "ivf_adc_scan_topk", "pq_search_workspace_bytes", "pq_search_topk", "pq_profile_enable", "pq_profile_read", "pq_last_error",
 ]
 
 
@@ -65,6 +65,10 @@ def load() -> ctypes.CDLL:
     lib.ivf_adc_scan_topk.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, vp, i32, i32, i32, vp, vp,
                                       vp, sz, vp]
     lib.ivf_adc_scan_topk.restype = i32
+    lib.pq_search_workspace_bytes.argtypes = [vp, i32, i64, i32]
+    lib.pq_search_workspace_bytes.restype = sz
+    lib.pq_search_topk.argtypes = [vp, vp, i32, vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.pq_search_topk.restype = i32
     lib.pq_profile_enable.argtypes = [i32]
     lib.pq_profile_enable.restype = None
     lib.pq_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double)]
@@ -184,6 +188,30 @@ def pq_adc_scan_topk(idx: PqIndex, qtables: torch.Tensor, qparams: torch.Tensor,
     _check(load().pq_adc_scan_topk(idx.handle, _ptr(qtables), _ptr(qparams), nq, _ptr(codes), n, R,
                                    _ptr(ids), _ptr(keys), _ptr(dist), _ptr(workspace),
                                    workspace.numel(), _stream(stream)))
+    return ids, keys, dist
+
+
+def pq_search_workspace_bytes(idx: PqIndex, nq: int, n: int, R: int) -> int:
+    return int(load().pq_search_workspace_bytes(idx.handle, nq, n, R))
+
+
+def pq_search_topk(idx: PqIndex, queries: torch.Tensor, codes: torch.Tensor, t: int, R: int,
+                   workspace: Optional[torch.Tensor] = None, out=None, stream=None):
+    _dev(queries, torch.float32)
+    _dev(codes, torch.uint8)
+    nq, n = queries.shape[0], codes.shape[0]
+    dev = codes.device
+    if workspace is None:
+        workspace = torch.empty(pq_search_workspace_bytes(idx, nq, n, R), dtype=torch.uint8,
+                                device=dev)
+    if out is None:
+        out = (torch.empty((nq, R), dtype=torch.int32, device=dev),
+               torch.empty((nq, R), dtype=torch.uint16, device=dev),
+               torch.empty((nq, R), dtype=torch.float32, device=dev))
+    ids, keys, dist = out
+    _check(load().pq_search_topk(idx.handle, _ptr(queries), nq, _ptr(codes), n, t, R, _ptr(ids),
+                                 _ptr(keys), _ptr(dist), _ptr(workspace), workspace.numel(),
+                                 _stream(stream)))
     return ids, keys, dist
 
 

@@ -25,7 +25,7 @@ static void plan_groups(DevLayout &L, int gmax) {
     int j = 0;
     while (j < L.m) {
         int g = L.ng++;
-        L.gfirst[g] = (uint8_t)j;
+        L.gfirst[g] = (int32_t)j;
         L.goff[g] = L.bitoff[j];
         int w = L.nbits[j];
         int cnt = 1;
@@ -33,9 +33,9 @@ static void plan_groups(DevLayout &L, int gmax) {
             w += L.nbits[j + cnt];
             ++cnt;
         }
-        L.gw[g] = (uint8_t)w;
-        L.gcount[g] = (uint8_t)cnt;
-        L.gbase[g] = (uint32_t)L.gtab_len;
+        L.gw[g] = (int32_t)w;
+        L.gcount[g] = (int32_t)cnt;
+        L.gbase[g] = (int32_t)L.gtab_len;
         L.gtab_len += 1 << w;
         j += cnt;
     }
@@ -66,12 +66,12 @@ extern "C" int pq_index_create(pq_index_t **out, int d, int m, const int32_t *nb
             qadc_set_error("pq_index_create: nbits[%d]=%d (1..8) dsub[%d]=%d (>=1)", j, nbits[j], j, dsub[j]);
             return PQ_EINVAL;
         }
-        L.nbits[j] = (uint8_t)nbits[j];
-        L.bitoff[j] = (uint16_t)bit;
-        L.toff[j] = (uint16_t)t;
-        L.dimoff[j] = (uint16_t)dim;
-        L.dsub[j] = (uint16_t)dsub[j];
-        L.cboff[j] = (uint32_t)cb;
+        L.nbits[j] = (int32_t)nbits[j];
+        L.bitoff[j] = (int32_t)bit;
+        L.toff[j] = (int32_t)t;
+        L.dimoff[j] = (int32_t)dim;
+        L.dsub[j] = (int32_t)dsub[j];
+        L.cboff[j] = (int32_t)cb;
         bit += nbits[j];
         t += 1 << nbits[j];
         dim += dsub[j];
@@ -141,18 +141,26 @@ ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R) {
     ScanPlan p;
     const int64_t tile_codes = 1024;
     int64_t tiles = (n + tile_codes - 1) / tile_codes;
-    int64_t gmax = 2048 / (nq > 0 ? nq : 1);
+    int64_t gmax = 32768 / (nq > 0 ? nq : 1);
     if (gmax < 64) gmax = 64;
     if (gmax > 2048) gmax = 2048;
     int64_t G = tiles < 1 ? 1 : (tiles > gmax ? gmax : tiles);
     p.G = (int)G;
-    p.cap_b = R <= 256 ? 512 : 2048;
-    int64_t pc = 32 * (int64_t)R;
-    if (pc < 16384) pc = 16384;
-    p.pilot_codes = n < pc ? n : pc;
+    // slots per block: four times the candidates expected when the bound comes from a
+    // 65536-code pilot (the quantizer's default), plus slack for ties
+    const int64_t per_block = (n + G - 1) / G;
+    int64_t est = per_block * (int64_t)R / 65536 + 1;
+    int64_t cap = 128;
+    while (cap < 4 * est + 64 && cap < 65536) cap <<= 1;
+    if (cap > per_block + 2) {  // never more slots than codes the block sees
+        cap = 128;
+        while (cap < per_block + 2) cap <<= 1;
+    }
+    p.cap_b = (int)cap;
+    p.pilot_codes = 0;
     p.state_off = 0;
-    p.counts_off = align_up(sizeof(ScanState), 256);
-    p.slots_off = p.counts_off + align_up((size_t)p.G * sizeof(uint32_t), 256);
+    p.counts_off = 0;
+    p.slots_off = align_up((size_t)p.G * sizeof(uint32_t), 256);
     p.per_query = p.slots_off + (size_t)p.G * (size_t)p.cap_b * sizeof(uint64_t);
     p.per_query = align_up(p.per_query, 256);
     p.total = p.per_query * (size_t)(nq > 0 ? nq : 0);

@@ -22,14 +22,15 @@ struct IvfLds {
     void *gtab;    // [gtab_len] of QT
     double *sc;    // {d_min, delta}
     int *flag;     // skip flag
+    uint8_t *esub; // [T] sub-quantizer of each table entry
 };
 
 __device__ inline size_t ivf_lds_bytes_dev(const DevLayout *L, size_t esz) {
-    return (size_t)L->d * 4 + (size_t)L->T * 4 + PQ_MAX_M * 4 + (size_t)L->T * 2 +
+    return (size_t)L->d * 4 + (size_t)L->T * 4 + PQ_MAX_M * 4 + (size_t)L->T * 4 +
            (((size_t)L->gtab_len * esz + 15) & ~(size_t)15) + 32;
 }
 static size_t ivf_lds_bytes(const DevLayout &L, size_t esz) {
-    return (size_t)L.d * 4 + (size_t)L.T * 4 + PQ_MAX_M * 4 + (size_t)L.T * 2 +
+    return (size_t)L.d * 4 + (size_t)L.T * 4 + PQ_MAX_M * 4 + (size_t)L.T * 4 +
            (((size_t)L.gtab_len * esz + 15) & ~(size_t)15) + 32;
 }
 
@@ -44,13 +45,14 @@ __device__ inline unsigned char *ivf_carve(const DevLayout *L, unsigned char *ba
     l.pmin = (float *)p;     p += PQ_MAX_M * 4;
     l.gtab = (void *)p;      p += (((size_t)L->gtab_len * esz + 15) & ~(size_t)15);
     l.qt = (uint16_t *)p;    p += (size_t)L->T * 2;
+    l.esub = (uint8_t *)p;   p += (size_t)L->T * 2;  // T bytes used; keeps what follows 4-byte aligned
     return p;
 }
 
 // Block-wide: residual, float tables (eq. (1)), p_min, d_min; with `quantize`
 // also delta from dmax, the quantized table and (with `groups`) the group
 // tables.  Returns false when the list is skipped (d_min > d_max).
-template <typename QT>
+template <int KIND, typename QT>
 __device__ inline bool ivf_setup(const DevLayout *L, const float *__restrict__ cb,
                                  const float *__restrict__ z, const float *__restrict__ cen,
                                  float dmax, bool quantize, bool groups, const IvfLds &l) {
@@ -58,8 +60,7 @@ __device__ inline bool ivf_setup(const DevLayout *L, const float *__restrict__ c
     for (int i = threadIdx.x; i < d; i += blockDim.x) l.zres[i] = __fsub_rn(z[i], cen[i]);
     __syncthreads();
     for (int e = threadIdx.x; e < T; e += blockDim.x) {
-        int j = 0;
-        while (j + 1 < m && (int)L->toff[j + 1] <= e) ++j;
+        const int j = l.esub[e];
         const int i = e - L->toff[j];
         const int ds = L->dsub[j];
         const float *c = cb + L->cboff[j] + (size_t)i * ds;
@@ -100,8 +101,7 @@ __device__ inline bool ivf_setup(const DevLayout *L, const float *__restrict__ c
     if (*l.flag) return false;
     const double delta = l.sc[1];
     for (int e = threadIdx.x; e < T; e += blockDim.x) {
-        int j = 0;
-        while (j + 1 < m && (int)L->toff[j + 1] <= e) ++j;
+        const int j = l.esub[e];
         uint32_t qv = 0;
         if (delta > 0.0) {
             double x = floor(((double)l.tab[e] - (double)l.pmin[j]) / delta);
@@ -110,7 +110,7 @@ __device__ inline bool ivf_setup(const DevLayout *L, const float *__restrict__ c
         l.qt[e] = (uint16_t)qv;
     }
     __syncthreads();
-    if (groups) build_gtab<QT, uint16_t>(L, l.qt, (QT *)l.gtab);
+    if (groups) build_gtab<KIND, QT>(L, l.qt, (QT *)l.gtab);
     return true;
 }
 
@@ -133,6 +133,7 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     IvfLds l;
     unsigned char *rest = ivf_carve(L, smem, 2, l);
     uint32_t *ord = (uint32_t *)rest;  // [want]
+    qadc_build_entry_map(L, l.esub);
     const size_t q = blockIdx.x;
     IvfState *st = (IvfState *)(ws + q * per_query);
     const int32_t *probes = probe_ids + q * nprobe;
@@ -169,7 +170,7 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         if (c < 0 || c >= K) continue;
         const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
         if (hi == lo) continue;
-        ivf_setup<uint16_t>(L, cb, z, coarse + (size_t)c * L->d, 0.f, false, false, l);
+        ivf_setup<SCAN_GENERIC, uint16_t>(L, cb, z, coarse + (size_t)c * L->d, 0.f, false, false, l);
         const int take = (int)((hi - lo) < (int64_t)(t_eff - seen) ? (hi - lo) : (int64_t)(t_eff - seen));
         for (int p = threadIdx.x; p < take; p += blockDim.x) {
             const uint8_t *code = list_codes + (size_t)(lo + p) * cs;
@@ -189,7 +190,7 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         if (c < 0 || c >= K) continue;
         const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
         if (hi == lo) continue;
-        const bool ok = ivf_setup<uint16_t>(L, cb, z, coarse + (size_t)c * L->d, dmax, true, false, l);
+        const bool ok = ivf_setup<SCAN_GENERIC, uint16_t>(L, cb, z, coarse + (size_t)c * L->d, dmax, true, false, l);
         const int take = (int)((hi - lo) < (int64_t)(t_eff - seen) ? (hi - lo) : (int64_t)(t_eff - seen));
         const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
         for (int p = threadIdx.x; p < take; p += blockDim.x) {
@@ -236,6 +237,7 @@ k_ivf_scan(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     __shared__ uint32_t s_count;
     IvfLds l;
     ivf_carve(L, smem, sizeof(QT), l);
+    qadc_build_entry_map(L, l.esub);
     const size_t q = blockIdx.y;
     const int a = blockIdx.x;
     char *wq = ws + q * per_query;
@@ -253,7 +255,7 @@ k_ivf_scan(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     }
     const float dmax = st->dmax, thr0 = st->thr0, blo = st->lo, bscale = st->scale;
     if (threadIdx.x == 0) s_count = 0;
-    const bool ok = ivf_setup<QT>(L, cb, queries + q * L->d, coarse + (size_t)c * L->d, dmax, true,
+    const bool ok = ivf_setup<KIND, QT>(L, cb, queries + q * L->d, coarse + (size_t)c * L->d, dmax, true,
                                   true, l);
     if (!ok) {
         if (threadIdx.x == 0) counts[a] = 0;
@@ -336,7 +338,7 @@ __device__ inline int ivf_exact_select(const DevLayout *L, const float *cb, cons
             if (c < 0 || c >= K) continue;
             const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
             if (hi == lo) continue;
-            if (!ivf_setup<QT>(L, cb, z, coarse + (size_t)c * L->d, dmax, true, true, l)) continue;
+            if (!ivf_setup<KIND, QT>(L, cb, z, coarse + (size_t)c * L->d, dmax, true, true, l)) continue;
             const QT *gtab = (const QT *)l.gtab;
             const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
             for (int64_t p = lo + threadIdx.x; p < hi; p += blockDim.x) {
@@ -427,6 +429,7 @@ k_ivf_final(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     if (slow) {
         IvfLds l;
         ivf_carve(L, smem + FINAL_CAP * 8, sizeof(QT), l);
+        qadc_build_entry_map(L, l.esub);
         na = ivf_exact_select<KIND, QT>(L, cb, coarse, list_offsets, list_codes, list_ids,
                                         queries + q * L->d, probe_ids + q * nprobe, nprobe, K,
                                         st->dmax, R, l, A, hist, sh);

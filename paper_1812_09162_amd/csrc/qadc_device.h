@@ -27,6 +27,16 @@ __device__ __forceinline__ uint32_t qadc_extract_group(const uint8_t *code, int 
     return (v >> sh) & ((1u << w) - 1u);
 }
 
+// esub[e] = sub-quantizer that table entry e belongs to.  Block-wide; ends with a barrier.
+__device__ inline void qadc_build_entry_map(const DevLayout *L, uint8_t *esub) {
+    const int m = L->m;
+    for (int j = 0; j < m; ++j) {
+        const int kj = 1 << L->nbits[j], t0 = L->toff[j];
+        for (int i = threadIdx.x; i < kj; i += blockDim.x) esub[t0 + i] = (uint8_t)j;
+    }
+    __syncthreads();
+}
+
 // Order-preserving map float -> uint32 (and back) for radix selection.
 __device__ __forceinline__ uint32_t qadc_f2ord(float f) {
     uint32_t u = __float_as_uint(f);
@@ -35,42 +45,6 @@ __device__ __forceinline__ uint32_t qadc_f2ord(float f) {
 __device__ __forceinline__ float qadc_ord2f(uint32_t o) {
     uint32_t u = (o & 0x80000000u) ? (o & 0x7fffffffu) : ~o;
     return __uint_as_float(u);
-}
-
-// k-th smallest (k >= 1) of cnt uint32 values in LDS by most-significant-byte
-// radix selection over the bytes [0, nbytes).  All threads of the block call
-// it; `hist` is 256 words of LDS, `sel` two words.  Returns the value to every
-// thread.
-__device__ inline uint32_t qadc_block_kth_u32(const uint32_t *vals, int cnt, int k, int nbytes,
-                                              uint32_t *hist, uint32_t *sel) {
-    uint32_t prefix = 0, mask = 0;
-    int kk = k;
-    for (int pass = nbytes - 1; pass >= 0; --pass) {
-        int shift = pass * 8;
-        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
-        __syncthreads();
-        for (int i = threadIdx.x; i < cnt; i += blockDim.x) {
-            uint32_t v = vals[i];
-            if ((v & mask) == prefix) atomicAdd(&hist[(v >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            uint32_t run = 0;
-            int b = 0;
-            for (; b < 255; ++b) {
-                if (run + hist[b] >= (uint32_t)kk) break;
-                run += hist[b];
-            }
-            sel[0] = (uint32_t)b;
-            sel[1] = (uint32_t)kk - run;
-        }
-        __syncthreads();
-        prefix |= sel[0] << shift;
-        mask |= 255u << shift;
-        kk = (int)sel[1];
-        __syncthreads();
-    }
-    return prefix;
 }
 
 // Wave-wide inclusive prefix sum (wave64).
@@ -92,3 +66,59 @@ __device__ __forceinline__ uint32_t qadc_wave_min(uint32_t v) {
     }
     return v;
 }
+
+// Over 256 bins: the smallest bin b with base + hist[0..b] >= kk (bin 255 if
+// none), and base + hist[0..b-1].  Called by one full wave; the result goes to
+// out[0], out[1] (LDS or registers of the caller via the return value).
+__device__ inline void qadc_wave_select_bin(const uint32_t *hist, uint32_t kk, uint32_t base,
+                                            uint32_t *out) {
+    const int lane = __lane_id();
+    uint32_t h[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) h[i] = hist[4 * lane + i];
+    const uint32_t s = h[0] + h[1] + h[2] + h[3];
+    uint32_t run = base + qadc_wave_incl_scan(s) - s;
+    uint32_t mine = 0xffffffffu, below = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t bin = (uint32_t)(4 * lane + i);
+        if (mine == 0xffffffffu && (run + h[i] >= kk || bin == 255u)) {
+            mine = bin;
+            below = run;
+        }
+        run += h[i];
+    }
+    const uint32_t best = qadc_wave_min(mine);
+    if (mine == best) {
+        out[0] = best;
+        out[1] = below;
+    }
+}
+
+// k-th smallest (k >= 1) of cnt uint32 values in LDS by most-significant-byte
+// radix selection over the bytes [0, nbytes).  All threads of the block call
+// it; `hist` is 256 words of LDS, `sel` two words.  Returns the value to every
+// thread.
+__device__ inline uint32_t qadc_block_kth_u32(const uint32_t *vals, int cnt, int k, int nbytes,
+                                              uint32_t *hist, uint32_t *sel) {
+    uint32_t prefix = 0, mask = 0;
+    int kk = k;
+    for (int pass = nbytes - 1; pass >= 0; --pass) {
+        int shift = pass * 8;
+        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < cnt; i += blockDim.x) {
+            uint32_t v = vals[i];
+            if ((v & mask) == prefix) atomicAdd(&hist[(v >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, (uint32_t)kk, 0u, sel);
+        __syncthreads();
+        prefix |= sel[0] << shift;
+        mask |= 255u << shift;
+        kk -= (int)sel[1];
+        __syncthreads();
+    }
+    return prefix;
+}
+

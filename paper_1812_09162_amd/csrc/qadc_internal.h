@@ -19,17 +19,19 @@ struct DevLayout {
     int32_t ng;        // number of groups
     int32_t gtab_len;  // total group-table entries
     int32_t kind;      // SCAN_* below
-    uint8_t nbits[PQ_MAX_M];
-    uint16_t bitoff[PQ_MAX_M];  // first code bit of sub-quantizer j
-    uint16_t toff[PQ_MAX_M];    // first table entry of sub-quantizer j
-    uint16_t dimoff[PQ_MAX_M];  // first vector dimension of sub-quantizer j
-    uint16_t dsub[PQ_MAX_M];
-    uint32_t cboff[PQ_MAX_M];   // first codebook float of sub-quantizer j
-    uint8_t gw[PQ_MAX_M];       // bits of group g
-    uint16_t goff[PQ_MAX_M];    // first code bit of group g
-    uint8_t gfirst[PQ_MAX_M];   // first sub-quantizer of group g
-    uint8_t gcount[PQ_MAX_M];   // sub-quantizers in group g
-    uint32_t gbase[PQ_MAX_M];   // first group-table entry of group g
+    // all 32-bit so that uniform reads compile to scalar loads (gfx9 has no
+    // sub-dword scalar loads)
+    int32_t nbits[PQ_MAX_M];
+    int32_t bitoff[PQ_MAX_M];  // first code bit of sub-quantizer j
+    int32_t toff[PQ_MAX_M];    // first table entry of sub-quantizer j
+    int32_t dimoff[PQ_MAX_M];  // first vector dimension of sub-quantizer j
+    int32_t dsub[PQ_MAX_M];
+    int32_t cboff[PQ_MAX_M];   // first codebook float of sub-quantizer j
+    int32_t gw[PQ_MAX_M];      // bits of group g
+    int32_t goff[PQ_MAX_M];    // first code bit of group g
+    int32_t gfirst[PQ_MAX_M];  // first sub-quantizer of group g
+    int32_t gcount[PQ_MAX_M];  // sub-quantizers in group g
+    int32_t gbase[PQ_MAX_M];   // first group-table entry of group g
 };
 
 enum { SCAN_GENERIC = 0, SCAN_NIB8 = 1, SCAN_NIB16 = 2, SCAN_C5 = 3 };
@@ -79,6 +81,10 @@ struct ScanPlan {
 
 void qadc_set_error(const char *fmt, ...);
 ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R);
+
+int qadc_quantize_launch(const pq_index *idx, const float *queries, const float *tables_in,
+                         float *tables_out, int nq, const uint8_t *codes, int64_t n, int t, int R,
+                         void *qtables, pq_qparams_t *qparams, hipStream_t s);
 
 // profiling hook (scan kernels only)
 void qadc_prof_begin(hipStream_t s);

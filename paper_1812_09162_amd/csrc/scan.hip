@@ -1,146 +1,168 @@
 // pq_adc_scan_topk: scan of packed codes with quantized tables (eq. (2),
 // Section 3.4 saturating sums, Section 3.5) and exact top-R by (key, id).
 //
-// Three kernels per call:
-//   k_pilot  one block per query: clears the per-query state and derives a first
-//            inclusive key threshold from the first few thousand codes;
-//   k_scan   G blocks per query stream the codes once; a code whose key bin is
-//            within the current threshold is appended to the block's private
-//            slot array and counted in a per-query histogram, from which any
-//            wave that appended tightens the shared threshold;
-//   k_final  one block per query gathers the surviving candidates, ranks them
-//            by (key, id) and writes the R best.  If any slot array overflowed
-//            (degenerate inputs with huge tie classes) it instead runs an exact
-//            two-pass selection over all codes.
-//
-// Why the threshold is safe: it is only ever lowered to a bin x for which at
-// least R codes of the data set are known to have bin <= x, so the R-th best
-// key lies in a bin <= x and no code in a higher bin can be a result.  The
-// result is defined as a sort by (key, id) and therefore does not depend on
-// the order in which blocks run.
+// Two kernels per call, no atomics on global memory, no state to initialise:
+//   k_scan   G blocks per query stream the codes once.  A code is kept when its
+//            key is <= qparams.key_bound (an upper bound on the R-th best key, so
+//            nothing that can be a result is dropped) and appended to the block's
+//            private slot array; the block finally stores how many it saw.
+//   k_final  one block per query gathers the kept candidates, finds the R-th
+//            key by histogram, ranks the few candidates up to it by (key, id) and
+//            writes the R best.  If a slot array overflowed (huge tie classes, or
+//            a caller that supplied no bound) it runs an exact two-pass selection
+//            over all codes instead.
+// The result is defined as a sort by (key, id), so it does not depend on the
+// order in which blocks run.
 #include <math.h>
 
 #include "scan_device.h"
 
-// --------------------------------------------------------------- k_pilot ---
-template <int KIND, typename QT>
-__global__ void __launch_bounds__(1024)
-k_pilot(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
-        const pq_qparams_t *__restrict__ qparams, const uint8_t *__restrict__ codes,
-        int64_t pilot_codes, int R, char *__restrict__ ws, size_t per_query) {
-    extern __shared__ unsigned char smem[];
-    QT *gtab = (QT *)smem;
-    __shared__ uint32_t hist[256];
-    const size_t q = blockIdx.x;
-    ScanState *st = (ScanState *)(ws + q * per_query);
-    const int shift = L->acc_bits == 8 ? 0 : 8;
-    for (int i = threadIdx.x; i < 256; i += blockDim.x) {
-        hist[i] = 0;
-        st->hist[i] = 0;
-    }
-    if (threadIdx.x == 0) st->overflow = 0;
-    build_gtab<QT>(L, (const QT *)qtables + q * L->T, gtab);
-    for (int64_t id = threadIdx.x; id < pilot_codes; id += blockDim.x)
-        atomicAdd(&hist[key_at<KIND, QT>(L, gtab, codes, id) >> shift], 1u);
-    __syncthreads();
-    if (threadIdx.x < QADC_WAVE) {
-        uint32_t b = wave_bound_from_hist(hist, (uint32_t)R);
-        uint32_t kb = qparams[q].key_bound;
-        if (kb > (uint32_t)L->qmax) kb = (uint32_t)L->qmax;
-        kb >>= shift;
-        if (b > 255u) b = 255u;
-        if (threadIdx.x == 0) st->thr = b < kb ? b : kb;
+#define SCAN_THREADS 256
+#define MAX_G 2048
+
+// Append the lanes with `pass` set to the block's slot list.  Wave-uniform call.
+__device__ __forceinline__ void slot_append(bool pass, uint32_t key, uint32_t id, uint64_t *slot,
+                                            uint32_t cap, uint32_t *lds_count) {
+    const uint64_t mask = __ballot(pass);
+    if (mask == 0) return;
+    const int lane = __lane_id();
+    const int leader = __ffsll((unsigned long long)mask) - 1;
+    uint32_t base = 0;
+    if (lane == leader) base = atomicAdd(lds_count, (uint32_t)__popcll(mask));
+    base = __shfl(base, leader, QADC_WAVE);
+    if (pass) {
+        const uint32_t pos = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+        if (pos < cap) slot[pos] = ((uint64_t)key << 32) | (uint64_t)id;
     }
 }
 
 // ---------------------------------------------------------------- k_scan ---
 template <int KIND, typename QT>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(SCAN_THREADS)
 k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
-       const uint8_t *__restrict__ codes, int64_t n, int R, char *__restrict__ ws,
-       size_t per_query, size_t counts_off, size_t slots_off, int cap_b) {
-    extern __shared__ unsigned char smem[];
+       const pq_qparams_t *__restrict__ qparams, const uint8_t *__restrict__ codes, int64_t n,
+       char *__restrict__ ws, size_t per_query, size_t slots_off, int cap_b) {
+    extern __shared__ __align__(16) unsigned char smem[];
     QT *gtab = (QT *)smem;
+    uint16_t *qs = (uint16_t *)(smem + (((size_t)L->gtab_len * sizeof(QT) + 15) & ~(size_t)15));
     __shared__ uint32_t s_count;
     const size_t q = blockIdx.y;
     const int b = blockIdx.x, G = gridDim.x;
     char *wq = ws + q * per_query;
-    ScanState *st = (ScanState *)wq;
-    uint32_t *counts = (uint32_t *)(wq + counts_off);
-    SlotRef ref;
-    ref.slot = (uint64_t *)(wq + slots_off) + (size_t)b * cap_b;
-    ref.cap = (uint32_t)cap_b;
-    ref.lds_count = &s_count;
-    ref.st = st;
-    if (threadIdx.x == 0) s_count = 0;
-    build_gtab<QT>(L, (const QT *)qtables + q * L->T, gtab);
-    const int shift = L->acc_bits == 8 ? 0 : 8;
+    uint32_t *counts = (uint32_t *)wq;
+    uint64_t *slot = (uint64_t *)(wq + slots_off) + (size_t)b * cap_b;
     const uint32_t qmax = (uint32_t)L->qmax;
-    const int64_t ntiles = (n + 1023) / 1024;  // 1024 codes per tile, 4 per thread
+    uint32_t thr = qparams[q].key_bound;
+    thr = thr > qmax ? qmax : thr;
+    if (threadIdx.x == 0) s_count = 0;
 
-    for (int64_t tile = b; tile < ntiles; tile += G) {
-        const uint32_t thr = __hip_atomic_load(&st->thr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        uint32_t key[4], id[4];
-        bool ok[4];
-        if (KIND == SCAN_NIB8) {
-            // two 16-byte chunks per thread, two codes per chunk
-            const int64_t nchunks = (n + 1) >> 1;
+    if (KIND == SCAN_NIB8) {
+        // 16-byte chunks of two codes; an odd last code is handled after the loop
+        const int64_t nfull = n >> 1;
+        const int64_t ntiles = (nfull + 2 * SCAN_THREADS - 1) / (2 * SCAN_THREADS);
+        const uint4 *__restrict__ p = (const uint4 *)codes;
+        uint4 cur[2], nxt[2];
+        int64_t tile = b;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int64_t c = tile * (2 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+            cur[u] = (tile < ntiles && c < nfull) ? p[c] : make_uint4(0, 0, 0, 0);
+        }
+        stage_qtable<QT>((const QT *)qtables + q * L->T, L->T, qs);
+        build_gtab<KIND, QT>(L, qs, gtab);
+        for (; tile < ntiles; tile += G) {
+            const int64_t tn = tile + G;
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const int64_t c = tile * 512 + u * 256 + threadIdx.x;
-                uint4 w = make_uint4(0, 0, 0, 0);
-                const bool c_ok = c < nchunks;
-                const bool second = c_ok && (2 * c + 1 < n);
-                if (second)
-                    w = *(const uint4 *)(codes + c * 16);
-                else if (c_ok) {
-                    uint2 h = *(const uint2 *)(codes + c * 16);
-                    w.x = h.x;
-                    w.y = h.y;
+                const int64_t c = tn * (2 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                nxt[u] = (tn < ntiles && c < nfull) ? p[c] : make_uint4(0, 0, 0, 0);
+            }
+            uint32_t s[4];
+            bool pass[4], any = false;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int64_t c = tile * (2 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                s[2 * u] = sum8(gtab, cur[u].x, cur[u].y);
+                s[2 * u + 1] = sum8(gtab, cur[u].z, cur[u].w);
+                pass[2 * u] = (c < nfull) && s[2 * u] <= thr;
+                pass[2 * u + 1] = (c < nfull) && s[2 * u + 1] <= thr;
+                any = any || pass[2 * u] || pass[2 * u + 1];
+            }
+            if (__ballot(any) != 0) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t c = tile * (2 * SCAN_THREADS) + (u >> 1) * SCAN_THREADS + threadIdx.x;
+                    slot_append(pass[u], s[u], (uint32_t)(2 * c + (u & 1)), slot, (uint32_t)cap_b,
+                                &s_count);
                 }
-                uint32_t s0 = sum8(gtab, w.x, w.y), s1 = sum8(gtab, w.z, w.w);
-                key[2 * u] = s0 > qmax ? qmax : s0;
-                key[2 * u + 1] = s1 > qmax ? qmax : s1;
-                id[2 * u] = (uint32_t)(2 * c);
-                id[2 * u + 1] = (uint32_t)(2 * c + 1);
-                ok[2 * u] = c_ok;
-                ok[2 * u + 1] = second;
             }
-        } else if (KIND == SCAN_NIB16) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int64_t c = tile * 1024 + u * 256 + threadIdx.x;
-                uint4 w = make_uint4(0, 0, 0, 0);
-                ok[u] = c < n;
-                if (ok[u]) w = *(const uint4 *)(codes + c * 16);
-                uint32_t s = sum8(gtab, w.x, w.y) + sum8(gtab + 2048, w.z, w.w);
-                key[u] = s > qmax ? qmax : s;
-                id[u] = (uint32_t)c;
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int64_t c = tile * 1024 + u * 256 + threadIdx.x;
-                ok[u] = c < n;
-                key[u] = ok[u] ? key_generic(L, gtab, codes + c * L->cs) : qmax;
-                id[u] = (uint32_t)c;
+            cur[0] = nxt[0];
+            cur[1] = nxt[1];
+        }
+        if ((n & 1) && b == 0) {  // the odd last code, by one wave of block 0
+            if (threadIdx.x < QADC_WAVE) {
+                const bool me = threadIdx.x == 0;
+                uint32_t key = 0;
+                if (me) {
+                    uint2 w = *(const uint2 *)(codes + (n - 1) * 8);
+                    key = sum8(gtab, w.x, w.y);
+                }
+                slot_append(me && key <= thr, key, (uint32_t)(n - 1), slot, (uint32_t)cap_b, &s_count);
             }
         }
-        bool pass[4], any = false;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            pass[u] = ok[u] && ((key[u] >> shift) <= thr);
-            any = any || pass[u];
+    } else {
+        const int64_t ntiles = (n + 4 * SCAN_THREADS - 1) / (4 * SCAN_THREADS);
+        if (KIND != SCAN_NIB16) {
+            stage_qtable<QT>((const QT *)qtables + q * L->T, L->T, qs);
+            build_gtab<KIND, QT>(L, qs, gtab);
         }
-        if (__ballot(any) != 0) {  // rare once the threshold has tightened
+        uint4 cur[4];
+        if (KIND == SCAN_NIB16) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) wave_append(pass[u], key[u], id[u], key[u] >> shift, ref);
-            uint32_t nb = wave_bound_from_hist(st->hist, (uint32_t)R);
-            if (__lane_id() == 0 && nb < thr) atomicMin(&st->thr, nb);
+            for (int u = 0; u < 4; ++u) {
+                const int64_t c = (int64_t)b * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                cur[u] = c < n ? ((const uint4 *)codes)[c] : make_uint4(0, 0, 0, 0);
+            }
+            stage_qtable<QT>((const QT *)qtables + q * L->T, L->T, qs);
+            build_gtab<KIND, QT>(L, qs, gtab);
+        }
+        for (int64_t tile = b; tile < ntiles; tile += G) {
+            uint32_t s[4];
+            bool pass[4], any = false;
+            uint4 nxt[4];
+            if (KIND == SCAN_NIB16) {
+                const int64_t tn = tile + G;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t c = tn * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                    nxt[u] = (tn < ntiles && c < n) ? ((const uint4 *)codes)[c] : make_uint4(0, 0, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t c = tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                if (KIND == SCAN_NIB16)
+                    s[u] = sum8(gtab, cur[u].x, cur[u].y) + sum8(gtab + 2048, cur[u].z, cur[u].w);
+                else
+                    s[u] = c < n ? key_generic(L, gtab, codes + c * L->cs) : 0u;
+                pass[u] = (c < n) && s[u] <= thr;
+                any = any || pass[u];
+            }
+            if (__ballot(any) != 0) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t c = tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                    slot_append(pass[u], s[u], (uint32_t)c, slot, (uint32_t)cap_b, &s_count);
+                }
+            }
+            if (KIND == SCAN_NIB16) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
+            }
         }
     }
     __syncthreads();
-    if (threadIdx.x == 0) counts[b] = s_count < (uint32_t)cap_b ? s_count : (uint32_t)cap_b;
+    if (threadIdx.x == 0) counts[b] = s_count;  // uncapped: > cap_b tells k_final about the overflow
 }
 
 // --------------------------------------------------------------- k_final ---
@@ -195,16 +217,7 @@ __device__ inline void exact_select(const DevLayout *L, const QT *gtab,
                 atomicAdd(&hist[key & 255u], 1u);
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
-            uint32_t run = below;
-            int bsel = 0;
-            for (; bsel < 255; ++bsel) {
-                if (run + hist[bsel] >= (uint32_t)Rn) break;
-                run += hist[bsel];
-            }
-            sh[0] = (uint32_t)bsel;
-            sh[1] = run;
-        }
+        if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, (uint32_t)Rn, below, sh);
         __syncthreads();
         kstar = (level == 0) ? sh[0] : ((kstar << 8) | sh[0]);
         below = sh[1];
@@ -245,18 +258,21 @@ template <int KIND, typename QT>
 __global__ void __launch_bounds__(1024)
 k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         const pq_qparams_t *__restrict__ qparams, const uint8_t *__restrict__ codes, int64_t n,
-        int R, char *__restrict__ ws, size_t per_query, size_t counts_off, size_t slots_off,
-        int cap_b, int G, int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_keys,
+        int R, const char *__restrict__ ws, size_t per_query, size_t slots_off, int cap_b, int G,
+        int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_keys,
         float *__restrict__ out_dist) {
-    extern __shared__ unsigned char smem[];
+    extern __shared__ __align__(16) unsigned char smem[];
     uint64_t *A = (uint64_t *)smem;                // FINAL_CAP entries
     QT *gtab = (QT *)(smem + FINAL_CAP * 8);       // only built on the slow path
+    uint16_t *qs = (uint16_t *)(smem + FINAL_CAP * 8 +
+                                (((size_t)L->gtab_len * sizeof(QT) + 15) & ~(size_t)15));
     __shared__ uint32_t hist[256];
+    __shared__ uint32_t whist[16][256];            // per-wave histograms: candidate keys share few bins
     __shared__ uint32_t sh[32];
+    __shared__ uint32_t wsum[16];
     const size_t q = blockIdx.x;
-    char *wq = ws + q * per_query;
-    ScanState *st = (ScanState *)wq;
-    const uint32_t *counts = (const uint32_t *)(wq + counts_off);
+    const char *wq = ws + q * per_query;
+    const uint32_t *counts = (const uint32_t *)wq;
     const uint64_t *slots = (const uint64_t *)(wq + slots_off);
     const int shift = L->acc_bits == 8 ? 0 : 8;
     const uint32_t qmax = (uint32_t)L->qmax;
@@ -265,34 +281,78 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     o.keys = out_keys + q * R;
     o.dist = out_dist + q * R;
     const pq_qparams_t prm = qparams[q];
+    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
 
+    // every thread owns up to two slot lists (G <= 2048)
+    uint32_t cnt[2];
+#pragma unroll
+    for (int l = 0; l < 2; ++l) {
+        const int list = (int)threadIdx.x + l * 1024;
+        cnt[l] = list < G ? counts[list] : 0u;
+    }
+    const bool over = cnt[0] > (uint32_t)cap_b || cnt[1] > (uint32_t)cap_b;
+    for (int i = threadIdx.x; i < 16 * 256; i += blockDim.x) (&whist[0][0])[i] = 0;
+    const uint32_t incl = qadc_wave_incl_scan(cnt[0] + cnt[1]);
+    if (lane == QADC_WAVE - 1) wsum[wave] = incl;
     if (threadIdx.x == 0) {
-        sh[0] = 0;  // na
-        sh[1] = st->overflow;
+        sh[0] = 0;  // entries gathered into A
+        sh[1] = 0;  // slow-path flag
     }
     __syncthreads();
-    const uint32_t thr = st->thr;
-    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
-    const int nwaves = blockDim.x / QADC_WAVE;
-    for (int b = wave; b < G; b += nwaves) {
-        const uint32_t cnt = counts[b];
-        for (uint32_t i = lane; i < cnt; i += QADC_WAVE) {
-            const uint64_t c = slots[(size_t)b * cap_b + i];
-            if ((((uint32_t)(c >> 32)) >> shift) <= thr) {
-                uint32_t pos = atomicAdd(&sh[0], 1u);
-                if (pos < FINAL_CAP)
-                    A[pos] = c;
-                else
-                    sh[1] = 1u;
+    uint32_t E = 0;
+    for (int w = 0; w < (int)(blockDim.x / QADC_WAVE); ++w) E += wsum[w];
+    if (over) sh[1] = 1u;
+    __syncthreads();
+    const bool slow0 = sh[1] != 0;
+
+    int na = 0;
+    bool slow = slow0;
+    if (!slow0) {
+        // pass 0: histogram of candidate key bins; pass 1: gather the candidates up to the R-th bin
+        uint32_t kbin = 255;
+        for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+            for (int l = 0; l < 2; ++l) {
+                const uint64_t *lst = slots + (size_t)((int)threadIdx.x + l * 1024) * cap_b;
+                for (uint32_t i0 = 0; i0 < cnt[l]; i0 += 8) {
+                    uint64_t c[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) c[u] = (i0 + u < cnt[l]) ? lst[i0 + u] : ~0ull;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        if (i0 + u >= cnt[l]) continue;
+                        const uint32_t bin = ((uint32_t)(c[u] >> 32)) >> shift;
+                        if (pass == 0) {
+                            atomicAdd(&whist[wave][bin], 1u);
+                        } else if (bin <= kbin) {
+                            const uint32_t pos = atomicAdd(&sh[0], 1u);
+                            if (pos < FINAL_CAP) A[pos] = c[u]; else sh[1] = 1u;
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+            if (pass == 0) {
+                if (threadIdx.x < 256) {
+                    uint32_t t = 0;
+#pragma unroll
+                    for (int w = 0; w < 16; ++w) t += whist[w][threadIdx.x];
+                    hist[threadIdx.x] = t;
+                }
+                __syncthreads();
+                const uint32_t kk = E < (uint32_t)R ? E : (uint32_t)R;
+                if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, kk, 0u, sh + 4);
+                __syncthreads();
+                kbin = sh[4];
             }
         }
+        na = (int)sh[0];
+        slow = sh[1] != 0;
+        __syncthreads();
     }
-    __syncthreads();
-    int na = (int)sh[0];
-    const bool slow = sh[1] != 0;
-    __syncthreads();
     if (slow) {
-        build_gtab<QT>(L, (const QT *)qtables + q * L->T, gtab);
+        stage_qtable<QT>((const QT *)qtables + q * L->T, L->T, qs);
+        build_gtab<KIND, QT>(L, qs, gtab);
         exact_select<KIND, QT>(L, gtab, codes, n, R, A, hist, sh);
         __syncthreads();
         na = (int)sh[2];
@@ -305,19 +365,55 @@ template <int KIND, typename QT>
 static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparams_t *qparams, int nq,
                        const uint8_t *codes, int64_t n, int R, int32_t *out_ids, uint16_t *out_keys,
                        float *out_dist, char *ws, const ScanPlan &p, hipStream_t s) {
-    const size_t gtab_bytes = (size_t)idx->h.gtab_len * sizeof(QT);
-    hipLaunchKernelGGL((k_pilot<KIND, QT>), dim3(nq), dim3(1024), gtab_bytes, s, idx->dev, qtables,
-                       qparams, codes, p.pilot_codes, R, ws, p.per_query);
-    QADC_LAUNCH_CHECK("k_pilot");
+    const size_t gtab_bytes = (((size_t)idx->h.gtab_len * sizeof(QT) + 15) & ~(size_t)15) +
+                              (size_t)idx->h.T * 2;
     qadc_prof_begin(s);
-    hipLaunchKernelGGL((k_scan<KIND, QT>), dim3(p.G, nq), dim3(256), gtab_bytes, s, idx->dev,
-                       qtables, codes, n, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b);
+    hipLaunchKernelGGL((k_scan<KIND, QT>), dim3(p.G, nq), dim3(SCAN_THREADS), gtab_bytes, s, idx->dev,
+                       qtables, qparams, codes, n, ws, p.per_query, p.slots_off, p.cap_b);
     qadc_prof_end(s);
     QADC_LAUNCH_CHECK("k_scan");
-    hipLaunchKernelGGL((k_final<KIND, QT>), dim3(nq), dim3(1024), FINAL_CAP * 8 + gtab_bytes, s,
-                       idx->dev, qtables, qparams, codes, n, R, ws, p.per_query, p.counts_off,
-                       p.slots_off, p.cap_b, p.G, out_ids, out_keys, out_dist);
+    const size_t lds_final = FINAL_CAP * 8 + gtab_bytes;
+    if (lds_final > 48 * 1024)
+        QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_final<KIND, QT>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_final));
+    hipLaunchKernelGGL((k_final<KIND, QT>), dim3(nq), dim3(1024), lds_final, s, idx->dev, qtables,
+                       qparams, codes, n, R, ws, p.per_query, p.slots_off, p.cap_b, p.G, out_ids,
+                       out_keys, out_dist);
     QADC_LAUNCH_CHECK("k_final");
+    return PQ_OK;
+}
+
+static int scan_dispatch(const pq_index *idx, const void *qtables, const pq_qparams_t *qparams,
+                         int nq, const uint8_t *codes, int64_t n, int R, int32_t *out_ids,
+                         uint16_t *out_keys, float *out_dist, char *ws, const ScanPlan &p,
+                         hipStream_t s) {
+    const bool u8 = idx->h.acc_bits == 8;
+#define QADC_GO(KIND, QT) \
+    return launch_scan<KIND, QT>(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s)
+    switch (idx->h.kind) {
+        case SCAN_NIB8:
+            if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);
+        case SCAN_NIB16:
+            if (u8) QADC_GO(SCAN_NIB16, uint8_t); else QADC_GO(SCAN_NIB16, uint16_t);
+        default:
+            if (u8) QADC_GO(SCAN_GENERIC, uint8_t); else QADC_GO(SCAN_GENERIC, uint16_t);
+    }
+#undef QADC_GO
+}
+
+static int check_scan_args(const char *who, const pq_index_t *idx, int nq, int64_t n, int R) {
+    if (!idx || nq < 0 || n < 0 || n >= ((int64_t)1 << 31)) {
+        qadc_set_error("%s: bad handle, nq or n (need 0 <= n < 2^31)", who);
+        return PQ_EINVAL;
+    }
+    if (R < 1 || R > PQ_MAX_R) {
+        qadc_set_error("%s: need 1<=R<=%d (got %d)", who, PQ_MAX_R, R);
+        return PQ_EINVAL;
+    }
+    if (nq > 65535) {
+        qadc_set_error("%s: at most 65535 queries per call (got %d)", who, nq);
+        return PQ_EINVAL;
+    }
     return PQ_OK;
 }
 
@@ -326,19 +422,9 @@ extern "C" int pq_adc_scan_topk(const pq_index_t *idx, const void *qtables,
                                 int64_t n, int R, int32_t *out_ids, uint16_t *out_keys,
                                 float *out_dist, void *workspace, size_t workspace_bytes,
                                 void *stream) {
-    if (!idx || nq < 0 || n < 0 || n >= ((int64_t)1 << 31)) {
-        qadc_set_error("pq_adc_scan_topk: bad handle, nq or n (need 0 <= n < 2^31)");
-        return PQ_EINVAL;
-    }
-    if (R < 1 || R > PQ_MAX_R) {
-        qadc_set_error("pq_adc_scan_topk: need 1<=R<=%d (got %d)", PQ_MAX_R, R);
-        return PQ_EINVAL;
-    }
+    int rc = check_scan_args("pq_adc_scan_topk", idx, nq, n, R);
+    if (rc != PQ_OK) return rc;
     if (nq == 0) return PQ_OK;
-    if (nq > 65535) {
-        qadc_set_error("pq_adc_scan_topk: at most 65535 queries per call (got %d)", nq);
-        return PQ_EINVAL;
-    }
     if (!qtables || !qparams || !out_ids || !out_keys || !out_dist || !workspace || (n > 0 && !codes)) {
         qadc_set_error("pq_adc_scan_topk: null pointer");
         return PQ_EINVAL;
@@ -352,18 +438,53 @@ extern "C" int pq_adc_scan_topk(const pq_index_t *idx, const void *qtables,
         qadc_set_error("pq_adc_scan_topk: workspace of %zu bytes, need %zu", workspace_bytes, p.total);
         return PQ_ENOMEM;
     }
-    hipStream_t s = (hipStream_t)stream;
-    char *ws = (char *)workspace;
-    const bool u8 = idx->h.acc_bits == 8;
-#define QADC_GO(KIND, QT) \
-    return launch_scan<KIND, QT>(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s)
-    switch (idx->h.kind) {
-        case SCAN_NIB8:
-            if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);
-        case SCAN_NIB16:
-            if (u8) QADC_GO(SCAN_NIB16, uint8_t); else QADC_GO(SCAN_NIB16, uint16_t);
-        default:
-            if (u8) QADC_GO(SCAN_GENERIC, uint8_t); else QADC_GO(SCAN_GENERIC, uint16_t);
+    return scan_dispatch(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist,
+                         (char *)workspace, p, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------- fused search call ---
+static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+extern "C" size_t pq_search_workspace_bytes(const pq_index_t *idx, int nq, int64_t n, int R) {
+    if (!idx || nq < 0 || n < 0 || R < 1) return 0;
+    const size_t esz = idx->h.acc_bits == 8 ? 1 : 2;
+    return up256((size_t)nq * sizeof(pq_qparams_t)) + up256((size_t)nq * idx->h.T * esz) +
+           pq_workspace_bytes(idx, nq, n, R);
+}
+
+extern "C" int pq_search_topk(const pq_index_t *idx, const float *queries, int nq,
+                              const uint8_t *codes, int64_t n, int t, int R, int32_t *out_ids,
+                              uint16_t *out_keys, float *out_dist, void *workspace,
+                              size_t workspace_bytes, void *stream) {
+    int rc = check_scan_args("pq_search_topk", idx, nq, n, R);
+    if (rc != PQ_OK) return rc;
+    const int64_t want = t > 4 * (int64_t)R ? t : 4 * (int64_t)R;
+    if (t < 1 || want > PQ_MAX_T_EFF) {
+        qadc_set_error("pq_search_topk: need t>=1 and max(t,4R)<=%d (got t=%d R=%d)", PQ_MAX_T_EFF, t, R);
+        return PQ_EINVAL;
     }
-#undef QADC_GO
+    if (nq == 0) return PQ_OK;
+    if (!queries || !out_ids || !out_keys || !out_dist || !workspace || (n > 0 && !codes)) {
+        qadc_set_error("pq_search_topk: null pointer");
+        return PQ_EINVAL;
+    }
+    if (((uintptr_t)codes & 15u) != 0 || ((uintptr_t)workspace & 255u) != 0) {
+        qadc_set_error("pq_search_topk: codes must be 16-byte and workspace 256-byte aligned");
+        return PQ_EINVAL;
+    }
+    const size_t need = pq_search_workspace_bytes(idx, nq, n, R);
+    if (workspace_bytes < need) {
+        qadc_set_error("pq_search_topk: workspace of %zu bytes, need %zu", workspace_bytes, need);
+        return PQ_ENOMEM;
+    }
+    const size_t esz = idx->h.acc_bits == 8 ? 1 : 2;
+    char *w = (char *)workspace;
+    pq_qparams_t *qparams = (pq_qparams_t *)w;
+    void *qtables = w + up256((size_t)nq * sizeof(pq_qparams_t));
+    char *ws = (char *)qtables + up256((size_t)nq * idx->h.T * esz);
+    hipStream_t s = (hipStream_t)stream;
+    rc = qadc_quantize_launch(idx, queries, nullptr, nullptr, nq, codes, n, t, R, qtables, qparams, s);
+    if (rc != PQ_OK) return rc;
+    const ScanPlan p = qadc_scan_plan(idx, nq, n, R);
+    return scan_dispatch(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s);
 }

@@ -8,25 +8,57 @@
 
 // ------------------------------------------------------------ group tables --
 // gtab[gbase[g] + e] = min(q_max, sum of the quantized entries of the
-// sub-quantizers of group g selected by the bits of e).
-template <typename QT, typename ST = QT>
-__device__ inline void build_gtab(const DevLayout *L, const ST *__restrict__ qtab, QT *gtab) {
+// sub-quantizers of group g selected by the bits of e).  `qs` is the quantized
+// table of one query as 16-bit words in LDS.  Ends with a block barrier.
+template <int KIND, typename QT>
+__device__ inline void build_gtab(const DevLayout *L, const uint16_t *qs, QT *gtab) {
     const uint32_t qmax = (uint32_t)L->qmax;
-    const int ng = L->ng;
-    for (int g = 0; g < ng; ++g) {
-        const int entries = 1 << L->gw[g];
-        const int first = L->gfirst[g], cnt = L->gcount[g];
-        const uint32_t base = L->gbase[g];
-        for (int e = threadIdx.x; e < entries; e += blockDim.x) {
-            uint32_t rem = (uint32_t)e, s = 0;
-            for (int c = 0; c < cnt; ++c) {
-                const int j = first + c, b = L->nbits[j];
-                s += qtab[L->toff[j] + (rem & ((1u << b) - 1u))];
-                rem >>= b;
+    if (KIND == SCAN_NIB8 || KIND == SCAN_NIB16) {
+        // group g = code byte g = sub-quantizers 2g (low nibble) and 2g+1 (high nibble);
+        // four consecutive entries share the high nibble
+        const int nquads = (KIND == SCAN_NIB8 ? 8 : 16) * 64;
+        for (int w = threadIdx.x; w < nquads; w += blockDim.x) {
+            const int g = w >> 6, e0 = (w & 63) << 2;
+            const uint16_t *lo = qs + 32 * g + (e0 & 15);
+            const uint32_t hv = qs[32 * g + 16 + (e0 >> 4)];
+            uint32_t v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t x = (uint32_t)lo[i] + hv;
+                v[i] = x > qmax ? qmax : x;
             }
-            gtab[base + e] = (QT)(s > qmax ? qmax : s);
+            if (sizeof(QT) == 1) {
+                ((uint32_t *)gtab)[w] = v[0] | (v[1] << 8) | (v[2] << 16) | (v[3] << 24);
+            } else {
+                ((uint32_t *)gtab)[2 * w] = v[0] | (v[1] << 16);
+                ((uint32_t *)gtab)[2 * w + 1] = v[2] | (v[3] << 16);
+            }
+        }
+    } else {
+        const int ng = L->ng;
+        for (int g = 0; g < ng; ++g) {
+            const int entries = 1 << L->gw[g];
+            const int first = L->gfirst[g], cnt = L->gcount[g];
+            const int base = L->gbase[g];
+            for (int e = threadIdx.x; e < entries; e += blockDim.x) {
+                uint32_t rem = (uint32_t)e, s = 0;
+                for (int c = 0; c < cnt; ++c) {
+                    const int j = first + c, bb = L->nbits[j];
+                    s += qs[L->toff[j] + (rem & ((1u << bb) - 1u))];
+                    rem >>= bb;
+                }
+                gtab[base + e] = (QT)(s > qmax ? qmax : s);
+            }
         }
     }
+    __syncthreads();
+}
+
+// Copy one query's quantized table from global memory into LDS as 16-bit words.
+// Ends with a block barrier.
+template <typename QT>
+__device__ inline void stage_qtable(const QT *__restrict__ qtab, int T, uint16_t *qs) {
+    for (int e = threadIdx.x; e < T; e += blockDim.x) qs[e] = (uint16_t)qtab[e];
     __syncthreads();
 }
 
@@ -65,6 +97,49 @@ __device__ __forceinline__ uint32_t key_at(const DevLayout *L, const QT *gtab,
         return s > qmax ? qmax : s;
     } else {
         return key_generic(L, gtab, codes + id * L->cs);
+    }
+}
+
+// Keys of U codes at positions base + u*stride (u < U) with all loads issued
+// before any lookup; positions >= n are clamped for the load and yield
+// 0xffffffff.  n must be >= 1.
+template <int KIND, typename QT, int U>
+__device__ __forceinline__ void keys_batch(const DevLayout *L, const QT *gtab,
+                                           const uint8_t *__restrict__ codes, int64_t base,
+                                           int64_t stride, int64_t n, uint32_t *key) {
+    const uint32_t qmax = (uint32_t)L->qmax;
+    if (KIND == SCAN_NIB8) {
+        uint2 w[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int64_t id = base + u * stride;
+            id = id < n ? id : n - 1;
+            w[u] = *(const uint2 *)(codes + id * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t s = sum8(gtab, w[u].x, w[u].y);
+            key[u] = (base + u * stride < n) ? (s > qmax ? qmax : s) : 0xffffffffu;
+        }
+    } else if (KIND == SCAN_NIB16) {
+        uint4 w[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int64_t id = base + u * stride;
+            id = id < n ? id : n - 1;
+            w[u] = *(const uint4 *)(codes + id * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t s = sum8(gtab, w[u].x, w[u].y) + sum8(gtab + 2048, w[u].z, w[u].w);
+            key[u] = (base + u * stride < n) ? (s > qmax ? qmax : s) : 0xffffffffu;
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t id = base + u * stride;
+            key[u] = id < n ? key_generic(L, gtab, codes + id * L->cs) : 0xffffffffu;
+        }
     }
 }
 

@@ -8,13 +8,13 @@ __global__ void __launch_bounds__(256)
 k_tables(const DevLayout *__restrict__ L, const float *__restrict__ cb,
          const float *__restrict__ queries, float *__restrict__ tables) {
     extern __shared__ float zs[];
-    const int d = L->d, m = L->m, T = L->T;
+    const int d = L->d, T = L->T;
+    uint8_t *esub = (uint8_t *)(zs + d);
     const size_t q = blockIdx.x;
     for (int i = threadIdx.x; i < d; i += blockDim.x) zs[i] = queries[q * d + i];
-    __syncthreads();
+    qadc_build_entry_map(L, esub);
     for (int e = threadIdx.x; e < T; e += blockDim.x) {
-        int j = 0;
-        while (j + 1 < m && (int)L->toff[j + 1] <= e) ++j;
+        const int j = esub[e];
         const int i = e - L->toff[j];
         const int ds = L->dsub[j];
         const float *c = cb + L->cboff[j] + (size_t)i * ds;
@@ -39,7 +39,7 @@ extern "C" int pq_compute_tables(const pq_index_t *idx, const float *queries, in
         qadc_set_error("pq_compute_tables: null pointer");
         return PQ_EINVAL;
     }
-    hipLaunchKernelGGL(k_tables, dim3(nq), dim3(256), idx->h.d * sizeof(float), (hipStream_t)stream,
+    hipLaunchKernelGGL(k_tables, dim3(nq), dim3(256), idx->h.d * sizeof(float) + idx->h.T, (hipStream_t)stream,
                        idx->dev, idx->codebooks, queries, tables);
     QADC_LAUNCH_CHECK("k_tables");
     return PQ_OK;

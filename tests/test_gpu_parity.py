@@ -65,7 +65,10 @@ def check_against_oracle(qb, pr, R, queries=None, t=T_CAL, stagewise=True):
             okeys = oracle.scan_keys(lay.nbits, lay.acc_bits, oqt, codes)
             te = oracle.t_eff(codes.shape[0], t, R)
             if te > 0:
-                assert prm["key_bound"][q] == np.sort(okeys[:te])[min(R, te) - 1]
+                # the pruning hint must bound the R-th best key of the whole list from above
+                # and be no weaker than what the calibration codes alone give
+                k = min(R, te)
+                assert np.sort(okeys)[k - 1] <= prm["key_bound"][q] <= np.sort(okeys[:te])[k - 1]
         oi, ok, od = oracle.search(lay.d, lay.nbits, lay.dsub, lay.acc_bits, cb, z, codes, t, R)
         gi = ids[q].cpu().numpy()
         assert np.array_equal(gi, oi), (q, gi[:10], oi[:10])
@@ -158,6 +161,27 @@ def test_batch_sizes_give_identical_results(qb):
         assert torch.equal(a, b)
     # and a sample of them is the oracle's answer
     check_against_oracle(qb, pr, 100, queries=pr.queries[:3], stagewise=False)
+    idx.close()
+
+
+@pytest.mark.parametrize("name,n,R", [("C0", 60_001, 100), ("C2", 20_000, 1000), ("C3", 25_000, 10)])
+def test_fused_search_equals_three_calls_and_oracle(qb, name, n, R):
+    pr = synth.build(synth.scaled(name, n=n, nq=5))
+    idx = make_index(qb, pr)
+    codes_d = pr.codes.to(dev())
+    qd = pr.queries.to(dev())
+    three = gpu_search(qb, idx, qd, codes_d, R)
+    fused = qb.pq_search_topk(idx, qd, codes_d, T_CAL, R)
+    torch.cuda.synchronize()
+    for a, b in zip(three[3:], fused):
+        assert torch.equal(a, b)
+    lay = pr.layout
+    for q in range(qd.shape[0]):
+        oi, ok, od = oracle.search(lay.d, lay.nbits, lay.dsub, lay.acc_bits, pr.codebooks.numpy(),
+                                   pr.queries[q].numpy(), pr.codes.numpy(), T_CAL, R)
+        assert np.array_equal(fused[0][q].cpu().numpy(), oi)
+        assert np.array_equal(fused[1][q].cpu().numpy().astype(np.uint16), ok)
+        assert np.array_equal(fused[2][q].cpu().numpy(), od)
     idx.close()
 
 
