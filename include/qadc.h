@@ -61,9 +61,13 @@ typedef struct pq_index pq_index_t;
  *   delta     bin width (d_max - d_min)/q_max; 0 when d_max <= d_min or when
  *             there was no code to calibrate on (all table entries are then 0)
  *   d_max     R-th smallest float ADC among the first t_eff codes
- *   key_bound R-th smallest *quantized* key among the calibration codes: an
- *             inclusive upper bound on the R-th best key of any superset.
- *             Only a pruning hint; set it to q_max if unknown.
+ *   key_bound an inclusive upper bound on the R-th best quantized key of the
+ *             list: pq_quantize_tables sets it to the R-th smallest key among
+ *             the first few ten thousand codes (a superset of the calibration
+ *             codes).  The scan keeps only codes with key <= key_bound, so a
+ *             caller who writes this record by hand must supply a valid bound;
+ *             q_max is always valid but makes the scan fall back to a slow
+ *             exact selection.
  */
 typedef struct pq_qparams {
     double d_min;
@@ -145,6 +149,21 @@ int pq_adc_scan_topk(const pq_index_t *idx, const void *qtables, const pq_qparam
                      size_t workspace_bytes, void *stream);
 
 /*
+ * The two halves of pq_adc_scan_topk as calls of their own (same arguments, same
+ * workspace): pq_adc_scan_candidates streams the codes and leaves, per query, the
+ * codes whose key is within qparams.key_bound in the workspace;
+ * pq_select_topk turns those candidates into the sorted top-R.  Calling the two
+ * in this order on one stream is exactly pq_adc_scan_topk.  Benchmarks use the
+ * first to time the scan kernel alone.
+ */
+int pq_adc_scan_candidates(const pq_index_t *idx, const void *qtables,
+                           const pq_qparams_t *qparams, int nq, const uint8_t *codes, int64_t n,
+                           int R, void *workspace, size_t workspace_bytes, void *stream);
+int pq_select_topk(const pq_index_t *idx, const void *qtables, const pq_qparams_t *qparams, int nq,
+                   const uint8_t *codes, int64_t n, int R, int32_t *out_ids, uint16_t *out_keys,
+                   float *out_dist, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The three calls above in one: tables (eq. (1)), distance quantizer (Section
  * 3.4) and scan + top-R (eq. (2), Section 3.5) for nq queries against one list
  * of codes, with the float tables kept on chip.  Same arithmetic, same results
@@ -184,17 +203,6 @@ int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_centroids, int 
                       const int32_t *list_ids, const float *queries, int nq,
                       const int32_t *probe_ids, int nprobe, int t, int R, int32_t *out_ids,
                       float *out_dist, void *workspace, size_t workspace_bytes, void *stream);
-
-/*
- * Timing hook for benchmarks: while enabled, the library brackets every launch
- * of the scan kernels (the dominant kernels of pq_adc_scan_topk and
- * ivf_adc_scan_topk) with HIP events on the caller's stream.
- * pq_profile_read synchronises those events, returns the number of launches
- * seen since the last read and their summed duration in milliseconds, and
- * clears the record.  Not thread-safe; off by default.
- */
-void pq_profile_enable(int on);
-int pq_profile_read(double *total_ms);
 
 /* Description of the last error on this thread ("" if none). */
 const char *pq_last_error(void);

@@ -24,7 +24,8 @@ QPARAMS_BYTES = 24
 EXPORTS = [
     "pq_index_create", "pq_index_destroy", "pq_code_size", "pq_table_len", "pq_workspace_bytes",
     "ivf_workspace_bytes", "pq_compute_tables", "pq_quantize_tables", "pq_adc_scan_topk",
-    "ivf_adc_scan_topk", "pq_search_workspace_bytes", "pq_search_topk", "pq_profile_enable", "pq_profile_read", "pq_last_error",
+    "ivf_adc_scan_topk", "pq_search_workspace_bytes", "pq_search_topk",
+    "pq_adc_scan_candidates", "pq_select_topk", "pq_last_error",
 ]
 
 
@@ -69,10 +70,10 @@ def load() -> ctypes.CDLL:
     lib.pq_search_workspace_bytes.restype = sz
     lib.pq_search_topk.argtypes = [vp, vp, i32, vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.pq_search_topk.restype = i32
-    lib.pq_profile_enable.argtypes = [i32]
-    lib.pq_profile_enable.restype = None
-    lib.pq_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double)]
-    lib.pq_profile_read.restype = i32
+    lib.pq_adc_scan_candidates.argtypes = [vp, vp, vp, i32, vp, i64, i32, vp, sz, vp]
+    lib.pq_adc_scan_candidates.restype = i32
+    lib.pq_select_topk.argtypes = [vp, vp, vp, i32, vp, i64, i32, vp, vp, vp, vp, sz, vp]
+    lib.pq_select_topk.restype = i32
     lib.pq_last_error.argtypes = []
     lib.pq_last_error.restype = ctypes.c_char_p
     _lib = lib
@@ -241,14 +242,27 @@ def ivf_adc_scan_topk(idx: PqIndex, coarse: torch.Tensor, list_offsets: torch.Te
     return ids, dist
 
 
-def pq_profile_enable(on: bool) -> None:
-    load().pq_profile_enable(1 if on else 0)
+def pq_adc_scan_candidates(idx: PqIndex, qtables: torch.Tensor, qparams: torch.Tensor,
+                           codes: torch.Tensor, R: int, workspace: torch.Tensor, stream=None) -> None:
+    _dev(codes, torch.uint8)
+    _check(load().pq_adc_scan_candidates(idx.handle, _ptr(qtables), _ptr(qparams), qtables.shape[0],
+                                         _ptr(codes), codes.shape[0], R, _ptr(workspace),
+                                         workspace.numel(), _stream(stream)))
 
 
-def pq_profile_read() -> Tuple[int, float]:
-    ms = ctypes.c_double(0.0)
-    cnt = load().pq_profile_read(ctypes.byref(ms))
-    return int(cnt), float(ms.value)
+def pq_select_topk(idx: PqIndex, qtables: torch.Tensor, qparams: torch.Tensor, codes: torch.Tensor,
+                   R: int, workspace: torch.Tensor, out=None, stream=None):
+    _dev(codes, torch.uint8)
+    nq, dev = qtables.shape[0], codes.device
+    if out is None:
+        out = (torch.empty((nq, R), dtype=torch.int32, device=dev),
+               torch.empty((nq, R), dtype=torch.uint16, device=dev),
+               torch.empty((nq, R), dtype=torch.float32, device=dev))
+    ids, keys, dist = out
+    _check(load().pq_select_topk(idx.handle, _ptr(qtables), _ptr(qparams), nq, _ptr(codes),
+                                 codes.shape[0], R, _ptr(ids), _ptr(keys), _ptr(dist),
+                                 _ptr(workspace), workspace.numel(), _stream(stream)))
+    return ids, keys, dist
 
 
 def unpack_qparams(qparams: torch.Tensor):

@@ -1,9 +1,8 @@
-// Index handle, layout planning, error reporting and the timing hook.
+// Index handle, layout planning and error reporting.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
-
-#include <vector>
 
 #include "qadc_internal.h"
 
@@ -141,8 +140,13 @@ ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R) {
     ScanPlan p;
     const int64_t tile_codes = 1024;
     int64_t tiles = (n + tile_codes - 1) / tile_codes;
+    // A single query gets 1024 blocks of 256 threads: four per compute unit, which
+    // streams at full rate and leaves half of every unit's wave slots to the small
+    // per-query kernels of other streams.
+    static const int64_t g1 = getenv("QADC_G") ? atoll(getenv("QADC_G")) : 1024;
     int64_t gmax = 32768 / (nq > 0 ? nq : 1);
     if (gmax < 64) gmax = 64;
+    if (gmax > g1) gmax = g1;
     if (gmax > 2048) gmax = 2048;
     int64_t G = tiles < 1 ? 1 : (tiles > gmax ? gmax : tiles);
     p.G = (int)G;
@@ -188,56 +192,4 @@ extern "C" size_t pq_workspace_bytes(const pq_index_t *idx, int nq, int64_t n, i
     if (!idx || nq < 0 || n < 0 || R < 1) return 0;
     size_t t = qadc_scan_plan(idx, nq, n, R).total;
     return t ? t : 256;
-}
-
-// ---------------------------------------------------------------- profiling --
-static bool g_prof_on = false;
-static std::vector<hipEvent_t> g_prof_ev;   // begin/end pairs
-static std::vector<hipEvent_t> g_prof_pool;
-
-static hipEvent_t prof_get_event() {
-    hipEvent_t e = nullptr;
-    if (!g_prof_pool.empty()) {
-        e = g_prof_pool.back();
-        g_prof_pool.pop_back();
-    } else if (hipEventCreate(&e) != hipSuccess) {
-        e = nullptr;
-    }
-    return e;
-}
-
-void qadc_prof_begin(hipStream_t s) {
-    if (!g_prof_on) return;
-    hipEvent_t e = prof_get_event();
-    if (e) (void)hipEventRecord(e, s);
-    g_prof_ev.push_back(e);
-}
-
-void qadc_prof_end(hipStream_t s) {
-    if (!g_prof_on) return;
-    hipEvent_t e = prof_get_event();
-    if (e) (void)hipEventRecord(e, s);
-    g_prof_ev.push_back(e);
-}
-
-extern "C" void pq_profile_enable(int on) { g_prof_on = on != 0; }
-
-extern "C" int pq_profile_read(double *total_ms) {
-    double tot = 0.0;
-    int cnt = 0;
-    for (size_t i = 0; i + 1 < g_prof_ev.size(); i += 2) {
-        hipEvent_t a = g_prof_ev[i], b = g_prof_ev[i + 1];
-        if (a && b && hipEventSynchronize(b) == hipSuccess) {
-            float ms = 0.f;
-            if (hipEventElapsedTime(&ms, a, b) == hipSuccess) {
-                tot += ms;
-                ++cnt;
-            }
-        }
-    }
-    for (hipEvent_t e : g_prof_ev)
-        if (e) g_prof_pool.push_back(e);
-    g_prof_ev.clear();
-    if (total_ms) *total_ms = tot;
-    return cnt;
 }

@@ -463,11 +463,9 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
                        coarse, list_offsets, list_codes, queries, probe_ids, nprobe, K, want, R, ws,
                        p.per_query);
     QADC_LAUNCH_CHECK("k_ivf_calib");
-    qadc_prof_begin(s);
     hipLaunchKernelGGL((k_ivf_scan<KIND, QT>), dim3(nprobe, nq), dim3(256), lds_scan, s, idx->dev,
                        idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,
                        probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b);
-    qadc_prof_end(s);
     QADC_LAUNCH_CHECK("k_ivf_scan");
     hipLaunchKernelGGL((k_ivf_final<KIND, QT>), dim3(nq), dim3(1024), lds_final, s, idx->dev,
                        idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,

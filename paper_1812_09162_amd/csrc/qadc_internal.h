@@ -86,9 +86,6 @@ int qadc_quantize_launch(const pq_index *idx, const float *queries, const float 
                          float *tables_out, int nq, const uint8_t *codes, int64_t n, int t, int R,
                          void *qtables, pq_qparams_t *qparams, hipStream_t s);
 
-// profiling hook (scan kernels only)
-void qadc_prof_begin(hipStream_t s);
-void qadc_prof_end(hipStream_t s);
 
 #define QADC_HIP_TRY(expr)                                                        \
     do {                                                                          \

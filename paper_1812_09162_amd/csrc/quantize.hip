@@ -16,7 +16,7 @@
 // `queries` non-null: tables are computed here (and stored to tables_out if
 // that is non-null); otherwise they are read from tables_in.
 template <int KIND, typename QT>
-__global__ void __launch_bounds__(1024)
+__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4)))
 k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
            const float *__restrict__ queries, const float *__restrict__ tables_in,
            float *__restrict__ tables_out, const uint8_t *__restrict__ codes, int t_eff, int k,
@@ -125,26 +125,58 @@ k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
             int lo = 0;
             for (int stage = 0; stage < 2 && lo < pilot; ++stage) {
                 const int hi = stage == 0 ? stage1 : pilot;
-                for (int base = lo; base < hi; base += 8 * (int)blockDim.x) {
-                    uint32_t key[8];
-                    keys_batch<KIND, QT, 8>(L, gtab, codes, (int64_t)base + threadIdx.x, blockDim.x,
-                                            (int64_t)hi, key);
+                // count one key (0xffffffff = none) in the histogram of this level
+                auto count_key = [&](uint32_t key) {
+                    uint32_t bin = 0xffffffffu;  // not counted
+                    if (key != 0xffffffffu) {
+                        if (!wide)
+                            bin = key;
+                        else if (level == 0)
+                            bin = key >> 8;
+                        else if ((key >> 8) == kstar)
+                            bin = key & 255u;
+                    }
+                    // the top bin collects every saturated key: count it once per wave
+                    const uint64_t top = __ballot(bin == 255u);
+                    if (top != 0 && cut == 255u && __lane_id() == 0)
+                        atomicAdd(&hist[255], (uint32_t)__popcll(top));
+                    if (bin < 255u && bin <= cut) atomicAdd(&hist[bin], 1u);
+                };
+                if (KIND == SCAN_NIB8) {
+                    // double-buffered: the loads of the next batch fly while this one is looked up
+                    const int step = 8 * (int)blockDim.x;
+                    uint2 cur[8], nxt[8];
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
-                        uint32_t bin = 0xffffffffu;  // not counted
-                        if (key[u] != 0xffffffffu) {
-                            if (!wide)
-                                bin = key[u];
-                            else if (level == 0)
-                                bin = key[u] >> 8;
-                            else if ((key[u] >> 8) == kstar)
-                                bin = key[u] & 255u;
+                        int id = lo + u * (int)blockDim.x + (int)threadIdx.x;
+                        id = id < hi ? id : hi - 1;
+                        cur[u] = *(const uint2 *)(codes + (size_t)id * 8);
+                    }
+                    for (int base = lo; base < hi; base += step) {
+                        if (base + step < hi) {
+#pragma unroll
+                            for (int u = 0; u < 8; ++u) {
+                                int id = base + step + u * (int)blockDim.x + (int)threadIdx.x;
+                                id = id < hi ? id : hi - 1;
+                                nxt[u] = *(const uint2 *)(codes + (size_t)id * 8);
+                            }
                         }
-                        // the top bin collects every saturated key: count it once per wave
-                        const uint64_t top = __ballot(bin == 255u);
-                        if (top != 0 && cut == 255u && __lane_id() == 0)
-                            atomicAdd(&hist[255], (uint32_t)__popcll(top));
-                        if (bin < 255u && bin <= cut) atomicAdd(&hist[bin], 1u);
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const int id = base + u * (int)blockDim.x + (int)threadIdx.x;
+                            const uint32_t sm = sum8(gtab, cur[u].x, cur[u].y);
+                            count_key(id < hi ? (sm > (uint32_t)qmax ? (uint32_t)qmax : sm) : 0xffffffffu);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) cur[u] = nxt[u];
+                    }
+                } else {
+                    for (int base = lo; base < hi; base += 8 * (int)blockDim.x) {
+                        uint32_t key[8];
+                        keys_batch<KIND, QT, 8>(L, gtab, codes, (int64_t)base + threadIdx.x,
+                                                blockDim.x, (int64_t)hi, key);
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) count_key(key[u]);
                     }
                 }
                 __syncthreads();

@@ -19,6 +19,7 @@
 
 #define SCAN_THREADS 256
 #define MAX_G 2048
+#define FINAL_REG 16  // candidates per thread kept in registers by k_final
 
 // Append the lanes with `pass` set to the block's slot list.  Wave-uniform call.
 __device__ __forceinline__ void slot_append(bool pass, uint32_t key, uint32_t id, uint64_t *slot,
@@ -255,7 +256,7 @@ __device__ inline void exact_select(const DevLayout *L, const QT *gtab,
 }
 
 template <int KIND, typename QT>
-__global__ void __launch_bounds__(1024)
+__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4)))
 k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         const pq_qparams_t *__restrict__ qparams, const uint8_t *__restrict__ codes, int64_t n,
         int R, const char *__restrict__ ws, size_t per_query, size_t slots_off, int cap_b, int G,
@@ -270,6 +271,7 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     __shared__ uint32_t whist[16][256];            // per-wave histograms: candidate keys share few bins
     __shared__ uint32_t sh[32];
     __shared__ uint32_t wsum[16];
+    __shared__ uint32_t off[MAX_G + 1];            // exclusive prefix of the per-block counts
     const size_t q = blockIdx.x;
     const char *wq = ws + q * per_query;
     const uint32_t *counts = (const uint32_t *)wq;
@@ -283,11 +285,11 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     const pq_qparams_t prm = qparams[q];
     const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
 
-    // every thread owns up to two slot lists (G <= 2048)
+    // exclusive prefix sum of the G per-block counts (G <= 2048: two per thread)
     uint32_t cnt[2];
 #pragma unroll
     for (int l = 0; l < 2; ++l) {
-        const int list = (int)threadIdx.x + l * 1024;
+        const int list = 2 * (int)threadIdx.x + l;
         cnt[l] = list < G ? counts[list] : 0u;
     }
     const bool over = cnt[0] > (uint32_t)cap_b || cnt[1] > (uint32_t)cap_b;
@@ -299,8 +301,14 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         sh[1] = 0;  // slow-path flag
     }
     __syncthreads();
-    uint32_t E = 0;
-    for (int w = 0; w < (int)(blockDim.x / QADC_WAVE); ++w) E += wsum[w];
+    uint32_t wbase = 0, E = 0;
+    for (int w = 0; w < (int)(blockDim.x / QADC_WAVE); ++w) {
+        wbase += (w < wave) ? wsum[w] : 0u;
+        E += wsum[w];
+    }
+    if (2 * (int)threadIdx.x < G) off[2 * threadIdx.x] = wbase + incl - cnt[0] - cnt[1];
+    if (2 * (int)threadIdx.x + 1 < G) off[2 * threadIdx.x + 1] = wbase + incl - cnt[1];
+    if (threadIdx.x == 0) off[G] = E;
     if (over) sh[1] = 1u;
     __syncthreads();
     const bool slow0 = sh[1] != 0;
@@ -308,26 +316,47 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     int na = 0;
     bool slow = slow0;
     if (!slow0) {
-        // pass 0: histogram of candidate key bins; pass 1: gather the candidates up to the R-th bin
+        // Candidates are dealt out evenly: thread t takes entries t, t+1024, ... of the
+        // concatenated slot lists, FINAL_REG at a time with all loads in flight together.
+        // pass 0: histogram of candidate key bins -> bin of the R-th key;
+        // pass 1: keep the candidates up to that bin.  When everything fits one batch
+        // the second pass reuses the registers of the first.
+        uint64_t c[FINAL_REG];
+        const bool single = E <= (uint32_t)(FINAL_REG * 1024);
         uint32_t kbin = 255;
         for (int pass = 0; pass < 2; ++pass) {
+            for (uint32_t base = 0; base < E; base += FINAL_REG * 1024) {
+                if (pass == 0 || !single) {
+                    // list of each entry: largest index with off[list] <= e, by a branch-free
+                    // binary search whose FINAL_REG chains run interleaved
+                    uint32_t pos[FINAL_REG];
 #pragma unroll
-            for (int l = 0; l < 2; ++l) {
-                const uint64_t *lst = slots + (size_t)((int)threadIdx.x + l * 1024) * cap_b;
-                for (uint32_t i0 = 0; i0 < cnt[l]; i0 += 8) {
-                    uint64_t c[8];
+                    for (int u = 0; u < FINAL_REG; ++u) pos[u] = 0;
+                    for (uint32_t s = MAX_G / 2; s >= 1; s >>= 1) {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) c[u] = (i0 + u < cnt[l]) ? lst[i0 + u] : ~0ull;
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) {
-                        if (i0 + u >= cnt[l]) continue;
-                        const uint32_t bin = ((uint32_t)(c[u] >> 32)) >> shift;
-                        if (pass == 0) {
-                            atomicAdd(&whist[wave][bin], 1u);
-                        } else if (bin <= kbin) {
-                            const uint32_t pos = atomicAdd(&sh[0], 1u);
-                            if (pos < FINAL_CAP) A[pos] = c[u]; else sh[1] = 1u;
+                        for (int u = 0; u < FINAL_REG; ++u) {
+                            const uint32_t e = base + u * 1024 + threadIdx.x;
+                            const uint32_t idx = pos[u] + s;
+                            const uint32_t v = idx < (uint32_t)G ? off[idx] : 0xffffffffu;
+                            pos[u] = v <= e ? idx : pos[u];
                         }
+                    }
+#pragma unroll
+                    for (int u = 0; u < FINAL_REG; ++u) {
+                        const uint32_t e = base + u * 1024 + threadIdx.x;
+                        c[u] = e < E ? slots[(size_t)pos[u] * cap_b + (e - off[pos[u]])] : ~0ull;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < FINAL_REG; ++u) {
+                    const uint32_t e = base + u * 1024 + threadIdx.x;
+                    if (e >= E) continue;
+                    const uint32_t bin = ((uint32_t)(c[u] >> 32)) >> shift;
+                    if (pass == 0) {
+                        atomicAdd(&whist[wave][bin], 1u);
+                    } else if (bin <= kbin) {
+                        const uint32_t pos = atomicAdd(&sh[0], 1u);
+                        if (pos < FINAL_CAP) A[pos] = c[u]; else sh[1] = 1u;
                     }
                 }
             }
@@ -364,14 +393,15 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
 template <int KIND, typename QT>
 static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparams_t *qparams, int nq,
                        const uint8_t *codes, int64_t n, int R, int32_t *out_ids, uint16_t *out_keys,
-                       float *out_dist, char *ws, const ScanPlan &p, hipStream_t s) {
+                       float *out_dist, char *ws, const ScanPlan &p, hipStream_t s, int what) {
     const size_t gtab_bytes = (((size_t)idx->h.gtab_len * sizeof(QT) + 15) & ~(size_t)15) +
                               (size_t)idx->h.T * 2;
-    qadc_prof_begin(s);
-    hipLaunchKernelGGL((k_scan<KIND, QT>), dim3(p.G, nq), dim3(SCAN_THREADS), gtab_bytes, s, idx->dev,
-                       qtables, qparams, codes, n, ws, p.per_query, p.slots_off, p.cap_b);
-    qadc_prof_end(s);
-    QADC_LAUNCH_CHECK("k_scan");
+    if (what & 1) {
+        hipLaunchKernelGGL((k_scan<KIND, QT>), dim3(p.G, nq), dim3(SCAN_THREADS), gtab_bytes, s,
+                           idx->dev, qtables, qparams, codes, n, ws, p.per_query, p.slots_off, p.cap_b);
+        QADC_LAUNCH_CHECK("k_scan");
+    }
+    if (!(what & 2)) return PQ_OK;
     const size_t lds_final = FINAL_CAP * 8 + gtab_bytes;
     if (lds_final > 48 * 1024)
         QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_final<KIND, QT>,
@@ -386,10 +416,10 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
 static int scan_dispatch(const pq_index *idx, const void *qtables, const pq_qparams_t *qparams,
                          int nq, const uint8_t *codes, int64_t n, int R, int32_t *out_ids,
                          uint16_t *out_keys, float *out_dist, char *ws, const ScanPlan &p,
-                         hipStream_t s) {
+                         hipStream_t s, int what = 3) {
     const bool u8 = idx->h.acc_bits == 8;
 #define QADC_GO(KIND, QT) \
-    return launch_scan<KIND, QT>(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s)
+    return launch_scan<KIND, QT>(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s, what)
     switch (idx->h.kind) {
         case SCAN_NIB8:
             if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);
@@ -417,29 +447,55 @@ static int check_scan_args(const char *who, const pq_index_t *idx, int nq, int64
     return PQ_OK;
 }
 
+// what: 1 = scan kernel, 2 = selection kernel, 3 = both
+static int scan_entry(const char *who, int what, const pq_index_t *idx, const void *qtables,
+                      const pq_qparams_t *qparams, int nq, const uint8_t *codes, int64_t n, int R,
+                      int32_t *out_ids, uint16_t *out_keys, float *out_dist, void *workspace,
+                      size_t workspace_bytes, void *stream) {
+    int rc = check_scan_args(who, idx, nq, n, R);
+    if (rc != PQ_OK) return rc;
+    if (nq == 0) return PQ_OK;
+    if (!qtables || !qparams || !workspace || (n > 0 && !codes) ||
+        ((what & 2) && (!out_ids || !out_keys || !out_dist))) {
+        qadc_set_error("%s: null pointer", who);
+        return PQ_EINVAL;
+    }
+    if (((uintptr_t)codes & 15u) != 0 || ((uintptr_t)workspace & 255u) != 0) {
+        qadc_set_error("%s: codes must be 16-byte and workspace 256-byte aligned", who);
+        return PQ_EINVAL;
+    }
+    const ScanPlan p = qadc_scan_plan(idx, nq, n, R);
+    if (workspace_bytes < p.total) {
+        qadc_set_error("%s: workspace of %zu bytes, need %zu", who, workspace_bytes, p.total);
+        return PQ_ENOMEM;
+    }
+    return scan_dispatch(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist,
+                         (char *)workspace, p, (hipStream_t)stream, what);
+}
+
 extern "C" int pq_adc_scan_topk(const pq_index_t *idx, const void *qtables,
                                 const pq_qparams_t *qparams, int nq, const uint8_t *codes,
                                 int64_t n, int R, int32_t *out_ids, uint16_t *out_keys,
                                 float *out_dist, void *workspace, size_t workspace_bytes,
                                 void *stream) {
-    int rc = check_scan_args("pq_adc_scan_topk", idx, nq, n, R);
-    if (rc != PQ_OK) return rc;
-    if (nq == 0) return PQ_OK;
-    if (!qtables || !qparams || !out_ids || !out_keys || !out_dist || !workspace || (n > 0 && !codes)) {
-        qadc_set_error("pq_adc_scan_topk: null pointer");
-        return PQ_EINVAL;
-    }
-    if (((uintptr_t)codes & 15u) != 0 || ((uintptr_t)workspace & 255u) != 0) {
-        qadc_set_error("pq_adc_scan_topk: codes must be 16-byte and workspace 256-byte aligned");
-        return PQ_EINVAL;
-    }
-    const ScanPlan p = qadc_scan_plan(idx, nq, n, R);
-    if (workspace_bytes < p.total) {
-        qadc_set_error("pq_adc_scan_topk: workspace of %zu bytes, need %zu", workspace_bytes, p.total);
-        return PQ_ENOMEM;
-    }
-    return scan_dispatch(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist,
-                         (char *)workspace, p, (hipStream_t)stream);
+    return scan_entry("pq_adc_scan_topk", 3, idx, qtables, qparams, nq, codes, n, R, out_ids,
+                      out_keys, out_dist, workspace, workspace_bytes, stream);
+}
+
+extern "C" int pq_adc_scan_candidates(const pq_index_t *idx, const void *qtables,
+                                      const pq_qparams_t *qparams, int nq, const uint8_t *codes,
+                                      int64_t n, int R, void *workspace, size_t workspace_bytes,
+                                      void *stream) {
+    return scan_entry("pq_adc_scan_candidates", 1, idx, qtables, qparams, nq, codes, n, R, nullptr,
+                      nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+extern "C" int pq_select_topk(const pq_index_t *idx, const void *qtables,
+                              const pq_qparams_t *qparams, int nq, const uint8_t *codes, int64_t n,
+                              int R, int32_t *out_ids, uint16_t *out_keys, float *out_dist,
+                              void *workspace, size_t workspace_bytes, void *stream) {
+    return scan_entry("pq_select_topk", 2, idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys,
+                      out_dist, workspace, workspace_bytes, stream);
 }
 
 // ------------------------------------------------------- fused search call ---

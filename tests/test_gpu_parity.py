@@ -172,9 +172,12 @@ def test_fused_search_equals_three_calls_and_oracle(qb, name, n, R):
     qd = pr.queries.to(dev())
     three = gpu_search(qb, idx, qd, codes_d, R)
     fused = qb.pq_search_topk(idx, qd, codes_d, T_CAL, R)
+    ws = torch.empty(qb.pq_workspace_bytes(idx, qd.shape[0], n, R), dtype=torch.uint8, device=dev())
+    qb.pq_adc_scan_candidates(idx, three[1], three[2], codes_d, R, ws)
+    split = qb.pq_select_topk(idx, three[1], three[2], codes_d, R, ws)
     torch.cuda.synchronize()
-    for a, b in zip(three[3:], fused):
-        assert torch.equal(a, b)
+    for a, b, c in zip(three[3:], fused, split):
+        assert torch.equal(a, b) and torch.equal(a, c)
     lay = pr.layout
     for q in range(qd.shape[0]):
         oi, ok, od = oracle.search(lay.d, lay.nbits, lay.dsub, lay.acc_bits, pr.codebooks.numpy(),
