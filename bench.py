@@ -45,6 +45,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the batch-32/256 legs")
     ap.add_argument("--cpu-queries", type=int, default=8)
+    ap.add_argument("--copy-calibration", type=int, default=0,
+                    help="also run this many plain 1 GiB device copies (library kernel k_copy, "
+                         "known traffic) so that hardware counters collected around this run "
+                         "can be scaled")
     return ap.parse_args()
 
 
@@ -193,6 +197,17 @@ def main():
     lay = pr.layout
     n, cs = pr.codes.shape
     idx = qb.PqIndex(lay.d, lay.nbits, lay.dsub, pr.codebooks, lay.acc_bits)
+
+    if a.copy_calibration:
+        # kernel k_copy on 1 GiB (larger than the 256 MB Infinity Cache): 2^30 bytes read from
+        # HBM and 2^30 written, i.e. 1048576 KiB each in FETCH_SIZE / WRITE_SIZE units
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(a.copy_calibration):
+            qb.pq_copy_bytes(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+
 
     # headline: whole path, `batch` queries per step
     run = Runner(qb, idx, pr.queries, pr.codes, a.batch, a.R, streams=a.streams, fused=not a.unfused)

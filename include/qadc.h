@@ -204,6 +204,14 @@ int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_centroids, int 
                       const int32_t *probe_ids, int nprobe, int t, int R, int32_t *out_ids,
                       float *out_dist, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Plain device-to-device copy by a library kernel (k_copy) whose traffic is known
+ * exactly: nbytes read and nbytes written.  For scaling hardware-counter readings
+ * (rocprofv3 FETCH_SIZE / WRITE_SIZE) taken in the same run as the scan kernel.
+ * dst, src [dev], 16-byte aligned, non-overlapping; nbytes a multiple of 16.
+ */
+int pq_copy_bytes(void *dst, const void *src, size_t nbytes, void *stream);
+
 /* Description of the last error on this thread ("" if none). */
 const char *pq_last_error(void);
 

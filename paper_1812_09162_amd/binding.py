@@ -25,7 +25,7 @@ EXPORTS = [
     "pq_index_create", "pq_index_destroy", "pq_code_size", "pq_table_len", "pq_workspace_bytes",
     "ivf_workspace_bytes", "pq_compute_tables", "pq_quantize_tables", "pq_adc_scan_topk",
     "ivf_adc_scan_topk", "pq_search_workspace_bytes", "pq_search_topk",
-    "pq_adc_scan_candidates", "pq_select_topk", "pq_last_error",
+    "pq_adc_scan_candidates", "pq_select_topk", "pq_copy_bytes", "pq_last_error",
 ]
 
 
@@ -74,6 +74,8 @@ def load() -> ctypes.CDLL:
     lib.pq_adc_scan_candidates.restype = i32
     lib.pq_select_topk.argtypes = [vp, vp, vp, i32, vp, i64, i32, vp, vp, vp, vp, sz, vp]
     lib.pq_select_topk.restype = i32
+    lib.pq_copy_bytes.argtypes = [vp, vp, sz, vp]
+    lib.pq_copy_bytes.restype = i32
     lib.pq_last_error.argtypes = []
     lib.pq_last_error.restype = ctypes.c_char_p
     _lib = lib
@@ -263,6 +265,12 @@ def pq_select_topk(idx: PqIndex, qtables: torch.Tensor, qparams: torch.Tensor, c
                                  codes.shape[0], R, _ptr(ids), _ptr(keys), _ptr(dist),
                                  _ptr(workspace), workspace.numel(), _stream(stream)))
     return ids, keys, dist
+
+
+def pq_copy_bytes(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(load().pq_copy_bytes(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
 
 
 def unpack_qparams(qparams: torch.Tensor):

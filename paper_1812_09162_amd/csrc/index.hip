@@ -193,3 +193,24 @@ extern "C" size_t pq_workspace_bytes(const pq_index_t *idx, int nq, int64_t n, i
     size_t t = qadc_scan_plan(idx, nq, n, R).total;
     return t ? t : 256;
 }
+
+// ------------------------------------------------------------ plain copy ---
+// A copy kernel of exactly known traffic (nbytes read, nbytes written), used to
+// scale hardware-counter readings taken around the scan kernel.
+__global__ void __launch_bounds__(256) k_copy(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                              size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256)
+        dst[i] = src[i];
+}
+
+extern "C" int pq_copy_bytes(void *dst, const void *src, size_t nbytes, void *stream) {
+    if (!dst || !src || (nbytes & 15u) || ((uintptr_t)dst & 15u) || ((uintptr_t)src & 15u)) {
+        qadc_set_error("pq_copy_bytes: need non-null 16-byte aligned pointers and a multiple of 16 bytes");
+        return PQ_EINVAL;
+    }
+    if (nbytes == 0) return PQ_OK;
+    hipLaunchKernelGGL(k_copy, dim3(2048), dim3(256), 0, (hipStream_t)stream, (const uint4 *)src,
+                       (uint4 *)dst, nbytes / 16);
+    QADC_LAUNCH_CHECK("k_copy");
+    return PQ_OK;
+}
