@@ -150,15 +150,21 @@ int pq_adc_scan_topk(const pq_index_t *idx, const void *qtables, const pq_qparam
 
 /*
  * The two halves of pq_adc_scan_topk as calls of their own (same arguments, same
- * workspace): pq_adc_scan_candidates streams the codes and leaves, per query, the
- * codes whose key is within qparams.key_bound in the workspace;
- * pq_select_topk turns those candidates into the sorted top-R.  Calling the two
- * in this order on one stream is exactly pq_adc_scan_topk.  Benchmarks use the
- * first to time the scan kernel alone.
+ * workspace): pq_adc_scan_candidates prepares the query's lookup tables in the
+ * workspace, streams the codes and leaves, per query, the codes whose key is
+ * within qparams.key_bound in the workspace; pq_select_topk turns those
+ * candidates into the sorted top-R.  Calling the two in this order on one stream
+ * is exactly pq_adc_scan_topk.  pq_adc_rescan_candidates repeats only the scan
+ * kernel with the tables a previous pq_adc_scan_candidates call on the same
+ * workspace and the same qtables prepared; benchmarks use it to time that kernel
+ * alone.
  */
 int pq_adc_scan_candidates(const pq_index_t *idx, const void *qtables,
                            const pq_qparams_t *qparams, int nq, const uint8_t *codes, int64_t n,
                            int R, void *workspace, size_t workspace_bytes, void *stream);
+int pq_adc_rescan_candidates(const pq_index_t *idx, const void *qtables,
+                             const pq_qparams_t *qparams, int nq, const uint8_t *codes, int64_t n,
+                             int R, void *workspace, size_t workspace_bytes, void *stream);
 int pq_select_topk(const pq_index_t *idx, const void *qtables, const pq_qparams_t *qparams, int nq,
                    const uint8_t *codes, int64_t n, int R, int32_t *out_ids, uint16_t *out_keys,
                    float *out_dist, void *workspace, size_t workspace_bytes, void *stream);

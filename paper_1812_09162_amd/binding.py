@@ -25,7 +25,7 @@ EXPORTS = [
     "pq_index_create", "pq_index_destroy", "pq_code_size", "pq_table_len", "pq_workspace_bytes",
     "ivf_workspace_bytes", "pq_compute_tables", "pq_quantize_tables", "pq_adc_scan_topk",
     "ivf_adc_scan_topk", "pq_search_workspace_bytes", "pq_search_topk",
-    "pq_adc_scan_candidates", "pq_select_topk", "pq_copy_bytes", "pq_last_error",
+    "pq_adc_scan_candidates", "pq_adc_rescan_candidates", "pq_select_topk", "pq_copy_bytes", "pq_last_error",
 ]
 
 
@@ -72,6 +72,8 @@ def load() -> ctypes.CDLL:
     lib.pq_search_topk.restype = i32
     lib.pq_adc_scan_candidates.argtypes = [vp, vp, vp, i32, vp, i64, i32, vp, sz, vp]
     lib.pq_adc_scan_candidates.restype = i32
+    lib.pq_adc_rescan_candidates.argtypes = [vp, vp, vp, i32, vp, i64, i32, vp, sz, vp]
+    lib.pq_adc_rescan_candidates.restype = i32
     lib.pq_select_topk.argtypes = [vp, vp, vp, i32, vp, i64, i32, vp, vp, vp, vp, sz, vp]
     lib.pq_select_topk.restype = i32
     lib.pq_copy_bytes.argtypes = [vp, vp, sz, vp]
@@ -250,6 +252,14 @@ def pq_adc_scan_candidates(idx: PqIndex, qtables: torch.Tensor, qparams: torch.T
     _check(load().pq_adc_scan_candidates(idx.handle, _ptr(qtables), _ptr(qparams), qtables.shape[0],
                                          _ptr(codes), codes.shape[0], R, _ptr(workspace),
                                          workspace.numel(), _stream(stream)))
+
+
+def pq_adc_rescan_candidates(idx: PqIndex, qtables: torch.Tensor, qparams: torch.Tensor,
+                             codes: torch.Tensor, R: int, workspace: torch.Tensor, stream=None) -> None:
+    _dev(codes, torch.uint8)
+    _check(load().pq_adc_rescan_candidates(idx.handle, _ptr(qtables), _ptr(qparams),
+                                           qtables.shape[0], _ptr(codes), codes.shape[0], R,
+                                           _ptr(workspace), workspace.numel(), _stream(stream)))
 
 
 def pq_select_topk(idx: PqIndex, qtables: torch.Tensor, qparams: torch.Tensor, codes: torch.Tensor,

@@ -21,6 +21,7 @@ extern "C" const char *pq_last_error(void) { return g_err; }
 static void plan_groups(DevLayout &L, int gmax) {
     L.ng = 0;
     L.gtab_len = 0;
+    L.g32ok = 1;
     int j = 0;
     while (j < L.m) {
         int g = L.ng++;
@@ -28,7 +29,9 @@ static void plan_groups(DevLayout &L, int gmax) {
         L.goff[g] = L.bitoff[j];
         int w = L.nbits[j];
         int cnt = 1;
-        while (j + cnt < L.m && w + L.nbits[j + cnt] <= gmax) {
+        // a group never crosses a 32-bit boundary of the code unless a single sub-quantizer does
+        while (j + cnt < L.m && w + L.nbits[j + cnt] <= gmax &&
+               (L.bitoff[j] % 32) + w + L.nbits[j + cnt] <= 32) {
             w += L.nbits[j + cnt];
             ++cnt;
         }
@@ -36,6 +39,7 @@ static void plan_groups(DevLayout &L, int gmax) {
         L.gcount[g] = (int32_t)cnt;
         L.gbase[g] = (int32_t)L.gtab_len;
         L.gtab_len += 1 << w;
+        if ((L.bitoff[j] % 32) + w > 32) L.g32ok = 0;
         j += cnt;
     }
 }
@@ -106,6 +110,8 @@ extern "C" int pq_index_create(pq_index_t **out, int d, int m, const int32_t *nb
     L.kind = SCAN_GENERIC;
     if (all4 && m == 16) L.kind = SCAN_NIB8;
     if (all4 && m == 32) L.kind = SCAN_NIB16;
+    if (L.kind == SCAN_GENERIC && L.cs == 8) L.kind = SCAN_W64;
+    if (L.kind == SCAN_GENERIC && L.cs == 5) L.kind = SCAN_C5;
 
     pq_index *idx = new pq_index;
     idx->h = L;
@@ -136,18 +142,17 @@ extern "C" size_t pq_table_len(const pq_index_t *idx) { return idx ? (size_t)idx
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R) {
-    (void)idx;
     ScanPlan p;
     const int64_t tile_codes = 1024;
     int64_t tiles = (n + tile_codes - 1) / tile_codes;
-    // A single query gets 1024 blocks of 256 threads: four per compute unit, which
-    // streams at full rate and leaves half of every unit's wave slots to the small
-    // per-query kernels of other streams.
+    // A single query gets several times more blocks than fit on the chip at once: blocks
+    // start cheaply (their tables are prepared beforehand) and the hardware hands the
+    // next block to whichever compute unit finishes first, which evens out the tail.
     static const int64_t g1 = getenv("QADC_G") ? atoll(getenv("QADC_G")) : 1024;
     int64_t gmax = 32768 / (nq > 0 ? nq : 1);
     if (gmax < 64) gmax = 64;
     if (gmax > g1) gmax = g1;
-    if (gmax > 2048) gmax = 2048;
+    if (gmax > 4096) gmax = 4096;
     int64_t G = tiles < 1 ? 1 : (tiles > gmax ? gmax : tiles);
     p.G = (int)G;
     // slots per block: four times the candidates expected when the bound comes from a
@@ -164,7 +169,8 @@ ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R) {
     p.pilot_codes = 0;
     p.state_off = 0;
     p.counts_off = 0;
-    p.slots_off = align_up((size_t)p.G * sizeof(uint32_t), 256);
+    p.gtab_off = align_up((size_t)p.G * sizeof(uint32_t), 256);
+    p.slots_off = p.gtab_off + align_up((size_t)idx->h.gtab_len * (idx->h.acc_bits == 8 ? 1 : 2), 256);
     p.per_query = p.slots_off + (size_t)p.G * (size_t)p.cap_b * sizeof(uint64_t);
     p.per_query = align_up(p.per_query, 256);
     p.total = p.per_query * (size_t)(nq > 0 ? nq : 0);

@@ -19,6 +19,7 @@ struct DevLayout {
     int32_t ng;        // number of groups
     int32_t gtab_len;  // total group-table entries
     int32_t kind;      // SCAN_* below
+    int32_t g32ok;     // 1 if no group field crosses a 32-bit boundary of the code
     // all 32-bit so that uniform reads compile to scalar loads (gfx9 has no
     // sub-dword scalar loads)
     int32_t nbits[PQ_MAX_M];
@@ -34,7 +35,12 @@ struct DevLayout {
     int32_t gbase[PQ_MAX_M];   // first group-table entry of group g
 };
 
-enum { SCAN_GENERIC = 0, SCAN_NIB8 = 1, SCAN_NIB16 = 2, SCAN_C5 = 3 };
+// Scan specialisations by code shape:
+//   NIB8 / NIB16  16 or 32 four-bit sub-quantizers (64- / 128-bit codes): one group per byte
+//   W64           any other 8-byte code: group fields cut out of one 64-bit word
+//   C5            5-byte codes (33..40 bits): four codes per lane from five dwords
+//   GENERIC       everything else, byte by byte
+enum { SCAN_GENERIC = 0, SCAN_NIB8 = 1, SCAN_NIB16 = 2, SCAN_C5 = 3, SCAN_W64 = 4 };
 
 struct pq_index {
     DevLayout h;          // host copy
@@ -76,15 +82,18 @@ struct ScanPlan {
     int64_t pilot_codes;
     size_t per_query;  // bytes per query
     size_t state_off, counts_off, slots_off;
+    size_t gtab_off;   // prepared group tables of the query (gtab_len entries)
     size_t total;
 };
 
 void qadc_set_error(const char *fmt, ...);
 ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R);
 
+// gtab_out: if non-null, query q's group tables are also written to gtab_out + q*gtab_stride bytes
 int qadc_quantize_launch(const pq_index *idx, const float *queries, const float *tables_in,
                          float *tables_out, int nq, const uint8_t *codes, int64_t n, int t, int R,
-                         void *qtables, pq_qparams_t *qparams, hipStream_t s);
+                         void *qtables, pq_qparams_t *qparams, char *gtab_out, size_t gtab_stride,
+                         hipStream_t s);
 
 
 #define QADC_HIP_TRY(expr)                                                        \

@@ -20,7 +20,8 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4)
 k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
            const float *__restrict__ queries, const float *__restrict__ tables_in,
            float *__restrict__ tables_out, const uint8_t *__restrict__ codes, int t_eff, int k,
-           int pilot, void *__restrict__ qtables, pq_qparams_t *__restrict__ qparams) {
+           int pilot, void *__restrict__ qtables, pq_qparams_t *__restrict__ qparams,
+           char *__restrict__ gtab_out, size_t gtab_stride) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int T = L->T, m = L->m, cs = L->cs, qmax = L->qmax, d = L->d;
     float *tab = (float *)smem;
@@ -113,8 +114,14 @@ k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     // atomics stay few and spread out.  16-bit keys: high byte first, then the low
     // byte among the keys that share the selected high byte.
     uint32_t bound = (uint32_t)qmax;
-    if (pilot > 0) {
+    if (pilot > 0 || gtab_out) {
         build_gtab<KIND, QT>(L, qt, gtab);
+        if (gtab_out) {  // hand the prepared group tables to the scan kernel
+            QT *dst = (QT *)(gtab_out + q * gtab_stride);
+            for (int e = threadIdx.x; e < L->gtab_len; e += blockDim.x) dst[e] = gtab[e];
+        }
+    }
+    if (pilot > 0) {
         const bool wide = sizeof(QT) != 1;
         const int stage1 = pilot / 8 > 4 * k ? pilot / 8 : pilot;
         uint32_t kstar = 0, below = 0;
@@ -221,14 +228,15 @@ static size_t quantize_lds(const DevLayout &h, int t_eff, size_t esz) {
 template <int KIND, typename QT>
 static int launch_quantize(const pq_index *idx, const float *queries, const float *tables_in,
                            float *tables_out, int nq, const uint8_t *codes, int t_eff, int k,
-                           int pilot, void *qtables, pq_qparams_t *qparams, hipStream_t s) {
+                           int pilot, void *qtables, pq_qparams_t *qparams, char *gtab_out,
+                           size_t gtab_stride, hipStream_t s) {
     const size_t lds = quantize_lds(idx->h, t_eff, sizeof(QT));
     if (lds > 48 * 1024)
         QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_quantize<KIND, QT>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL((k_quantize<KIND, QT>), dim3(nq), dim3(1024), lds, s, idx->dev,
                        idx->codebooks, queries, tables_in, tables_out, codes, t_eff, k, pilot,
-                       qtables, qparams);
+                       qtables, qparams, gtab_out, gtab_stride);
     QADC_LAUNCH_CHECK("k_quantize");
     return PQ_OK;
 }
@@ -236,7 +244,8 @@ static int launch_quantize(const pq_index *idx, const float *queries, const floa
 // Shared by pq_quantize_tables (queries == null) and the fused search call.
 int qadc_quantize_launch(const pq_index *idx, const float *queries, const float *tables_in,
                          float *tables_out, int nq, const uint8_t *codes, int64_t n, int t, int R,
-                         void *qtables, pq_qparams_t *qparams, hipStream_t s) {
+                         void *qtables, pq_qparams_t *qparams, char *gtab_out, size_t gtab_stride,
+                         hipStream_t s) {
     const int64_t want = t > 4 * (int64_t)R ? t : 4 * (int64_t)R;
     const int t_eff = (int)(n < want ? n : want);
     const int k = R < t_eff ? R : t_eff;
@@ -248,12 +257,16 @@ int qadc_quantize_launch(const pq_index *idx, const float *queries, const float 
     const bool u8 = idx->h.acc_bits == 8;
 #define QADC_GO(KIND, QT)                                                                        \
     return launch_quantize<KIND, QT>(idx, queries, tables_in, tables_out, nq, codes, t_eff, k, \
-                                     pilot, qtables, qparams, s)
+                                     pilot, qtables, qparams, gtab_out, gtab_stride, s)
     switch (idx->h.kind) {
         case SCAN_NIB8:
             if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);
         case SCAN_NIB16:
             if (u8) QADC_GO(SCAN_NIB16, uint8_t); else QADC_GO(SCAN_NIB16, uint16_t);
+        case SCAN_W64:
+            if (u8) QADC_GO(SCAN_W64, uint8_t); else QADC_GO(SCAN_W64, uint16_t);
+        case SCAN_C5:
+            if (u8) QADC_GO(SCAN_C5, uint8_t); else QADC_GO(SCAN_C5, uint16_t);
         default:
             if (u8) QADC_GO(SCAN_GENERIC, uint8_t); else QADC_GO(SCAN_GENERIC, uint16_t);
     }
@@ -286,5 +299,5 @@ extern "C" int pq_quantize_tables(const pq_index_t *idx, const float *tables, in
         return PQ_EINVAL;
     }
     return qadc_quantize_launch(idx, nullptr, tables, nullptr, nq, codes, n, t, R, qtables, qparams,
-                                (hipStream_t)stream);
+                                nullptr, 0, (hipStream_t)stream);
 }

@@ -14,12 +14,25 @@
 // The result is defined as a sort by (key, id), so it does not depend on the
 // order in which blocks run.
 #include <math.h>
+#include <string.h>
 
 #include "scan_device.h"
 
 #define SCAN_THREADS 256
-#define MAX_G 2048
+#define MAX_G 4096
+#define FINAL_LPT (MAX_G / 1024)  // slot lists per k_final thread
 #define FINAL_REG 16  // candidates per thread kept in registers by k_final
+#ifndef QADC_U8
+#define QADC_U8 2
+#endif
+#ifndef QADC_DBUF
+#define QADC_DBUF 0  // 1: prefetch the next tile while looking up the current one (measured slower)
+#endif
+#ifndef QADC_U5
+#define QADC_U5 2
+#endif
+constexpr int U8 = QADC_U8;  // 16-byte chunks per thread and tile, 8-byte codes
+constexpr int U5 = QADC_U5;  // 20-byte chunks per thread and tile, 5-byte codes
 
 // Append the lanes with `pass` set to the block's slot list.  Wave-uniform call.
 __device__ __forceinline__ void slot_append(bool pass, uint32_t key, uint32_t id, uint64_t *slot,
@@ -37,68 +50,143 @@ __device__ __forceinline__ void slot_append(bool pass, uint32_t key, uint32_t id
     }
 }
 
+// Append the (lane, slot) pairs with pass[u] set, NS slots per lane, to the block's list:
+// one LDS atomic per call, positions from ballots and lane-mask popcounts.  Wave-uniform
+// call.  The order within the list does not matter.
+template <int NS>
+__device__ __forceinline__ void slot_append_multi(const bool *pass, const uint32_t *key,
+                                                  const uint32_t *id, uint64_t *slot, uint32_t cap,
+                                                  uint32_t *lds_count) {
+    uint64_t m[NS];
+    uint32_t total = 0;
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+        m[u] = __ballot(pass[u]);
+        total += (uint32_t)__popcll(m[u]);
+    }
+    if (total == 0) return;
+    const int lane = __lane_id();
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(lds_count, total);
+    base = __builtin_amdgcn_readfirstlane(base);
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+        const uint32_t pos = base + (uint32_t)__popcll(m[u] & ((1ull << lane) - 1ull));
+        if (pass[u] && pos < cap) slot[pos] = ((uint64_t)key[u] << 32) | (uint64_t)id[u];
+        base += (uint32_t)__popcll(m[u]);
+    }
+}
+
+// ------------------------------------------------------------- k_prepare ---
+// One block per query: the query's group tables, written where k_scan blocks pick them up.
+template <int KIND, typename QT>
+__global__ void __launch_bounds__(256)
+k_prepare(const DevLayout *__restrict__ L, const void *__restrict__ qtables, char *__restrict__ ws,
+          size_t per_query, size_t gtab_off) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    QT *gtab = (QT *)smem;
+    uint16_t *qs = (uint16_t *)(smem + (((size_t)L->gtab_len * sizeof(QT) + 15) & ~(size_t)15));
+    const size_t q = blockIdx.x;
+    stage_qtable<QT>((const QT *)qtables + q * L->T, L->T, qs);
+    build_gtab<KIND, QT>(L, qs, gtab);
+    QT *dst = (QT *)(ws + q * per_query + gtab_off);
+    for (int e = threadIdx.x; e < L->gtab_len; e += blockDim.x) dst[e] = gtab[e];
+}
+
+// Copy prepared group tables (a multiple of 16 bytes is allocated for them) into LDS.
+template <typename QT>
+__device__ __forceinline__ void load_gtab(const char *__restrict__ src, int gtab_len, QT *gtab) {
+    const int n16 = (gtab_len * (int)sizeof(QT) + 15) >> 4;
+    for (int i = threadIdx.x; i < n16; i += blockDim.x) ((uint4 *)gtab)[i] = ((const uint4 *)src)[i];
+    __syncthreads();
+}
+
 // ---------------------------------------------------------------- k_scan ---
 template <int KIND, typename QT>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
        const pq_qparams_t *__restrict__ qparams, const uint8_t *__restrict__ codes, int64_t n,
-       char *__restrict__ ws, size_t per_query, size_t slots_off, int cap_b) {
+       char *__restrict__ ws, size_t per_query, size_t slots_off, size_t gtab_off, int cap_b,
+       int gtab_len, uint32_t qmax, int g32ok, GroupDesc gd) {
     extern __shared__ __align__(16) unsigned char smem[];
     QT *gtab = (QT *)smem;
-    uint16_t *qs = (uint16_t *)(smem + (((size_t)L->gtab_len * sizeof(QT) + 15) & ~(size_t)15));
     __shared__ uint32_t s_count;
     const size_t q = blockIdx.y;
     const int b = blockIdx.x, G = gridDim.x;
     char *wq = ws + q * per_query;
     uint32_t *counts = (uint32_t *)wq;
     uint64_t *slot = (uint64_t *)(wq + slots_off) + (size_t)b * cap_b;
-    const uint32_t qmax = (uint32_t)L->qmax;
+    const char *gsrc = wq + gtab_off;
     uint32_t thr = qparams[q].key_bound;
     thr = thr > qmax ? qmax : thr;
     if (threadIdx.x == 0) s_count = 0;
+    // fast field extraction: at most eight groups, none crossing a dword boundary
+    const bool g32 = g32ok != 0;
 
-    if (KIND == SCAN_NIB8) {
-        // 16-byte chunks of two codes; an odd last code is handled after the loop
+    if (KIND == SCAN_NIB8 || KIND == SCAN_W64) {
+        // 16-byte chunks of two codes, U8 chunks per thread and tile, double-buffered so that
+        // 2*U8*16 bytes per lane are in flight; an odd last code is handled after the loop
+        constexpr int U = U8;
         const int64_t nfull = n >> 1;
-        const int64_t ntiles = (nfull + 2 * SCAN_THREADS - 1) / (2 * SCAN_THREADS);
+        const int64_t ntiles = (nfull + U * SCAN_THREADS - 1) / (U * SCAN_THREADS);
         const uint4 *__restrict__ p = (const uint4 *)codes;
-        uint4 cur[2], nxt[2];
+        uint4 cur[U], nxt[U];
         int64_t tile = b;
+        if (QADC_DBUF) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int64_t c = tile * (2 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
-            cur[u] = (tile < ntiles && c < nfull) ? p[c] : make_uint4(0, 0, 0, 0);
-        }
-        stage_qtable<QT>((const QT *)qtables + q * L->T, L->T, qs);
-        build_gtab<KIND, QT>(L, qs, gtab);
-        for (; tile < ntiles; tile += G) {
-            const int64_t tn = tile + G;
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int64_t c = tn * (2 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
-                nxt[u] = (tn < ntiles && c < nfull) ? p[c] : make_uint4(0, 0, 0, 0);
+            for (int u = 0; u < U; ++u) {
+                const int64_t c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                cur[u] = (tile < ntiles && c < nfull) ? p[c] : make_uint4(0, 0, 0, 0);
             }
-            uint32_t s[4];
-            bool pass[4], any = false;
+        }
+        load_gtab<QT>(gsrc, gtab_len, gtab);
+        for (; tile < ntiles; tile += G) {
+            if (QADC_DBUF) {
+                const int64_t tn = tile + G;
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int64_t c = tile * (2 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
-                s[2 * u] = sum8(gtab, cur[u].x, cur[u].y);
-                s[2 * u + 1] = sum8(gtab, cur[u].z, cur[u].w);
+                for (int u = 0; u < U; ++u) {
+                    const int64_t c = tn * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                    nxt[u] = (tn < ntiles && c < nfull) ? p[c] : make_uint4(0, 0, 0, 0);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                    cur[u] = c < nfull ? p[c] : make_uint4(0, 0, 0, 0);
+                }
+            }
+            uint32_t s[2 * U];
+            bool pass[2 * U], any = false;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                if (KIND == SCAN_NIB8) {
+                    s[2 * u] = sum8(gtab, cur[u].x, cur[u].y);
+                    s[2 * u + 1] = sum8(gtab, cur[u].z, cur[u].w);
+                } else if (g32) {
+                    s[2 * u] = sum_groups_desc(gd, gtab, cur[u].x, cur[u].y);
+                    s[2 * u + 1] = sum_groups_desc(gd, gtab, cur[u].z, cur[u].w);
+                } else {
+                    s[2 * u] = sum_groups64(L, gtab, ((uint64_t)cur[u].y << 32) | cur[u].x);
+                    s[2 * u + 1] = sum_groups64(L, gtab, ((uint64_t)cur[u].w << 32) | cur[u].z);
+                }
                 pass[2 * u] = (c < nfull) && s[2 * u] <= thr;
                 pass[2 * u + 1] = (c < nfull) && s[2 * u + 1] <= thr;
                 any = any || pass[2 * u] || pass[2 * u + 1];
             }
             if (__ballot(any) != 0) {
+                uint32_t id[2 * U];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int64_t c = tile * (2 * SCAN_THREADS) + (u >> 1) * SCAN_THREADS + threadIdx.x;
-                    slot_append(pass[u], s[u], (uint32_t)(2 * c + (u & 1)), slot, (uint32_t)cap_b,
-                                &s_count);
+                for (int u = 0; u < 2 * U; ++u) {
+                    const int64_t c = tile * (U * SCAN_THREADS) + (u >> 1) * SCAN_THREADS + threadIdx.x;
+                    id[u] = (uint32_t)(2 * c + (u & 1));
                 }
+                slot_append_multi<2 * U>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
             }
-            cur[0] = nxt[0];
-            cur[1] = nxt[1];
+            if (QADC_DBUF) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+            }
         }
         if ((n & 1) && b == 0) {  // the odd last code, by one wave of block 0
             if (threadIdx.x < QADC_WAVE) {
@@ -106,17 +194,81 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 uint32_t key = 0;
                 if (me) {
                     uint2 w = *(const uint2 *)(codes + (n - 1) * 8);
-                    key = sum8(gtab, w.x, w.y);
+                    key = KIND == SCAN_NIB8 ? sum8(gtab, w.x, w.y)
+                                            : sum_groups64(L, gtab, ((uint64_t)w.y << 32) | w.x);
                 }
                 slot_append(me && key <= thr, key, (uint32_t)(n - 1), slot, (uint32_t)cap_b, &s_count);
             }
         }
+    } else if (KIND == SCAN_C5) {
+        // 20-byte chunks of four 5-byte codes: five dwords per lane, U5 chunks per thread and
+        // tile, double-buffered; the last n % 4 codes are handled after the loop
+        constexpr int U = U5;
+        const int64_t nfull = n >> 2;
+        const int64_t ntiles = (nfull + U * SCAN_THREADS - 1) / (U * SCAN_THREADS);
+        const uint32_t *__restrict__ p = (const uint32_t *)codes;
+        uint32_t cur[U][5], nxt[U][5];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t c = (int64_t)b * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+#pragma unroll
+            for (int i = 0; i < 5; ++i) cur[u][i] = (b < ntiles && c < nfull) ? p[c * 5 + i] : 0u;
+        }
+        load_gtab<QT>(gsrc, gtab_len, gtab);
+        for (int64_t tile = b; tile < ntiles; tile += G) {
+            const int64_t tn = tile + G;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t c = tn * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+#pragma unroll
+                for (int i = 0; i < 5; ++i) nxt[u][i] = (tn < ntiles && c < nfull) ? p[c * 5 + i] : 0u;
+            }
+            uint32_t s[4 * U];
+            bool pass[4 * U], any = false;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                // code v = bits [40v, 40v+40) of the 160-bit chunk, as (low dword, high byte)
+                uint32_t lo[4], hi[4];
+                lo[0] = cur[u][0];
+                hi[0] = cur[u][1] & 0xffu;
+                lo[1] = __builtin_amdgcn_alignbit(cur[u][2], cur[u][1], 8);
+                hi[1] = (cur[u][2] >> 8) & 0xffu;
+                lo[2] = __builtin_amdgcn_alignbit(cur[u][3], cur[u][2], 16);
+                hi[2] = (cur[u][3] >> 16) & 0xffu;
+                lo[3] = __builtin_amdgcn_alignbit(cur[u][4], cur[u][3], 24);
+                hi[3] = cur[u][4] >> 24;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    s[4 * u + v] = g32 ? sum_groups_desc(gd, gtab, lo[v], hi[v])
+                                       : sum_groups64(L, gtab, ((uint64_t)hi[v] << 32) | lo[v]);
+                    pass[4 * u + v] = (c < nfull) && s[4 * u + v] <= thr;
+                    any = any || pass[4 * u + v];
+                }
+            }
+            if (__ballot(any) != 0) {
+                uint32_t id[4 * U];
+#pragma unroll
+                for (int u = 0; u < 4 * U; ++u) {
+                    const int64_t c = tile * (U * SCAN_THREADS) + (u >> 2) * SCAN_THREADS + threadIdx.x;
+                    id[u] = (uint32_t)(4 * c + (u & 3));
+                }
+                slot_append_multi<4 * U>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int i = 0; i < 5; ++i) cur[u][i] = nxt[u][i];
+        }
+        if ((n & 3) && b == 0 && threadIdx.x < QADC_WAVE) {  // the last n % 4 codes
+            const int64_t id = (nfull << 2) + threadIdx.x;
+            const bool me = id < n;
+            uint32_t key = me ? key_at<KIND, QT>(L, gtab, codes, id) : 0u;
+            slot_append(me && key <= thr, key, (uint32_t)id, slot, (uint32_t)cap_b, &s_count);
+        }
     } else {
         const int64_t ntiles = (n + 4 * SCAN_THREADS - 1) / (4 * SCAN_THREADS);
-        if (KIND != SCAN_NIB16) {
-            stage_qtable<QT>((const QT *)qtables + q * L->T, L->T, qs);
-            build_gtab<KIND, QT>(L, qs, gtab);
-        }
+        if (KIND != SCAN_NIB16) load_gtab<QT>(gsrc, gtab_len, gtab);
         uint4 cur[4];
         if (KIND == SCAN_NIB16) {
 #pragma unroll
@@ -124,8 +276,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 const int64_t c = (int64_t)b * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
                 cur[u] = c < n ? ((const uint4 *)codes)[c] : make_uint4(0, 0, 0, 0);
             }
-            stage_qtable<QT>((const QT *)qtables + q * L->T, L->T, qs);
-            build_gtab<KIND, QT>(L, qs, gtab);
+            load_gtab<QT>(gsrc, gtab_len, gtab);
         }
         for (int64_t tile = b; tile < ntiles; tile += G) {
             uint32_t s[4];
@@ -150,11 +301,11 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 any = any || pass[u];
             }
             if (__ballot(any) != 0) {
+                uint32_t id[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int64_t c = tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
-                    slot_append(pass[u], s[u], (uint32_t)c, slot, (uint32_t)cap_b, &s_count);
-                }
+                for (int u = 0; u < 4; ++u)
+                    id[u] = (uint32_t)(tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x);
+                slot_append_multi<4>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
             }
             if (KIND == SCAN_NIB16) {
 #pragma unroll
@@ -285,16 +436,18 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     const pq_qparams_t prm = qparams[q];
     const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
 
-    // exclusive prefix sum of the G per-block counts (G <= 2048: two per thread)
-    uint32_t cnt[2];
+    // exclusive prefix sum of the G per-block counts: FINAL_LPT consecutive lists per thread
+    uint32_t cnt[FINAL_LPT], mine = 0;
+    bool over = false;
 #pragma unroll
-    for (int l = 0; l < 2; ++l) {
-        const int list = 2 * (int)threadIdx.x + l;
+    for (int l = 0; l < FINAL_LPT; ++l) {
+        const int list = FINAL_LPT * (int)threadIdx.x + l;
         cnt[l] = list < G ? counts[list] : 0u;
+        over = over || cnt[l] > (uint32_t)cap_b;
+        mine += cnt[l];
     }
-    const bool over = cnt[0] > (uint32_t)cap_b || cnt[1] > (uint32_t)cap_b;
     for (int i = threadIdx.x; i < 16 * 256; i += blockDim.x) (&whist[0][0])[i] = 0;
-    const uint32_t incl = qadc_wave_incl_scan(cnt[0] + cnt[1]);
+    const uint32_t incl = qadc_wave_incl_scan(mine);
     if (lane == QADC_WAVE - 1) wsum[wave] = incl;
     if (threadIdx.x == 0) {
         sh[0] = 0;  // entries gathered into A
@@ -306,8 +459,15 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         wbase += (w < wave) ? wsum[w] : 0u;
         E += wsum[w];
     }
-    if (2 * (int)threadIdx.x < G) off[2 * threadIdx.x] = wbase + incl - cnt[0] - cnt[1];
-    if (2 * (int)threadIdx.x + 1 < G) off[2 * threadIdx.x + 1] = wbase + incl - cnt[1];
+    {
+        uint32_t run = wbase + incl - mine;
+#pragma unroll
+        for (int l = 0; l < FINAL_LPT; ++l) {
+            const int list = FINAL_LPT * (int)threadIdx.x + l;
+            if (list < G) off[list] = run;
+            run += cnt[l];
+        }
+    }
     if (threadIdx.x == 0) off[G] = E;
     if (over) sh[1] = 1u;
     __syncthreads();
@@ -390,19 +550,35 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
 }
 
 // ------------------------------------------------------------------ host ---
+// what: 4 = prepare the group tables, 1 = scan kernel, 2 = selection kernel
 template <int KIND, typename QT>
 static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparams_t *qparams, int nq,
                        const uint8_t *codes, int64_t n, int R, int32_t *out_ids, uint16_t *out_keys,
                        float *out_dist, char *ws, const ScanPlan &p, hipStream_t s, int what) {
-    const size_t gtab_bytes = (((size_t)idx->h.gtab_len * sizeof(QT) + 15) & ~(size_t)15) +
-                              (size_t)idx->h.T * 2;
+    const DevLayout &h = idx->h;
+    const size_t gtab_bytes = ((size_t)h.gtab_len * sizeof(QT) + 15) & ~(size_t)15;
+    if (what & 4) {
+        hipLaunchKernelGGL((k_prepare<KIND, QT>), dim3(nq), dim3(256), gtab_bytes + (size_t)h.T * 2, s,
+                           idx->dev, qtables, ws, p.per_query, p.gtab_off);
+        QADC_LAUNCH_CHECK("k_prepare");
+    }
     if (what & 1) {
+        GroupDesc gd;
+        memset(&gd, 0, sizeof(gd));
+        gd.ng = h.ng;
+        for (int g = 0; g < QADC_MAXG_FAST && g < h.ng; ++g) {
+            gd.off[g] = h.goff[g];
+            gd.w[g] = h.gw[g];
+            gd.base[g] = h.gbase[g];
+        }
+        const int g32 = h.g32ok != 0 && h.ng <= QADC_MAXG_FAST;
         hipLaunchKernelGGL((k_scan<KIND, QT>), dim3(p.G, nq), dim3(SCAN_THREADS), gtab_bytes, s,
-                           idx->dev, qtables, qparams, codes, n, ws, p.per_query, p.slots_off, p.cap_b);
+                           idx->dev, qtables, qparams, codes, n, ws, p.per_query, p.slots_off,
+                           p.gtab_off, p.cap_b, h.gtab_len, (uint32_t)h.qmax, g32, gd);
         QADC_LAUNCH_CHECK("k_scan");
     }
     if (!(what & 2)) return PQ_OK;
-    const size_t lds_final = FINAL_CAP * 8 + gtab_bytes;
+    const size_t lds_final = FINAL_CAP * 8 + gtab_bytes + (size_t)h.T * 2;
     if (lds_final > 48 * 1024)
         QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_final<KIND, QT>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_final));
@@ -416,7 +592,7 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
 static int scan_dispatch(const pq_index *idx, const void *qtables, const pq_qparams_t *qparams,
                          int nq, const uint8_t *codes, int64_t n, int R, int32_t *out_ids,
                          uint16_t *out_keys, float *out_dist, char *ws, const ScanPlan &p,
-                         hipStream_t s, int what = 3) {
+                         hipStream_t s, int what) {
     const bool u8 = idx->h.acc_bits == 8;
 #define QADC_GO(KIND, QT) \
     return launch_scan<KIND, QT>(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s, what)
@@ -425,6 +601,10 @@ static int scan_dispatch(const pq_index *idx, const void *qtables, const pq_qpar
             if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);
         case SCAN_NIB16:
             if (u8) QADC_GO(SCAN_NIB16, uint8_t); else QADC_GO(SCAN_NIB16, uint16_t);
+        case SCAN_W64:
+            if (u8) QADC_GO(SCAN_W64, uint8_t); else QADC_GO(SCAN_W64, uint16_t);
+        case SCAN_C5:
+            if (u8) QADC_GO(SCAN_C5, uint8_t); else QADC_GO(SCAN_C5, uint16_t);
         default:
             if (u8) QADC_GO(SCAN_GENERIC, uint8_t); else QADC_GO(SCAN_GENERIC, uint16_t);
     }
@@ -447,7 +627,6 @@ static int check_scan_args(const char *who, const pq_index_t *idx, int nq, int64
     return PQ_OK;
 }
 
-// what: 1 = scan kernel, 2 = selection kernel, 3 = both
 static int scan_entry(const char *who, int what, const pq_index_t *idx, const void *qtables,
                       const pq_qparams_t *qparams, int nq, const uint8_t *codes, int64_t n, int R,
                       int32_t *out_ids, uint16_t *out_keys, float *out_dist, void *workspace,
@@ -478,7 +657,7 @@ extern "C" int pq_adc_scan_topk(const pq_index_t *idx, const void *qtables,
                                 int64_t n, int R, int32_t *out_ids, uint16_t *out_keys,
                                 float *out_dist, void *workspace, size_t workspace_bytes,
                                 void *stream) {
-    return scan_entry("pq_adc_scan_topk", 3, idx, qtables, qparams, nq, codes, n, R, out_ids,
+    return scan_entry("pq_adc_scan_topk", 7, idx, qtables, qparams, nq, codes, n, R, out_ids,
                       out_keys, out_dist, workspace, workspace_bytes, stream);
 }
 
@@ -486,7 +665,15 @@ extern "C" int pq_adc_scan_candidates(const pq_index_t *idx, const void *qtables
                                       const pq_qparams_t *qparams, int nq, const uint8_t *codes,
                                       int64_t n, int R, void *workspace, size_t workspace_bytes,
                                       void *stream) {
-    return scan_entry("pq_adc_scan_candidates", 1, idx, qtables, qparams, nq, codes, n, R, nullptr,
+    return scan_entry("pq_adc_scan_candidates", 5, idx, qtables, qparams, nq, codes, n, R, nullptr,
+                      nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+extern "C" int pq_adc_rescan_candidates(const pq_index_t *idx, const void *qtables,
+                                        const pq_qparams_t *qparams, int nq, const uint8_t *codes,
+                                        int64_t n, int R, void *workspace, size_t workspace_bytes,
+                                        void *stream) {
+    return scan_entry("pq_adc_rescan_candidates", 1, idx, qtables, qparams, nq, codes, n, R, nullptr,
                       nullptr, nullptr, workspace, workspace_bytes, stream);
 }
 
@@ -539,8 +726,9 @@ extern "C" int pq_search_topk(const pq_index_t *idx, const float *queries, int n
     void *qtables = w + up256((size_t)nq * sizeof(pq_qparams_t));
     char *ws = (char *)qtables + up256((size_t)nq * idx->h.T * esz);
     hipStream_t s = (hipStream_t)stream;
-    rc = qadc_quantize_launch(idx, queries, nullptr, nullptr, nq, codes, n, t, R, qtables, qparams, s);
-    if (rc != PQ_OK) return rc;
     const ScanPlan p = qadc_scan_plan(idx, nq, n, R);
-    return scan_dispatch(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s);
+    rc = qadc_quantize_launch(idx, queries, nullptr, nullptr, nq, codes, n, t, R, qtables, qparams,
+                              ws + p.gtab_off, p.per_query, s);
+    if (rc != PQ_OK) return rc;
+    return scan_dispatch(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s, 3);
 }

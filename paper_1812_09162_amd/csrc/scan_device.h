@@ -40,14 +40,27 @@ __device__ inline void build_gtab(const DevLayout *L, const uint16_t *qs, QT *gt
             const int entries = 1 << L->gw[g];
             const int first = L->gfirst[g], cnt = L->gcount[g];
             const int base = L->gbase[g];
-            for (int e = threadIdx.x; e < entries; e += blockDim.x) {
-                uint32_t rem = (uint32_t)e, s = 0;
-                for (int c = 0; c < cnt; ++c) {
-                    const int j = first + c, bb = L->nbits[j];
-                    s += qs[L->toff[j] + (rem & ((1u << bb) - 1u))];
-                    rem >>= bb;
+            if (cnt <= 3) {
+                // descriptors of the (at most three) sub-quantizers of the group in registers
+                const int b0 = L->nbits[first], t0 = L->toff[first];
+                const int b1 = cnt > 1 ? L->nbits[first + 1] : 0, t1 = cnt > 1 ? L->toff[first + 1] : 0;
+                const int b2 = cnt > 2 ? L->nbits[first + 2] : 0, t2 = cnt > 2 ? L->toff[first + 2] : 0;
+                for (int e = threadIdx.x; e < entries; e += blockDim.x) {
+                    uint32_t s = qs[t0 + (e & ((1 << b0) - 1))];
+                    if (cnt > 1) s += qs[t1 + ((e >> b0) & ((1 << b1) - 1))];
+                    if (cnt > 2) s += qs[t2 + ((e >> (b0 + b1)) & ((1 << b2) - 1))];
+                    gtab[base + e] = (QT)(s > qmax ? qmax : s);
                 }
-                gtab[base + e] = (QT)(s > qmax ? qmax : s);
+            } else {
+                for (int e = threadIdx.x; e < entries; e += blockDim.x) {
+                    uint32_t rem = (uint32_t)e, s = 0;
+                    for (int c = 0; c < cnt; ++c) {
+                        const int j = first + c, bb = L->nbits[j];
+                        s += qs[L->toff[j] + (rem & ((1u << bb) - 1u))];
+                        rem >>= bb;
+                    }
+                    gtab[base + e] = (QT)(s > qmax ? qmax : s);
+                }
             }
         }
     }
@@ -82,6 +95,64 @@ __device__ __forceinline__ uint32_t key_generic(const DevLayout *L, const QT *gt
     return s > qmax ? qmax : s;
 }
 
+// sum of the group entries selected by the fields of a code held in one 64-bit word
+template <typename QT>
+__device__ __forceinline__ uint32_t sum_groups64(const DevLayout *L, const QT *gtab, uint64_t v) {
+    const int ng = L->ng;
+    uint32_t s = 0;
+    for (int g = 0; g < ng; ++g)
+        s += gtab[L->gbase[g] + ((uint32_t)(v >> L->goff[g]) & ((1u << L->gw[g]) - 1u))];
+    return s;
+}
+
+// the same for a code of at most 64 bits given as two dwords, when no group field crosses
+// the dword boundary (DevLayout::g32ok): one select and one bit-field extract per group
+template <typename QT>
+__device__ __forceinline__ uint32_t sum_groups32(const DevLayout *L, const QT *gtab, uint32_t lo,
+                                                 uint32_t hi) {
+    const int ng = L->ng;
+    uint32_t s = 0;
+    for (int g = 0; g < ng; ++g) {
+        const int off = L->goff[g];
+        const uint32_t x = off >= 32 ? hi : lo;
+        s += gtab[L->gbase[g] + __builtin_amdgcn_ubfe(x, (uint32_t)(off & 31), (uint32_t)L->gw[g])];
+    }
+    return s;
+}
+
+// Group descriptors of a layout with at most eight groups, read once into (scalar)
+// registers so that the scan loop does no descriptor loads.
+#define QADC_MAXG_FAST 8
+struct GroupDesc {
+    int ng;
+    int off[QADC_MAXG_FAST], w[QADC_MAXG_FAST], base[QADC_MAXG_FAST];
+};
+__device__ __forceinline__ GroupDesc load_group_desc(const DevLayout *L) {
+    GroupDesc d;
+    d.ng = L->ng;
+#pragma unroll
+    for (int g = 0; g < QADC_MAXG_FAST; ++g) {
+        d.off[g] = L->goff[g];
+        d.w[g] = L->gw[g];
+        d.base[g] = L->gbase[g];
+    }
+    return d;
+}
+// code of at most 64 bits as two dwords, no group crossing the dword boundary
+template <typename QT>
+__device__ __forceinline__ uint32_t sum_groups_desc(const GroupDesc &d, const QT *gtab, uint32_t lo,
+                                                    uint32_t hi) {
+    uint32_t s = 0;
+#pragma unroll
+    for (int g = 0; g < QADC_MAXG_FAST; ++g) {
+        if (g < d.ng) {
+            const uint32_t x = d.off[g] >= 32 ? hi : lo;
+            s += gtab[d.base[g] + __builtin_amdgcn_ubfe(x, (uint32_t)(d.off[g] & 31), (uint32_t)d.w[g])];
+        }
+    }
+    return s;
+}
+
 // key of the code at position id (simple per-code loads; used off the hot loop)
 template <int KIND, typename QT>
 __device__ __forceinline__ uint32_t key_at(const DevLayout *L, const QT *gtab,
@@ -94,6 +165,16 @@ __device__ __forceinline__ uint32_t key_at(const DevLayout *L, const QT *gtab,
     } else if (KIND == SCAN_NIB16) {
         uint4 w = *(const uint4 *)(codes + id * 16);
         uint32_t s = sum8(gtab, w.x, w.y) + sum8(gtab + 2048, w.z, w.w);
+        return s > qmax ? qmax : s;
+    } else if (KIND == SCAN_W64) {
+        uint2 w = *(const uint2 *)(codes + id * 8);
+        uint32_t s = sum_groups64(L, gtab, ((uint64_t)w.y << 32) | w.x);
+        return s > qmax ? qmax : s;
+    } else if (KIND == SCAN_C5) {
+        const uint8_t *c = codes + id * 5;
+        const uint64_t v = (uint64_t)c[0] | ((uint64_t)c[1] << 8) | ((uint64_t)c[2] << 16) |
+                           ((uint64_t)c[3] << 24) | ((uint64_t)c[4] << 32);
+        uint32_t s = sum_groups64(L, gtab, v);
         return s > qmax ? qmax : s;
     } else {
         return key_generic(L, gtab, codes + id * L->cs);
@@ -134,11 +215,24 @@ __device__ __forceinline__ void keys_batch(const DevLayout *L, const QT *gtab,
             const uint32_t s = sum8(gtab, w[u].x, w[u].y) + sum8(gtab + 2048, w[u].z, w[u].w);
             key[u] = (base + u * stride < n) ? (s > qmax ? qmax : s) : 0xffffffffu;
         }
+    } else if (KIND == SCAN_W64) {
+        uint2 w[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int64_t id = base + u * stride;
+            id = id < n ? id : n - 1;
+            w[u] = *(const uint2 *)(codes + id * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t s = sum_groups64(L, gtab, ((uint64_t)w[u].y << 32) | w[u].x);
+            key[u] = (base + u * stride < n) ? (s > qmax ? qmax : s) : 0xffffffffu;
+        }
     } else {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int64_t id = base + u * stride;
-            key[u] = id < n ? key_generic(L, gtab, codes + id * L->cs) : 0xffffffffu;
+            key[u] = id < n ? key_at<KIND, QT>(L, gtab, codes, id) : 0xffffffffu;
         }
     }
 }
