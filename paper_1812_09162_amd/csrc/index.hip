@@ -180,7 +180,7 @@ ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R) {
 IvfPlan qadc_ivf_plan(const pq_index *idx, int nq, int nprobe, int R) {
     (void)idx;
     IvfPlan p;
-    p.cap_b = R <= 256 ? 1024 : 4096;
+    p.cap_b = R <= 128 ? 1024 : 4096;
     p.counts_off = align_up(sizeof(IvfState), 256);
     p.slots_off = p.counts_off + align_up((size_t)nprobe * sizeof(uint32_t), 256);
     p.per_query = align_up(p.slots_off + (size_t)nprobe * (size_t)p.cap_b * sizeof(uint64_t), 256);

@@ -4,14 +4,17 @@
 //
 //   k_ivf_calib  one block per query: float ADC of the first t_eff probed codes
 //                (each with its own cell's tables) -> d_max; then the quantized
-//                distances of the same codes -> a first bound thr0 on the R-th
-//                best distance and the binning (lo, scale) used for pruning.
+//                distances of the first few thousand probed codes -> thr0, the
+//                R-th smallest of them, an upper bound on the R-th best distance
+//                of the query, and a monotone 256-bin map of [lo, thr0].
 //   k_ivf_scan   one block per (query, probed cell): residual tables, the
 //                cell's p_min / d_min / delta from the shared d_max, quantized
-//                group tables in LDS, scan of the list; candidates are
-//                (distance, stored id) packed into a sortable 64-bit word.
-//   k_ivf_final  one block per query: rank the surviving candidates; exact
-//                multi-pass selection over all probed codes if a slot overflowed.
+//                group tables in LDS, scan of the list; codes with distance
+//                <= thr0 go to the block's slot list as
+//                (ordered float distance << 32 | stored id).
+//   k_ivf_final  one block per query: gather the candidates, find the bin of the
+//                R-th, rank the few up to it; exact multi-pass selection over
+//                all probed codes if a slot list overflowed.
 #include "scan_device.h"
 
 struct IvfLds {
@@ -124,15 +127,15 @@ __global__ void __launch_bounds__(256)
 k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
             const float *__restrict__ coarse, const int64_t *__restrict__ list_offsets,
             const uint8_t *__restrict__ list_codes, const float *__restrict__ queries,
-            const int32_t *__restrict__ probe_ids, int nprobe, int K, int want, int R,
-            char *__restrict__ ws, size_t per_query) {
+            const int32_t *__restrict__ probe_ids, int nprobe, int K, int want, int pilot_want,
+            int R, char *__restrict__ ws, size_t per_query) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sel[2];
     __shared__ long long s_np;
     IvfLds l;
     unsigned char *rest = ivf_carve(L, smem, 2, l);
-    uint32_t *ord = (uint32_t *)rest;  // [want]
+    uint32_t *ord = (uint32_t *)rest;  // [max(want, pilot_want)]
     qadc_build_entry_map(L, l.esub);
     const size_t q = blockIdx.x;
     IvfState *st = (IvfState *)(ws + q * per_query);
@@ -148,14 +151,12 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         }
         s_np = np;
     }
-    for (int i = threadIdx.x; i < 256; i += blockDim.x) st->hist[i] = 0;
     __syncthreads();
     const int t_eff = (int)(s_np < (long long)want ? s_np : (long long)want);
+    const int pilot = (int)(s_np < (long long)pilot_want ? s_np : (long long)pilot_want);
     const int k = R < t_eff ? R : t_eff;
     if (t_eff == 0) {
         if (threadIdx.x == 0) {
-            st->thr = 255u;
-            st->overflow = 0u;
             st->dmax = INFINITY;
             st->thr0 = INFINITY;
             st->lo = 0.f;
@@ -183,15 +184,15 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         __syncthreads();
     }
     const float dmax = qadc_ord2f(qadc_block_kth_u32(ord, t_eff, k, 4, hist, sel));
-    // pass 2: quantized distances of the same codes -> thr0 and the binning
+    // pass 2: quantized distances of the first `pilot` probed codes -> thr0 and the binning
     seen = 0;
-    for (int a = 0; a < nprobe && seen < t_eff; ++a) {
+    for (int a = 0; a < nprobe && seen < pilot; ++a) {
         const int c = probes[a];
         if (c < 0 || c >= K) continue;
         const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
         if (hi == lo) continue;
         const bool ok = ivf_setup<SCAN_GENERIC, uint16_t>(L, cb, z, coarse + (size_t)c * L->d, dmax, true, false, l);
-        const int take = (int)((hi - lo) < (int64_t)(t_eff - seen) ? (hi - lo) : (int64_t)(t_eff - seen));
+        const int take = (int)((hi - lo) < (int64_t)(pilot - seen) ? (hi - lo) : (int64_t)(pilot - seen));
         const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
         for (int p = threadIdx.x; p < take; p += blockDim.x) {
             uint32_t o = 0xffffffffu;
@@ -209,14 +210,12 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         __syncthreads();
     }
     const uint32_t inf_o = qadc_f2ord(INFINITY);
-    uint32_t t0 = qadc_block_kth_u32(ord, t_eff, k, 4, hist, sel);
-    uint32_t l0 = qadc_block_kth_u32(ord, t_eff, 1, 4, hist, sel);
+    uint32_t t0 = qadc_block_kth_u32(ord, pilot, k, 4, hist, sel);
+    uint32_t l0 = qadc_block_kth_u32(ord, pilot, 1, 4, hist, sel);
     if (threadIdx.x == 0) {
         const float thr0 = t0 > inf_o ? INFINITY : qadc_ord2f(t0);
         const float lo = l0 > inf_o ? 0.f : qadc_ord2f(l0);
         const float span = thr0 - lo;
-        st->thr = 255u;
-        st->overflow = 0u;
         st->dmax = dmax;
         st->thr0 = thr0;
         st->lo = lo;
@@ -253,7 +252,7 @@ k_ivf_scan(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         if (threadIdx.x == 0) counts[a] = 0;
         return;
     }
-    const float dmax = st->dmax, thr0 = st->thr0, blo = st->lo, bscale = st->scale;
+    const float dmax = st->dmax, thr0 = st->thr0;
     if (threadIdx.x == 0) s_count = 0;
     const bool ok = ivf_setup<KIND, QT>(L, cb, queries + q * L->d, coarse + (size_t)c * L->d, dmax, true,
                                   true, l);
@@ -263,39 +262,29 @@ k_ivf_scan(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     }
     const QT *gtab = (const QT *)l.gtab;
     const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
-    SlotRef ref;
-    ref.slot = (uint64_t *)(wq + slots_off) + (size_t)a * cap_b;
-    ref.cap = (uint32_t)cap_b;
-    ref.lds_count = &s_count;
-    ref.st = (ScanState *)st;
+    uint64_t *slot = (uint64_t *)(wq + slots_off) + (size_t)a * cap_b;
     for (int64_t base = lo; base < hi; base += 1024) {
-        const uint32_t thr = __hip_atomic_load(&st->thr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        float dist[4];
-        uint32_t bin[4];
+        uint32_t key[4], ord[4], id[4];
         bool pass[4], any = false;
+        keys_batch<KIND, QT, 4>(L, gtab, list_codes, base + threadIdx.x, 256, hi, key);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int64_t p = base + u * 256 + threadIdx.x;
-            const bool valid = p < hi;
-            const uint32_t key = valid ? key_at<KIND, QT>(L, gtab, list_codes, p) : 0u;
-            dist[u] = fmaf((float)key, fdelta, fdmin);
-            bin[u] = dist_bin(dist[u], blo, bscale);
-            pass[u] = valid && dist[u] <= thr0 && bin[u] <= thr;
+            const float dist = fmaf((float)(key[u] == 0xffffffffu ? 0u : key[u]), fdelta, fdmin);
+            ord[u] = qadc_f2ord(dist);
+            pass[u] = key[u] != 0xffffffffu && dist <= thr0;
             any = any || pass[u];
         }
         if (__ballot(any) != 0) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int64_t p = base + u * 256 + threadIdx.x;
-                const uint32_t id = pass[u] ? (uint32_t)list_ids[p] : 0u;
-                wave_append(pass[u], qadc_f2ord(dist[u]), id, bin[u], ref);
+                id[u] = pass[u] ? (uint32_t)list_ids[p] : 0u;
             }
-            uint32_t nb = wave_bound_from_hist(st->hist, (uint32_t)R);
-            if (__lane_id() == 0 && nb < thr) atomicMin(&st->thr, nb);
+            slot_append_multi<4>(pass, ord, id, slot, (uint32_t)cap_b, &s_count);
         }
     }
     __syncthreads();
-    if (threadIdx.x == 0) counts[a] = s_count < (uint32_t)cap_b ? s_count : (uint32_t)cap_b;
+    if (threadIdx.x == 0) counts[a] = s_count;  // uncapped: > cap_b tells k_ivf_final about the overflow
 }
 
 // ------------------------------------------------------------ k_ivf_final ---
@@ -393,39 +382,28 @@ k_ivf_final(const DevLayout *__restrict__ L, const float *__restrict__ cb,
             int cap_b, int32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t sh[8];
+    __shared__ uint32_t whist[16][256];
+    __shared__ uint32_t sh[32];
+    __shared__ uint32_t wsum[16];
+    __shared__ uint32_t off[MAX_G + 1];
     uint64_t *A = (uint64_t *)smem;  // FINAL_CAP entries
     const size_t q = blockIdx.x;
     char *wq = ws + q * per_query;
     IvfState *st = (IvfState *)wq;
     const uint32_t *counts = (const uint32_t *)(wq + counts_off);
     const uint64_t *slots = (const uint64_t *)(wq + slots_off);
-    if (threadIdx.x == 0) {
-        sh[0] = 0;
-        sh[1] = st->overflow;
-    }
-    __syncthreads();
-    const uint32_t thr = st->thr;
     const float blo = st->lo, bscale = st->scale;
-    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
-    const int nwaves = blockDim.x / QADC_WAVE;
-    for (int a = wave; a < nprobe; a += nwaves) {
-        const uint32_t cnt = counts[a];
-        for (uint32_t i = lane; i < cnt; i += QADC_WAVE) {
-            const uint64_t c = slots[(size_t)a * cap_b + i];
-            if (dist_bin(qadc_ord2f((uint32_t)(c >> 32)), blo, bscale) <= thr) {
-                uint32_t pos = atomicAdd(&sh[0], 1u);
-                if (pos < FINAL_CAP)
-                    A[pos] = c;
-                else
-                    sh[1] = 1u;
-            }
-        }
-    }
-    __syncthreads();
-    int na = (int)sh[0];
-    const bool slow = sh[1] != 0;
-    __syncthreads();
+    FinalShared S;
+    S.hist = hist;
+    S.whist = whist;
+    S.sh = sh;
+    S.wsum = wsum;
+    S.off = off;
+    int na = 0;
+    const bool slow = gather_select(
+        counts, slots, nprobe, cap_b, R,
+        [blo, bscale](uint64_t c) { return dist_bin(qadc_ord2f((uint32_t)(c >> 32)), blo, bscale); }, A,
+        S, na);
     if (slow) {
         IvfLds l;
         ivf_carve(L, smem + FINAL_CAP * 8, sizeof(QT), l);
@@ -452,7 +430,9 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
                       const uint8_t *list_codes, const int32_t *list_ids, const float *queries,
                       int nq, const int32_t *probe_ids, int nprobe, int K, int want, int R,
                       int32_t *out_ids, float *out_dist, char *ws, const IvfPlan &p, hipStream_t s) {
-    const size_t lds_calib = ivf_lds_bytes(idx->h, 2) + (size_t)want * 4;
+    int pilot_want = 4096 > 32 * R ? 4096 : 32 * R;
+    if (pilot_want < want) pilot_want = want;
+    const size_t lds_calib = ivf_lds_bytes(idx->h, 2) + (size_t)pilot_want * 4;
     const size_t lds_scan = ivf_lds_bytes(idx->h, sizeof(QT));
     const size_t lds_final = FINAL_CAP * 8 + lds_scan;
     int rc;
@@ -460,7 +440,7 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     if ((rc = allow_lds(k_ivf_scan<KIND, QT>, lds_scan)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_final<KIND, QT>, lds_final)) != PQ_OK) return rc;
     hipLaunchKernelGGL(k_ivf_calib, dim3(nq), dim3(256), lds_calib, s, idx->dev, idx->codebooks,
-                       coarse, list_offsets, list_codes, queries, probe_ids, nprobe, K, want, R, ws,
+                       coarse, list_offsets, list_codes, queries, probe_ids, nprobe, K, want, pilot_want, R, ws,
                        p.per_query);
     QADC_LAUNCH_CHECK("k_ivf_calib");
     hipLaunchKernelGGL((k_ivf_scan<KIND, QT>), dim3(nprobe, nq), dim3(256), lds_scan, s, idx->dev,

@@ -49,23 +49,11 @@ struct pq_index {
     int device;
 };
 
-// Per-query scratch state at the head of the scan workspace.
-struct ScanState {
-    uint32_t hist[256];  // candidates appended so far, per coarse key bin
-    uint32_t thr;        // current inclusive bin threshold
-    uint32_t overflow;   // a candidate slot overflowed: take the exact slow path
-    uint32_t pad[2];
-};
-
-// Per-query state of the inverted-list search; its head is laid out like ScanState.
+// Per-query state of the inverted-list search.
 struct IvfState {
-    uint32_t hist[256];  // candidates appended so far, per bin of the unquantized distance
-    uint32_t thr;        // current inclusive bin threshold
-    uint32_t overflow;
-    float dmax;          // calibration bound (Section 3.4) shared by the probed lists
-    float thr0;          // static bound on a result's distance from the calibration codes
-    float lo, scale;     // bin(dist) = min(255, (dist - lo) * scale), 0 below lo
-    uint32_t pad[2];
+    float dmax;        // calibration bound (Section 3.4) shared by the probed lists
+    float thr0;        // bound on a result's distance: R-th smallest among the pilot codes
+    float lo, scale;   // bin(dist) = min(255, (dist - lo) * scale), 0 below lo
 };
 
 struct IvfPlan {

@@ -19,9 +19,6 @@
 #include "scan_device.h"
 
 #define SCAN_THREADS 256
-#define MAX_G 4096
-#define FINAL_LPT (MAX_G / 1024)  // slot lists per k_final thread
-#define FINAL_REG 16  // candidates per thread kept in registers by k_final
 #ifndef QADC_U8
 #define QADC_U8 2
 #endif
@@ -33,49 +30,6 @@
 #endif
 constexpr int U8 = QADC_U8;  // 16-byte chunks per thread and tile, 8-byte codes
 constexpr int U5 = QADC_U5;  // 20-byte chunks per thread and tile, 5-byte codes
-
-// Append the lanes with `pass` set to the block's slot list.  Wave-uniform call.
-__device__ __forceinline__ void slot_append(bool pass, uint32_t key, uint32_t id, uint64_t *slot,
-                                            uint32_t cap, uint32_t *lds_count) {
-    const uint64_t mask = __ballot(pass);
-    if (mask == 0) return;
-    const int lane = __lane_id();
-    const int leader = __ffsll((unsigned long long)mask) - 1;
-    uint32_t base = 0;
-    if (lane == leader) base = atomicAdd(lds_count, (uint32_t)__popcll(mask));
-    base = __shfl(base, leader, QADC_WAVE);
-    if (pass) {
-        const uint32_t pos = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-        if (pos < cap) slot[pos] = ((uint64_t)key << 32) | (uint64_t)id;
-    }
-}
-
-// Append the (lane, slot) pairs with pass[u] set, NS slots per lane, to the block's list:
-// one LDS atomic per call, positions from ballots and lane-mask popcounts.  Wave-uniform
-// call.  The order within the list does not matter.
-template <int NS>
-__device__ __forceinline__ void slot_append_multi(const bool *pass, const uint32_t *key,
-                                                  const uint32_t *id, uint64_t *slot, uint32_t cap,
-                                                  uint32_t *lds_count) {
-    uint64_t m[NS];
-    uint32_t total = 0;
-#pragma unroll
-    for (int u = 0; u < NS; ++u) {
-        m[u] = __ballot(pass[u]);
-        total += (uint32_t)__popcll(m[u]);
-    }
-    if (total == 0) return;
-    const int lane = __lane_id();
-    uint32_t base = 0;
-    if (lane == 0) base = atomicAdd(lds_count, total);
-    base = __builtin_amdgcn_readfirstlane(base);
-#pragma unroll
-    for (int u = 0; u < NS; ++u) {
-        const uint32_t pos = base + (uint32_t)__popcll(m[u] & ((1ull << lane) - 1ull));
-        if (pass[u] && pos < cap) slot[pos] = ((uint64_t)key[u] << 32) | (uint64_t)id[u];
-        base += (uint32_t)__popcll(m[u]);
-    }
-}
 
 // ------------------------------------------------------------- k_prepare ---
 // One block per query: the query's group tables, written where k_scan blocks pick them up.
@@ -434,111 +388,16 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     o.keys = out_keys + q * R;
     o.dist = out_dist + q * R;
     const pq_qparams_t prm = qparams[q];
-    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
 
-    // exclusive prefix sum of the G per-block counts: FINAL_LPT consecutive lists per thread
-    uint32_t cnt[FINAL_LPT], mine = 0;
-    bool over = false;
-#pragma unroll
-    for (int l = 0; l < FINAL_LPT; ++l) {
-        const int list = FINAL_LPT * (int)threadIdx.x + l;
-        cnt[l] = list < G ? counts[list] : 0u;
-        over = over || cnt[l] > (uint32_t)cap_b;
-        mine += cnt[l];
-    }
-    for (int i = threadIdx.x; i < 16 * 256; i += blockDim.x) (&whist[0][0])[i] = 0;
-    const uint32_t incl = qadc_wave_incl_scan(mine);
-    if (lane == QADC_WAVE - 1) wsum[wave] = incl;
-    if (threadIdx.x == 0) {
-        sh[0] = 0;  // entries gathered into A
-        sh[1] = 0;  // slow-path flag
-    }
-    __syncthreads();
-    uint32_t wbase = 0, E = 0;
-    for (int w = 0; w < (int)(blockDim.x / QADC_WAVE); ++w) {
-        wbase += (w < wave) ? wsum[w] : 0u;
-        E += wsum[w];
-    }
-    {
-        uint32_t run = wbase + incl - mine;
-#pragma unroll
-        for (int l = 0; l < FINAL_LPT; ++l) {
-            const int list = FINAL_LPT * (int)threadIdx.x + l;
-            if (list < G) off[list] = run;
-            run += cnt[l];
-        }
-    }
-    if (threadIdx.x == 0) off[G] = E;
-    if (over) sh[1] = 1u;
-    __syncthreads();
-    const bool slow0 = sh[1] != 0;
-
+    FinalShared S;
+    S.hist = hist;
+    S.whist = whist;
+    S.sh = sh;
+    S.wsum = wsum;
+    S.off = off;
     int na = 0;
-    bool slow = slow0;
-    if (!slow0) {
-        // Candidates are dealt out evenly: thread t takes entries t, t+1024, ... of the
-        // concatenated slot lists, FINAL_REG at a time with all loads in flight together.
-        // pass 0: histogram of candidate key bins -> bin of the R-th key;
-        // pass 1: keep the candidates up to that bin.  When everything fits one batch
-        // the second pass reuses the registers of the first.
-        uint64_t c[FINAL_REG];
-        const bool single = E <= (uint32_t)(FINAL_REG * 1024);
-        uint32_t kbin = 255;
-        for (int pass = 0; pass < 2; ++pass) {
-            for (uint32_t base = 0; base < E; base += FINAL_REG * 1024) {
-                if (pass == 0 || !single) {
-                    // list of each entry: largest index with off[list] <= e, by a branch-free
-                    // binary search whose FINAL_REG chains run interleaved
-                    uint32_t pos[FINAL_REG];
-#pragma unroll
-                    for (int u = 0; u < FINAL_REG; ++u) pos[u] = 0;
-                    for (uint32_t s = MAX_G / 2; s >= 1; s >>= 1) {
-#pragma unroll
-                        for (int u = 0; u < FINAL_REG; ++u) {
-                            const uint32_t e = base + u * 1024 + threadIdx.x;
-                            const uint32_t idx = pos[u] + s;
-                            const uint32_t v = idx < (uint32_t)G ? off[idx] : 0xffffffffu;
-                            pos[u] = v <= e ? idx : pos[u];
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < FINAL_REG; ++u) {
-                        const uint32_t e = base + u * 1024 + threadIdx.x;
-                        c[u] = e < E ? slots[(size_t)pos[u] * cap_b + (e - off[pos[u]])] : ~0ull;
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < FINAL_REG; ++u) {
-                    const uint32_t e = base + u * 1024 + threadIdx.x;
-                    if (e >= E) continue;
-                    const uint32_t bin = ((uint32_t)(c[u] >> 32)) >> shift;
-                    if (pass == 0) {
-                        atomicAdd(&whist[wave][bin], 1u);
-                    } else if (bin <= kbin) {
-                        const uint32_t pos = atomicAdd(&sh[0], 1u);
-                        if (pos < FINAL_CAP) A[pos] = c[u]; else sh[1] = 1u;
-                    }
-                }
-            }
-            __syncthreads();
-            if (pass == 0) {
-                if (threadIdx.x < 256) {
-                    uint32_t t = 0;
-#pragma unroll
-                    for (int w = 0; w < 16; ++w) t += whist[w][threadIdx.x];
-                    hist[threadIdx.x] = t;
-                }
-                __syncthreads();
-                const uint32_t kk = E < (uint32_t)R ? E : (uint32_t)R;
-                if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, kk, 0u, sh + 4);
-                __syncthreads();
-                kbin = sh[4];
-            }
-        }
-        na = (int)sh[0];
-        slow = sh[1] != 0;
-        __syncthreads();
-    }
+    const bool slow = gather_select(counts, slots, G, cap_b, R,
+                                    [shift](uint64_t c) { return ((uint32_t)(c >> 32)) >> shift; }, A, S, na);
     if (slow) {
         stage_qtable<QT>((const QT *)qtables + q * L->T, L->T, qs);
         build_gtab<KIND, QT>(L, qs, gtab);

@@ -237,50 +237,175 @@ __device__ __forceinline__ void keys_batch(const DevLayout *L, const QT *gtab,
     }
 }
 
-// -------------------------------------------------------------- threshold --
-// Smallest bin x with hist[0..x] summing to >= R, or 0xffffffff.  One wave.
-__device__ inline uint32_t wave_bound_from_hist(const uint32_t *hist, uint32_t R) {
-    const int lane = __lane_id();
-    uint32_t h[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-        h[i] = __hip_atomic_load(&hist[4 * lane + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    uint32_t s = h[0] + h[1] + h[2] + h[3];
-    uint32_t run = qadc_wave_incl_scan(s) - s;
-    uint32_t mine = 0xffffffffu;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        run += h[i];
-        if (run >= R && mine == 0xffffffffu) mine = (uint32_t)(4 * lane + i);
-    }
-    return qadc_wave_min(mine);
-}
+// ------------------------------------------------------------ slot lists ---
+#define MAX_G 4096                 // slot lists per query a final kernel can gather
+#define FINAL_LPT (MAX_G / 1024)   // slot lists per thread of a 1024-thread final kernel
+#define FINAL_REG 16               // candidates per thread kept in registers
 
-struct SlotRef {
-    uint64_t *slot;
-    uint32_t cap;
-    uint32_t *lds_count;
-    ScanState *st;
-};
-
-// Append the lanes with `pass` set.  Wave-uniform call.
-__device__ __forceinline__ void wave_append(bool pass, uint32_t key, uint32_t id, uint32_t bin,
-                                            const SlotRef &r) {
+// Append the lanes with `pass` set to the block's slot list.  Wave-uniform call.
+__device__ __forceinline__ void slot_append(bool pass, uint32_t key, uint32_t id, uint64_t *slot,
+                                            uint32_t cap, uint32_t *lds_count) {
     const uint64_t mask = __ballot(pass);
     if (mask == 0) return;
     const int lane = __lane_id();
     const int leader = __ffsll((unsigned long long)mask) - 1;
     uint32_t base = 0;
-    if (lane == leader) base = atomicAdd(r.lds_count, (uint32_t)__popcll(mask));
+    if (lane == leader) base = atomicAdd(lds_count, (uint32_t)__popcll(mask));
     base = __shfl(base, leader, QADC_WAVE);
     if (pass) {
-        uint32_t pos = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-        if (pos < r.cap) {
-            r.slot[pos] = ((uint64_t)key << 32) | (uint64_t)id;
-            atomicAdd(&r.st->hist[bin], 1u);
-        } else {
-            r.st->overflow = 1u;
-        }
+        const uint32_t pos = base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+        if (pos < cap) slot[pos] = ((uint64_t)key << 32) | (uint64_t)id;
     }
 }
 
+// Append the (lane, slot) pairs with pass[u] set, NS slots per lane, to the block's list:
+// one LDS atomic per call, positions from ballots and lane-mask popcounts.  Wave-uniform
+// call.  The order within the list does not matter.
+template <int NS>
+__device__ __forceinline__ void slot_append_multi(const bool *pass, const uint32_t *key,
+                                                  const uint32_t *id, uint64_t *slot, uint32_t cap,
+                                                  uint32_t *lds_count) {
+    uint64_t m[NS];
+    uint32_t total = 0;
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+        m[u] = __ballot(pass[u]);
+        total += (uint32_t)__popcll(m[u]);
+    }
+    if (total == 0) return;
+    const int lane = __lane_id();
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(lds_count, total);
+    base = __builtin_amdgcn_readfirstlane(base);
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+        const uint32_t pos = base + (uint32_t)__popcll(m[u] & ((1ull << lane) - 1ull));
+        if (pass[u] && pos < cap) slot[pos] = ((uint64_t)key[u] << 32) | (uint64_t)id[u];
+        base += (uint32_t)__popcll(m[u]);
+    }
+}
+
+
+struct FinalShared {
+    uint32_t *hist;            // [256]
+    uint32_t (*whist)[256];    // [16][256] per-wave histograms
+    uint32_t *sh;              // [32] scalars
+    uint32_t *wsum;            // [16]
+    uint32_t *off;             // [MAX_G + 1] exclusive prefix of the list lengths
+};
+
+// Block-wide (1024 threads): gather the candidates of G slot lists (counts[], slots[][cap_b]),
+// find the bin of the R-th smallest by histogram (binf maps a candidate to a bin 0..255 that
+// is monotone in its sort key) and leave the candidates up to that bin in A (at most
+// FINAL_CAP).  Returns true if a list overflowed or A would overflow: the caller must then
+// select exactly by other means.  na = entries in A.
+template <class BinF>
+__device__ inline bool gather_select(const uint32_t *__restrict__ counts,
+                                     const uint64_t *__restrict__ slots, int G, int cap_b, int R,
+                                     BinF binf, uint64_t *A, const FinalShared &S, int &na) {
+    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
+    // exclusive prefix sum of the G per-block counts: FINAL_LPT consecutive lists per thread
+    uint32_t cnt[FINAL_LPT], mine = 0;
+    bool over = false;
+#pragma unroll
+    for (int l = 0; l < FINAL_LPT; ++l) {
+        const int list = FINAL_LPT * (int)threadIdx.x + l;
+        cnt[l] = list < G ? counts[list] : 0u;
+        over = over || cnt[l] > (uint32_t)cap_b;
+        mine += cnt[l];
+    }
+    for (int i = threadIdx.x; i < 16 * 256; i += blockDim.x) (&S.whist[0][0])[i] = 0;
+    const uint32_t incl = qadc_wave_incl_scan(mine);
+    if (lane == QADC_WAVE - 1) S.wsum[wave] = incl;
+    if (threadIdx.x == 0) {
+        S.sh[0] = 0;  // entries gathered into A
+        S.sh[1] = 0;  // slow-path flag
+    }
+    __syncthreads();
+    uint32_t wbase = 0, E = 0;
+    for (int w = 0; w < (int)(blockDim.x / QADC_WAVE); ++w) {
+        wbase += (w < wave) ? S.wsum[w] : 0u;
+        E += S.wsum[w];
+    }
+    {
+        uint32_t run = wbase + incl - mine;
+#pragma unroll
+        for (int l = 0; l < FINAL_LPT; ++l) {
+            const int list = FINAL_LPT * (int)threadIdx.x + l;
+            if (list < G) S.off[list] = run;
+            run += cnt[l];
+        }
+    }
+    if (threadIdx.x == 0) S.off[G] = E;
+    if (over) S.sh[1] = 1u;
+    __syncthreads();
+    const bool slow0 = S.sh[1] != 0;
+
+    na = 0;
+    bool slow = slow0;
+    if (!slow0) {
+        // Candidates are dealt out evenly: thread t takes entries t, t+1024, ... of the
+        // concatenated slot lists, FINAL_REG at a time with all loads in flight together.
+        // pass 0: histogram of candidate key bins -> bin of the R-th key;
+        // pass 1: keep the candidates up to that bin.  When everything fits one batch
+        // the second pass reuses the registers of the first.
+        uint64_t c[FINAL_REG];
+        const bool single = E <= (uint32_t)(FINAL_REG * 1024);
+        uint32_t kbin = 255;
+        for (int pass = 0; pass < 2; ++pass) {
+            for (uint32_t base = 0; base < E; base += FINAL_REG * 1024) {
+                if (pass == 0 || !single) {
+                    // list of each entry: largest index with S.off[list] <= e, by a branch-free
+                    // binary search whose FINAL_REG chains run interleaved
+                    uint32_t pos[FINAL_REG];
+#pragma unroll
+                    for (int u = 0; u < FINAL_REG; ++u) pos[u] = 0;
+                    for (uint32_t s = MAX_G / 2; s >= 1; s >>= 1) {
+#pragma unroll
+                        for (int u = 0; u < FINAL_REG; ++u) {
+                            const uint32_t e = base + u * 1024 + threadIdx.x;
+                            const uint32_t idx = pos[u] + s;
+                            const uint32_t v = idx < (uint32_t)G ? S.off[idx] : 0xffffffffu;
+                            pos[u] = v <= e ? idx : pos[u];
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < FINAL_REG; ++u) {
+                        const uint32_t e = base + u * 1024 + threadIdx.x;
+                        c[u] = e < E ? slots[(size_t)pos[u] * cap_b + (e - S.off[pos[u]])] : ~0ull;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < FINAL_REG; ++u) {
+                    const uint32_t e = base + u * 1024 + threadIdx.x;
+                    if (e >= E) continue;
+                    const uint32_t bin = binf(c[u]);
+                    if (pass == 0) {
+                        atomicAdd(&S.whist[wave][bin], 1u);
+                    } else if (bin <= kbin) {
+                        const uint32_t pos = atomicAdd(&S.sh[0], 1u);
+                        if (pos < FINAL_CAP) A[pos] = c[u]; else S.sh[1] = 1u;
+                    }
+                }
+            }
+            __syncthreads();
+            if (pass == 0) {
+                if (threadIdx.x < 256) {
+                    uint32_t t = 0;
+#pragma unroll
+                    for (int w = 0; w < 16; ++w) t += S.whist[w][threadIdx.x];
+                    S.hist[threadIdx.x] = t;
+                }
+                __syncthreads();
+                const uint32_t kk = E < (uint32_t)R ? E : (uint32_t)R;
+                if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(S.hist, kk, 0u, S.sh + 4);
+                __syncthreads();
+                kbin = S.sh[4];
+            }
+        }
+        na = (int)S.sh[0];
+        slow = S.sh[1] != 0;
+        __syncthreads();
+    }
+    return slow;
+}
