@@ -14,6 +14,7 @@
 // The result is defined as a sort by (key, id), so it does not depend on the
 // order in which blocks run.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "scan_device.h"
@@ -271,6 +272,127 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     if (threadIdx.x == 0) counts[b] = s_count;  // uncapped: > cap_b tells k_final about the overflow
 }
 
+// -------------------------------------------------------------- k_scan_mq ---
+// Four queries per pass over the codes (m x 4 layouts with 8-bit tables).  The four
+// queries' byte-indexed group tables are interleaved in LDS as one 8-byte entry
+// {u16 q0, u16 q1, u16 q2, u16 q3}, so one ds_read_b64 serves four queries and two plain
+// 32-bit adds accumulate them (eight or sixteen addends of at most 255 cannot carry out
+// of a 16-bit field).  Code bytes are loaded and split into indices once for all four.
+// NG = groups per code (8: 64-bit codes, 16: 128-bit codes).
+#define MQ 4
+template <int NG>
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__restrict__ codes,
+          int64_t n, char *__restrict__ ws, size_t per_query, size_t slots_off, size_t gtab_off,
+          int cap_b, uint32_t qmax) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint2 *tab = (uint2 *)smem;  // [NG][256]
+    __shared__ uint32_t s_count[MQ];
+    const int q0 = blockIdx.y * MQ;
+    const int b = blockIdx.x, G = gridDim.x;
+    uint32_t thr[MQ];
+    uint64_t *slot[MQ];
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) {
+        const bool have = q0 + j < nq;
+        const size_t q = have ? q0 + j : q0;
+        uint32_t t = qparams[q].key_bound;
+        thr[j] = t > qmax ? qmax : t;
+        slot[j] = (uint64_t *)(ws + q * per_query + slots_off) + (size_t)b * cap_b;
+    }
+    if (threadIdx.x < MQ) s_count[threadIdx.x] = 0;
+    // interleave the four prepared tables: thread handles 4 consecutive entries at a time
+    for (int w = threadIdx.x; w < NG * 64; w += SCAN_THREADS) {
+        uint32_t v[MQ];
+#pragma unroll
+        for (int j = 0; j < MQ; ++j) {
+            const size_t q = (q0 + j < nq) ? q0 + j : q0;
+            v[j] = ((const uint32_t *)(ws + q * per_query + gtab_off))[w];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint2 e;
+            e.x = ((v[0] >> (8 * i)) & 255u) | (((v[1] >> (8 * i)) & 255u) << 16);
+            e.y = ((v[2] >> (8 * i)) & 255u) | (((v[3] >> (8 * i)) & 255u) << 16);
+            tab[4 * w + i] = e;
+        }
+    }
+    __syncthreads();
+
+    constexpr int CPC = NG == 8 ? 2 : 1;  // codes per 16-byte chunk
+    constexpr int U = 2;                  // chunks per thread and tile
+    const int64_t nfull = NG == 8 ? (n >> 1) : n;
+    const int64_t ntiles = (nfull + U * SCAN_THREADS - 1) / (U * SCAN_THREADS);
+    const uint4 *__restrict__ p = (const uint4 *)codes;
+    for (int64_t tile = b; tile < ntiles; tile += G) {
+        uint4 cur[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+            cur[u] = c < nfull ? p[c] : make_uint4(0, 0, 0, 0);
+        }
+        uint32_t sum[MQ][U * CPC], id[U * CPC];
+        bool ok[U * CPC];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+            const uint32_t w[4] = {cur[u].x, cur[u].y, cur[u].z, cur[u].w};
+#pragma unroll
+            for (int k = 0; k < CPC; ++k) {
+                uint32_t lo = 0, hi = 0;
+#pragma unroll
+                for (int g = 0; g < NG; ++g) {
+                    const uint32_t word = w[(NG == 8 ? 2 * k : 0) + (g >> 2)];
+                    const uint32_t byte = (word >> (8 * (g & 3))) & 255u;
+                    const uint2 e = tab[g * 256 + byte];
+                    lo += e.x;
+                    hi += e.y;
+                }
+                const int sidx = u * CPC + k;
+                sum[0][sidx] = lo & 0xffffu;
+                sum[1][sidx] = lo >> 16;
+                sum[2][sidx] = hi & 0xffffu;
+                sum[3][sidx] = hi >> 16;
+                id[sidx] = (uint32_t)(CPC * c + k);
+                ok[sidx] = c < nfull;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < MQ; ++j) {
+            bool pass[U * CPC], any = false;
+#pragma unroll
+            for (int i = 0; i < U * CPC; ++i) {
+                pass[i] = ok[i] && sum[j][i] <= thr[j] && (q0 + j < nq);
+                any = any || pass[i];
+            }
+            if (__ballot(any) != 0)
+                slot_append_multi<U * CPC>(pass, sum[j], id, slot[j], (uint32_t)cap_b, &s_count[j]);
+        }
+    }
+    if (NG == 8 && (n & 1) && b == 0 && threadIdx.x < QADC_WAVE) {  // the odd last 64-bit code
+        const bool me = threadIdx.x == 0;
+        uint32_t lo = 0, hi = 0;
+        if (me) {
+            const uint2 w = *(const uint2 *)(codes + (n - 1) * 8);
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                const uint32_t byte = ((g < 4 ? w.x : w.y) >> (8 * (g & 3))) & 255u;
+                const uint2 e = tab[g * 256 + byte];
+                lo += e.x;
+                hi += e.y;
+            }
+        }
+        const uint32_t sj[MQ] = {lo & 0xffffu, lo >> 16, hi & 0xffffu, hi >> 16};
+#pragma unroll
+        for (int j = 0; j < MQ; ++j)
+            slot_append(me && (q0 + j < nq) && sj[j] <= thr[j], sj[j], (uint32_t)(n - 1), slot[j],
+                        (uint32_t)cap_b, &s_count[j]);
+    }
+    __syncthreads();
+    if (threadIdx.x < MQ && q0 + (int)threadIdx.x < nq)
+        ((uint32_t *)(ws + (size_t)(q0 + threadIdx.x) * per_query))[b] = s_count[threadIdx.x];
+}
+
 // --------------------------------------------------------------- k_final ---
 struct FinalOut {
     int32_t *ids;
@@ -421,7 +543,20 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
                            idx->dev, qtables, ws, p.per_query, p.gtab_off);
         QADC_LAUNCH_CHECK("k_prepare");
     }
-    if (what & 1) {
+    if ((what & 1) && sizeof(QT) == 1 && nq >= 2 && (KIND == SCAN_NIB8 || KIND == SCAN_NIB16) &&
+        !getenv("QADC_NO_MQ")) {
+        // several queries: four of them share every pass over the codes
+        const int groups = (nq + MQ - 1) / MQ;
+        if (KIND == SCAN_NIB8)
+            hipLaunchKernelGGL((k_scan_mq<8>), dim3(p.G, groups), dim3(SCAN_THREADS), 8 * 256 * 8, s,
+                               qparams, nq, codes, n, ws, p.per_query, p.slots_off, p.gtab_off,
+                               p.cap_b, (uint32_t)h.qmax);
+        else
+            hipLaunchKernelGGL((k_scan_mq<16>), dim3(p.G, groups), dim3(SCAN_THREADS), 16 * 256 * 8, s,
+                               qparams, nq, codes, n, ws, p.per_query, p.slots_off, p.gtab_off,
+                               p.cap_b, (uint32_t)h.qmax);
+        QADC_LAUNCH_CHECK("k_scan_mq");
+    } else if (what & 1) {
         GroupDesc gd;
         memset(&gd, 0, sizeof(gd));
         gd.ng = h.ng;
