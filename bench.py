@@ -35,7 +35,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=4000)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--batch", type=int, default=1, help="queries per step")
-    ap.add_argument("--streams", type=int, default=4, help="HIP streams the steps rotate over")
+    ap.add_argument("--streams", type=int, default=32, help="HIP streams the steps rotate over")
+    ap.add_argument("--hw-queues", type=int, default=16,
+                    help="hardware queues the HIP runtime may use for this process "
+                         "(GPU_MAX_HW_QUEUES); streams beyond it share queues")
     ap.add_argument("--unfused", action="store_true",
                     help="issue pq_compute_tables, pq_quantize_tables and pq_adc_scan_topk as three "
                          "calls instead of the fused pq_search_topk (same arithmetic)")
@@ -180,6 +183,9 @@ def main():
         print("bench.py: this build is single-GPU; run with --gpus 1 (multi-GPU sharding is a "
               "design note only, no collective code exists)", file=sys.stderr)
         sys.exit(2)
+    # must be in the environment before the HIP runtime starts: independent requests only
+    # overlap on the GPU when their streams sit on different hardware queues
+    os.environ["GPU_MAX_HW_QUEUES"] = str(max(1, min(a.hw_queues, 32)))
     import numpy as np
     import torch
     from paper_1812_09162_amd import binding as qb, synth
@@ -253,7 +259,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{a.workload}: exhaustive ADC, N={n}, d={lay.d}, m={lay.m}, "
                                f"bits={sorted(set(lay.nbits))}, code_bytes={cs}, R={a.R}, t=400, "
-                               f"batch={a.batch}, streams={a.streams}, entry={entry}",
+                               f"batch={a.batch}, streams={a.streams}, hw_queues={a.hw_queues}, entry={entry}",
                    "seed": cfg["seed"], "dataset_build_s": round(t_build, 2)},
         "whole_path_hbm_gbs": codes_per_s * cs / 1e9,
         "host_issue_ms_per_step": run.issue_s / a.steps * 1e3,
