@@ -131,7 +131,7 @@ class Runner:
         return b["ids"].cpu().numpy(), b["keys"].cpu().numpy(), b["dist"].cpu().numpy()
 
 
-def scan_kernel_time(qb, idx, queries, codes, batch, R, nsamples=12, reps=25, t=400):
+def scan_kernel_time(qb, idx, queries, codes, batch, R, nsamples=8, reps=200, t=400):
     """Average duration of one scan-kernel launch: `reps` back-to-back launches between two
     HIP events on the launching stream, for `nsamples` different query batches."""
     import torch

@@ -148,7 +148,7 @@ ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R) {
     // A single query gets several times more blocks than fit on the chip at once: blocks
     // start cheaply (their tables are prepared beforehand) and the hardware hands the
     // next block to whichever compute unit finishes first, which evens out the tail.
-    static const int64_t g1 = getenv("QADC_G") ? atoll(getenv("QADC_G")) : 1024;
+    static const int64_t g1 = getenv("QADC_G") ? atoll(getenv("QADC_G")) : 2048;
     int64_t gmax = 32768 / (nq > 0 ? nq : 1);
     if (gmax < 64) gmax = 64;
     if (gmax > g1) gmax = g1;

@@ -19,12 +19,11 @@
 
 #include "scan_device.h"
 
+#ifndef SCAN_THREADS
 #define SCAN_THREADS 256
+#endif
 #ifndef QADC_U8
 #define QADC_U8 2
-#endif
-#ifndef QADC_DBUF
-#define QADC_DBUF 0  // 1: prefetch the next tile while looking up the current one (measured slower)
 #endif
 #ifndef QADC_U5
 #define QADC_U5 2
@@ -57,12 +56,14 @@ __device__ __forceinline__ void load_gtab(const char *__restrict__ src, int gtab
 }
 
 // ---------------------------------------------------------------- k_scan ---
-template <int KIND, typename QT>
+// NG > 0: the layout has NG groups, none crossing a dword boundary of the code (8-byte and
+// 5-byte kinds only); NG == 0: group descriptors are read from the layout.
+template <int KIND, typename QT, int NG>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
        const pq_qparams_t *__restrict__ qparams, const uint8_t *__restrict__ codes, int64_t n,
        char *__restrict__ ws, size_t per_query, size_t slots_off, size_t gtab_off, int cap_b,
-       int gtab_len, uint32_t qmax, int g32ok, GroupDesc gd) {
+       int gtab_len, uint32_t qmax, GroupDesc gd) {
     extern __shared__ __align__(16) unsigned char smem[];
     QT *gtab = (QT *)smem;
     __shared__ uint32_t s_count;
@@ -75,41 +76,27 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     uint32_t thr = qparams[q].key_bound;
     thr = thr > qmax ? qmax : thr;
     if (threadIdx.x == 0) s_count = 0;
-    // fast field extraction: at most eight groups, none crossing a dword boundary
-    const bool g32 = g32ok != 0;
+    constexpr bool g32 = NG > 0;
 
     if (KIND == SCAN_NIB8 || KIND == SCAN_W64) {
-        // 16-byte chunks of two codes, U8 chunks per thread and tile, double-buffered so that
-        // 2*U8*16 bytes per lane are in flight; an odd last code is handled after the loop
+        // 16-byte chunks of two codes, U8 chunks per thread and tile (U8*16 bytes per lane in
+        // flight); an odd last code is handled after the loop
         constexpr int U = U8;
         const int64_t nfull = n >> 1;
         const int64_t ntiles = (nfull + U * SCAN_THREADS - 1) / (U * SCAN_THREADS);
         const uint4 *__restrict__ p = (const uint4 *)codes;
-        uint4 cur[U], nxt[U];
+        uint4 cur[U];
         int64_t tile = b;
-        if (QADC_DBUF) {
+        auto load_tile = [&](int64_t t) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
-                cur[u] = (tile < ntiles && c < nfull) ? p[c] : make_uint4(0, 0, 0, 0);
+                const int64_t c = t * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                cur[u] = (t < ntiles && c < nfull) ? p[c] : make_uint4(0, 0, 0, 0);
             }
-        }
+        };
+        load_tile(tile);  // the first tile is in flight while the tables are staged
         load_gtab<QT>(gsrc, gtab_len, gtab);
-        for (; tile < ntiles; tile += G) {
-            if (QADC_DBUF) {
-                const int64_t tn = tile + G;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int64_t c = tn * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
-                    nxt[u] = (tn < ntiles && c < nfull) ? p[c] : make_uint4(0, 0, 0, 0);
-                }
-            } else {
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int64_t c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
-                    cur[u] = c < nfull ? p[c] : make_uint4(0, 0, 0, 0);
-                }
-            }
+        while (tile < ntiles) {
             uint32_t s[2 * U];
             bool pass[2 * U], any = false;
 #pragma unroll
@@ -119,8 +106,8 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                     s[2 * u] = sum8(gtab, cur[u].x, cur[u].y);
                     s[2 * u + 1] = sum8(gtab, cur[u].z, cur[u].w);
                 } else if (g32) {
-                    s[2 * u] = sum_groups_desc(gd, gtab, cur[u].x, cur[u].y);
-                    s[2 * u + 1] = sum_groups_desc(gd, gtab, cur[u].z, cur[u].w);
+                    s[2 * u] = sum_groups_desc<NG>(gd, gtab, cur[u].x, cur[u].y);
+                    s[2 * u + 1] = sum_groups_desc<NG>(gd, gtab, cur[u].z, cur[u].w);
                 } else {
                     s[2 * u] = sum_groups64(L, gtab, ((uint64_t)cur[u].y << 32) | cur[u].x);
                     s[2 * u + 1] = sum_groups64(L, gtab, ((uint64_t)cur[u].w << 32) | cur[u].z);
@@ -138,10 +125,8 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 }
                 slot_append_multi<2 * U>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
             }
-            if (QADC_DBUF) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) cur[u] = nxt[u];
-            }
+            tile += G;
+            if (tile < ntiles) load_tile(tile);
         }
         if ((n & 1) && b == 0) {  // the odd last code, by one wave of block 0
             if (threadIdx.x < QADC_WAVE) {
@@ -157,27 +142,24 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         }
     } else if (KIND == SCAN_C5) {
         // 20-byte chunks of four 5-byte codes: five dwords per lane, U5 chunks per thread and
-        // tile, double-buffered; the last n % 4 codes are handled after the loop
+        // tile; the last n % 4 codes are handled after the loop
         constexpr int U = U5;
         const int64_t nfull = n >> 2;
         const int64_t ntiles = (nfull + U * SCAN_THREADS - 1) / (U * SCAN_THREADS);
         const uint32_t *__restrict__ p = (const uint32_t *)codes;
-        uint32_t cur[U][5], nxt[U][5];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t c = (int64_t)b * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
-#pragma unroll
-            for (int i = 0; i < 5; ++i) cur[u][i] = (b < ntiles && c < nfull) ? p[c * 5 + i] : 0u;
-        }
-        load_gtab<QT>(gsrc, gtab_len, gtab);
-        for (int64_t tile = b; tile < ntiles; tile += G) {
-            const int64_t tn = tile + G;
+        uint32_t cur[U][5];
+        int64_t tile = b;
+        auto load_tile = [&](int64_t t) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t c = tn * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                const int64_t c = t * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
 #pragma unroll
-                for (int i = 0; i < 5; ++i) nxt[u][i] = (tn < ntiles && c < nfull) ? p[c * 5 + i] : 0u;
+                for (int i = 0; i < 5; ++i) cur[u][i] = (t < ntiles && c < nfull) ? p[c * 5 + i] : 0u;
             }
+        };
+        load_tile(tile);  // the first tile is in flight while the tables are staged
+        load_gtab<QT>(gsrc, gtab_len, gtab);
+        while (tile < ntiles) {
             uint32_t s[4 * U];
             bool pass[4 * U], any = false;
 #pragma unroll
@@ -195,7 +177,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 hi[3] = cur[u][4] >> 24;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    s[4 * u + v] = g32 ? sum_groups_desc(gd, gtab, lo[v], hi[v])
+                    s[4 * u + v] = g32 ? sum_groups_desc<NG>(gd, gtab, lo[v], hi[v])
                                        : sum_groups64(L, gtab, ((uint64_t)hi[v] << 32) | lo[v]);
                     pass[4 * u + v] = (c < nfull) && s[4 * u + v] <= thr;
                     any = any || pass[4 * u + v];
@@ -210,10 +192,8 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 }
                 slot_append_multi<4 * U>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
             }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int i = 0; i < 5; ++i) cur[u][i] = nxt[u][i];
+            tile += G;
+            if (tile < ntiles) load_tile(tile);
         }
         if ((n & 3) && b == 0 && threadIdx.x < QADC_WAVE) {  // the last n % 4 codes
             const int64_t id = (nfull << 2) + threadIdx.x;
@@ -223,28 +203,21 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         }
     } else {
         const int64_t ntiles = (n + 4 * SCAN_THREADS - 1) / (4 * SCAN_THREADS);
-        if (KIND != SCAN_NIB16) load_gtab<QT>(gsrc, gtab_len, gtab);
         uint4 cur[4];
-        if (KIND == SCAN_NIB16) {
+        int64_t tile = b;
+        auto load_tile = [&](int64_t t) {
+            if (KIND != SCAN_NIB16) return;  // other layouts read their codes byte by byte
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int64_t c = (int64_t)b * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
-                cur[u] = c < n ? ((const uint4 *)codes)[c] : make_uint4(0, 0, 0, 0);
+                const int64_t c = t * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                cur[u] = (t < ntiles && c < n) ? ((const uint4 *)codes)[c] : make_uint4(0, 0, 0, 0);
             }
-            load_gtab<QT>(gsrc, gtab_len, gtab);
-        }
-        for (int64_t tile = b; tile < ntiles; tile += G) {
+        };
+        load_tile(tile);  // the first tile is in flight while the tables are staged
+        load_gtab<QT>(gsrc, gtab_len, gtab);
+        while (tile < ntiles) {
             uint32_t s[4];
             bool pass[4], any = false;
-            uint4 nxt[4];
-            if (KIND == SCAN_NIB16) {
-                const int64_t tn = tile + G;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int64_t c = tn * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
-                    nxt[u] = (tn < ntiles && c < n) ? ((const uint4 *)codes)[c] : make_uint4(0, 0, 0, 0);
-                }
-            }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int64_t c = tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
@@ -262,10 +235,8 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                     id[u] = (uint32_t)(tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x);
                 slot_append_multi<4>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
             }
-            if (KIND == SCAN_NIB16) {
-#pragma unroll
-                for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
-            }
+            tile += G;
+            if (tile < ntiles) load_tile(tile);
         }
     }
     __syncthreads();
@@ -518,7 +489,7 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     S.wsum = wsum;
     S.off = off;
     int na = 0;
-    const bool slow = gather_select(counts, slots, G, cap_b, R,
+    const bool slow = gather_select_rows(counts, slots, G, cap_b, R,
                                     [shift](uint64_t c) { return ((uint32_t)(c >> 32)) >> shift; }, A, S, na);
     if (slow) {
         stage_qtable<QT>((const QT *)qtables + q * L->T, L->T, qs);
@@ -565,10 +536,28 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
             gd.w[g] = h.gw[g];
             gd.base[g] = h.gbase[g];
         }
-        const int g32 = h.g32ok != 0 && h.ng <= QADC_MAXG_FAST;
-        hipLaunchKernelGGL((k_scan<KIND, QT>), dim3(p.G, nq), dim3(SCAN_THREADS), gtab_bytes, s,
-                           idx->dev, qtables, qparams, codes, n, ws, p.per_query, p.slots_off,
-                           p.gtab_off, p.cap_b, h.gtab_len, (uint32_t)h.qmax, g32, gd);
+        const bool fast = (KIND == SCAN_W64 || KIND == SCAN_C5) && h.g32ok != 0 && h.ng >= 1 &&
+                          h.ng <= QADC_MAXG_FAST;
+#define QADC_SCAN_NG(NGV)                                                                          \
+    hipLaunchKernelGGL((k_scan<KIND, QT, NGV>), dim3(p.G, nq), dim3(SCAN_THREADS), gtab_bytes, s, \
+                       idx->dev, qtables, qparams, codes, n, ws, p.per_query, p.slots_off,        \
+                       p.gtab_off, p.cap_b, h.gtab_len, (uint32_t)h.qmax, gd)
+        if (KIND == SCAN_W64 || KIND == SCAN_C5) {
+            switch (fast ? h.ng : 0) {
+                case 1: QADC_SCAN_NG(1); break;
+                case 2: QADC_SCAN_NG(2); break;
+                case 3: QADC_SCAN_NG(3); break;
+                case 4: QADC_SCAN_NG(4); break;
+                case 5: QADC_SCAN_NG(5); break;
+                case 6: QADC_SCAN_NG(6); break;
+                case 7: QADC_SCAN_NG(7); break;
+                case 8: QADC_SCAN_NG(8); break;
+                default: QADC_SCAN_NG(0); break;
+            }
+        } else {
+            QADC_SCAN_NG(0);
+        }
+#undef QADC_SCAN_NG
         QADC_LAUNCH_CHECK("k_scan");
     }
     if (!(what & 2)) return PQ_OK;

@@ -138,17 +138,16 @@ __device__ __forceinline__ GroupDesc load_group_desc(const DevLayout *L) {
     }
     return d;
 }
-// code of at most 64 bits as two dwords, no group crossing the dword boundary
-template <typename QT>
+// code of at most 64 bits as two dwords, no group crossing the dword boundary; NG = number
+// of groups, fixed at compile time so that all lookups of a code are issued together
+template <int NG, typename QT>
 __device__ __forceinline__ uint32_t sum_groups_desc(const GroupDesc &d, const QT *gtab, uint32_t lo,
                                                     uint32_t hi) {
     uint32_t s = 0;
 #pragma unroll
-    for (int g = 0; g < QADC_MAXG_FAST; ++g) {
-        if (g < d.ng) {
-            const uint32_t x = d.off[g] >= 32 ? hi : lo;
-            s += gtab[d.base[g] + __builtin_amdgcn_ubfe(x, (uint32_t)(d.off[g] & 31), (uint32_t)d.w[g])];
-        }
+    for (int g = 0; g < NG; ++g) {
+        const uint32_t x = d.off[g] >= 32 ? hi : lo;
+        s += gtab[d.base[g] + __builtin_amdgcn_ubfe(x, (uint32_t)(d.off[g] & 31), (uint32_t)d.w[g])];
     }
     return s;
 }
@@ -407,5 +406,123 @@ __device__ inline bool gather_select(const uint32_t *__restrict__ counts,
         slow = S.sh[1] != 0;
         __syncthreads();
     }
+    return slow;
+}// Block-wide (1024 threads), for many short slot lists (the exhaustive scan leaves one list
+// per scan block, a dozen entries each): same contract as gather_select.  ROWS_W adjacent
+// threads read the first ROWS_W entries of a list (consecutive 128-byte lines), each thread
+// serving ROWS_KU lists, so that all loads of the common case, the list lengths included,
+// are independent and in flight together; longer lists take extra rounds.  Entries beyond a
+// list's length are loaded and ignored, which needs cap_b >= ROWS_W.
+#define ROWS_W 32   // entries of a list read per round
+#define ROWS_KU 32  // lists per thread and batch
+template <class BinF>
+__device__ inline bool gather_select_rows(const uint32_t *__restrict__ counts,
+                                          const uint64_t *__restrict__ slots, int G, int cap_b,
+                                          int R, BinF binf, uint64_t *A, const FinalShared &S,
+                                          int &na) {
+    constexpr int LP = 1024 / ROWS_W;  // lists per batch row
+    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
+    const int sub = threadIdx.x % ROWS_W, row = threadIdx.x / ROWS_W;
+    for (int i = threadIdx.x; i < 16 * 256; i += blockDim.x) (&S.whist[0][0])[i] = 0;
+    if (threadIdx.x < 8) S.sh[threadIdx.x] = 0;  // 0: entries in A, 1: slow flag, 2: candidates
+    __syncthreads();
+    const bool single = G <= LP * ROWS_KU;  // one batch: pass 1 reuses the registers of pass 0
+    uint32_t kbin = 255;
+    uint64_t c[ROWS_KU];
+    uint32_t valid = 0;   // bit u: c[u] is an entry of its list
+    uint32_t longer = 0;  // bit u: list u of this thread has more than ROWS_W entries
+    for (int pass = 0; pass < 2; ++pass) {
+        uint32_t mine = 0;
+        bool over = false;
+        for (int kb = 0; kb < G; kb += LP * ROWS_KU) {
+            if (pass == 0 || !single) {
+                uint32_t cnt[ROWS_KU];
+#pragma unroll
+                for (int u = 0; u < ROWS_KU; ++u) {
+                    const int list = kb + row + LP * u;
+                    const bool have = list < G;
+                    cnt[u] = have ? counts[list] : 0u;
+                    c[u] = have ? slots[(size_t)list * cap_b + sub] : ~0ull;
+                }
+                valid = 0;
+                longer = 0;
+#pragma unroll
+                for (int u = 0; u < ROWS_KU; ++u) {
+                    valid |= ((uint32_t)sub < cnt[u] ? 1u : 0u) << u;
+                    longer |= (cnt[u] > (uint32_t)ROWS_W ? 1u : 0u) << u;
+                    if (pass == 0 && sub == 0) {
+                        mine += cnt[u];
+                        over = over || cnt[u] > (uint32_t)cap_b;
+                    }
+                }
+            }
+            if (pass == 0) {
+#pragma unroll
+                for (int u = 0; u < ROWS_KU; ++u)
+                    if ((valid >> u) & 1u) atomicAdd(&S.whist[wave][binf(c[u])], 1u);
+            } else {
+                // keep the candidates up to the bin of the R-th: one LDS atomic per wave
+                uint32_t keep = 0, total = 0;
+#pragma unroll
+                for (int u = 0; u < ROWS_KU; ++u)
+                    keep |= ((((valid >> u) & 1u) != 0 && binf(c[u]) <= kbin) ? 1u : 0u) << u;
+#pragma unroll
+                for (int u = 0; u < ROWS_KU; ++u) total += (uint32_t)__popcll(__ballot((keep >> u) & 1u));
+                if (total != 0) {
+                    uint32_t base = 0;
+                    if (lane == 0) base = atomicAdd(&S.sh[0], total);
+                    base = __builtin_amdgcn_readfirstlane(base);
+                    if (base + total > FINAL_CAP && lane == 0) S.sh[1] = 1u;
+#pragma unroll
+                    for (int u = 0; u < ROWS_KU; ++u) {
+                        const uint64_t m = __ballot((keep >> u) & 1u);
+                        const uint32_t pos = base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+                        if (((keep >> u) & 1u) && pos < FINAL_CAP) A[pos] = c[u];
+                        base += (uint32_t)__popcll(m);
+                    }
+                }
+            }
+            // lists longer than one round (rare): entry by entry
+            for (uint32_t rest = longer; rest != 0; rest &= rest - 1) {
+                const int u = __ffs(rest) - 1;
+                const int list = kb + row + LP * u;
+                uint32_t lim = counts[list];
+                lim = lim > (uint32_t)cap_b ? (uint32_t)cap_b : lim;
+                for (uint32_t r = ROWS_W + sub; r < lim; r += ROWS_W) {
+                    const uint64_t e = slots[(size_t)list * cap_b + r];
+                    const uint32_t bin = binf(e);
+                    if (pass == 0) {
+                        atomicAdd(&S.whist[wave][bin], 1u);
+                    } else if (bin <= kbin) {
+                        const uint32_t pos = atomicAdd(&S.sh[0], 1u);
+                        if (pos < FINAL_CAP) A[pos] = e; else S.sh[1] = 1u;
+                    }
+                }
+            }
+        }
+        if (pass == 0) {
+            if (over) S.sh[1] = 1u;
+            if (mine) atomicAdd(&S.sh[2], mine);
+        }
+        __syncthreads();
+        if (S.sh[1] != 0) break;
+        if (pass == 0) {
+            if (threadIdx.x < 256) {
+                uint32_t t = 0;
+#pragma unroll
+                for (int w = 0; w < 16; ++w) t += S.whist[w][threadIdx.x];
+                S.hist[threadIdx.x] = t;
+            }
+            __syncthreads();
+            const uint32_t E = S.sh[2];
+            const uint32_t kk = E < (uint32_t)R ? E : (uint32_t)R;
+            if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(S.hist, kk, 0u, S.sh + 4);
+            __syncthreads();
+            kbin = S.sh[4];
+        }
+    }
+    const bool slow = S.sh[1] != 0;
+    na = slow ? 0 : (int)S.sh[0];
+    __syncthreads();
     return slow;
 }
