@@ -174,7 +174,17 @@ ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R) {
     p.per_query = p.slots_off + (size_t)p.G * (size_t)p.cap_b * sizeof(uint64_t);
     p.per_query = align_up(p.per_query, 256);
     p.total = p.per_query * (size_t)(nq > 0 ? nq : 0);
+    p.logw = qadc_rows_logw(n, p.G, R, 65536);
     return p;
+}
+
+// Slot-list entries the selection kernel reads per list and round (as a power of two): about
+// twice the candidates a scan block is expected to keep when the bound came from a pilot of
+// `pilot` codes, within [4, 32].
+int qadc_rows_logw(int64_t n, int G, int R, int64_t pilot) {
+    if (pilot < 1) pilot = 1;
+    const double est = (double)(n / (G > 0 ? G : 1) + 1) * (double)R / (double)pilot;
+    return est <= 1.5 ? 2 : (est <= 3.0 ? 3 : (est <= 7.0 ? 4 : 5));
 }
 
 IvfPlan qadc_ivf_plan(const pq_index *idx, int nq, int nprobe, int R) {

@@ -72,16 +72,28 @@ struct ScanPlan {
     size_t state_off, counts_off, slots_off;
     size_t gtab_off;   // prepared group tables of the query (gtab_len entries)
     size_t total;
+    int logw;     // log2 of the slot-list entries the selection kernel reads per round
 };
 
 void qadc_set_error(const char *fmt, ...);
 ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R);
+int qadc_rows_logw(int64_t n, int G, int R, int64_t pilot);
 
-// gtab_out: if non-null, query q's group tables are also written to gtab_out + q*gtab_stride bytes
+// Pilot of the distance quantizer: `pilot` codes, counted by P blocks per query, `slice` each.
+struct PilotPlan {
+    int pilot, P, slice;
+};
+int qadc_pilot_blocks_max(int nq);
+size_t qadc_pilot_scratch_bytes(int nq);
+PilotPlan qadc_pilot_plan(int nq, int64_t n, int t_eff, int R, bool have_scratch);
+
+// gtab_out: if non-null, query q's group tables are also written to gtab_out + q*gtab_stride bytes.
+// scratch: null, or qadc_pilot_scratch_bytes(nq) bytes (256-byte aligned, any contents) that let
+// several blocks share a query's pilot.  pilot_used: if non-null, receives the pilot size.
 int qadc_quantize_launch(const pq_index *idx, const float *queries, const float *tables_in,
                          float *tables_out, int nq, const uint8_t *codes, int64_t n, int t, int R,
                          void *qtables, pq_qparams_t *qparams, char *gtab_out, size_t gtab_stride,
-                         hipStream_t s);
+                         char *scratch, int *pilot_used, hipStream_t s);
 
 
 #define QADC_HIP_TRY(expr)                                                        \

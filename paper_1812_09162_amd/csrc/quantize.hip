@@ -1,18 +1,47 @@
 // pq_quantize_tables: the query-time distance quantizer of Section 3.4.
 #include <math.h>
 #include <stdlib.h>
+#include <time.h>
+#include <unistd.h>
+
 
 #include "scan_device.h"
 
-// One block per query.
+// Last-arrival test for the P blocks that work on one query.  `w` is a 64-bit word of
+// caller-provided scratch: its upper 48 bits hold a tag derived from the scratch address, the
+// lower 16 the number of blocks that have arrived.  Normally the word reads (tag, 0), left by
+// the previous call, and arriving is one atomic add.  A word with any other tag (memory used
+// for the first time) is re-tagged by compare-and-swap and the arrival repeated; a failed
+// swap means that another block changed the word, so every block gets through after at most
+// P + 1 rounds.  The block that arrives last must leave (tag, 0) behind when it is done.
+__device__ inline bool qadc_arrive_last(unsigned long long *w, unsigned long long tag, uint32_t P) {
+    unsigned long long old = atomicAdd(w, 1ull);
+    while ((old >> 16) != tag) {
+        unsigned long long cur = __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((cur >> 16) != tag) {
+            atomicCAS(w, cur, tag << 16);
+            cur = __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if ((cur >> 16) == tag) old = atomicAdd(w, 1ull);
+    }
+    return (uint32_t)(old & 0xffffull) + 1u == P;
+}
+
+// P blocks per query (grid = nq * P, block q*P + p).  Every block of a query computes
 //   0. (fused form only) the float table from the query, eq. (1)
 //   1. p_min(j), d_min = sum_j p_min(j) (fp64, ascending j)
 //   2. float ADC (eq. (2), fp32, ascending j) of the first t_eff codes; d_max is
 //      the k-th smallest of them, k = min(R, t_eff)
 //   3. delta = (d_max - d_min)/q_max; q = min(q_max, floor((p - p_min)/delta))
-//   4. key_bound: the k-th smallest quantized key among the first `pilot` codes
-//      (pilot >= t_eff).  It bounds the R-th best key of the whole list from
-//      above and lets the scan drop almost every code with one compare.
+// (a few thousand operations, cheaper to repeat than to hand over between kernels) and then
+// its share of
+//   4. key_bound: an upper bound of the k-th smallest quantized key among the first `pilot`
+//      codes (pilot >= t_eff), from a 256-bin histogram of the keys (of their high bytes for
+//      16-bit keys).  It bounds the R-th best key of the whole list from above and lets the
+//      scan drop almost every code with one compare.
+// Block p counts the codes [p*slice, (p+1)*slice) of the pilot; with P > 1 the histograms
+// meet in `partial` and the block that arrives last adds them up.  Block 0 of a query stores
+// the tables, that last block the parameters.
 // `queries` non-null: tables are computed here (and stored to tables_out if
 // that is non-null); otherwise they are read from tables_in.
 template <int KIND, typename QT>
@@ -20,8 +49,10 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4)
 k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
            const float *__restrict__ queries, const float *__restrict__ tables_in,
            float *__restrict__ tables_out, const uint8_t *__restrict__ codes, int t_eff, int k,
-           int pilot, void *__restrict__ qtables, pq_qparams_t *__restrict__ qparams,
-           char *__restrict__ gtab_out, size_t gtab_stride) {
+           int pilot, int slice, int P, void *__restrict__ qtables,
+           pq_qparams_t *__restrict__ qparams, char *__restrict__ gtab_out, size_t gtab_stride,
+           uint32_t *__restrict__ partial, unsigned long long *__restrict__ sync,
+           unsigned long long tag) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int T = L->T, m = L->m, cs = L->cs, qmax = L->qmax, d = L->d;
     float *tab = (float *)smem;
@@ -36,8 +67,26 @@ k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     __shared__ uint32_t sel[2];
     __shared__ double s_dmin, s_delta;
     __shared__ float s_dmax;
+    __shared__ int s_last;
 
-    const size_t q = blockIdx.x;
+    const size_t q = blockIdx.x / (unsigned)P;
+    const int p = (int)(blockIdx.x % (unsigned)P);
+    const bool first = p == 0;
+    const int lo = (int64_t)p * slice < pilot ? p * slice : pilot;
+    const int hi = (int64_t)lo + slice < pilot ? lo + slice : pilot;
+    const int step = 8 * (int)blockDim.x;
+
+    // The first batch of this block's pilot codes is requested now and used at the very end.
+    uint2 pc[8];
+    if (KIND == SCAN_NIB8 && hi > lo) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            int id = lo + u * (int)blockDim.x + (int)threadIdx.x;
+            id = id < hi ? id : hi - 1;
+            pc[u] = *(const uint2 *)(codes + (size_t)id * 8);
+        }
+    }
+
     if (queries) {
         float *zs = (float *)ord;  // the query lives where the ADC sums go later
         for (int i = threadIdx.x; i < d; i += blockDim.x) zs[i] = queries[q * d + i];
@@ -54,7 +103,7 @@ k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
                 acc = __fadd_rn(acc, __fmul_rn(diff, diff));
             }
             tab[e] = acc;
-            if (tables_out) tables_out[q * T + e] = acc;
+            if (tables_out && first) tables_out[q * T + e] = acc;
         }
         __syncthreads();
     } else {
@@ -70,12 +119,12 @@ k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         pmin[j] = mn;
     }
     // float ADC of the calibration codes
-    for (int p = threadIdx.x; p < t_eff; p += blockDim.x) {
-        const uint8_t *code = codes + (size_t)p * cs;
+    for (int pp = threadIdx.x; pp < t_eff; pp += blockDim.x) {
+        const uint8_t *code = codes + (size_t)pp * cs;
         float s = 0.0f;
         for (int j = 0; j < m; ++j)
             s = __fadd_rn(s, tab[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])]);
-        ord[p] = qadc_f2ord(s);
+        ord[pp] = qadc_f2ord(s);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -102,102 +151,94 @@ k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
             qv = (x >= (double)qmax) ? (uint32_t)qmax : (uint32_t)x;
         }
         qt[e] = (uint16_t)qv;
-        if (sizeof(QT) == 1)
-            ((uint8_t *)qtables)[q * T + e] = (uint8_t)qv;
-        else
-            ((uint16_t *)qtables)[q * T + e] = (uint16_t)qv;
+        if (first) {
+            if (sizeof(QT) == 1)
+                ((uint8_t *)qtables)[q * T + e] = (uint8_t)qv;
+            else
+                ((uint16_t *)qtables)[q * T + e] = (uint16_t)qv;
+        }
     }
     __syncthreads();
-    // Pilot: the k-th smallest quantized key of the first `pilot` codes by histogram
-    // selection.  The bound is tightened in stages (1/8 of the codes, then the rest)
-    // and only keys within the current bound are counted, so that the histogram
-    // atomics stay few and spread out.  16-bit keys: high byte first, then the low
-    // byte among the keys that share the selected high byte.
     uint32_t bound = (uint32_t)qmax;
     if (pilot > 0 || gtab_out) {
         build_gtab<KIND, QT>(L, qt, gtab);
-        if (gtab_out) {  // hand the prepared group tables to the scan kernel
+        if (gtab_out && first) {  // hand the prepared group tables to the scan kernel
             QT *dst = (QT *)(gtab_out + q * gtab_stride);
             for (int e = threadIdx.x; e < L->gtab_len; e += blockDim.x) dst[e] = gtab[e];
         }
     }
     if (pilot > 0) {
-        const bool wide = sizeof(QT) != 1;
-        const int stage1 = pilot / 8 > 4 * k ? pilot / 8 : pilot;
-        uint32_t kstar = 0, below = 0;
-        for (int level = 0; level < (wide ? 2 : 1); ++level) {
-            for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
-            uint32_t cut = 255;  // bins above `cut` cannot hold the k-th key and are not counted
-            __syncthreads();
-            int lo = 0;
-            for (int stage = 0; stage < 2 && lo < pilot; ++stage) {
-                const int hi = stage == 0 ? stage1 : pilot;
-                // count one key (0xffffffff = none) in the histogram of this level
-                auto count_key = [&](uint32_t key) {
-                    uint32_t bin = 0xffffffffu;  // not counted
-                    if (key != 0xffffffffu) {
-                        if (!wide)
-                            bin = key;
-                        else if (level == 0)
-                            bin = key >> 8;
-                        else if ((key >> 8) == kstar)
-                            bin = key & 255u;
-                    }
-                    // the top bin collects every saturated key: count it once per wave
-                    const uint64_t top = __ballot(bin == 255u);
-                    if (top != 0 && cut == 255u && __lane_id() == 0)
-                        atomicAdd(&hist[255], (uint32_t)__popcll(top));
-                    if (bin < 255u && bin <= cut) atomicAdd(&hist[bin], 1u);
-                };
-                if (KIND == SCAN_NIB8) {
-                    // double-buffered: the loads of the next batch fly while this one is looked up
-                    const int step = 8 * (int)blockDim.x;
-                    uint2 cur[8], nxt[8];
+        const int shift = sizeof(QT) == 1 ? 0 : 8;
+        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+        __syncthreads();
+        // count one key (0xffffffff = none); the top bin collects every saturated key and
+        // is counted once per wave
+        auto count_key = [&](uint32_t key) {
+            const uint32_t bin = key == 0xffffffffu ? 0xffffffffu : key >> shift;
+            const uint64_t top = __ballot(bin == 255u);
+            if (top != 0 && __lane_id() == 0) atomicAdd(&hist[255], (uint32_t)__popcll(top));
+            if (bin < 255u) atomicAdd(&hist[bin], 1u);
+        };
+        if (KIND == SCAN_NIB8) {
+            for (int base = lo; base < hi; base += step) {
+                if (base != lo) {
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
-                        int id = lo + u * (int)blockDim.x + (int)threadIdx.x;
+                        int id = base + u * (int)blockDim.x + (int)threadIdx.x;
                         id = id < hi ? id : hi - 1;
-                        cur[u] = *(const uint2 *)(codes + (size_t)id * 8);
-                    }
-                    for (int base = lo; base < hi; base += step) {
-                        if (base + step < hi) {
-#pragma unroll
-                            for (int u = 0; u < 8; ++u) {
-                                int id = base + step + u * (int)blockDim.x + (int)threadIdx.x;
-                                id = id < hi ? id : hi - 1;
-                                nxt[u] = *(const uint2 *)(codes + (size_t)id * 8);
-                            }
-                        }
-#pragma unroll
-                        for (int u = 0; u < 8; ++u) {
-                            const int id = base + u * (int)blockDim.x + (int)threadIdx.x;
-                            const uint32_t sm = sum8(gtab, cur[u].x, cur[u].y);
-                            count_key(id < hi ? (sm > (uint32_t)qmax ? (uint32_t)qmax : sm) : 0xffffffffu);
-                        }
-#pragma unroll
-                        for (int u = 0; u < 8; ++u) cur[u] = nxt[u];
-                    }
-                } else {
-                    for (int base = lo; base < hi; base += 8 * (int)blockDim.x) {
-                        uint32_t key[8];
-                        keys_batch<KIND, QT, 8>(L, gtab, codes, (int64_t)base + threadIdx.x,
-                                                blockDim.x, (int64_t)hi, key);
-#pragma unroll
-                        for (int u = 0; u < 8; ++u) count_key(key[u]);
+                        pc[u] = *(const uint2 *)(codes + (size_t)id * 8);
                     }
                 }
-                __syncthreads();
-                if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, (uint32_t)k, below, sel);
-                __syncthreads();
-                cut = sel[0];
-                lo = hi;
-                __syncthreads();
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int id = base + u * (int)blockDim.x + (int)threadIdx.x;
+                    const uint32_t sm = sum8(gtab, pc[u].x, pc[u].y);
+                    count_key(id < hi ? (sm > (uint32_t)qmax ? (uint32_t)qmax : sm) : 0xffffffffu);
+                }
             }
-            kstar = (level == 0) ? sel[0] : ((kstar << 8) | sel[0]);
-            below = sel[1];
-            __syncthreads();
+        } else {
+            for (int base = lo; base < hi; base += step) {
+                uint32_t key[8];
+                keys_batch<KIND, QT, 8>(L, gtab, codes, (int64_t)base + threadIdx.x, blockDim.x,
+                                        (int64_t)hi, key);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) count_key(key[u]);
+            }
         }
-        bound = kstar;
+        __syncthreads();
+        if (P > 1) {
+            uint32_t *mine = partial + ((size_t)q * P + p) * 256;
+            if (threadIdx.x < 256) {
+                mine[threadIdx.x] = hist[threadIdx.x];
+                __threadfence();
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) s_last = qadc_arrive_last(sync + q, tag, (uint32_t)P) ? 1 : 0;
+            __syncthreads();
+            if (!s_last) return;
+            // The partial histograms are read with device-scope atomic loads, which see what
+            // the other blocks released before they arrived; all loads are issued together.
+            for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+            __syncthreads();
+            const uint32_t *all = partial + (size_t)q * P * 256;
+            uint32_t v[16];  // P <= 64 blocks of 256 bins over 1024 threads
+#pragma unroll
+            for (int it = 0; it < 16; ++it) {
+                const int i = it * 1024 + (int)threadIdx.x;
+                v[it] = i < P * 256
+                            ? __hip_atomic_load(all + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                            : 0u;
+            }
+#pragma unroll
+            for (int it = 0; it < 16; ++it)
+                if (v[it]) atomicAdd(&hist[threadIdx.x & 255], v[it]);
+            __syncthreads();
+            if (threadIdx.x == 0)  // ready for the next call on this scratch
+                __hip_atomic_store(sync + q, tag << 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, (uint32_t)k, 0u, sel);
+        __syncthreads();
+        bound = sizeof(QT) == 1 ? sel[0] : ((sel[0] << 8) | 255u);
     }
     if (threadIdx.x == 0) {
         pq_qparams_t prm;
@@ -209,14 +250,61 @@ k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     }
 }
 
-static int64_t pilot_default() {
-    static int64_t v = -1;
-    if (v < 0) {
-        const char *e = getenv("QADC_PILOT");
-        v = e ? atoll(e) : 65536;
-        if (v < 0) v = 0;
-    }
-    return v;
+static int64_t pilot_env(const char *name, int64_t dflt) {
+    const char *e = getenv(name);
+    int64_t v = e ? atoll(e) : dflt;
+    return v < 0 ? 0 : v;
+}
+
+// Codes one pilot block counts per batch (eight per thread) and at most in total.
+#define PILOT_BATCH 8192
+#define PILOT_BLOCK_MAX 65536
+
+int qadc_pilot_blocks_max(int nq) {
+    static const int64_t cap = pilot_env("QADC_PILOT_BLOCKS", 8);
+    int pmax = 256 / (nq > 0 ? nq : 1);
+    pmax = pmax < 1 ? 1 : (pmax > 64 ? 64 : pmax);
+    return cap >= 1 && cap < pmax ? (int)cap : pmax;
+}
+
+size_t qadc_pilot_scratch_bytes(int nq) {
+    const size_t part = (size_t)(nq > 0 ? nq : 0) * (size_t)qadc_pilot_blocks_max(nq) * 256 * sizeof(uint32_t);
+    const size_t sync = ((size_t)(nq > 0 ? nq : 0) * sizeof(unsigned long long) + 255) & ~(size_t)255;
+    return part + sync;
+}
+
+// The pilot of a call: how many codes, split over how many blocks per query.  With scratch
+// memory (the fused search) a small batch of queries spreads a large pilot over many
+// blocks; without it every query has one block and the pilot stays small.
+PilotPlan qadc_pilot_plan(int nq, int64_t n, int t_eff, int R, bool have_scratch) {
+    static const int64_t multi = pilot_env("QADC_PILOT", 262144);
+    static const int64_t single = pilot_env("QADC_PILOT1", PILOT_BLOCK_MAX);
+    PilotPlan pp;
+    const int pmax = have_scratch ? qadc_pilot_blocks_max(nq) : 1;
+    int64_t want = pmax > 1 ? multi : single;
+    if (want > (int64_t)pmax * PILOT_BLOCK_MAX) want = (int64_t)pmax * PILOT_BLOCK_MAX;
+    if (want < 64 * (int64_t)R) want = 64 * (int64_t)R;
+    if (want < t_eff) want = t_eff;
+    if (want > n) want = n;
+    int64_t P = (want + PILOT_BATCH - 1) / PILOT_BATCH;
+    if (P > pmax) P = pmax;
+    if (P < 1) P = 1;
+    int64_t slice = (want + P - 1) / P;
+    slice = (slice + 1023) / 1024 * 1024;
+    if (slice < 1024) slice = 1024;
+    pp.pilot = (int)want;
+    pp.P = (int)P;
+    pp.slice = (int)slice;
+    return pp;
+}
+
+// Tag of a scratch area: its address mixed with a per-process value, 48 bits, never zero.
+static unsigned long long scratch_tag(const void *scratch) {
+    static const unsigned long long salt =
+        (((unsigned long long)time(nullptr) << 24) ^ ((unsigned long long)getpid() << 4)) * 0x9E3779B97F4A7C15ull;
+    unsigned long long t = (((unsigned long long)(uintptr_t)scratch >> 8) * 0xD6E8FEB86659FD93ull) ^ salt;
+    t = (t >> 16) & 0xffffffffffffull;
+    return t ? t : 1ull;
 }
 
 static size_t quantize_lds(const DevLayout &h, int t_eff, size_t esz) {
@@ -228,36 +316,42 @@ static size_t quantize_lds(const DevLayout &h, int t_eff, size_t esz) {
 template <int KIND, typename QT>
 static int launch_quantize(const pq_index *idx, const float *queries, const float *tables_in,
                            float *tables_out, int nq, const uint8_t *codes, int t_eff, int k,
-                           int pilot, void *qtables, pq_qparams_t *qparams, char *gtab_out,
-                           size_t gtab_stride, hipStream_t s) {
+                           const PilotPlan &pp, void *qtables, pq_qparams_t *qparams, char *gtab_out,
+                           size_t gtab_stride, uint32_t *partial, unsigned long long *sync,
+                           hipStream_t s) {
     const size_t lds = quantize_lds(idx->h, t_eff, sizeof(QT));
     if (lds > 48 * 1024)
         QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_quantize<KIND, QT>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL((k_quantize<KIND, QT>), dim3(nq), dim3(1024), lds, s, idx->dev,
-                       idx->codebooks, queries, tables_in, tables_out, codes, t_eff, k, pilot,
-                       qtables, qparams, gtab_out, gtab_stride);
+    hipLaunchKernelGGL((k_quantize<KIND, QT>), dim3((unsigned)nq * (unsigned)pp.P), dim3(1024), lds, s,
+                       idx->dev, idx->codebooks, queries, tables_in, tables_out, codes, t_eff, k,
+                       pp.pilot, pp.slice, pp.P, qtables, qparams, gtab_out, gtab_stride, partial,
+                       sync, pp.P > 1 ? scratch_tag(partial) : 0ull);
     QADC_LAUNCH_CHECK("k_quantize");
     return PQ_OK;
 }
 
-// Shared by pq_quantize_tables (queries == null) and the fused search call.
+// Shared by pq_quantize_tables (queries == null) and the fused search call.  `scratch`
+// (qadc_pilot_scratch_bytes(nq) bytes, 256-byte aligned, any contents) lets several blocks
+// share a query's pilot; null keeps one block per query.
 int qadc_quantize_launch(const pq_index *idx, const float *queries, const float *tables_in,
                          float *tables_out, int nq, const uint8_t *codes, int64_t n, int t, int R,
                          void *qtables, pq_qparams_t *qparams, char *gtab_out, size_t gtab_stride,
-                         hipStream_t s) {
+                         char *scratch, int *pilot_used, hipStream_t s) {
     const int64_t want = t > 4 * (int64_t)R ? t : 4 * (int64_t)R;
     const int t_eff = (int)(n < want ? n : want);
     const int k = R < t_eff ? R : t_eff;
-    int64_t pil = pilot_default();
-    if (pil < 64 * (int64_t)R) pil = 64 * (int64_t)R;
-    if (pil < t_eff) pil = t_eff;
-    if (pil > n) pil = n;
-    const int pilot = (int)pil;
+    const PilotPlan pp = qadc_pilot_plan(nq, n, t_eff, R, scratch != nullptr);
+    if (pilot_used) *pilot_used = pp.pilot;
+    uint32_t *partial = (uint32_t *)scratch;
+    unsigned long long *sync = nullptr;
+    if (scratch)
+        sync = (unsigned long long *)(scratch + (size_t)nq * (size_t)qadc_pilot_blocks_max(nq) * 256 *
+                                                    sizeof(uint32_t));
     const bool u8 = idx->h.acc_bits == 8;
-#define QADC_GO(KIND, QT)                                                                        \
+#define QADC_GO(KIND, QT)                                                                       \
     return launch_quantize<KIND, QT>(idx, queries, tables_in, tables_out, nq, codes, t_eff, k, \
-                                     pilot, qtables, qparams, gtab_out, gtab_stride, s)
+                                     pp, qtables, qparams, gtab_out, gtab_stride, partial, sync, s)
     switch (idx->h.kind) {
         case SCAN_NIB8:
             if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);
@@ -299,5 +393,5 @@ extern "C" int pq_quantize_tables(const pq_index_t *idx, const float *tables, in
         return PQ_EINVAL;
     }
     return qadc_quantize_launch(idx, nullptr, tables, nullptr, nq, codes, n, t, R, qtables, qparams,
-                                nullptr, 0, (hipStream_t)stream);
+                                nullptr, 0, nullptr, nullptr, (hipStream_t)stream);
 }

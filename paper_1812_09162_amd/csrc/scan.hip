@@ -372,18 +372,48 @@ struct FinalOut {
 };
 
 // Rank the na candidates of A by (key, id) and write the first R, padding the rest.
+// `rank` is 512 words of LDS.  Few candidates: several threads share one candidate, each
+// counting over a part of A.
 __device__ inline void rank_and_write(const uint64_t *A, int na, int R, const pq_qparams_t &prm,
-                                      uint32_t qmax, const FinalOut &o) {
+                                      uint32_t qmax, const FinalOut &o, uint32_t *rank) {
     const float fdelta = (float)prm.delta, fdmin = (float)prm.d_min;
-    for (int i = threadIdx.x; i < na; i += blockDim.x) {
-        const uint64_t mine = A[i];
-        int rank = 0;
-        for (int j = 0; j < na; ++j) rank += (A[j] < mine) ? 1 : 0;
-        if (rank < R) {
-            const uint32_t key = (uint32_t)(mine >> 32);
-            o.ids[rank] = (int32_t)(uint32_t)mine;
-            o.keys[rank] = (uint16_t)key;
-            o.dist[rank] = fmaf((float)key, fdelta, fdmin);
+    if (na <= 512) {
+        // 2^lt threads per candidate, each counting over its share of A
+        int lt = 1;
+        while (lt < 4 && (na << (lt + 1)) <= 1024) ++lt;
+        if ((int)threadIdx.x < na) rank[threadIdx.x] = 0;
+        __syncthreads();
+        const int i = threadIdx.x >> lt, part = threadIdx.x & ((1 << lt) - 1);
+        if (i < na) {
+            const uint64_t mine = A[i];
+            const int per = (na + (1 << lt) - 1) >> lt;
+            const int j1 = (part + 1) * per < na ? (part + 1) * per : na;
+            uint32_t r = 0;
+            for (int j = part * per; j < j1; ++j) r += (A[j] < mine) ? 1u : 0u;
+            if (r) atomicAdd(&rank[i], r);
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < na) {
+            const int r = (int)rank[threadIdx.x];
+            if (r < R) {
+                const uint64_t mine = A[threadIdx.x];
+                const uint32_t key = (uint32_t)(mine >> 32);
+                o.ids[r] = (int32_t)(uint32_t)mine;
+                o.keys[r] = (uint16_t)key;
+                o.dist[r] = fmaf((float)key, fdelta, fdmin);
+            }
+        }
+    } else {
+        for (int i = threadIdx.x; i < na; i += blockDim.x) {
+            const uint64_t mine = A[i];
+            int r = 0;
+            for (int j = 0; j < na; ++j) r += (A[j] < mine) ? 1 : 0;
+            if (r < R) {
+                const uint32_t key = (uint32_t)(mine >> 32);
+                o.ids[r] = (int32_t)(uint32_t)mine;
+                o.keys[r] = (uint16_t)key;
+                o.dist[r] = fmaf((float)key, fdelta, fdmin);
+            }
         }
     }
     for (int r = (na < R ? na : R) + threadIdx.x; r < R; r += blockDim.x) {
@@ -458,7 +488,7 @@ __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4)
 k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         const pq_qparams_t *__restrict__ qparams, const uint8_t *__restrict__ codes, int64_t n,
         int R, const char *__restrict__ ws, size_t per_query, size_t slots_off, int cap_b, int G,
-        int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_keys,
+        int logw, int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_keys,
         float *__restrict__ out_dist) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint64_t *A = (uint64_t *)smem;                // FINAL_CAP entries
@@ -489,8 +519,15 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     S.wsum = wsum;
     S.off = off;
     int na = 0;
-    const bool slow = gather_select_rows(counts, slots, G, cap_b, R,
-                                    [shift](uint64_t c) { return ((uint32_t)(c >> 32)) >> shift; }, A, S, na);
+    auto binf = [shift](uint64_t c) { return ((uint32_t)(c >> 32)) >> shift; };
+    const int per_batch = (G + (1024 >> logw) - 1) / (1024 >> logw);  // lists per thread
+    bool slow;
+    if (per_batch <= 8)
+        slow = gather_select_rows<8>(counts, slots, G, cap_b, R, logw, binf, A, S, na);
+    else if (per_batch <= 16)
+        slow = gather_select_rows<16>(counts, slots, G, cap_b, R, logw, binf, A, S, na);
+    else
+        slow = gather_select_rows<32>(counts, slots, G, cap_b, R, logw, binf, A, S, na);
     if (slow) {
         stage_qtable<QT>((const QT *)qtables + q * L->T, L->T, qs);
         build_gtab<KIND, QT>(L, qs, gtab);
@@ -498,7 +535,7 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         __syncthreads();
         na = (int)sh[2];
     }
-    rank_and_write(A, na, R, prm, qmax, o);
+    rank_and_write(A, na, R, prm, qmax, o, &whist[0][0]);
 }
 
 // ------------------------------------------------------------------ host ---
@@ -566,8 +603,8 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
         QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_final<KIND, QT>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_final));
     hipLaunchKernelGGL((k_final<KIND, QT>), dim3(nq), dim3(1024), lds_final, s, idx->dev, qtables,
-                       qparams, codes, n, R, ws, p.per_query, p.slots_off, p.cap_b, p.G, out_ids,
-                       out_keys, out_dist);
+                       qparams, codes, n, R, ws, p.per_query, p.slots_off, p.cap_b, p.G, p.logw,
+                       out_ids, out_keys, out_dist);
     QADC_LAUNCH_CHECK("k_final");
     return PQ_OK;
 }
@@ -675,7 +712,7 @@ extern "C" size_t pq_search_workspace_bytes(const pq_index_t *idx, int nq, int64
     if (!idx || nq < 0 || n < 0 || R < 1) return 0;
     const size_t esz = idx->h.acc_bits == 8 ? 1 : 2;
     return up256((size_t)nq * sizeof(pq_qparams_t)) + up256((size_t)nq * idx->h.T * esz) +
-           pq_workspace_bytes(idx, nq, n, R);
+           up256(pq_workspace_bytes(idx, nq, n, R)) + qadc_pilot_scratch_bytes(nq);
 }
 
 extern "C" int pq_search_topk(const pq_index_t *idx, const float *queries, int nq,
@@ -709,9 +746,12 @@ extern "C" int pq_search_topk(const pq_index_t *idx, const float *queries, int n
     void *qtables = w + up256((size_t)nq * sizeof(pq_qparams_t));
     char *ws = (char *)qtables + up256((size_t)nq * idx->h.T * esz);
     hipStream_t s = (hipStream_t)stream;
-    const ScanPlan p = qadc_scan_plan(idx, nq, n, R);
+    ScanPlan p = qadc_scan_plan(idx, nq, n, R);
+    char *scratch = ws + up256(p.total);
+    int pilot = 0;
     rc = qadc_quantize_launch(idx, queries, nullptr, nullptr, nq, codes, n, t, R, qtables, qparams,
-                              ws + p.gtab_off, p.per_query, s);
+                              ws + p.gtab_off, p.per_query, scratch, &pilot, s);
     if (rc != PQ_OK) return rc;
+    p.logw = qadc_rows_logw(n, p.G, R, pilot);
     return scan_dispatch(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s, 3);
 }

@@ -408,37 +408,36 @@ __device__ inline bool gather_select(const uint32_t *__restrict__ counts,
     }
     return slow;
 }// Block-wide (1024 threads), for many short slot lists (the exhaustive scan leaves one list
-// per scan block, a dozen entries each): same contract as gather_select.  ROWS_W adjacent
-// threads read the first ROWS_W entries of a list (consecutive 128-byte lines), each thread
-// serving ROWS_KU lists, so that all loads of the common case, the list lengths included,
-// are independent and in flight together; longer lists take extra rounds.  Entries beyond a
-// list's length are loaded and ignored, which needs cap_b >= ROWS_W.
-#define ROWS_W 32   // entries of a list read per round
-#define ROWS_KU 32  // lists per thread and batch
-template <class BinF>
+// per scan block, a few entries each): same contract as gather_select.  W = 2^logw adjacent
+// threads (4 <= W <= 32) read the first W entries of a list, each thread serving NU lists
+// per batch, so that all loads of the common case, the list lengths included, are
+// independent and in flight together; longer lists take extra rounds.  Entries beyond a
+// list's length are loaded and ignored, which needs cap_b >= W.  NU is 8, 16 or 32.
+template <int NU, class BinF>
 __device__ inline bool gather_select_rows(const uint32_t *__restrict__ counts,
                                           const uint64_t *__restrict__ slots, int G, int cap_b,
-                                          int R, BinF binf, uint64_t *A, const FinalShared &S,
-                                          int &na) {
-    constexpr int LP = 1024 / ROWS_W;  // lists per batch row
+                                          int R, int logw, BinF binf, uint64_t *A,
+                                          const FinalShared &S, int &na) {
+    const int W = 1 << logw;
+    const int LP = 1024 >> logw;  // lists per batch row
     const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
-    const int sub = threadIdx.x % ROWS_W, row = threadIdx.x / ROWS_W;
+    const int sub = threadIdx.x & (W - 1), row = threadIdx.x >> logw;
     for (int i = threadIdx.x; i < 16 * 256; i += blockDim.x) (&S.whist[0][0])[i] = 0;
     if (threadIdx.x < 8) S.sh[threadIdx.x] = 0;  // 0: entries in A, 1: slow flag, 2: candidates
     __syncthreads();
-    const bool single = G <= LP * ROWS_KU;  // one batch: pass 1 reuses the registers of pass 0
+    const bool single = G <= LP * NU;  // one batch: pass 1 reuses the registers of pass 0
     uint32_t kbin = 255;
-    uint64_t c[ROWS_KU];
+    uint64_t c[NU];
     uint32_t valid = 0;   // bit u: c[u] is an entry of its list
-    uint32_t longer = 0;  // bit u: list u of this thread has more than ROWS_W entries
+    uint32_t longer = 0;  // bit u: list u of this thread has more than W entries
     for (int pass = 0; pass < 2; ++pass) {
         uint32_t mine = 0;
         bool over = false;
-        for (int kb = 0; kb < G; kb += LP * ROWS_KU) {
+        for (int kb = 0; kb < G; kb += LP * NU) {
             if (pass == 0 || !single) {
-                uint32_t cnt[ROWS_KU];
+                uint32_t cnt[NU];
 #pragma unroll
-                for (int u = 0; u < ROWS_KU; ++u) {
+                for (int u = 0; u < NU; ++u) {
                     const int list = kb + row + LP * u;
                     const bool have = list < G;
                     cnt[u] = have ? counts[list] : 0u;
@@ -447,9 +446,9 @@ __device__ inline bool gather_select_rows(const uint32_t *__restrict__ counts,
                 valid = 0;
                 longer = 0;
 #pragma unroll
-                for (int u = 0; u < ROWS_KU; ++u) {
+                for (int u = 0; u < NU; ++u) {
                     valid |= ((uint32_t)sub < cnt[u] ? 1u : 0u) << u;
-                    longer |= (cnt[u] > (uint32_t)ROWS_W ? 1u : 0u) << u;
+                    longer |= (cnt[u] > (uint32_t)W ? 1u : 0u) << u;
                     if (pass == 0 && sub == 0) {
                         mine += cnt[u];
                         over = over || cnt[u] > (uint32_t)cap_b;
@@ -458,23 +457,23 @@ __device__ inline bool gather_select_rows(const uint32_t *__restrict__ counts,
             }
             if (pass == 0) {
 #pragma unroll
-                for (int u = 0; u < ROWS_KU; ++u)
+                for (int u = 0; u < NU; ++u)
                     if ((valid >> u) & 1u) atomicAdd(&S.whist[wave][binf(c[u])], 1u);
             } else {
                 // keep the candidates up to the bin of the R-th: one LDS atomic per wave
                 uint32_t keep = 0, total = 0;
 #pragma unroll
-                for (int u = 0; u < ROWS_KU; ++u)
+                for (int u = 0; u < NU; ++u)
                     keep |= ((((valid >> u) & 1u) != 0 && binf(c[u]) <= kbin) ? 1u : 0u) << u;
 #pragma unroll
-                for (int u = 0; u < ROWS_KU; ++u) total += (uint32_t)__popcll(__ballot((keep >> u) & 1u));
+                for (int u = 0; u < NU; ++u) total += (uint32_t)__popcll(__ballot((keep >> u) & 1u));
                 if (total != 0) {
                     uint32_t base = 0;
                     if (lane == 0) base = atomicAdd(&S.sh[0], total);
                     base = __builtin_amdgcn_readfirstlane(base);
                     if (base + total > FINAL_CAP && lane == 0) S.sh[1] = 1u;
 #pragma unroll
-                    for (int u = 0; u < ROWS_KU; ++u) {
+                    for (int u = 0; u < NU; ++u) {
                         const uint64_t m = __ballot((keep >> u) & 1u);
                         const uint32_t pos = base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
                         if (((keep >> u) & 1u) && pos < FINAL_CAP) A[pos] = c[u];
@@ -488,7 +487,7 @@ __device__ inline bool gather_select_rows(const uint32_t *__restrict__ counts,
                 const int list = kb + row + LP * u;
                 uint32_t lim = counts[list];
                 lim = lim > (uint32_t)cap_b ? (uint32_t)cap_b : lim;
-                for (uint32_t r = ROWS_W + sub; r < lim; r += ROWS_W) {
+                for (uint32_t r = W + sub; r < lim; r += W) {
                     const uint64_t e = slots[(size_t)list * cap_b + r];
                     const uint32_t bin = binf(e);
                     if (pass == 0) {
