@@ -28,6 +28,15 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
+# HBM bytes per scan-kernel launch from hardware counters (rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE, one run each, scaled by the same counters over the library's copy kernel of
+# known size); the summaries with the commands are under profiles/.  None = not profiled.
+MEASURED_TRAFFIC_BYTES = {
+    ("C1", 1): (78207.0 + 234.0) * 1024,     # profiles/k_scan_C1_batch1.md
+    ("C2", 1): (312608.5 + 749.1) * 1024,    # profiles/k_scan_C2_batch1.md
+    ("C3", 1): (49002.5 + 219.3) * 1024,     # profiles/k_scan_C3_batch1.md
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -42,12 +51,16 @@ def parse():
     ap.add_argument("--unfused", action="store_true",
                     help="issue pq_compute_tables, pq_quantize_tables and pq_adc_scan_topk as three "
                          "calls instead of the fused pq_search_topk (same arithmetic)")
-    ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3"])
+    ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4"],
+                    help="C4 is the inverted-list search (ivf_adc_scan_topk); a step is one batch of "
+                         "--batch queries (default there: 1000)")
+    ap.add_argument("--kmeans-iters", type=int, default=3,
+                    help="C4 only: Lloyd iterations for the synthetic coarse quantizer")
     ap.add_argument("--n", type=int, default=0, help="override the number of codes")
     ap.add_argument("--R", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the batch-32/256 legs")
-    ap.add_argument("--cpu-queries", type=int, default=8)
+    ap.add_argument("--cpu-queries", type=int, default=24)
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="also run this many plain 1 GiB device copies (library kernel k_copy, "
                          "known traffic) so that hardware counters collected around this run "
@@ -158,6 +171,48 @@ def scan_kernel_time(qb, idx, queries, codes, batch, R, nsamples=8, reps=200, t=
     return total_ms / launches, launches
 
 
+def isolated_latency(run, nsteps=200):
+    """One query at a time on one stream with a device synchronisation after each: the wall
+    time a lone request sees.  Returns (median_ms, min_ms)."""
+    torch = run.torch
+    times = []
+    for i in range(nsteps + 20):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run.step(0, off=(i * run.batch) % run.nq_total)
+        torch.cuda.synchronize()
+        if i >= 20:
+            times.append((time.perf_counter() - t0) * 1e3)
+    times.sort()
+    return times[len(times) // 2], times[0]
+
+
+def cold_scan_kernel_time(qb, idx, queries, codes, R, copies=5, reps=40, t=400):
+    """The scan kernel over `copies` separate copies of the code array in turn (together larger
+    than the 256 MB last-level cache), so that every launch streams its codes from HBM."""
+    import torch
+    n = codes.shape[0]
+    bufs = [codes] + [codes.clone() for _ in range(copies - 1)]
+    q = queries[:1].contiguous()
+    tables = qb.pq_compute_tables(idx, q)
+    qt, qp = qb.pq_quantize_tables(idx, tables, codes, t, R)
+    wss = []
+    for b in bufs:
+        ws = torch.empty(qb.pq_workspace_bytes(idx, 1, n, R), dtype=torch.uint8, device=codes.device)
+        qb.pq_adc_scan_candidates(idx, qt, qp, b, R, ws)
+        wss.append(ws)
+    torch.cuda.synchronize()
+    stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for r in range(reps):
+        for b, ws in zip(bufs, wss):
+            qb.pq_adc_rescan_candidates(idx, qt, qp, b, R, ws)
+    e1.record(stream)
+    e1.synchronize()
+    return e0.elapsed_time(e1) / (reps * copies)
+
+
 def cpu_baseline(pr, R, nq, t=400):
     """The oracle, as it stands, on a bounded sample: nq whole-list queries, one per thread."""
     import oracle
@@ -186,6 +241,8 @@ def main():
     # must be in the environment before the HIP runtime starts: independent requests only
     # overlap on the GPU when their streams sit on different hardware queues
     os.environ["GPU_MAX_HW_QUEUES"] = str(max(1, min(a.hw_queues, 32)))
+    if a.workload == "C4":
+        return main_ivf(a)
     import numpy as np
     import torch
     from paper_1812_09162_amd import binding as qb, synth
@@ -229,6 +286,15 @@ def main():
 
     extras = {}
     if not a.no_extras:
+        lat = Runner(qb, idx, pr.queries, pr.codes, a.batch, a.R, streams=1, fused=not a.unfused)
+        med, mn = isolated_latency(lat)
+        extras["isolated_latency_ms"] = {"median": med, "min": mn,
+                                         "note": "one step at a time, host-synchronised"}
+        if n * cs <= (1 << 30):
+            cold_ms = cold_scan_kernel_time(qb, idx, pr.queries, pr.codes, a.R)
+            extras["scan_kernel_cold"] = {"kernel_avg_ms": cold_ms, "gb_per_s": alg_bytes / cold_ms / 1e6,
+                                          "frac_of_peak": alg_bytes / cold_ms / 1e6 / HBM_PEAK_GBS,
+                                          "note": "5 copies of the code array scanned in turn"}
         for bs, st in ((32, 60), (256, 12)):
             r2 = Runner(qb, idx, pr.queries, pr.codes, bs, a.R, streams=min(a.streams, 2),
                         fused=not a.unfused)
@@ -245,7 +311,9 @@ def main():
     entry = ("pq_compute_tables+pq_quantize_tables+pq_adc_scan_topk" if a.unfused
              else "pq_search_topk")
     out = {
-        "metric": "billion codes scanned/sec per GPU (PQ 16x4, R=100), whole path per query",
+        "metric": ("billion codes scanned/sec per GPU (PQ 16x4, R=100), whole path per query"
+                   if a.workload == "C1" and a.R == 100 else
+                   f"billion codes scanned/sec per GPU ({a.workload}, R={a.R}), whole path per query"),
         "value": codes_per_s / 1e9,
         "unit": "Gcodes/s",
         "n_gpus": 1,
@@ -265,7 +333,7 @@ def main():
         "host_issue_ms_per_step": run.issue_s / a.steps * 1e3,
         "roofline": {"bound": "hbm", "kernel": "k_scan", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "kernel_avg_ms": k_avg_ms, "launches": k_cnt,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, a.batch)), "kernel_avg_ms": k_avg_ms, "launches": k_cnt,
                      "algorithmic_bytes_per_launch": alg_bytes},
         "batched": extras,
     }
@@ -286,6 +354,69 @@ def main():
                     keys[j].astype(np.uint16), okk) and np.array_equal(dist[j], od)
         out["parity_sample"] = {"queries": a.cpu_queries, "bit_exact": bool(ok)}
     print(json.dumps(out))
+
+
+def main_ivf(a):
+    """Workload C4: residual PQ 16x4 behind a coarse quantizer, nprobe lists per query."""
+    import numpy as np
+    import torch
+    from paper_1812_09162_amd import binding as qb, synth
+    assert torch.cuda.is_available(), "bench.py needs the GPU; there is no CPU fallback"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = dict(synth.CONFIGS["C4"])
+    cfg["kmeans_iters"] = a.kmeans_iters
+    if a.n:
+        cfg["n"] = a.n
+        cfg["K"] = max(64, int(cfg["K"] * a.n / synth.CONFIGS["C4"]["n"]))
+    t_build = time.perf_counter()
+    ip = synth.build(cfg, device=dev)
+    torch.cuda.synchronize()
+    t_build = time.perf_counter() - t_build
+    lay = ip.layout
+    idx = qb.PqIndex(lay.d, lay.nbits, lay.dsub, ip.codebooks, lay.acc_bits)
+    nq_all, nprobe = ip.probe_ids.shape
+    bs = a.batch if a.batch > 1 else 1000
+    bs = min(bs, nq_all)
+    sizes = ip.list_offsets[1:] - ip.list_offsets[:-1]
+    probed = sizes[ip.probe_ids.long()].sum(dim=1)  # codes scanned per query
+    ws = torch.empty(qb.ivf_workspace_bytes(idx, bs, nprobe, a.R), dtype=torch.uint8, device=dev)
+    out = (torch.empty((bs, a.R), dtype=torch.int32, device=dev),
+           torch.empty((bs, a.R), dtype=torch.float32, device=dev))
+
+    def go(i):
+        lo = (i * bs) % (nq_all - bs + 1)
+        qb.ivf_adc_scan_topk(idx, ip.coarse, ip.list_offsets, ip.list_codes, ip.list_ids,
+                             ip.queries[lo:lo + bs], ip.probe_ids[lo:lo + bs], 400, a.R,
+                             workspace=ws, out=out)
+        return lo
+
+    steps = min(a.steps, 200)
+    for i in range(min(a.warmup, 5)):
+        go(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        go(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    per_step = float(probed.float().mean().item()) * bs
+    cs = ip.list_codes.shape[1]
+    out_d = {
+        "metric": "billion codes scanned/sec per GPU (IVF, residual PQ 16x4, R=100), whole path",
+        "value": per_step * steps / dt / 1e9, "unit": "Gcodes/s", "n_gpus": 1, "steps": steps,
+        "warmup": min(a.warmup, 5), "ms_per_step": dt / steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"C4: IVF ADC, N={ip.list_codes.shape[0]}, K={ip.coarse.shape[0]}, "
+                               f"nprobe={nprobe}, d={lay.d}, m={lay.m}, code_bytes={cs}, R={a.R}, t=400, "
+                               f"batch={bs}, coarse k-means iterations={a.kmeans_iters}, "
+                               f"entry=ivf_adc_scan_topk",
+                   "seed": cfg["seed"], "dataset_build_s": round(t_build, 1),
+                   "codes_scanned_per_query": float(probed.float().mean().item())},
+        "us_per_query": dt / steps / bs * 1e6,
+        "list_bytes_per_s_gb": per_step * steps / dt * (cs + 0) / 1e9,
+    }
+    print(json.dumps(out_d))
 
 
 if __name__ == "__main__":
