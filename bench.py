@@ -51,7 +51,7 @@ def parse():
     ap.add_argument("--unfused", action="store_true",
                     help="issue pq_compute_tables, pq_quantize_tables and pq_adc_scan_topk as three "
                          "calls instead of the fused pq_search_topk (same arithmetic)")
-    ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4"],
+    ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4", "L8x8", "L664", "L655", "L16x8", "L664x2"],
                     help="C4 is the inverted-list search (ivf_adc_scan_topk); a step is one batch of "
                          "--batch queries (default there: 1000)")
     ap.add_argument("--kmeans-iters", type=int, default=3,

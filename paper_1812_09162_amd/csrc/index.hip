@@ -93,7 +93,7 @@ extern "C" int pq_index_create(pq_index_t **out, int d, int m, const int32_t *nb
     L.code_bits = bit;
     L.cs = (bit + 7) / 8;
 
-    // group plan: widest groups whose tables stay within 16 KB of LDS
+    // group plan: widest groups whose tables stay within 18 KB of LDS (eight scan blocks per CU)
     const int esz = acc_bits == 8 ? 1 : 2;
     bool all4 = true;
     for (int j = 0; j < m; ++j) all4 = all4 && nbits[j] == 4;
@@ -103,7 +103,7 @@ extern "C" int pq_index_create(pq_index_t **out, int d, int m, const int32_t *nb
         int gmax = 11;
         for (; gmax >= 8; --gmax) {
             plan_groups(L, gmax);
-            if ((size_t)L.gtab_len * esz <= 16384) break;
+            if ((size_t)L.gtab_len * esz <= 18432) break;
         }
         if (gmax < 8) plan_groups(L, 1);  // every sub-quantizer alone: T entries
     }
@@ -112,6 +112,14 @@ extern "C" int pq_index_create(pq_index_t **out, int d, int m, const int32_t *nb
     if (all4 && m == 32) L.kind = SCAN_NIB16;
     if (L.kind == SCAN_GENERIC && L.cs == 8) L.kind = SCAN_W64;
     if (L.kind == SCAN_GENERIC && L.cs == 5) L.kind = SCAN_C5;
+    if (L.kind == SCAN_GENERIC && L.cs == 16 && L.code_bits == 128 && L.g32ok && L.ng % 2 == 0 &&
+        L.ng <= 16) {
+        // two 64-bit halves with the same group pattern
+        bool same = true;
+        for (int g = 0; g < L.ng / 2; ++g)
+            same = same && L.goff[g + L.ng / 2] == L.goff[g] + 64 && L.gw[g + L.ng / 2] == L.gw[g];
+        if (same) L.kind = SCAN_W128;
+    }
 
     pq_index *idx = new pq_index;
     idx->h = L;

@@ -508,6 +508,8 @@ extern "C" int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_cent
             if (u8) QADC_GO(SCAN_W64, uint8_t); else QADC_GO(SCAN_W64, uint16_t);
         case SCAN_C5:
             if (u8) QADC_GO(SCAN_C5, uint8_t); else QADC_GO(SCAN_C5, uint16_t);
+        case SCAN_W128:
+            if (u8) QADC_GO(SCAN_W128, uint8_t); else QADC_GO(SCAN_W128, uint16_t);
         default:
             if (u8) QADC_GO(SCAN_GENERIC, uint8_t); else QADC_GO(SCAN_GENERIC, uint16_t);
     }

@@ -40,7 +40,7 @@ struct DevLayout {
 //   W64           any other 8-byte code: group fields cut out of one 64-bit word
 //   C5            5-byte codes (33..40 bits): four codes per lane from five dwords
 //   GENERIC       everything else, byte by byte
-enum { SCAN_GENERIC = 0, SCAN_NIB8 = 1, SCAN_NIB16 = 2, SCAN_C5 = 3, SCAN_W64 = 4 };
+enum { SCAN_GENERIC = 0, SCAN_NIB8 = 1, SCAN_NIB16 = 2, SCAN_C5 = 3, SCAN_W64 = 4, SCAN_W128 = 5 };
 
 struct pq_index {
     DevLayout h;          // host copy

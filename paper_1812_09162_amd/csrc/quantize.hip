@@ -361,6 +361,8 @@ int qadc_quantize_launch(const pq_index *idx, const float *queries, const float 
             if (u8) QADC_GO(SCAN_W64, uint8_t); else QADC_GO(SCAN_W64, uint16_t);
         case SCAN_C5:
             if (u8) QADC_GO(SCAN_C5, uint8_t); else QADC_GO(SCAN_C5, uint16_t);
+        case SCAN_W128:
+            if (u8) QADC_GO(SCAN_W128, uint8_t); else QADC_GO(SCAN_W128, uint16_t);
         default:
             if (u8) QADC_GO(SCAN_GENERIC, uint8_t); else QADC_GO(SCAN_GENERIC, uint16_t);
     }

@@ -56,8 +56,8 @@ __device__ __forceinline__ void load_gtab(const char *__restrict__ src, int gtab
 }
 
 // ---------------------------------------------------------------- k_scan ---
-// NG > 0: the layout has NG groups, none crossing a dword boundary of the code (8-byte and
-// 5-byte kinds only); NG == 0: group descriptors are read from the layout.
+// NG > 0: the layout has NG groups (per 64-bit half for 16-byte irregular codes), none
+// crossing a dword boundary of the code; NG == 0: group descriptors are read from the layout.
 template <int KIND, typename QT, int NG>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
@@ -206,7 +206,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         uint4 cur[4];
         int64_t tile = b;
         auto load_tile = [&](int64_t t) {
-            if (KIND != SCAN_NIB16) return;  // other layouts read their codes byte by byte
+            if (KIND != SCAN_NIB16 && KIND != SCAN_W128) return;  // others read byte by byte
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int64_t c = t * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
@@ -223,6 +223,9 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 const int64_t c = tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
                 if (KIND == SCAN_NIB16)
                     s[u] = sum8(gtab, cur[u].x, cur[u].y) + sum8(gtab + 2048, cur[u].z, cur[u].w);
+                else if (KIND == SCAN_W128)
+                    s[u] = sum_groups_desc<NG>(gd, gtab, cur[u].x, cur[u].y) +
+                           sum_groups_desc<NG>(gd, gtab, cur[u].z, cur[u].w, true);
                 else
                     s[u] = c < n ? key_generic(L, gtab, codes + c * L->cs) : 0u;
                 pass[u] = (c < n) && s[u] <= thr;
@@ -573,14 +576,17 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
             gd.w[g] = h.gw[g];
             gd.base[g] = h.gbase[g];
         }
+        if (KIND == SCAN_W128)  // NG = groups per 64-bit half
+            for (int g = 0; g < h.ng / 2; ++g) gd.base2[g] = h.gbase[g + h.ng / 2];
         const bool fast = (KIND == SCAN_W64 || KIND == SCAN_C5) && h.g32ok != 0 && h.ng >= 1 &&
                           h.ng <= QADC_MAXG_FAST;
+        const int ngt = KIND == SCAN_W128 ? h.ng / 2 : (fast ? h.ng : 0);
 #define QADC_SCAN_NG(NGV)                                                                          \
     hipLaunchKernelGGL((k_scan<KIND, QT, NGV>), dim3(p.G, nq), dim3(SCAN_THREADS), gtab_bytes, s, \
                        idx->dev, qtables, qparams, codes, n, ws, p.per_query, p.slots_off,        \
                        p.gtab_off, p.cap_b, h.gtab_len, (uint32_t)h.qmax, gd)
-        if (KIND == SCAN_W64 || KIND == SCAN_C5) {
-            switch (fast ? h.ng : 0) {
+        if (KIND == SCAN_W64 || KIND == SCAN_C5 || KIND == SCAN_W128) {
+            switch (ngt) {
                 case 1: QADC_SCAN_NG(1); break;
                 case 2: QADC_SCAN_NG(2); break;
                 case 3: QADC_SCAN_NG(3); break;
@@ -625,6 +631,8 @@ static int scan_dispatch(const pq_index *idx, const void *qtables, const pq_qpar
             if (u8) QADC_GO(SCAN_W64, uint8_t); else QADC_GO(SCAN_W64, uint16_t);
         case SCAN_C5:
             if (u8) QADC_GO(SCAN_C5, uint8_t); else QADC_GO(SCAN_C5, uint16_t);
+        case SCAN_W128:
+            if (u8) QADC_GO(SCAN_W128, uint8_t); else QADC_GO(SCAN_W128, uint16_t);
         default:
             if (u8) QADC_GO(SCAN_GENERIC, uint8_t); else QADC_GO(SCAN_GENERIC, uint16_t);
     }

@@ -126,6 +126,7 @@ __device__ __forceinline__ uint32_t sum_groups32(const DevLayout *L, const QT *g
 struct GroupDesc {
     int ng;
     int off[QADC_MAXG_FAST], w[QADC_MAXG_FAST], base[QADC_MAXG_FAST];
+    int base2[QADC_MAXG_FAST];  // 128-bit codes: table bases of the same groups in the upper half
 };
 __device__ __forceinline__ GroupDesc load_group_desc(const DevLayout *L) {
     GroupDesc d;
@@ -142,12 +143,27 @@ __device__ __forceinline__ GroupDesc load_group_desc(const DevLayout *L) {
 // of groups, fixed at compile time so that all lookups of a code are issued together
 template <int NG, typename QT>
 __device__ __forceinline__ uint32_t sum_groups_desc(const GroupDesc &d, const QT *gtab, uint32_t lo,
-                                                    uint32_t hi) {
+                                                    uint32_t hi, bool upper = false) {
     uint32_t s = 0;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
         const uint32_t x = d.off[g] >= 32 ? hi : lo;
-        s += gtab[d.base[g] + __builtin_amdgcn_ubfe(x, (uint32_t)(d.off[g] & 31), (uint32_t)d.w[g])];
+        const int base = upper ? d.base2[g] : d.base[g];
+        s += gtab[base + __builtin_amdgcn_ubfe(x, (uint32_t)(d.off[g] & 31), (uint32_t)d.w[g])];
+    }
+    return s;
+}
+
+// 128-bit code as two 64-bit words, no group crossing the word boundary (descriptors from the layout)
+template <typename QT>
+__device__ __forceinline__ uint32_t sum_groups128(const DevLayout *L, const QT *gtab, uint64_t lo,
+                                                  uint64_t hi) {
+    const int ng = L->ng;
+    uint32_t s = 0;
+    for (int g = 0; g < ng; ++g) {
+        const int off = L->goff[g];
+        const uint64_t v = off >= 64 ? hi : lo;
+        s += gtab[L->gbase[g] + ((uint32_t)(v >> (off & 63)) & ((1u << L->gw[g]) - 1u))];
     }
     return s;
 }
@@ -168,6 +184,10 @@ __device__ __forceinline__ uint32_t key_at(const DevLayout *L, const QT *gtab,
     } else if (KIND == SCAN_W64) {
         uint2 w = *(const uint2 *)(codes + id * 8);
         uint32_t s = sum_groups64(L, gtab, ((uint64_t)w.y << 32) | w.x);
+        return s > qmax ? qmax : s;
+    } else if (KIND == SCAN_W128) {
+        uint4 w = *(const uint4 *)(codes + id * 16);
+        uint32_t s = sum_groups128(L, gtab, ((uint64_t)w.y << 32) | w.x, ((uint64_t)w.w << 32) | w.z);
         return s > qmax ? qmax : s;
     } else if (KIND == SCAN_C5) {
         const uint8_t *c = codes + id * 5;
@@ -212,6 +232,20 @@ __device__ __forceinline__ void keys_batch(const DevLayout *L, const QT *gtab,
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint32_t s = sum8(gtab, w[u].x, w[u].y) + sum8(gtab + 2048, w[u].z, w[u].w);
+            key[u] = (base + u * stride < n) ? (s > qmax ? qmax : s) : 0xffffffffu;
+        }
+    } else if (KIND == SCAN_W128) {
+        uint4 w[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int64_t id = base + u * stride;
+            id = id < n ? id : n - 1;
+            w[u] = *(const uint4 *)(codes + id * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t s = sum_groups128(L, gtab, ((uint64_t)w[u].y << 32) | w[u].x,
+                                             ((uint64_t)w[u].w << 32) | w[u].z);
             key[u] = (base + u * stride < n) ? (s > qmax ? qmax : s) : 0xffffffffu;
         }
     } else if (KIND == SCAN_W64) {

@@ -328,6 +328,17 @@ CONFIGS = {
     "C4": dict(kind="ivf", n=100_000_000, nq=10_000, d=96, nbits=[4] * 16, acc_bits=8,
                dist="aniso_gauss", seed=BASE_SEED + 4, K=65_536, nprobe=64,
                train_n=1_000_000, R=[100]),
+    # further layouts of the paper (Sections 3.1-3.3): 64-bit and 128-bit codes, 16-bit tables
+    "L8x8": dict(kind="flat", n=10_000_000, nq=1_000, d=128, nbits=[8] * 8, acc_bits=16,
+                 dist="gamma_ints", seed=BASE_SEED + 5, train_n=100_000, R=[100]),
+    "L664": dict(kind="flat", n=10_000_000, nq=1_000, d=128, nbits=[6, 6, 4] * 4, acc_bits=16,
+                 dist="gamma_ints", seed=BASE_SEED + 6, train_n=100_000, R=[100]),
+    "L655": dict(kind="flat", n=10_000_000, nq=1_000, d=128, nbits=[6, 5, 5] * 4, acc_bits=16,
+                 dist="gamma_ints", seed=BASE_SEED + 7, train_n=100_000, R=[100]),
+    "L16x8": dict(kind="flat", n=10_000_000, nq=1_000, d=128, nbits=[8] * 16, acc_bits=16,
+                  dist="gamma_ints", seed=BASE_SEED + 8, train_n=100_000, R=[100]),
+    "L664x2": dict(kind="flat", n=10_000_000, nq=1_000, d=128, nbits=[6, 6, 4] * 8, acc_bits=16,
+                   dist="gamma_ints", seed=BASE_SEED + 9, train_n=100_000, R=[100]),
 }
 
 

@@ -95,7 +95,8 @@ def test_scaled_configs_bit_exact(qb, name, n, R):
 @pytest.mark.parametrize("nbits,d,acc", [
     ([6, 6, 4] * 4, 128, 16), ([6, 5, 5] * 4, 128, 16), ([5, 5, 5], 15, 16), ([8] * 8, 32, 16),
     ([8] * 8, 32, 8), ([3, 7, 1, 2], 13, 8), ([4] * 16, 32, 16), ([4] * 32, 64, 16),
-    ([4] * 8, 16, 8), ([6, 6, 4] * 8, 128, 8),
+    ([4] * 8, 16, 8), ([6, 6, 4] * 8, 128, 8), ([6, 6, 4] * 8, 128, 16), ([8] * 16, 64, 16),
+    ([6, 5, 5] * 8, 128, 16), ([6, 6, 4] * 4 + [8] * 8, 96, 16), ([8] * 15 + [4, 4], 68, 8),
 ])
 def test_other_layouts_bit_exact(qb, nbits, d, acc):
     pr = synth.make_problem(n=5003, nq=3, d=d, nbits=nbits, acc_bits=acc, dist="gamma_ints",
