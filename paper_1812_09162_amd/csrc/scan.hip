@@ -58,7 +58,9 @@ __device__ __forceinline__ void load_gtab(const char *__restrict__ src, int gtab
 // ---------------------------------------------------------------- k_scan ---
 // NG > 0: the layout has NG groups (per 64-bit half for 16-byte irregular codes), none
 // crossing a dword boundary of the code; NG == 0: group descriptors are read from the layout.
-template <int KIND, typename QT, int NG>
+// MODE says where the groups lie: 0 = decided per group at run time, 1 = the first NG/2 in the
+// low dword, 2 = all but the last in the low dword.
+template <int KIND, typename QT, int NG, int MODE>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
        const pq_qparams_t *__restrict__ qparams, const uint8_t *__restrict__ codes, int64_t n,
@@ -77,6 +79,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     thr = thr > qmax ? qmax : thr;
     if (threadIdx.x == 0) s_count = 0;
     constexpr bool g32 = NG > 0;
+    constexpr int NLO = MODE == 1 ? NG / 2 : (MODE == 2 ? NG - 1 : -1);
 
     if (KIND == SCAN_NIB8 || KIND == SCAN_W64) {
         // 16-byte chunks of two codes, U8 chunks per thread and tile (U8*16 bytes per lane in
@@ -106,8 +109,8 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                     s[2 * u] = sum8(gtab, cur[u].x, cur[u].y);
                     s[2 * u + 1] = sum8(gtab, cur[u].z, cur[u].w);
                 } else if (g32) {
-                    s[2 * u] = sum_groups_desc<NG>(gd, gtab, cur[u].x, cur[u].y);
-                    s[2 * u + 1] = sum_groups_desc<NG>(gd, gtab, cur[u].z, cur[u].w);
+                    s[2 * u] = sum_groups_desc<NG, NLO>(gd, gtab, cur[u].x, cur[u].y);
+                    s[2 * u + 1] = sum_groups_desc<NG, NLO>(gd, gtab, cur[u].z, cur[u].w);
                 } else {
                     s[2 * u] = sum_groups64(L, gtab, ((uint64_t)cur[u].y << 32) | cur[u].x);
                     s[2 * u + 1] = sum_groups64(L, gtab, ((uint64_t)cur[u].w << 32) | cur[u].z);
@@ -177,7 +180,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 hi[3] = cur[u][4] >> 24;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    s[4 * u + v] = g32 ? sum_groups_desc<NG>(gd, gtab, lo[v], hi[v])
+                    s[4 * u + v] = g32 ? sum_groups_desc<NG, NLO>(gd, gtab, lo[v], hi[v])
                                        : sum_groups64(L, gtab, ((uint64_t)hi[v] << 32) | lo[v]);
                     pass[4 * u + v] = (c < nfull) && s[4 * u + v] <= thr;
                     any = any || pass[4 * u + v];
@@ -224,8 +227,8 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 if (KIND == SCAN_NIB16)
                     s[u] = sum8(gtab, cur[u].x, cur[u].y) + sum8(gtab + 2048, cur[u].z, cur[u].w);
                 else if (KIND == SCAN_W128)
-                    s[u] = sum_groups_desc<NG>(gd, gtab, cur[u].x, cur[u].y) +
-                           sum_groups_desc<NG>(gd, gtab, cur[u].z, cur[u].w, true);
+                    s[u] = sum_groups_desc<NG, NLO>(gd, gtab, cur[u].x, cur[u].y) +
+                           sum_groups_desc<NG, NLO>(gd, gtab, cur[u].z, cur[u].w, true);
                 else
                     s[u] = c < n ? key_generic(L, gtab, codes + c * L->cs) : 0u;
                 pass[u] = (c < n) && s[u] <= thr;
@@ -581,10 +584,23 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
         const bool fast = (KIND == SCAN_W64 || KIND == SCAN_C5) && h.g32ok != 0 && h.ng >= 1 &&
                           h.ng <= QADC_MAXG_FAST;
         const int ngt = KIND == SCAN_W128 ? h.ng / 2 : (fast ? h.ng : 0);
-#define QADC_SCAN_NG(NGV)                                                                          \
-    hipLaunchKernelGGL((k_scan<KIND, QT, NGV>), dim3(p.G, nq), dim3(SCAN_THREADS), gtab_bytes, s, \
-                       idx->dev, qtables, qparams, codes, n, ws, p.per_query, p.slots_off,        \
+        // where the groups lie (see k_scan's MODE)
+        int nlo = 0;
+        const int gper = KIND == SCAN_W128 ? h.ng / 2 : h.ng;
+        for (int g = 0; g < gper; ++g) nlo += h.goff[g] < 32 ? 1 : 0;
+        const int mode = (ngt > 0 && ngt % 2 == 0 && nlo == ngt / 2) ? 1 : ((ngt > 1 && nlo == ngt - 1) ? 2 : 0);
+#define QADC_SCAN_GO(NGV, MODEV)                                                                       \
+    hipLaunchKernelGGL((k_scan<KIND, QT, NGV, MODEV>), dim3(p.G, nq), dim3(SCAN_THREADS), gtab_bytes, \
+                       s, idx->dev, qtables, qparams, codes, n, ws, p.per_query, p.slots_off,         \
                        p.gtab_off, p.cap_b, h.gtab_len, (uint32_t)h.qmax, gd)
+#define QADC_SCAN_NG(NGV)                                            \
+    do {                                                             \
+        if (KIND == SCAN_C5) {                                       \
+            if (mode == 2) QADC_SCAN_GO(NGV, 2); else QADC_SCAN_GO(NGV, 0); \
+        } else {                                                     \
+            if (mode == 1) QADC_SCAN_GO(NGV, 1); else QADC_SCAN_GO(NGV, 0); \
+        }                                                            \
+    } while (0)
         if (KIND == SCAN_W64 || KIND == SCAN_C5 || KIND == SCAN_W128) {
             switch (ngt) {
                 case 1: QADC_SCAN_NG(1); break;
@@ -595,11 +611,12 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
                 case 6: QADC_SCAN_NG(6); break;
                 case 7: QADC_SCAN_NG(7); break;
                 case 8: QADC_SCAN_NG(8); break;
-                default: QADC_SCAN_NG(0); break;
+                default: QADC_SCAN_GO(0, 0); break;
             }
         } else {
-            QADC_SCAN_NG(0);
+            QADC_SCAN_GO(0, 0);
         }
+#undef QADC_SCAN_GO
 #undef QADC_SCAN_NG
         QADC_LAUNCH_CHECK("k_scan");
     }

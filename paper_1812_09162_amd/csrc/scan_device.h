@@ -141,13 +141,15 @@ __device__ __forceinline__ GroupDesc load_group_desc(const DevLayout *L) {
 }
 // code of at most 64 bits as two dwords, no group crossing the dword boundary; NG = number
 // of groups, fixed at compile time so that all lookups of a code are issued together
-template <int NG, typename QT>
+// NLO >= 0: the first NLO groups lie in the low dword and the rest in the high one, known at
+// compile time; NLO < 0: decided per group from its offset.
+template <int NG, int NLO, typename QT>
 __device__ __forceinline__ uint32_t sum_groups_desc(const GroupDesc &d, const QT *gtab, uint32_t lo,
                                                     uint32_t hi, bool upper = false) {
     uint32_t s = 0;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-        const uint32_t x = d.off[g] >= 32 ? hi : lo;
+        const uint32_t x = NLO >= 0 ? (g < NLO ? lo : hi) : (d.off[g] >= 32 ? hi : lo);
         const int base = upper ? d.base2[g] : d.base[g];
         s += gtab[base + __builtin_amdgcn_ubfe(x, (uint32_t)(d.off[g] & 31), (uint32_t)d.w[g])];
     }
