@@ -4,6 +4,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <vector>
+
 #include "qadc_internal.h"
 
 static thread_local char g_err[512] = "";
@@ -107,6 +109,9 @@ extern "C" int pq_index_create(pq_index_t **out, int d, int m, const int32_t *nb
         }
         if (gmax < 8) plan_groups(L, 1);  // every sub-quantizer alone: T entries
     }
+    L.ds_uniform = dsub[0] <= 8 ? dsub[0] : 0;
+    for (int j = 1; j < m; ++j)
+        if (dsub[j] != dsub[0]) L.ds_uniform = 0;
     L.kind = SCAN_GENERIC;
     if (all4 && m == 16) L.kind = SCAN_NIB8;
     if (all4 && m == 32) L.kind = SCAN_NIB16;
@@ -125,9 +130,23 @@ extern "C" int pq_index_create(pq_index_t **out, int d, int m, const int32_t *nb
     idx->h = L;
     idx->codebooks = codebooks;
     idx->dev = nullptr;
+    std::vector<EntryDesc> ed((size_t)L.T);
+    for (int j = 0; j < m; ++j)
+        for (int i = 0; i < (1 << L.nbits[j]); ++i) {
+            EntryDesc &x = ed[(size_t)L.toff[j] + i];
+            x.j = j;
+            x.cb_off = L.cboff[j] + i * L.dsub[j];
+            x.dim_off = L.dimoff[j];
+            x.ds = L.dsub[j];
+        }
+    const size_t lay_bytes = (sizeof(DevLayout) + 15) & ~(size_t)15;
     hipError_t e = hipGetDevice(&idx->device);
-    if (e == hipSuccess) e = hipMalloc((void **)&idx->dev, sizeof(DevLayout));
+    if (e == hipSuccess) e = hipMalloc((void **)&idx->dev, lay_bytes + ed.size() * sizeof(EntryDesc));
     if (e == hipSuccess) e = hipMemcpy(idx->dev, &L, sizeof(DevLayout), hipMemcpyHostToDevice);
+    if (e == hipSuccess) {
+        idx->edesc = (const EntryDesc *)((char *)idx->dev + lay_bytes);
+        e = hipMemcpy((void *)idx->edesc, ed.data(), ed.size() * sizeof(EntryDesc), hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
         qadc_set_error("pq_index_create: %s", hipGetErrorString(e));
         if (idx->dev) (void)hipFree(idx->dev);

@@ -176,8 +176,15 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         for (int p = threadIdx.x; p < take; p += blockDim.x) {
             const uint8_t *code = list_codes + (size_t)(lo + p) * cs;
             float s = 0.0f;
-            for (int j = 0; j < m; ++j)
-                s = __fadd_rn(s, l.tab[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])]);
+            if (cs <= 16) {
+                uint32_t w[4];
+                qadc_load_code16(code, cs, w);
+                for (int j = 0; j < m; ++j)
+                    s = __fadd_rn(s, l.tab[L->toff[j] + qadc_extract_sub16(w, L->bitoff[j], L->nbits[j])]);
+            } else {
+                for (int j = 0; j < m; ++j)
+                    s = __fadd_rn(s, l.tab[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])]);
+            }
             ord[seen + p] = qadc_f2ord(s);
         }
         seen += take;
@@ -199,8 +206,15 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
             if (ok) {
                 const uint8_t *code = list_codes + (size_t)(lo + p) * cs;
                 uint32_t acc = 0;
-                for (int j = 0; j < m; ++j)
-                    acc += l.qt[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])];
+                if (cs <= 16) {
+                    uint32_t w[4];
+                    qadc_load_code16(code, cs, w);
+                    for (int j = 0; j < m; ++j)
+                        acc += l.qt[L->toff[j] + qadc_extract_sub16(w, L->bitoff[j], L->nbits[j])];
+                } else {
+                    for (int j = 0; j < m; ++j)
+                        acc += l.qt[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])];
+                }
                 if (acc > (uint32_t)qmax) acc = (uint32_t)qmax;
                 o = qadc_f2ord(fmaf((float)acc, fdelta, fdmin));
             }
@@ -211,7 +225,16 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     }
     const uint32_t inf_o = qadc_f2ord(INFINITY);
     uint32_t t0 = qadc_block_kth_u32(ord, pilot, k, 4, hist, sel);
-    uint32_t l0 = qadc_block_kth_u32(ord, pilot, 1, 4, hist, sel);
+    // smallest pilot distance: block minimum
+    uint32_t l0 = 0xffffffffu;
+    for (int p = threadIdx.x; p < pilot; p += blockDim.x) l0 = ord[p] < l0 ? ord[p] : l0;
+    l0 = qadc_wave_min(l0);
+    __syncthreads();
+    if (threadIdx.x == 0) sel[0] = 0xffffffffu;
+    __syncthreads();
+    if (threadIdx.x % QADC_WAVE == 0) atomicMin(&sel[0], l0);
+    __syncthreads();
+    l0 = sel[0];
     if (threadIdx.x == 0) {
         const float thr0 = t0 > inf_o ? INFINITY : qadc_ord2f(t0);
         const float lo = l0 > inf_o ? 0.f : qadc_ord2f(l0);
@@ -224,25 +247,48 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
 }
 
 // ------------------------------------------------------------- k_ivf_scan ---
-template <int KIND, typename QT>
-__global__ void __launch_bounds__(256)
-k_ivf_scan(const DevLayout *__restrict__ L, const float *__restrict__ cb,
-           const float *__restrict__ coarse, const int64_t *__restrict__ list_offsets,
-           const uint8_t *__restrict__ list_codes, const int32_t *__restrict__ list_ids,
-           const float *__restrict__ queries, const int32_t *__restrict__ probe_ids, int nprobe,
-           int K, int R, char *__restrict__ ws, size_t per_query, size_t counts_off, size_t slots_off,
-           int cap_b) {
+// One block per (query, probed cell).  The block is latency bound (a few thousand codes
+// behind a chain of small dependent steps), so the set-up is ordered for few round trips:
+//   A  probe id, query state, query, entry descriptors      (independent loads)
+//   B  list bounds, centroid, codebook values of the entries (need A)
+//   C  the first codes of the list                           (need B; used after the set-up)
+// NE = table entries per thread (1, 2 or 4; 0 = the general set-up routine, no early loads).
+#ifndef QADC_IVF_PF
+#define QADC_IVF_PF 2
+#endif
+template <int KIND, typename QT, int NE>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8)))
+k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
+           const float *__restrict__ cb, const float *__restrict__ coarse,
+           const int64_t *__restrict__ list_offsets, const uint8_t *__restrict__ list_codes,
+           const int32_t *__restrict__ list_ids, const float *__restrict__ queries,
+           const int32_t *__restrict__ probe_ids, int nprobe, int K, int R, char *__restrict__ ws,
+           size_t per_query, size_t counts_off, size_t slots_off, int cap_b) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t s_count;
     IvfLds l;
     ivf_carve(L, smem, sizeof(QT), l);
-    qadc_build_entry_map(L, l.esub);
     const size_t q = blockIdx.y;
     const int a = blockIdx.x;
+    const int bd = (int)blockDim.x;
     char *wq = ws + q * per_query;
-    IvfState *st = (IvfState *)wq;
+    const IvfState *st = (const IvfState *)wq;
     uint32_t *counts = (uint32_t *)(wq + counts_off);
+    constexpr int MAXDS = 8;  // codebook values per entry held in registers
+    const int d = L->d, T = L->T, m = L->m, qmax = L->qmax;
+
+    // A
     const int c = probe_ids[q * nprobe + a];
+    const float dmax = st->dmax, thr0 = st->thr0;
+    EntryDesc ed[NE > 0 ? NE : 1];
+    if (NE > 0) {
+#pragma unroll
+        for (int k = 0; k < NE; ++k) {
+            const int e = (int)threadIdx.x + k * bd;
+            ed[k] = edesc[e < T ? e : T - 1];
+        }
+        for (int i = threadIdx.x; i < d; i += bd) l.zres[i] = queries[q * d + i];
+    }
     int64_t lo = 0, hi = 0;
     if (c >= 0 && c < K) {
         lo = list_offsets[c];
@@ -252,10 +298,121 @@ k_ivf_scan(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         if (threadIdx.x == 0) counts[a] = 0;
         return;
     }
-    const float dmax = st->dmax, thr0 = st->thr0;
     if (threadIdx.x == 0) s_count = 0;
-    const bool ok = ivf_setup<KIND, QT>(L, cb, queries + q * L->d, coarse + (size_t)c * L->d, dmax, true,
-                                  true, l);
+    bool ok;
+    // 64-bit m x 4 codes are read two at a time: the list from its first even position
+    constexpr int PF = QADC_IVF_PF;  // 16-byte loads per lane in flight
+    const int64_t lo2 = (lo + 1) & ~(int64_t)1;
+    const int64_t npair = hi > lo2 ? (hi - lo2) >> 1 : 0;
+    const uint4 *__restrict__ pairs = (const uint4 *)(list_codes + lo2 * 8);
+    uint4 pp[PF];
+    if (NE > 0) {
+        // B
+        // sub-space width if all sub-quantizers share one (then a scalar, and nothing below
+        // needs per-lane predicates), else 0
+        const int dsu = L->ds_uniform;
+        float cv[NE > 0 ? NE : 1][MAXDS];
+#pragma unroll
+        for (int k = 0; k < NE; ++k)
+#pragma unroll
+            for (int t = 0; t < MAXDS; ++t) {
+                if (dsu > 0) {
+                    if (t < dsu) cv[k][t] = cb[ed[k].cb_off + t];
+                } else {
+                    cv[k][t] = t < ed[k].ds ? cb[ed[k].cb_off + t] : 0.0f;
+                }
+            }
+        __syncthreads();  // the query is in LDS
+        for (int i = threadIdx.x; i < d; i += bd)
+            l.zres[i] = __fsub_rn(l.zres[i], coarse[(size_t)c * d + i]);
+        // C: the first PF 16-byte pairs of codes per lane, from the first even position on
+        if (KIND == SCAN_NIB8 && npair > 0) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                int64_t pi = (int64_t)u * bd + threadIdx.x;
+                pi = pi < npair ? pi : npair - 1;
+                pp[u] = pairs[pi];
+            }
+        }
+        __syncthreads();  // the residual is in LDS
+        // eq. (1), terms in ascending dimension order
+#pragma unroll
+        for (int k = 0; k < NE; ++k) {
+            const int e = (int)threadIdx.x + k * bd;
+            if (e < T) {
+                const float *zz = l.zres + ed[k].dim_off;
+                float acc = 0.0f;
+#pragma unroll
+                for (int t = 0; t < MAXDS; ++t) {
+                    if (dsu > 0 ? t < dsu : t < ed[k].ds) {
+                        const float diff = __fsub_rn(zz[t], cv[k][t]);
+                        acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                    }
+                }
+                for (int t = MAXDS; t < ed[k].ds; ++t) {  // wider sub-spaces: the rest from memory
+                    const float diff = __fsub_rn(zz[t], cb[ed[k].cb_off + t]);
+                    acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                }
+                l.tab[e] = acc;
+            }
+        }
+        if (KIND == SCAN_NIB8 || KIND == SCAN_NIB16) {
+            // 16 entries per sub-quantizer, held by 16 adjacent lanes: minimum by exchange
+#pragma unroll
+            for (int k = 0; k < NE; ++k) {
+                const int e = (int)threadIdx.x + k * bd;
+                float mn = e < T ? l.tab[e] : INFINITY;  // own entry, just written by this thread
+#pragma unroll
+                for (int sft = 1; sft < 16; sft <<= 1) {
+                    const float o = __shfl_xor(mn, sft, QADC_WAVE);
+                    mn = o < mn ? o : mn;
+                }
+                if (e < T && (e & 15) == 0) l.pmin[e >> 4] = mn;
+            }
+        } else {
+            __syncthreads();
+            if ((int)threadIdx.x < m) {
+                const int j = threadIdx.x;
+                const int kj = 1 << L->nbits[j];
+                const float *tj = l.tab + L->toff[j];
+                float mn = tj[0];
+                for (int i = 1; i < kj; ++i) mn = tj[i] < mn ? tj[i] : mn;
+                l.pmin[j] = mn;
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double dm = 0.0;
+            for (int j = 0; j < m; ++j) dm = dm + (double)l.pmin[j];
+            l.sc[0] = dm;
+            double delta = ((double)dmax - dm) / (double)qmax;
+            if (!((delta > 0.0) && isfinite(delta))) delta = 0.0;
+            l.sc[1] = delta;
+            *l.flag = dm > (double)dmax;
+        }
+        __syncthreads();
+        ok = *l.flag == 0;
+        if (ok) {
+            const double delta = l.sc[1];
+#pragma unroll
+            for (int k = 0; k < NE; ++k) {
+                const int e = (int)threadIdx.x + k * bd;
+                if (e < T) {
+                    uint32_t qv = 0;
+                    if (delta > 0.0) {
+                        double x = floor(((double)l.tab[e] - (double)l.pmin[ed[k].j]) / delta);
+                        qv = (x >= (double)qmax) ? (uint32_t)qmax : (uint32_t)x;
+                    }
+                    l.qt[e] = (uint16_t)qv;
+                }
+            }
+            __syncthreads();
+            build_gtab<KIND, QT>(L, l.qt, (QT *)l.gtab);
+        }
+    } else {
+        qadc_build_entry_map(L, l.esub);
+        ok = ivf_setup<KIND, QT>(L, cb, queries + q * d, coarse + (size_t)c * d, dmax, true, true, l);
+    }
     if (!ok) {
         if (threadIdx.x == 0) counts[a] = 0;
         return;
@@ -263,24 +420,75 @@ k_ivf_scan(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     const QT *gtab = (const QT *)l.gtab;
     const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
     uint64_t *slot = (uint64_t *)(wq + slots_off) + (size_t)a * cap_b;
-    for (int64_t base = lo; base < hi; base += 1024) {
-        uint32_t key[4], ord[4], id[4];
-        bool pass[4], any = false;
-        keys_batch<KIND, QT, 4>(L, gtab, list_codes, base + threadIdx.x, 256, hi, key);
+    if (NE > 0 && KIND == SCAN_NIB8) {
+        for (int64_t pb = 0; pb < npair; pb += (int64_t)PF * bd) {
+            if (pb != 0) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float dist = fmaf((float)(key[u] == 0xffffffffu ? 0u : key[u]), fdelta, fdmin);
-            ord[u] = qadc_f2ord(dist);
-            pass[u] = key[u] != 0xffffffffu && dist <= thr0;
-            any = any || pass[u];
+                for (int u = 0; u < PF; ++u) {
+                    int64_t pi = pb + (int64_t)u * bd + threadIdx.x;
+                    pi = pi < npair ? pi : npair - 1;
+                    pp[u] = pairs[pi];
+                }
+            }
+            uint32_t ord[2 * PF], id[2 * PF];
+            bool pass[2 * PF], any = false;
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                const int64_t pi = pb + (int64_t)u * bd + threadIdx.x;
+                const uint32_t k0 = sum8(gtab, pp[u].x, pp[u].y), k1 = sum8(gtab, pp[u].z, pp[u].w);
+                const float d0 = fmaf((float)(k0 > (uint32_t)qmax ? (uint32_t)qmax : k0), fdelta, fdmin);
+                const float d1 = fmaf((float)(k1 > (uint32_t)qmax ? (uint32_t)qmax : k1), fdelta, fdmin);
+                ord[2 * u] = qadc_f2ord(d0);
+                ord[2 * u + 1] = qadc_f2ord(d1);
+                pass[2 * u] = pi < npair && d0 <= thr0;
+                pass[2 * u + 1] = pi < npair && d1 <= thr0;
+                any = any || pass[2 * u] || pass[2 * u + 1];
+            }
+            if (__ballot(any) != 0) {
+#pragma unroll
+                for (int u = 0; u < 2 * PF; ++u) {
+                    const int64_t pos = lo2 + 2 * (pb + (int64_t)(u >> 1) * bd + threadIdx.x) + (u & 1);
+                    id[u] = pass[u] ? (uint32_t)list_ids[pos] : 0u;
+                }
+                slot_append_multi<2 * PF>(pass, ord, id, slot, (uint32_t)cap_b, &s_count);
+            }
         }
-        if (__ballot(any) != 0) {
+        // the codes outside the pairs: position lo if it is odd, position hi-1 if one is left over
+        if (threadIdx.x < QADC_WAVE) {
+            int64_t pos = -1;
+            if (threadIdx.x == 0 && lo2 != lo) pos = lo;
+            if (threadIdx.x == 1 && lo2 + 2 * npair < hi) pos = hi - 1;
+            uint32_t o = 0, idv = 0;
+            bool ps = false;
+            if (pos >= 0) {
+                const uint32_t key = key_at<KIND, QT>(L, gtab, list_codes, pos);
+                const float dist = fmaf((float)key, fdelta, fdmin);
+                o = qadc_f2ord(dist);
+                ps = dist <= thr0;
+                idv = ps ? (uint32_t)list_ids[pos] : 0u;
+            }
+            slot_append(ps, o, idv, slot, (uint32_t)cap_b, &s_count);
+        }
+    } else {
+        for (int64_t base = lo; base < hi; base += 4 * bd) {
+            uint32_t key[4], ord[4], id[4];
+            bool pass[4], any = false;
+            keys_batch<KIND, QT, 4>(L, gtab, list_codes, base + threadIdx.x, bd, hi, key);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int64_t p = base + u * 256 + threadIdx.x;
-                id[u] = pass[u] ? (uint32_t)list_ids[p] : 0u;
+                const float dist = fmaf((float)(key[u] == 0xffffffffu ? 0u : key[u]), fdelta, fdmin);
+                ord[u] = qadc_f2ord(dist);
+                pass[u] = key[u] != 0xffffffffu && dist <= thr0;
+                any = any || pass[u];
             }
-            slot_append_multi<4>(pass, ord, id, slot, (uint32_t)cap_b, &s_count);
+            if (__ballot(any) != 0) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t p = base + u * bd + threadIdx.x;
+                    id[u] = pass[u] ? (uint32_t)list_ids[p] : 0u;
+                }
+                slot_append_multi<4>(pass, ord, id, slot, (uint32_t)cap_b, &s_count);
+            }
         }
     }
     __syncthreads();
@@ -437,15 +645,25 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     const size_t lds_final = FINAL_CAP * 8 + lds_scan;
     int rc;
     if ((rc = allow_lds(k_ivf_calib, lds_calib)) != PQ_OK) return rc;
-    if ((rc = allow_lds(k_ivf_scan<KIND, QT>, lds_scan)) != PQ_OK) return rc;
+    if ((rc = allow_lds(k_ivf_scan<KIND, QT, 0>, lds_scan)) != PQ_OK) return rc;
+    if ((rc = allow_lds(k_ivf_scan<KIND, QT, 1>, lds_scan)) != PQ_OK) return rc;
+    if ((rc = allow_lds(k_ivf_scan<KIND, QT, 2>, lds_scan)) != PQ_OK) return rc;
+    if ((rc = allow_lds(k_ivf_scan<KIND, QT, 4>, lds_scan)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_final<KIND, QT>, lds_final)) != PQ_OK) return rc;
     hipLaunchKernelGGL(k_ivf_calib, dim3(nq), dim3(256), lds_calib, s, idx->dev, idx->codebooks,
                        coarse, list_offsets, list_codes, queries, probe_ids, nprobe, K, want, pilot_want, R, ws,
                        p.per_query);
     QADC_LAUNCH_CHECK("k_ivf_calib");
-    hipLaunchKernelGGL((k_ivf_scan<KIND, QT>), dim3(nprobe, nq), dim3(256), lds_scan, s, idx->dev,
-                       idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,
-                       probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b);
+    static const int scan_threads = getenv("QADC_IVF_THREADS") ? atoi(getenv("QADC_IVF_THREADS")) : 128;
+    // table entries per thread: the low-latency set-up holds up to four in registers
+    const int ne = idx->h.T <= scan_threads ? 1 : (idx->h.T <= 2 * scan_threads ? 2 : (idx->h.T <= 4 * scan_threads ? 4 : 0));
+#define QADC_IVF_SCAN(NEV)                                                                          \
+    hipLaunchKernelGGL((k_ivf_scan<KIND, QT, NEV>), dim3(nprobe, nq), dim3(scan_threads), lds_scan, s, \
+                       idx->dev, idx->edesc, idx->codebooks, coarse, list_offsets, list_codes,     \
+                       list_ids, queries, probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off,  \
+                       p.slots_off, p.cap_b)
+    if (ne == 1) QADC_IVF_SCAN(1); else if (ne == 2) QADC_IVF_SCAN(2); else if (ne == 4) QADC_IVF_SCAN(4); else QADC_IVF_SCAN(0);
+#undef QADC_IVF_SCAN
     QADC_LAUNCH_CHECK("k_ivf_scan");
     hipLaunchKernelGGL((k_ivf_final<KIND, QT>), dim3(nq), dim3(1024), lds_final, s, idx->dev,
                        idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,

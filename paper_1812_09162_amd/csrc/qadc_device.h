@@ -17,6 +17,32 @@ __device__ __forceinline__ uint32_t qadc_extract_sub(const uint8_t *code, int of
     return v & ((1u << b) - 1u);
 }
 
+// A code of at most 16 bytes as four little-endian dwords (missing bytes read as zero): one
+// 8- or 16-byte load when the size allows, byte loads otherwise.
+__device__ __forceinline__ void qadc_load_code16(const uint8_t *code, int cs, uint32_t w[4]) {
+    if (cs == 8) {
+        const uint2 v = *(const uint2 *)code;
+        w[0] = v.x; w[1] = v.y; w[2] = 0; w[3] = 0;
+    } else if (cs == 16) {
+        const uint4 v = *(const uint4 *)code;
+        w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+    } else {
+        w[0] = w[1] = w[2] = w[3] = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (i < cs) w[i >> 2] |= (uint32_t)code[i] << (8 * (i & 3));
+    }
+}
+
+// Sub-code of `b` <= 8 bits at bit `off` (uniform across the wave) of a code held as dwords.
+__device__ __forceinline__ uint32_t qadc_extract_sub16(const uint32_t w[4], int off, int b) {
+    const int i = off >> 5, sh = off & 31;
+    const uint32_t lo = i == 0 ? w[0] : (i == 1 ? w[1] : (i == 2 ? w[2] : w[3]));
+    const uint32_t hi = i == 0 ? w[1] : (i == 1 ? w[2] : (i == 2 ? w[3] : 0u));
+    const uint32_t v = sh == 0 ? lo : ((lo >> sh) | (hi << (32 - sh)));
+    return v & ((1u << b) - 1u);
+}
+
 // Group field extraction: `w` <= 12 bits starting at bit `off` of a code of
 // `cs` bytes; touches at most three bytes, never past the end of the code.
 __device__ __forceinline__ uint32_t qadc_extract_group(const uint8_t *code, int cs, int off, int w) {

@@ -20,6 +20,7 @@ struct DevLayout {
     int32_t gtab_len;  // total group-table entries
     int32_t kind;      // SCAN_* below
     int32_t g32ok;     // 1 if no group field crosses a 32-bit boundary of the code
+    int32_t ds_uniform;  // the sub-space width if all sub-quantizers share one (at most 8), else 0
     // all 32-bit so that uniform reads compile to scalar loads (gfx9 has no
     // sub-dword scalar loads)
     int32_t nbits[PQ_MAX_M];
@@ -42,9 +43,16 @@ struct DevLayout {
 //   GENERIC       everything else, byte by byte
 enum { SCAN_GENERIC = 0, SCAN_NIB8 = 1, SCAN_NIB16 = 2, SCAN_C5 = 3, SCAN_W64 = 4, SCAN_W128 = 5 };
 
+// One table entry: its sub-quantizer, where its centroid starts in the codebook array (in
+// floats), the first dimension of its sub-space and that sub-space's width.
+struct EntryDesc {
+    int32_t j, cb_off, dim_off, ds;
+};
+
 struct pq_index {
     DevLayout h;          // host copy
-    DevLayout *dev;       // device copy
+    DevLayout *dev;       // device copy; T EntryDesc records follow it in the same allocation
+    const EntryDesc *edesc;  // device
     const float *codebooks;
     int device;
 };
