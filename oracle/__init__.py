@@ -156,3 +156,13 @@ def search_ivf(d, nbits, dsub, acc_bits, codebooks, coarse, list_offsets, list_c
                               _p(lo), _p(lc), _p(li), _p(z), _p(pr), int(pr.shape[0]), int(t),
                               int(R), _p(ids), _p(od), _p(dmax))
     return ids, od, float(dmax[0])
+
+
+def coarse_search(centroids, z, nprobe):
+    """O7 for one query: (ids[nprobe], scores[nprobe]) of the nearest cells."""
+    cen, z = _f32(centroids), _f32(z)
+    K, d = cen.shape
+    ids = np.empty(nprobe, dtype=np.int32)
+    sc = np.empty(nprobe, dtype=np.float32)
+    _load().oracle_coarse_search(int(d), ctypes.c_int64(K), _p(cen), _p(z), int(nprobe), _p(ids), _p(sc))
+    return ids, sc

@@ -385,3 +385,37 @@ void oracle_search_ivf(int d, int m, const int32_t *nbits, const int32_t *dsub, 
     free(qtable);
     free(pmin);
 }
+
+/*
+ * O7: coarse-quantizer search (Section 2.1.1: a query is routed to the cells whose centroids
+ * are nearest).  Cells are ranked by  score(c) = ||c||^2 - 2 z.c , the squared distance minus
+ * ||z||^2, which is the same for every cell.  fp32 throughout:
+ *   z.c     acc = fma(z[l], c[l], acc), l ascending from 0
+ *   ||c||^2 acc = fma(c[l], c[l], acc), l ascending from 0
+ *   score   = fma(-2, z.c, ||c||^2)
+ * The nprobe cells with the smallest (score, id) are returned in that order; when nprobe > K
+ * the rest is padded with id -1 and score +inf.
+ */
+void oracle_coarse_search(int d, int64_t K, const float *centroids, const float *z, int nprobe,
+                          int32_t *out_ids, float *out_scores) {
+    fid_t *cand = (fid_t *)malloc(sizeof(fid_t) * (size_t)(K > 0 ? K : 1));
+    for (int64_t c = 0; c < K; ++c) {
+        const float *cen = centroids + (size_t)c * d;
+        float dot = 0.0f, nrm = 0.0f;
+        for (int l = 0; l < d; ++l) dot = fmaf(z[l], cen[l], dot);
+        for (int l = 0; l < d; ++l) nrm = fmaf(cen[l], cen[l], nrm);
+        cand[c].dist = fmaf(-2.0f, dot, nrm);
+        cand[c].id = (int32_t)c;
+    }
+    qsort(cand, (size_t)K, sizeof(fid_t), cmp_fid);
+    for (int r = 0; r < nprobe; ++r) {
+        if (r < K) {
+            out_ids[r] = cand[r].id;
+            out_scores[r] = cand[r].dist;
+        } else {
+            out_ids[r] = -1;
+            out_scores[r] = INFINITY;
+        }
+    }
+    free(cand);
+}
