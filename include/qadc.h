@@ -211,6 +211,27 @@ int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_centroids, int 
                       float *out_dist, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Coarse-quantizer search (Section 2.1.1: a query is routed to the cells of the
+ * inverted index whose centroids are nearest).  For every query the nprobe
+ * cells with the smallest (score, id), score = ||c||^2 - 2 z.c, i.e. the
+ * squared distance minus the query's own norm, are returned in that order.
+ * Arithmetic (fp32): z.c and ||c||^2 are chains of fused multiply-adds over the
+ * dimensions in ascending order, score = fma(-2, z.c, ||c||^2).  The output is
+ * what ivf_adc_scan_topk takes as probe_ids.
+ *   queries      [dev][nq][d] float32     centroids [dev][K][d] float32
+ *   nprobe       1..1024; when nprobe > K the tail is padded with id -1, score +inf
+ *   probe_ids    [dev][nq][nprobe] int32
+ *   probe_scores [dev][nq][nprobe] float32, or NULL
+ *   workspace    >= ivf_coarse_workspace_bytes(nq, K), 256-byte aligned, any content
+ * Queries are processed in passes whose score matrix stays within 256 MB.
+ * Errors: PQ_EINVAL (shape, null, alignment), PQ_ENOMEM (workspace), PQ_EHIP.
+ */
+size_t ivf_coarse_workspace_bytes(int nq, int K);
+int ivf_coarse_search(const float *queries, int nq, const float *centroids, int K, int d, int nprobe,
+                      int32_t *probe_ids, float *probe_scores, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/*
  * Plain device-to-device copy by a library kernel (k_copy) whose traffic is known
  * exactly: nbytes read and nbytes written.  For scaling hardware-counter readings
  * (rocprofv3 FETCH_SIZE / WRITE_SIZE) taken in the same run as the scan kernel.

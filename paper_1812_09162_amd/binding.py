@@ -26,6 +26,7 @@ EXPORTS = [
     "ivf_workspace_bytes", "pq_compute_tables", "pq_quantize_tables", "pq_adc_scan_topk",
     "ivf_adc_scan_topk", "pq_search_workspace_bytes", "pq_search_topk",
     "pq_adc_scan_candidates", "pq_adc_rescan_candidates", "pq_select_topk", "pq_copy_bytes", "pq_last_error",
+    "ivf_coarse_workspace_bytes", "ivf_coarse_search",
 ]
 
 
@@ -80,6 +81,10 @@ def load() -> ctypes.CDLL:
     lib.pq_copy_bytes.restype = i32
     lib.pq_last_error.argtypes = []
     lib.pq_last_error.restype = ctypes.c_char_p
+    lib.ivf_coarse_workspace_bytes.argtypes = [i32, i32]
+    lib.ivf_coarse_workspace_bytes.restype = sz
+    lib.ivf_coarse_search.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp, vp, sz, vp]
+    lib.ivf_coarse_search.restype = i32
     _lib = lib
     return lib
 
@@ -289,3 +294,29 @@ def unpack_qparams(qparams: torch.Tensor):
     raw = qparams.detach().cpu().numpy()
     rec = np.dtype([("d_min", "<f8"), ("delta", "<f8"), ("d_max", "<f4"), ("key_bound", "<u4")])
     return raw.view(rec).reshape(-1)
+
+
+def ivf_coarse_workspace_bytes(nq: int, K: int) -> int:
+    return int(load().ivf_coarse_workspace_bytes(nq, K))
+
+
+def ivf_coarse_search(queries: torch.Tensor, centroids: torch.Tensor, nprobe: int,
+                      workspace: Optional[torch.Tensor] = None, out=None, want_scores: bool = True,
+                      stream=None):
+    """Returns (probe_ids [nq, nprobe] int32, probe_scores [nq, nprobe] float32 or None)."""
+    _dev(queries, torch.float32)
+    _dev(centroids, torch.float32)
+    nq, d = queries.shape
+    K = centroids.shape[0]
+    assert centroids.shape[1] == d
+    dev = queries.device
+    if workspace is None:
+        workspace = torch.empty(ivf_coarse_workspace_bytes(nq, K), dtype=torch.uint8, device=dev)
+    if out is None:
+        out = (torch.empty((nq, nprobe), dtype=torch.int32, device=dev),
+               torch.empty((nq, nprobe), dtype=torch.float32, device=dev) if want_scores else None)
+    ids, sc = out
+    _check(load().ivf_coarse_search(_ptr(queries), nq, _ptr(centroids), K, d, nprobe, _ptr(ids),
+                                    _ptr(sc) if sc is not None else None, _ptr(workspace),
+                                    workspace.numel(), _stream(stream)))
+    return ids, sc

@@ -1,0 +1,114 @@
+"""GPU parity of ivf_coarse_search (through the C ABI) against the CPU oracle: probe ids and
+scores bit for bit, on float and on integer-valued data, ragged shapes, ties and padding; and
+the chain coarse search -> inverted-list search against the oracle's own chain."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1812_09162_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def qb():
+    from paper_1812_09162_amd import binding
+    binding.load()
+    return binding
+
+
+def dev():
+    return torch.device("cuda:0")
+
+
+def check(qb, cen, qs, nprobe, nq_oracle=None):
+    ids, sc = qb.ivf_coarse_search(torch.from_numpy(qs).to(dev()), torch.from_numpy(cen).to(dev()), nprobe)
+    torch.cuda.synchronize()
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy()
+    sel = range(qs.shape[0]) if nq_oracle is None else np.linspace(0, qs.shape[0] - 1, nq_oracle).astype(int)
+    for q in sel:
+        oi, os_ = oracle.coarse_search(cen, qs[q], nprobe)
+        assert np.array_equal(ids[q], oi), (q, ids[q][:8], oi[:8])
+        assert np.array_equal(sc[q], os_), (q, sc[q][:4], os_[:4])
+    return ids
+
+
+@pytest.mark.parametrize("K,d,nq,nprobe,seed", [
+    (1000, 96, 37, 64, 0), (4099, 128, 130, 16, 1), (257, 13, 5, 8, 2), (128, 32, 128, 128, 3),
+    (33, 7, 3, 40, 4), (1, 4, 2, 1, 5), (5000, 96, 300, 1, 6), (700, 100, 260, 1024, 7),
+])
+def test_coarse_search_float_data_bit_exact(qb, K, d, nq, nprobe, seed):
+    rng = np.random.default_rng(seed)
+    cen = rng.normal(size=(K, d)).astype(np.float32)
+    qs = rng.normal(size=(nq, d)).astype(np.float32)
+    check(qb, cen, qs, nprobe)
+
+
+def test_coarse_search_integer_data_with_duplicates(qb):
+    rng = np.random.default_rng(11)
+    K, d, nq = 3000, 24, 50
+    cen = rng.integers(-3, 4, (K, d)).astype(np.float32)   # few distinct values: many exact ties
+    cen[1000:1100] = cen[0]                                # a hundred copies of one centroid
+    qs = rng.integers(-3, 4, (nq, d)).astype(np.float32)
+    qs[0] = cen[0]
+    ids = check(qb, cen, qs, 64)
+    # exact arithmetic: the oracle's answer is the exact squared-L2 ranking with ties by id
+    dist = ((cen.astype(np.int64)[None] - qs.astype(np.int64)[:, None]) ** 2).sum(2)
+    for q in range(nq):
+        assert ids[q].tolist() == np.lexsort((np.arange(K), dist[q]))[:64].tolist()
+
+
+def test_coarse_search_all_equal_scores(qb):
+    cen = np.ones((2500, 8), np.float32)
+    qs = np.zeros((3, 8), np.float32)
+    ids = check(qb, cen, qs, 100)
+    assert ids[0].tolist() == list(range(100))
+
+
+def test_coarse_search_c4_shape_and_chain_into_ivf(qb):
+    """The C4 shape at a fortieth of its size: cells found on the GPU feed the inverted-list
+    search; both stages match the oracle fed with its own cells."""
+    cfg = synth.scaled("C4", n=200_000, nq=12, K=1638, train_n=20_000, kmeans_iters=3)
+    ip = synth.build(cfg, device=dev())
+    lay = ip.layout
+    nprobe = ip.probe_ids.shape[1]
+    pid, _ = qb.ivf_coarse_search(ip.queries, ip.coarse, nprobe)
+    idx = qb.PqIndex(lay.d, lay.nbits, lay.dsub, ip.codebooks, lay.acc_bits)
+    gi, gd = qb.ivf_adc_scan_topk(idx, ip.coarse, ip.list_offsets, ip.list_codes, ip.list_ids,
+                                  ip.queries, pid, 400, 100)
+    torch.cuda.synchronize()
+    coarse, qs = ip.coarse.cpu().numpy(), ip.queries.cpu().numpy()
+    for q in range(qs.shape[0]):
+        oi, _ = oracle.coarse_search(coarse, qs[q], nprobe)
+        assert np.array_equal(pid[q].cpu().numpy(), oi)
+        ri, rd, _ = oracle.search_ivf(lay.d, lay.nbits, lay.dsub, lay.acc_bits, ip.codebooks.cpu().numpy(),
+                                      coarse, ip.list_offsets.cpu().numpy(), ip.list_codes.cpu().numpy(),
+                                      ip.list_ids.cpu().numpy(), qs[q], oi, 400, 100)
+        assert np.array_equal(gi[q].cpu().numpy(), ri)
+        assert np.array_equal(gd[q].cpu().numpy(), rd)
+    idx.close()
+
+
+def test_coarse_search_full_k_sampled(qb):
+    """K = 65,536 cells, d = 96, 2,100 queries (three passes of the score matrix would need more;
+    here two tiles of queries are ragged): a sample of queries against the oracle."""
+    rng = np.random.default_rng(21)
+    K, d, nq = 65_536, 96, 2100
+    cen = rng.normal(size=(K, d)).astype(np.float32)
+    cen /= np.linalg.norm(cen, axis=1, keepdims=True)
+    qs = rng.normal(size=(nq, d)).astype(np.float32)
+    check(qb, cen, qs, 64, nq_oracle=12)
+
+
+def test_coarse_search_errors(qb):
+    cen = torch.zeros((10, 4), dtype=torch.float32, device=dev())
+    qs = torch.zeros((2, 4), dtype=torch.float32, device=dev())
+    with pytest.raises(qb.QadcError):
+        qb.ivf_coarse_search(qs, cen, 0)
+    with pytest.raises(qb.QadcError):
+        qb.ivf_coarse_search(qs, cen, 2000)
+    with pytest.raises(qb.QadcError):
+        qb.ivf_coarse_search(qs, cen, 4, workspace=torch.empty(256, dtype=torch.uint8, device=dev()))
+    ids, _ = qb.ivf_coarse_search(qs[:0], cen, 4)
+    assert ids.shape == (0, 4)
