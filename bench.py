@@ -51,7 +51,7 @@ def parse():
     ap.add_argument("--unfused", action="store_true",
                     help="issue pq_compute_tables, pq_quantize_tables and pq_adc_scan_topk as three "
                          "calls instead of the fused pq_search_topk (same arithmetic)")
-    ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4", "L8x8", "L664", "L655", "L16x8", "L664x2"],
+    ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4", "C4coarse", "L8x8", "L664", "L655", "L16x8", "L664x2"],
                     help="C4 is the inverted-list search (ivf_adc_scan_topk); a step is one batch of "
                          "--batch queries (default there: 1000)")
     ap.add_argument("--kmeans-iters", type=int, default=3,
@@ -243,6 +243,8 @@ def main():
     os.environ["GPU_MAX_HW_QUEUES"] = str(max(1, min(a.hw_queues, 32)))
     if a.workload == "C4":
         return main_ivf(a)
+    if a.workload == "C4coarse":
+        return main_coarse(a)
     import numpy as np
     import torch
     from paper_1812_09162_amd import binding as qb, synth
@@ -417,6 +419,51 @@ def main_ivf(a):
         "list_bytes_per_s_gb": per_step * steps / dt * (cs + 0) / 1e9,
     }
     print(json.dumps(out_d))
+
+
+def main_coarse(a):
+    """The step before workload C4: nearest 64 of 65,536 cells for 10,000 queries, d = 96
+    (ivf_coarse_search).  A step is one call over all queries.  Roofline: fp32 matrix cores."""
+    import torch
+    from paper_1812_09162_amd import binding as qb
+    assert torch.cuda.is_available(), "bench.py needs the GPU; there is no CPU fallback"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, d, nq, nprobe = 65_536, 96, 10_000, 64
+    g = torch.Generator(device=dev).manual_seed(18120921)
+    cen = torch.randn((K, d), generator=g, device=dev, dtype=torch.float32)
+    cen = cen / cen.norm(dim=1, keepdim=True)
+    qs = torch.randn((nq, d), generator=g, device=dev, dtype=torch.float32)
+    qs = qs / qs.norm(dim=1, keepdim=True)
+    ws = torch.empty(qb.ivf_coarse_workspace_bytes(nq, K), dtype=torch.uint8, device=dev)
+    out = (torch.empty((nq, nprobe), dtype=torch.int32, device=dev),
+           torch.empty((nq, nprobe), dtype=torch.float32, device=dev))
+    steps = min(a.steps, 20)
+    for _ in range(2):
+        qb.ivf_coarse_search(qs, cen, nprobe, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        qb.ivf_coarse_search(qs, cen, nprobe, workspace=ws, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    flops = 2.0 * nq * K * d
+    ms = e0.elapsed_time(e1) / steps
+    print(json.dumps({
+        "metric": "queries routed/sec per GPU (nearest 64 of 65,536 cells, d=96)",
+        "value": nq * steps / dt, "unit": "queries/s", "n_gpus": 1, "steps": steps, "warmup": 2,
+        "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"C4coarse: K={K}, d={d}, nq={nq}, nprobe={nprobe}, entry=ivf_coarse_search",
+                   "seed": 18120921},
+        "roofline": {"bound": "mfma", "kernel": "k_scores + k_select (whole call)",
+                     "achieved": flops / (ms * 1e-3) / 1e12, "peak": 157.3, "unit": "TFLOP/s",
+                     "frac": flops / (ms * 1e-3) / 1e12 / 157.3, "traffic": None,
+                     "call_ms_by_events": ms, "flops_per_call": flops},
+    }))
 
 
 if __name__ == "__main__":

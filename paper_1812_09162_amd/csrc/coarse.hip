@@ -15,8 +15,8 @@
 //   k_scores   128 x 128 score tiles per block of four waves, each wave a 64 x 64 quarter as
 //              2 x 2 MFMA tiles; operands staged through LDS in chunks of 32 dimensions, the
 //              next chunk prefetched into registers while the current one is multiplied
-//   k_select   one block per query: exact radix selection of the nprobe-th smallest
-//              (score, id), then ranking of the selected cells by counting
+//   k_select   one block per query: the cells in the low tail of the score range are gathered
+//              and ranked by (score, id); exact radix selection when that tail is crowded
 #include <math.h>
 #include <string.h>
 
@@ -141,17 +141,57 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
 }
 
 // -------------------------------------------------------------------- k_select ---
-// One block of 1024 threads per query.  keys = order-preserving integers of the scores.
-// Four radix passes give the k-th smallest key (k = min(nprobe, K)) and how many keys lie
-// below it; a last pass collects the keys below it and the first k - below cells that equal
-// it, in id order; the k cells are then ranked by (key, id).
+// One block of 1024 threads per query; keys = order-preserving integers of the scores; the
+// result is the k = min(nprobe, K) smallest (key, id), ascending.
+//
+// Fast path: the keys are binned by (key - min) >> shift into 256 bins spanning [min, max]; the
+// nearest cells sit in the sparse low tail, so the bin that holds the k-th key and the bins
+// below it hold only a few cells more than k.  They are gathered into LDS and ranked by
+// counting.  Three passes over the query's scores (range, histogram, gather), which stay in L2.
+// Exact path (taken when those bins hold more than CS_CAND cells, e.g. many equal scores): four
+// radix passes give the k-th key and how many keys lie below it; the keys below it and the
+// lowest ids among its equals are collected and ranked.
+#define CS_CAND 2048
+
+// histogram increment: one LDS atomic per wave when all its active lanes hit the same bin
+// (crowded keys), else one per lane
+__device__ __forceinline__ void cs_hist_add(uint32_t *hist, uint32_t bin, bool active) {
+    const uint64_t act = __ballot(active);
+    if (act == 0) return;
+    const int leader = __ffsll((unsigned long long)act) - 1;
+    const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
+    if (__ballot(active && bin != b) == 0) {
+        if (__lane_id() == leader) atomicAdd(&hist[b], (uint32_t)__popcll(act));
+    } else if (active) {
+        atomicAdd(&hist[bin], 1u);
+    }
+}
+
+__device__ inline void cs_rank_and_write(const uint64_t *A, int na, int k, int nprobe, int32_t *oid,
+                                         float *osc) {
+    for (int i = threadIdx.x; i < na; i += blockDim.x) {
+        const uint64_t mine = A[i];
+        int r = 0;
+        for (int j = 0; j < na; ++j) r += A[j] < mine ? 1 : 0;
+        if (r < k) {
+            oid[r] = (int32_t)(uint32_t)mine;
+            if (osc) osc[r] = qadc_ord2f((uint32_t)(mine >> 32));
+        }
+    }
+    for (int r = k + threadIdx.x; r < nprobe; r += blockDim.x) {
+        oid[r] = -1;
+        if (osc) osc[r] = INFINITY;
+    }
+}
+
 __global__ void __launch_bounds__(1024)
 k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
          int32_t *__restrict__ probe_ids, float *__restrict__ probe_scores) {
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sel[2];
-    __shared__ uint64_t A[CS_MAX_NPROBE];
+    __shared__ uint64_t A[CS_CAND];
     __shared__ uint32_t wcnt[16];
+    __shared__ uint32_t s_lo[16], s_hi[16];
     __shared__ uint32_t s_taken, s_ties;
     const size_t q = blockIdx.x;
     const float *s = scores + q * ld;
@@ -159,35 +199,127 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
     float *osc = probe_scores ? probe_scores + q * nprobe : nullptr;
     const int k = nprobe < K ? nprobe : K;
     const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
-
-    uint32_t prefix = 0, mask = 0, kk = (uint32_t)k;
-    for (int pass = 3; pass >= 0; --pass) {
-        const int shift = pass * 8;
-        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
-        __syncthreads();
-        for (int i = threadIdx.x; i < K; i += blockDim.x) {
-            const uint32_t v = qadc_f2ord(s[i]);
-            if ((v & mask) == prefix) atomicAdd(&hist[(v >> shift) & 255u], 1u);
+    // 16-byte loads: thread t takes scores 4*(j*1024 + t) .. +3, UB loads in flight together.
+    // Row starts are 128-byte aligned and padded to a multiple of 32 scores; what lies past K is
+    // masked by index.
+    constexpr int UB = 8;
+    const int nj = (K + 4095) / 4096;
+    auto load_keys = [&](int j0, uint32_t (&v)[UB][4]) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int i = ((j0 + u) * 1024 + (int)threadIdx.x) * 4;
+            float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i < K) f = *(const float4 *)(s + i);
+            v[u][0] = i + 0 < K ? qadc_f2ord(f.x) : 0xffffffffu;
+            v[u][1] = i + 1 < K ? qadc_f2ord(f.y) : 0xffffffffu;
+            v[u][2] = i + 2 < K ? qadc_f2ord(f.z) : 0xffffffffu;
+            v[u][3] = i + 3 < K ? qadc_f2ord(f.w) : 0xffffffffu;
         }
-        __syncthreads();
-        if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, kk, 0u, sel);
-        __syncthreads();
-        prefix |= sel[0] << shift;
-        mask |= 255u << shift;
-        kk -= sel[1];
-        __syncthreads();
+    };
+
+    // range of the keys
+    uint32_t lo = 0xffffffffu, hi = 0u;
+    for (int j0 = 0; j0 < nj; j0 += UB) {
+        uint32_t v[UB][4];
+        load_keys(j0, v);
+#pragma unroll
+        for (int u = 0; u < UB; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (((j0 + u) * 1024 + (int)threadIdx.x) * 4 + c < K) {
+                    lo = v[u][c] < lo ? v[u][c] : lo;
+                    hi = v[u][c] > hi ? v[u][c] : hi;
+                }
+            }
     }
-    // prefix = the k-th smallest key; kk = how many cells with that key belong to the result
-    const uint32_t kth = prefix, need = kk;
+    lo = qadc_wave_min(lo);
+    hi = ~qadc_wave_min(~hi);
+    if (lane == 0) {
+        s_lo[wave] = lo;
+        s_hi[wave] = hi;
+    }
+    for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
     if (threadIdx.x == 0) {
         s_taken = 0;
         s_ties = 0;
     }
     __syncthreads();
-    // cells below the k-th key (k - need of them), in any order
-    for (int i0 = 0; i0 < K; i0 += blockDim.x) {
-        const int i = i0 + threadIdx.x;
-        const uint32_t v = i < K ? qadc_f2ord(s[i]) : 0xffffffffu;
+#pragma unroll
+    for (int w2 = 0; w2 < 16; ++w2) {
+        lo = s_lo[w2] < lo ? s_lo[w2] : lo;
+        hi = s_hi[w2] > hi ? s_hi[w2] : hi;
+    }
+    const uint32_t span = hi - lo;
+    const int shift = span < 256u ? 0 : 24 - __clz(span);  // (span >> shift) < 256
+    for (int j0 = 0; j0 < nj; j0 += UB) {
+        uint32_t v[UB][4];
+        load_keys(j0, v);
+#pragma unroll
+        for (int u = 0; u < UB; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bool in = ((j0 + u) * 1024 + (int)threadIdx.x) * 4 + c < K;
+                cs_hist_add(hist, in ? (v[u][c] - lo) >> shift : 0u, in);
+            }
+    }
+    __syncthreads();
+    if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, (uint32_t)k, 0u, sel);
+    __syncthreads();
+    const uint32_t kbin = sel[0];
+    const uint32_t cand = sel[1] + hist[kbin];  // cells in the bins up to kbin
+    if (cand <= CS_CAND) {
+        for (int j0 = 0; j0 < nj; j0 += UB) {
+            uint32_t v[UB][4];
+            load_keys(j0, v);
+#pragma unroll
+            for (int u = 0; u < UB; ++u)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int i = ((j0 + u) * 1024 + (int)threadIdx.x) * 4 + c;
+                    const bool take = i < K && ((v[u][c] - lo) >> shift) <= kbin;
+                    const uint64_t m = __ballot(take);
+                    if (m != 0) {
+                        uint32_t base = 0;
+                        if (lane == 0) base = atomicAdd(&s_taken, (uint32_t)__popcll(m));
+                        base = __builtin_amdgcn_readfirstlane(base);
+                        if (take)
+                            A[base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] =
+                                ((uint64_t)v[u][c] << 32) | (uint32_t)i;
+                    }
+                }
+        }
+        __syncthreads();
+        cs_rank_and_write(A, (int)cand, k, nprobe, oid, osc);
+        return;
+    }
+
+    // exact path: the keys are re-read from memory in every pass
+#define CS_KEYM(j) ((j) * 1024 + (int)threadIdx.x < K ? qadc_f2ord(s[(j) * 1024 + threadIdx.x]) : 0xffffffffu)
+    const int njm = (K + 1023) / 1024;
+    __syncthreads();
+    uint32_t prefix = 0, mask = 0, kk = (uint32_t)k;
+    for (int pass = 3; pass >= 0; --pass) {
+        const int sh = pass * 8;
+        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+        __syncthreads();
+        for (int j = 0; j < njm; ++j) {
+            const uint32_t v = CS_KEYM(j);
+            const bool in = j * 1024 + (int)threadIdx.x < K && (v & mask) == prefix;
+            cs_hist_add(hist, (v >> sh) & 255u, in);
+        }
+        __syncthreads();
+        if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, kk, 0u, sel);
+        __syncthreads();
+        prefix |= sel[0] << sh;
+        mask |= 255u << sh;
+        kk -= sel[1];
+        __syncthreads();
+    }
+    // prefix = the k-th smallest key; kk = how many cells with that key belong to the result
+    const uint32_t kth = prefix, need = kk, below = (uint32_t)k - need;
+    for (int j = 0; j < njm; ++j) {  // cells below the k-th key, in any order
+        const uint32_t v = CS_KEYM(j);
+        const int i = j * 1024 + (int)threadIdx.x;
         const bool lt = i < K && v < kth;
         const uint64_t m = __ballot(lt);
         if (m != 0) {
@@ -198,12 +330,11 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
         }
     }
     __syncthreads();
-    // cells equal to the k-th key: the `need` lowest ids.  Chunks of 1024 consecutive ids are
-    // visited in order; within a chunk positions come from wave counts.
-    const uint32_t below = (uint32_t)k - need;
-    for (int i0 = 0; i0 < K; i0 += blockDim.x) {
-        const int i = i0 + threadIdx.x;
-        const bool eq = i < K && qadc_f2ord(s[i]) == kth;
+    // cells equal to the k-th key: the `need` lowest ids.  Rounds of 1024 consecutive ids in
+    // ascending order; within a round positions come from the wave counts.
+    for (int j = 0; j < njm; ++j) {
+        const int i = j * 1024 + (int)threadIdx.x;
+        const bool eq = i < K && CS_KEYM(j) == kth;
         const uint64_t m = __ballot(eq);
         if (lane == 0) wcnt[wave] = (uint32_t)__popcll(m);
         __syncthreads();
@@ -222,18 +353,8 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
         if (s_ties >= need) break;
     }
     __syncthreads();
-    // rank the k selected cells
-    for (int i = threadIdx.x; i < k; i += blockDim.x) {
-        const uint64_t mine = A[i];
-        int r = 0;
-        for (int j = 0; j < k; ++j) r += A[j] < mine ? 1 : 0;
-        oid[r] = (int32_t)(uint32_t)mine;
-        if (osc) osc[r] = qadc_ord2f((uint32_t)(mine >> 32));
-    }
-    for (int r = k + threadIdx.x; r < nprobe; r += blockDim.x) {
-        oid[r] = -1;
-        if (osc) osc[r] = INFINITY;
-    }
+    cs_rank_and_write(A, k, k, nprobe, oid, osc);
+#undef CS_KEYM
 }
 
 // ------------------------------------------------------------------------ host ---
@@ -292,9 +413,9 @@ extern "C" int ivf_coarse_search(const float *queries, int nq, const float *cent
                            dim3(256), 0, s, queries + (size_t)q0 * d, nqc, centroids, K, d, cnorm,
                            scores, ld, vec);
         QADC_LAUNCH_CHECK("k_scores");
-        hipLaunchKernelGGL(k_select, dim3(nqc), dim3(1024), 0, s, scores, ld, K, nprobe,
-                           probe_ids + (size_t)q0 * nprobe,
-                           probe_scores ? probe_scores + (size_t)q0 * nprobe : nullptr);
+        int32_t *pid = probe_ids + (size_t)q0 * nprobe;
+        float *psc = probe_scores ? probe_scores + (size_t)q0 * nprobe : nullptr;
+        hipLaunchKernelGGL(k_select, dim3(nqc), dim3(1024), 0, s, scores, ld, K, nprobe, pid, psc);
         QADC_LAUNCH_CHECK("k_select");
     }
     return PQ_OK;
