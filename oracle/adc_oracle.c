@@ -17,6 +17,7 @@
  *                                  Section 3.4, d = (sum q) Delta + d_min
  *   O6  inverted-list search       Section 2.1.1 (residuals), Section 2.1.3
  *                                  (one table set per probed cell)
+ *   O7  coarse-quantizer search    Section 2.1.1 (the cells a query is routed to)
  *
  * Precision: the paper stores tables as 32-bit floats (Section 3.4, first
  * paragraph), so table entries and float ADC sums are fp32, evaluated in a
