@@ -166,3 +166,14 @@ def coarse_search(centroids, z, nprobe):
     sc = np.empty(nprobe, dtype=np.float32)
     _load().oracle_coarse_search(int(d), ctypes.c_int64(K), _p(cen), _p(z), int(nprobe), _p(ids), _p(sc))
     return ids, sc
+
+
+def encode(d, nbits, dsub, codebooks, x, shift=None) -> np.ndarray:
+    """O8: packed codes [n, code_size] of the vectors x [n, d] (minus shift [n, d], if given)."""
+    nb, ds, cb, x = _i32(nbits), _i32(dsub), _f32(codebooks), _f32(x)
+    sh = _f32(shift) if shift is not None else None
+    n = x.shape[0]
+    codes = np.empty((n, code_size(nbits)), dtype=np.uint8)
+    _load().oracle_encode(int(d), len(nb), _p(nb), _p(ds), _p(cb), _p(x), _p(sh), ctypes.c_int64(n),
+                          _p(codes))
+    return codes

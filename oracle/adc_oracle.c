@@ -420,3 +420,38 @@ void oracle_coarse_search(int d, int64_t K, const float *centroids, const float 
     }
     free(cand);
 }
+
+/*
+ * O8: encoding (Section 2.1.2: a vector is encoded by the index of the nearest centroid in each
+ * sub-space; Section 2.1.1: with an inverted index the residual x - centroid is what is
+ * encoded; Section 3.3, packing paragraph: the sub-codes form a little-endian bit stream).
+ * For vector x (minus shift, if given) the distances to the centroids of sub-quantizer j are
+ * exactly the table entries of eq. (1) for z = x; sub-code j is the index of the smallest, the
+ * lowest index among equals.
+ *   x      [n][d]            shift  [n][d] or NULL
+ *   codes  [n][code_size], every byte written (unused high bits zero)
+ */
+void oracle_encode(int d, int m, const int32_t *nbits, const int32_t *dsub, const float *codebooks,
+                   const float *x, const float *shift, int64_t n, uint8_t *codes) {
+    layout_t L = {d, m, nbits, dsub, 8};
+    int T = table_len(&L), cs = code_size(&L);
+    float *table = (float *)malloc(sizeof(float) * (size_t)T);
+    for (int64_t v = 0; v < n; ++v) {
+        oracle_tables(d, m, nbits, dsub, codebooks, x + v * d, shift ? shift + v * d : NULL, table);
+        uint8_t *code = codes + v * cs;
+        memset(code, 0, (size_t)cs);
+        int off = 0, t = 0;
+        for (int j = 0; j < m; ++j) {
+            int k = 1 << nbits[j], best = 0;
+            for (int i = 1; i < k; ++i)
+                if (table[t + i] < table[t + best]) best = i;
+            for (int b = 0; b < nbits[j]; ++b) {
+                int pos = off + b;
+                code[pos >> 3] |= (uint8_t)(((best >> b) & 1) << (pos & 7));
+            }
+            off += nbits[j];
+            t += k;
+        }
+    }
+    free(table);
+}

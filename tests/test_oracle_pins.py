@@ -487,3 +487,76 @@ def test_coarse_search_score_is_fma_chain():
             dot = fma32(z[l], cen[c, l], dot)
             nrm = fma32(cen[c, l], cen[c, l], nrm)
         assert fma32(np.float32(-2), dot, nrm) == s
+
+
+# ---------------------------------------------------------------- O8: encoding and packing
+def _one_dim_codebooks(nbits):
+    """One dimension per sub-quantizer, centroid i of sub-quantizer j at value i: encoding the
+    vector of wanted sub-codes must reproduce them."""
+    return np.concatenate([np.arange(1 << b, dtype=np.float32) for b in nbits])
+
+
+def test_encode_packs_as_the_hand_worked_layouts():
+    cases = json.load(open(os.path.join(GOLD, "bit_layout.json")))["cases"]
+    for c in cases:
+        nb = c["nbits"]
+        x = np.array([c["sub"]], dtype=np.float32)
+        codes = oracle.encode(len(nb), nb, [1] * len(nb), _one_dim_codebooks(nb), x)
+        assert codes[0].tolist() == c["bytes"], c
+
+
+@pytest.mark.parametrize("name,d,nbits,acc", LAYOUTS)
+def test_encode_is_nearest_centroid_in_every_subspace(name, d, nbits, acc):
+    lay = synth.make_layout(d, nbits, acc)
+    rng = np.random.default_rng(17)
+    cb = rng.normal(size=sum((1 << b) * s for b, s in zip(lay.nbits, lay.dsub))).astype(np.float32)
+    x = rng.normal(size=(200, d)).astype(np.float32)
+    sub = oracle.unpack(nbits, oracle.encode(d, nbits, lay.dsub, cb, x))
+    o = c0 = 0
+    for j, (b, s) in enumerate(zip(lay.nbits, lay.dsub)):
+        cen = cb[c0:c0 + (1 << b) * s].reshape(1 << b, s).astype(np.float64)
+        dist = ((x[:, None, o:o + s].astype(np.float64) - cen[None]) ** 2).sum(2)
+        best = dist.min(1)
+        chosen = dist[np.arange(len(x)), sub[:, j]]
+        assert np.all(chosen <= best * (1 + 1e-5) + 1e-6), (name, j)   # nearest up to fp32 rounding
+        clear = np.sort(dist, 1)[:, 1] > best * (1 + 1e-4) + 1e-5      # no near-tie: must be the argmin
+        assert np.array_equal(sub[clear, j], dist.argmin(1)[clear])
+        o += s
+        c0 += (1 << b) * s
+
+
+def test_encode_fixed_points_ties_and_shift():
+    nbits, d = [3, 2, 5], 7
+    lay = synth.make_layout(d, nbits, 16)
+    rng = np.random.default_rng(23)
+    cb = rng.integers(-9, 10, sum((1 << b) * s for b, s in zip(lay.nbits, lay.dsub))).astype(np.float32)
+    # every concatenation of centroids encodes to its own indices unless an earlier equal centroid exists
+    sub = np.stack([rng.integers(0, 1 << b, 64) for b in nbits], 1)
+    x = np.zeros((64, d), np.float32)
+    first = []
+    o = c0 = 0
+    for j, (b, s) in enumerate(zip(lay.nbits, lay.dsub)):
+        cen = cb[c0:c0 + (1 << b) * s].reshape(1 << b, s)
+        x[:, o:o + s] = cen[sub[:, j]]
+        first.append([int(np.flatnonzero((cen == cen[i]).all(1))[0]) for i in sub[:, j]])   # lowest equal index
+        o += s
+        c0 += (1 << b) * s
+    got = oracle.unpack(nbits, oracle.encode(d, nbits, lay.dsub, cb, x))
+    assert np.array_equal(got, np.array(first).T)
+    # with a shift the residual is what is encoded
+    shift = rng.integers(-5, 6, (64, d)).astype(np.float32)
+    assert np.array_equal(oracle.encode(d, nbits, lay.dsub, cb, x + shift, shift), oracle.encode(d, nbits, lay.dsub, cb, x))
+
+
+def test_encode_agrees_with_the_input_fabricator_on_exact_data():
+    """The harness encoder is a separate implementation (matrix form); on small integers both
+    are exact and must agree bit for bit, packing included."""
+    pr = synth.make_problem(n=400, nq=1, d=12, nbits=[4, 3, 5, 4], acc_bits=16, dist="gamma_ints",
+                            seed=5, train_n=400, kmeans_iters=0)
+    lay = pr.layout
+    rng = np.random.default_rng(1)
+    x = rng.integers(0, 6, (300, lay.d)).astype(np.float32)
+    cb = np.round(pr.codebooks.numpy())          # integer centroids
+    want = synth.pack_codes(synth.encode(torch.from_numpy(x), lay, torch.from_numpy(cb)), lay).numpy()
+    # ties are possible with integer centroids: both break them towards the lowest index
+    assert np.array_equal(oracle.encode(lay.d, lay.nbits, lay.dsub, cb, x), want)
