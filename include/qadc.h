@@ -211,6 +211,25 @@ int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_centroids, int 
                       float *out_dist, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Encode vectors (Section 2.1.2: every sub-vector is replaced by the index of its
+ * nearest centroid; Section 2.1.1: behind an inverted index the residual
+ * x - centroid is encoded; Section 3.3: sub-codes are packed as a little-endian
+ * bit stream, sub-code j in bits [off_j, off_j + nbits[j])).  The distance of
+ * sub-vector j to centroid i is eq. (1) with z = x (fp32, dimensions ascending,
+ * separate subtract / multiply / add); sub-code j is the index of the smallest,
+ * the lowest index among equals.
+ *   vectors     [dev][n][d] float32
+ *   shift_rows  [dev][K][d] float32 and shift_ids [dev][n] int32 (each in 0..K-1):
+ *               vector v is encoded as vectors[v] - shift_rows[shift_ids[v]]; both
+ *               NULL: vectors are encoded as they are
+ *   codes       [dev][n][pq_code_size(idx)], every byte written
+ * Needs 64 * ((d | 1) * 4 + m) bytes of LDS per block (d up to about 630).
+ * Errors: PQ_EINVAL (null, only one of the shift arguments, d too large), PQ_EHIP.
+ */
+int pq_encode(const pq_index_t *idx, const float *vectors, int64_t n, const float *shift_rows,
+              const int32_t *shift_ids, uint8_t *codes, void *stream);
+
+/*
  * Coarse-quantizer search (Section 2.1.1: a query is routed to the cells of the
  * inverted index whose centroids are nearest).  For every query the nprobe
  * cells with the smallest (score, id), score = ||c||^2 - 2 z.c, i.e. the

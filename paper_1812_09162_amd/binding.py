@@ -26,7 +26,7 @@ EXPORTS = [
     "ivf_workspace_bytes", "pq_compute_tables", "pq_quantize_tables", "pq_adc_scan_topk",
     "ivf_adc_scan_topk", "pq_search_workspace_bytes", "pq_search_topk",
     "pq_adc_scan_candidates", "pq_adc_rescan_candidates", "pq_select_topk", "pq_copy_bytes", "pq_last_error",
-    "ivf_coarse_workspace_bytes", "ivf_coarse_search",
+    "ivf_coarse_workspace_bytes", "ivf_coarse_search", "pq_encode",
 ]
 
 
@@ -81,6 +81,8 @@ def load() -> ctypes.CDLL:
     lib.pq_copy_bytes.restype = i32
     lib.pq_last_error.argtypes = []
     lib.pq_last_error.restype = ctypes.c_char_p
+    lib.pq_encode.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    lib.pq_encode.restype = i32
     lib.ivf_coarse_workspace_bytes.argtypes = [i32, i32]
     lib.ivf_coarse_workspace_bytes.restype = sz
     lib.ivf_coarse_search.argtypes = [vp, i32, vp, i32, i32, i32, vp, vp, vp, sz, vp]
@@ -320,3 +322,19 @@ def ivf_coarse_search(queries: torch.Tensor, centroids: torch.Tensor, nprobe: in
                                     _ptr(sc) if sc is not None else None, _ptr(workspace),
                                     workspace.numel(), _stream(stream)))
     return ids, sc
+
+
+def pq_encode(idx: PqIndex, vectors: torch.Tensor, shift_rows: Optional[torch.Tensor] = None,
+              shift_ids: Optional[torch.Tensor] = None, codes: Optional[torch.Tensor] = None,
+              stream=None) -> torch.Tensor:
+    """Packed codes [n, code_size] uint8 of vectors [n, d] (minus shift_rows[shift_ids], if given)."""
+    _dev(vectors, torch.float32)
+    if shift_rows is not None:
+        _dev(shift_rows, torch.float32)
+        _dev(shift_ids, torch.int32)
+    n = vectors.shape[0]
+    if codes is None:
+        codes = torch.empty((n, idx.code_size), dtype=torch.uint8, device=vectors.device)
+    _check(load().pq_encode(idx.handle, _ptr(vectors), n, _ptr(shift_rows), _ptr(shift_ids),
+                            _ptr(codes), _stream(stream)))
+    return codes

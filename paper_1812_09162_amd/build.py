@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqadc.so")
-SOURCES = ["index.hip", "tables.hip", "quantize.hip", "scan.hip", "ivf.hip", "coarse.hip"]
+SOURCES = ["index.hip", "tables.hip", "quantize.hip", "scan.hip", "ivf.hip", "coarse.hip", "encode.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

@@ -1,0 +1,123 @@
+// pq_encode: vectors -> packed codes (Section 2.1.2: each sub-vector is replaced by the index of
+// its nearest centroid; Section 2.1.1: behind an inverted index the residual x - centroid is
+// encoded; Section 3.3: the sub-codes are packed as a little-endian bit stream).
+//
+// The distance of sub-vector j to centroid i is the table entry D^j[i] of eq. (1) for z = x:
+// fp32, dimensions ascending, separate subtract / multiply / add.  Sub-code j is the index of
+// the smallest distance, the lowest index among equals.
+//
+// One block of 256 threads encodes 64 vectors: they are staged (minus the shift) in LDS; wave w
+// takes the sub-quantizers w, w+4, ... and lane v the vector v, so that centroid values are
+// uniform across a wave and come through scalar loads; a second step packs the sub-codes.
+#include "qadc_device.h"
+
+#define ENC_VB 64  // vectors per block
+
+__global__ void __launch_bounds__(256)
+k_encode(const DevLayout *__restrict__ L, const float *__restrict__ cb,
+         const float *__restrict__ x, int64_t n, const float *__restrict__ shift_rows,
+         const int32_t *__restrict__ shift_ids, uint8_t *__restrict__ codes) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int d = L->d, m = L->m, cs = L->cs;
+    const int ldx = d | 1;  // odd row stride: lanes of a wave (consecutive vectors) hit distinct banks
+    float *xs = (float *)smem;                             // [ENC_VB][ldx]
+    uint8_t *sub = (uint8_t *)(xs + (size_t)ENC_VB * ldx);  // [ENC_VB][m]
+    const int64_t v0 = (int64_t)blockIdx.x * ENC_VB;
+    const int nv = n - v0 < ENC_VB ? (int)(n - v0) : ENC_VB;
+
+    for (int e = threadIdx.x; e < nv * d; e += blockDim.x) {
+        const int v = e / d, l = e - v * d;
+        float val = x[(size_t)v0 * d + e];
+        if (shift_rows) val = __fsub_rn(val, shift_rows[(size_t)shift_ids[v0 + v] * d + l]);
+        xs[v * ldx + l] = val;
+    }
+    __syncthreads();
+
+    const int v = threadIdx.x % ENC_VB, w = threadIdx.x / ENC_VB;
+    for (int j = w; j < m; j += 4) {
+        const int ds = L->dsub[j], kj = 1 << L->nbits[j];
+        const float *c = cb + L->cboff[j];
+        const float *xv = xs + v * ldx + L->dimoff[j];
+        float best = INFINITY;
+        int besti = 0;
+        if (ds <= 8) {
+            float xr[8];
+#pragma unroll
+            for (int l = 0; l < 8; ++l) xr[l] = l < ds ? xv[l] : 0.0f;
+            for (int i = 0; i < kj; ++i) {
+                float acc = 0.0f;
+#pragma unroll
+                for (int l = 0; l < 8; ++l) {
+                    if (l < ds) {
+                        const float diff = __fsub_rn(xr[l], c[i * ds + l]);
+                        acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                    }
+                }
+                if (i == 0 || acc < best) {
+                    best = acc;
+                    besti = i;
+                }
+            }
+        } else {
+            for (int i = 0; i < kj; ++i) {
+                float acc = 0.0f;
+                for (int l = 0; l < ds; ++l) {
+                    const float diff = __fsub_rn(xv[l], c[i * ds + l]);
+                    acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                }
+                if (i == 0 || acc < best) {
+                    best = acc;
+                    besti = i;
+                }
+            }
+        }
+        if (v < nv) sub[v * m + j] = (uint8_t)besti;
+    }
+    __syncthreads();
+
+    // pack: one output byte per thread and round
+    for (int e = threadIdx.x; e < nv * cs; e += blockDim.x) {
+        const int vv = e / cs, b = e - vv * cs;
+        uint32_t byte = 0;
+        for (int j = 0; j < m; ++j) {
+            const int off = L->bitoff[j], nb = L->nbits[j];
+            if (off + nb <= 8 * b || off >= 8 * b + 8) continue;
+            const uint32_t val = sub[vv * m + j];
+            const int rel = off - 8 * b;  // position of the sub-code's bit 0 relative to this byte
+            byte |= rel >= 0 ? (val << rel) : (val >> (-rel));
+        }
+        codes[(size_t)v0 * cs + e] = (uint8_t)(byte & 255u);
+    }
+}
+
+extern "C" int pq_encode(const pq_index_t *idx, const float *vectors, int64_t n,
+                         const float *shift_rows, const int32_t *shift_ids, uint8_t *codes,
+                         void *stream) {
+    if (!idx || n < 0) {
+        qadc_set_error("pq_encode: bad handle or n");
+        return PQ_EINVAL;
+    }
+    if (n == 0) return PQ_OK;
+    if (!vectors || !codes || ((shift_rows == nullptr) != (shift_ids == nullptr))) {
+        qadc_set_error("pq_encode: null pointer (shift_rows and shift_ids go together)");
+        return PQ_EINVAL;
+    }
+    const DevLayout &h = idx->h;
+    const size_t lds = (size_t)ENC_VB * (size_t)(h.d | 1) * sizeof(float) + (size_t)ENC_VB * (size_t)h.m;
+    if (lds > 160 * 1024) {
+        qadc_set_error("pq_encode: d=%d needs %zu bytes of LDS per block, more than 163840", h.d, lds);
+        return PQ_EINVAL;
+    }
+    if (lds > 48 * 1024)
+        QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_encode, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)lds));
+    const int64_t blocks = (n + ENC_VB - 1) / ENC_VB;
+    if (blocks > 0x7fffffffLL) {
+        qadc_set_error("pq_encode: n=%lld too large for one call", (long long)n);
+        return PQ_EINVAL;
+    }
+    hipLaunchKernelGGL(k_encode, dim3((unsigned)blocks), dim3(256), lds, (hipStream_t)stream, idx->dev,
+                       idx->codebooks, vectors, n, shift_rows, shift_ids, codes);
+    QADC_LAUNCH_CHECK("k_encode");
+    return PQ_OK;
+}
