@@ -51,7 +51,7 @@ def parse():
     ap.add_argument("--unfused", action="store_true",
                     help="issue pq_compute_tables, pq_quantize_tables and pq_adc_scan_topk as three "
                          "calls instead of the fused pq_search_topk (same arithmetic)")
-    ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4", "C4coarse", "L8x8", "L664", "L655", "L16x8", "L664x2"],
+    ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4", "C4coarse", "C1encode", "L8x8", "L664", "L655", "L16x8", "L664x2"],
                     help="C4 is the inverted-list search (ivf_adc_scan_topk); a step is one batch of "
                          "--batch queries (default there: 1000)")
     ap.add_argument("--kmeans-iters", type=int, default=3,
@@ -245,6 +245,8 @@ def main():
         return main_ivf(a)
     if a.workload == "C4coarse":
         return main_coarse(a)
+    if a.workload == "C1encode":
+        return main_encode(a)
     import numpy as np
     import torch
     from paper_1812_09162_amd import binding as qb, synth
@@ -463,6 +465,53 @@ def main_coarse(a):
                      "achieved": flops / (ms * 1e-3) / 1e12, "peak": 157.3, "unit": "TFLOP/s",
                      "frac": flops / (ms * 1e-3) / 1e12 / 157.3, "traffic": None,
                      "call_ms_by_events": ms, "flops_per_call": flops},
+    }))
+
+
+def main_encode(a):
+    """Index build side of workload C1: 10,000,000 vectors of d = 96 encoded to 16x4 codes
+    (pq_encode).  A step is one call over all vectors.  Roofline: vector ALU.  eq. (1) read
+    literally is a subtract, a multiply and an add per (centroid, dimension), none fused or
+    packed, so the ceiling is one such operation per lane and cycle: 256 CUs x 4 SIMDs x 16
+    lanes x 2.4 GHz = 39.3 T operations/s."""
+    import torch
+    from paper_1812_09162_amd import binding as qb, synth
+    assert torch.cuda.is_available(), "bench.py needs the GPU; there is no CPU fallback"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = synth.scaled("C1", n=100_000, nq=1)
+    pr = synth.build(cfg, device=dev)
+    lay = pr.layout
+    n = a.n or 10_000_000
+    g = torch.Generator(device=dev).manual_seed(18120922)
+    x = torch.randn((n, lay.d), generator=g, device=dev, dtype=torch.float32)
+    idx = qb.PqIndex(lay.d, lay.nbits, lay.dsub, pr.codebooks, lay.acc_bits)
+    codes = torch.empty((n, idx.code_size), dtype=torch.uint8, device=dev)
+    steps = min(a.steps, 20)
+    for _ in range(2):
+        qb.pq_encode(idx, x, codes=codes)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        qb.pq_encode(idx, x, codes=codes)
+    e1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = e0.elapsed_time(e1) / steps
+    nbytes = float(n) * (lay.d * 4 + idx.code_size)
+    ops = float(n) * 3.0 * sum((1 << b) * s for b, s in zip(lay.nbits, lay.dsub))
+    print(json.dumps({
+        "metric": "vectors encoded/sec per GPU (PQ 16x4, d=96)",
+        "value": n * steps / dt, "unit": "vectors/s", "n_gpus": 1, "steps": steps, "warmup": 2,
+        "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"C1encode: n={n}, d={lay.d}, m={lay.m}, bits=4, entry=pq_encode", "seed": 18120922},
+        "roofline": {"bound": "alu", "kernel": "k_encode", "achieved": ops / (ms * 1e-3) / 1e12,
+                     "peak": 39.3, "unit": "TFLOP/s", "frac": ops / (ms * 1e-3) / 1e12 / 39.3,
+                     "traffic": None, "kernel_avg_ms": ms, "flops_per_launch": ops,
+                     "hbm_gb_per_s": nbytes / (ms * 1e-3) / 1e9},
     }))
 
 

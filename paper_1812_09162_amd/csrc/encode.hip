@@ -6,9 +6,10 @@
 // fp32, dimensions ascending, separate subtract / multiply / add.  Sub-code j is the index of
 // the smallest distance, the lowest index among equals.
 //
-// One block of 256 threads encodes 64 vectors: they are staged (minus the shift) in LDS; wave w
-// takes the sub-quantizers w, w+4, ... and lane v the vector v, so that centroid values are
-// uniform across a wave and come through scalar loads; a second step packs the sub-codes.
+// One block of 256 threads encodes 64 vectors: they are staged (minus the shift) in LDS, and so
+// are the codebooks when they fit; wave w takes the sub-quantizers w, w+4, ... and lane v the
+// vector v, so that centroid values are uniform across a wave (one LDS word broadcast to 64
+// lanes); a second step packs the sub-codes.
 #include "qadc_device.h"
 
 #define ENC_VB 64  // vectors per block
@@ -16,12 +17,13 @@
 __global__ void __launch_bounds__(256)
 k_encode(const DevLayout *__restrict__ L, const float *__restrict__ cb,
          const float *__restrict__ x, int64_t n, const float *__restrict__ shift_rows,
-         const int32_t *__restrict__ shift_ids, uint8_t *__restrict__ codes) {
+         const int32_t *__restrict__ shift_ids, uint8_t *__restrict__ codes, int cb_floats) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int d = L->d, m = L->m, cs = L->cs;
     const int ldx = d | 1;  // odd row stride: lanes of a wave (consecutive vectors) hit distinct banks
     float *xs = (float *)smem;                             // [ENC_VB][ldx]
-    uint8_t *sub = (uint8_t *)(xs + (size_t)ENC_VB * ldx);  // [ENC_VB][m]
+    float *cbs = xs + (size_t)ENC_VB * ldx;                 // [cb_floats] (0 if they do not fit)
+    uint8_t *sub = (uint8_t *)(cbs + cb_floats);            // [ENC_VB][m]
     const int64_t v0 = (int64_t)blockIdx.x * ENC_VB;
     const int nv = n - v0 < ENC_VB ? (int)(n - v0) : ENC_VB;
 
@@ -31,12 +33,13 @@ k_encode(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         if (shift_rows) val = __fsub_rn(val, shift_rows[(size_t)shift_ids[v0 + v] * d + l]);
         xs[v * ldx + l] = val;
     }
+    for (int e = threadIdx.x; e < cb_floats; e += blockDim.x) cbs[e] = cb[e];
     __syncthreads();
 
     const int v = threadIdx.x % ENC_VB, w = threadIdx.x / ENC_VB;
     for (int j = w; j < m; j += 4) {
         const int ds = L->dsub[j], kj = 1 << L->nbits[j];
-        const float *c = cb + L->cboff[j];
+        const float *c = (cb_floats ? (const float *)cbs : cb) + L->cboff[j];
         const float *xv = xs + v * ldx + L->dimoff[j];
         float best = INFINITY;
         int besti = 0;
@@ -103,7 +106,11 @@ extern "C" int pq_encode(const pq_index_t *idx, const float *vectors, int64_t n,
         return PQ_EINVAL;
     }
     const DevLayout &h = idx->h;
-    const size_t lds = (size_t)ENC_VB * (size_t)(h.d | 1) * sizeof(float) + (size_t)ENC_VB * (size_t)h.m;
+    size_t cbf = 0;  // codebook floats
+    for (int j = 0; j < h.m; ++j) cbf += ((size_t)1 << h.nbits[j]) * (size_t)h.dsub[j];
+    const size_t base_lds = (size_t)ENC_VB * (size_t)(h.d | 1) * sizeof(float) + (size_t)ENC_VB * (size_t)h.m;
+    if (cbf * sizeof(float) > 48 * 1024 || base_lds + cbf * sizeof(float) > 96 * 1024) cbf = 0;
+    const size_t lds = base_lds + cbf * sizeof(float);
     if (lds > 160 * 1024) {
         qadc_set_error("pq_encode: d=%d needs %zu bytes of LDS per block, more than 163840", h.d, lds);
         return PQ_EINVAL;
@@ -117,7 +124,7 @@ extern "C" int pq_encode(const pq_index_t *idx, const float *vectors, int64_t n,
         return PQ_EINVAL;
     }
     hipLaunchKernelGGL(k_encode, dim3((unsigned)blocks), dim3(256), lds, (hipStream_t)stream, idx->dev,
-                       idx->codebooks, vectors, n, shift_rows, shift_ids, codes);
+                       idx->codebooks, vectors, n, shift_rows, shift_ids, codes, (int)cbf);
     QADC_LAUNCH_CHECK("k_encode");
     return PQ_OK;
 }

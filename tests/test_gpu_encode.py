@@ -34,7 +34,7 @@ def layout_and_codebooks(d, nbits, seed, integer=False):
     (128, [4] * 16), (96, [4] * 16), (128, [4] * 32), (128, synth.C3_BITS), (128, [8] * 8),
     (128, [6, 6, 4] * 8), (13, [3, 7, 1, 2]), (64, [8] * 16), (256, [4] * 16), (15, [5, 5, 5]),
 ])
-@pytest.mark.parametrize("n", [1, 63, 64, 65, 1000])
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 127, 129, 1000])
 def test_encode_bit_exact(qb, d, nbits, n):
     lay, cb = layout_and_codebooks(d, nbits, seed=len(nbits) + d)
     rng = np.random.default_rng(n)
