@@ -18,6 +18,7 @@
  *   O6  inverted-list search       Section 2.1.1 (residuals), Section 2.1.3
  *                                  (one table set per probed cell)
  *   O7  coarse-quantizer search    Section 2.1.1 (the cells a query is routed to)
+ *   O8  encoding and packing       Sections 2.1.2, 2.1.1, 3.3
  *
  * Precision: the paper stores tables as 32-bit floats (Section 3.4, first
  * paragraph), so table entries and float ADC sums are fp32, evaluated in a
