@@ -84,27 +84,28 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     if (KIND == SCAN_NIB8 || KIND == SCAN_W64) {
         // 16-byte chunks of two codes, U8 chunks per thread and tile (U8*16 bytes per lane in
         // flight); an odd last code is handled after the loop
+        // (chunk indices fit 32 bits: ids are int32, so n < 2^31)
         constexpr int U = U8;
-        const int64_t nfull = n >> 1;
-        const int64_t ntiles = (nfull + U * SCAN_THREADS - 1) / (U * SCAN_THREADS);
+        const int nfull = (int)(n >> 1);
+        const int ntiles = (nfull + U * SCAN_THREADS - 1) / (U * SCAN_THREADS);
         const uint4 *__restrict__ p = (const uint4 *)codes;
         uint4 cur[U];
-        int64_t tile = b;
-        auto load_tile = [&](int64_t t) {
+        int tile = b;
+        auto load_tile = [&](int t) {  // t < ntiles, hence nfull >= 1; past the end: the last chunk again
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t c = t * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
-                cur[u] = (t < ntiles && c < nfull) ? p[c] : make_uint4(0, 0, 0, 0);
+                const int c = t * (U * SCAN_THREADS) + u * SCAN_THREADS + (int)threadIdx.x;
+                cur[u] = p[c < nfull ? c : nfull - 1];
             }
         };
-        load_tile(tile);  // the first tile is in flight while the tables are staged
+        if (tile < ntiles) load_tile(tile);  // in flight while the tables are staged
         load_gtab<QT>(gsrc, gtab_len, gtab);
         while (tile < ntiles) {
             uint32_t s[2 * U];
             bool pass[2 * U], any = false;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                const int c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + (int)threadIdx.x;
                 if (KIND == SCAN_NIB8) {
                     s[2 * u] = sum8(gtab, cur[u].x, cur[u].y);
                     s[2 * u + 1] = sum8(gtab, cur[u].z, cur[u].w);
@@ -123,7 +124,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 uint32_t id[2 * U];
 #pragma unroll
                 for (int u = 0; u < 2 * U; ++u) {
-                    const int64_t c = tile * (U * SCAN_THREADS) + (u >> 1) * SCAN_THREADS + threadIdx.x;
+                    const int c = tile * (U * SCAN_THREADS) + (u >> 1) * SCAN_THREADS + (int)threadIdx.x;
                     id[u] = (uint32_t)(2 * c + (u & 1));
                 }
                 slot_append_multi<2 * U>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
