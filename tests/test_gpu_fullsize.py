@@ -88,6 +88,12 @@ def test_c3_full_size(qb):
     run_flat(qb, "C3", [100], nq_oracle=4)
 
 
+@pytest.mark.parametrize("name", ["L8x8", "L664", "L16x8", "L664x2"])
+def test_further_layouts_full_size(qb, name):
+    """The 64- and 128-bit layouts bench.py offers as workloads, at their 10^7 codes."""
+    run_flat(qb, name, [100], nq_oracle=2, nq_gpu=32)
+
+
 def run_ivf(qb, cfg, nq_oracle, R=100):
     ip = synth.build(cfg, device=dev())
     lay = ip.layout
