@@ -340,6 +340,10 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, a.batch)), "kernel_avg_ms": k_avg_ms, "launches": k_cnt,
                      "algorithmic_bytes_per_launch": alg_bytes},
         "batched": extras,
+        # the paper's own figure for this layout, another machine and size: context, not a baseline
+        "paper_context": {"value": 1.89, "unit": "Gcodes/s",
+                          "what": "Table 3, m x {4,4} 64-bit codes, uint8, AVX-512BW shuffles: 0.53 ms per "
+                                  "query over 1,000,000 codes, one core of a Xeon Platinum 8175 (Section 4.1)"},
     }
 
     if not a.no_cpu_baseline:
