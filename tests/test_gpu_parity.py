@@ -104,6 +104,42 @@ def test_other_layouts_bit_exact(qb, nbits, d, acc):
     check_against_oracle(qb, pr, 50)
 
 
+def _random_layouts(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        m = int(rng.integers(1, 25))
+        nbits = [int(b) for b in rng.integers(1, 9, m)]
+        if sum(1 << b for b in nbits) > 4096:
+            continue
+        d = -(-sum(nbits) // min(nbits)) + int(rng.integers(0, 40))  # every sub-space gets a dimension
+        out.append((nbits, d, int(rng.choice([8, 16])), int(rng.integers(1, 4000)), int(rng.choice([1, 7, 64]))))
+    return out
+
+
+@pytest.mark.parametrize("nbits,d,acc,n,R", _random_layouts(24, seed=20240607))
+def test_random_layouts_all_stages_and_fused_and_encode(qb, nbits, d, acc, n, R):
+    """Arbitrary sub-quantizer widths (1..8 bits, any order), dimensions, list lengths: every
+    stage, the fused call and the encoder against the oracle."""
+    pr = synth.make_problem(n=n, nq=2, d=d, nbits=nbits, acc_bits=acc, dist="gamma_ints",
+                            seed=len(nbits) * 131 + d, train_n=max(300, min(n, 1500)), kmeans_iters=2)
+    check_against_oracle(qb, pr, R)
+    lay = pr.layout
+    idx = make_index(qb, pr)
+    fused = qb.pq_search_topk(idx, pr.queries.to(dev()), pr.codes.to(dev()), T_CAL, R)
+    rng = np.random.default_rng(n)
+    x = rng.integers(0, 40, (257, d)).astype(np.float32)
+    enc = qb.pq_encode(idx, torch.from_numpy(x).to(dev()))
+    torch.cuda.synchronize()
+    for q in range(2):
+        oi, ok, od = oracle.search(lay.d, lay.nbits, lay.dsub, lay.acc_bits, pr.codebooks.numpy(),
+                                   pr.queries[q].numpy(), pr.codes.numpy(), T_CAL, R)
+        assert np.array_equal(fused[0][q].cpu().numpy(), oi)
+        assert np.array_equal(fused[2][q].cpu().numpy(), od)
+    assert np.array_equal(enc.cpu().numpy(), oracle.encode(lay.d, lay.nbits, lay.dsub, pr.codebooks.numpy(), x))
+    idx.close()
+
+
 @pytest.mark.parametrize("n", [0, 1, 2, 3, 63, 99, 100, 101, 1023, 1024, 1025, 2049])
 @pytest.mark.parametrize("name", ["C0", "C2", "C3"])
 def test_tiny_and_ragged_sizes(qb, name, n):
