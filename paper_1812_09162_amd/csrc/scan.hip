@@ -371,6 +371,159 @@ k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__res
         ((uint32_t *)(ws + (size_t)(q0 + threadIdx.x) * per_query))[b] = s_count[threadIdx.x];
 }
 
+// ------------------------------------------------------------- k_scan_mqg ---
+// The same for the irregular layouts (5-, 8- and 16-byte codes with group descriptors, 8- or
+// 16-bit tables): entry e of the interleaved table holds the four queries' values of group
+// table entry e as {u16 q0, u16 q1, u16 q2, u16 q3}; a code's four sums live in two packed words.
+typedef unsigned short mq_u16x2 __attribute__((ext_vector_type(2)));
+// a += b on both 16-bit halves, saturating at 65535 (one packed instruction)
+__device__ __forceinline__ uint32_t mq_add_sat16(uint32_t a, uint32_t b) {
+    const mq_u16x2 r = __builtin_elementwise_add_sat(__builtin_bit_cast(mq_u16x2, a), __builtin_bit_cast(mq_u16x2, b));
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// Sums of four queries as two packed words: a = q0 | q1 << 16, b = q2 | q3 << 16.  8-bit tables:
+// plain adds (at most 16 groups of at most 255 cannot carry).  16-bit tables: saturating packed
+// adds, which is the saturating accumulation of Section 3.4 itself (q_max = 65535).
+template <typename QT>
+struct MqAcc {
+    uint32_t a, b;
+    __device__ __forceinline__ void zero() { a = b = 0; }
+    __device__ __forceinline__ void add(const uint2 e) {
+        if (sizeof(QT) == 1) {
+            a += e.x;
+            b += e.y;
+        } else {
+            a = mq_add_sat16(a, e.x);
+            b = mq_add_sat16(b, e.y);
+        }
+    }
+    __device__ __forceinline__ uint32_t sum(int j) const {
+        return j == 0 ? (a & 0xffffu) : j == 1 ? (a >> 16) : j == 2 ? (b & 0xffffu) : (b >> 16);
+    }
+};
+
+template <int NG, int NLO, typename QT>
+__device__ __forceinline__ void mq_add_groups(const GroupDesc &d, const uint2 *tab, uint32_t lo,
+                                              uint32_t hi, bool upper, MqAcc<QT> &acc) {
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        const uint32_t x = NLO >= 0 ? (g < NLO ? lo : hi) : (d.off[g] >= 32 ? hi : lo);
+        const int base = upper ? d.base2[g] : d.base[g];
+        acc.add(tab[base + __builtin_amdgcn_ubfe(x, (uint32_t)(d.off[g] & 31), (uint32_t)d.w[g])]);
+    }
+}
+
+template <int KIND, typename QT, int NG, int MODE>
+__global__ void __launch_bounds__(SCAN_THREADS)
+k_scan_mqg(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__restrict__ codes,
+           int64_t n, char *__restrict__ ws, size_t per_query, size_t slots_off, size_t gtab_off,
+           int cap_b, int gtab_len, uint32_t qmax, GroupDesc gd) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint2 *tab = (uint2 *)smem;  // [gtab_len]
+    __shared__ uint32_t s_count[MQ];
+    constexpr int NLO = MODE == 1 ? NG / 2 : (MODE == 2 ? NG - 1 : -1);
+    constexpr int NC = KIND == SCAN_W128 ? 2 : 4;  // codes per thread and tile
+    const int q0 = blockIdx.y * MQ;
+    const int b = blockIdx.x, G = gridDim.x;
+    uint32_t thr[MQ];
+    uint64_t *slot[MQ];
+    const QT *src[MQ];
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) {
+        const size_t q = (q0 + j < nq) ? q0 + j : q0;
+        uint32_t t = qparams[q].key_bound;
+        thr[j] = t > qmax ? qmax : t;
+        slot[j] = (uint64_t *)(ws + q * per_query + slots_off) + (size_t)b * cap_b;
+        src[j] = (const QT *)(ws + q * per_query + gtab_off);
+    }
+    if (threadIdx.x < MQ) s_count[threadIdx.x] = 0;
+    for (int e = threadIdx.x; e < gtab_len; e += SCAN_THREADS) {
+        uint2 v;
+        v.x = (uint32_t)src[0][e] | ((uint32_t)src[1][e] << 16);
+        v.y = (uint32_t)src[2][e] | ((uint32_t)src[3][e] << 16);
+        tab[e] = v;
+    }
+    __syncthreads();
+
+    // tiles of NC * SCAN_THREADS codes; thread t takes the codes NC*t .. NC*t+NC-1 of a tile
+    const int ntiles = (int)((n + NC * SCAN_THREADS - 1) / (NC * SCAN_THREADS));
+    for (int tile = b; tile < ntiles; tile += G) {
+        const int64_t first = ((int64_t)tile * SCAN_THREADS + threadIdx.x) * NC;  // first code of this thread
+        MqAcc<QT> acc[NC];
+#pragma unroll
+        for (int i = 0; i < NC; ++i) acc[i].zero();
+        if (KIND == SCAN_W64) {
+            // four 8-byte codes: two 16-byte loads (first is a multiple of 4 and the array is
+            // 16-byte aligned); code by code in the ragged last tile
+            uint2 cw[4];
+            if (first + 3 < n) {
+                const uint4 x0 = *(const uint4 *)(codes + first * 8);
+                const uint4 x1 = *(const uint4 *)(codes + first * 8 + 16);
+                cw[0] = make_uint2(x0.x, x0.y);
+                cw[1] = make_uint2(x0.z, x0.w);
+                cw[2] = make_uint2(x1.x, x1.y);
+                cw[3] = make_uint2(x1.z, x1.w);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    cw[i] = first + i < n ? *(const uint2 *)(codes + (first + i) * 8) : make_uint2(0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mq_add_groups<NG, NLO, QT>(gd, tab, cw[i].x, cw[i].y, false, acc[i]);
+        } else if (KIND == SCAN_C5) {
+            // five dwords: four 5-byte codes (first is a multiple of 4, so the chunk is 4-byte aligned)
+            uint32_t w[5] = {0, 0, 0, 0, 0};
+            if (first + 3 < n) {
+                const uint32_t *p = (const uint32_t *)(codes + first * 5);
+#pragma unroll
+                for (int i = 0; i < 5; ++i) w[i] = p[i];
+            } else {
+                for (int i = 0; i < 20; ++i)
+                    if (first * 5 + i < n * 5) w[i >> 2] |= (uint32_t)codes[first * 5 + i] << (8 * (i & 3));
+            }
+            uint32_t lo[4], hi[4];
+            lo[0] = w[0];
+            hi[0] = w[1] & 0xffu;
+            lo[1] = __builtin_amdgcn_alignbit(w[2], w[1], 8);
+            hi[1] = (w[2] >> 8) & 0xffu;
+            lo[2] = __builtin_amdgcn_alignbit(w[3], w[2], 16);
+            hi[2] = (w[3] >> 16) & 0xffu;
+            lo[3] = __builtin_amdgcn_alignbit(w[4], w[3], 24);
+            hi[3] = w[4] >> 24;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mq_add_groups<NG, NLO, QT>(gd, tab, lo[i], hi[i], false, acc[i]);
+        } else {
+            // two 16-byte codes
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int64_t c = first + i < n ? first + i : (n > 0 ? n - 1 : 0);
+                const uint4 w = *(const uint4 *)(codes + c * 16);
+                mq_add_groups<NG, NLO, QT>(gd, tab, w.x, w.y, false, acc[i]);
+                mq_add_groups<NG, NLO, QT>(gd, tab, w.z, w.w, true, acc[i]);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < MQ; ++j) {
+            bool pass[NC], any = false;
+            uint32_t key[NC], id[NC];
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                const uint32_t sm = acc[i].sum(j);
+                key[i] = sm > qmax ? qmax : sm;
+                id[i] = (uint32_t)(first + i);
+                pass[i] = first + i < n && key[i] <= thr[j] && (q0 + j < nq);
+                any = any || pass[i];
+            }
+            if (__ballot(any) != 0)
+                slot_append_multi<NC>(pass, key, id, slot[j], (uint32_t)cap_b, &s_count[j]);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < MQ && q0 + (int)threadIdx.x < nq)
+        ((uint32_t *)(ws + (size_t)(q0 + threadIdx.x) * per_query))[b] = s_count[threadIdx.x];
+}
+
 // --------------------------------------------------------------- k_final ---
 struct FinalOut {
     int32_t *ids;
@@ -558,8 +711,8 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
                            idx->dev, qtables, ws, p.per_query, p.gtab_off);
         QADC_LAUNCH_CHECK("k_prepare");
     }
-    if ((what & 1) && sizeof(QT) == 1 && nq >= 2 && (KIND == SCAN_NIB8 || KIND == SCAN_NIB16) &&
-        !getenv("QADC_NO_MQ")) {
+    static const bool no_mq_nib = getenv("QADC_NO_MQ") != nullptr;
+    if ((what & 1) && sizeof(QT) == 1 && nq >= 2 && (KIND == SCAN_NIB8 || KIND == SCAN_NIB16) && !no_mq_nib) {
         // several queries: four of them share every pass over the codes
         const int groups = (nq + MQ - 1) / MQ;
         if (KIND == SCAN_NIB8)
@@ -602,6 +755,33 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
             if (mode == 1) QADC_SCAN_GO(NGV, 1); else QADC_SCAN_GO(NGV, 0); \
         }                                                            \
     } while (0)
+        // several queries over an irregular layout: four of them share every pass over the codes
+        static const bool no_mq = getenv("QADC_NO_MQ") != nullptr;
+        const size_t mq_lds = (size_t)h.gtab_len * sizeof(uint2);
+        const bool mqg = nq >= 2 && ngt > 0 && mq_lds <= 96 * 1024 && !no_mq &&
+                         (KIND == SCAN_W64 || KIND == SCAN_C5 || KIND == SCAN_W128);
+#define QADC_MQG_GO(NGV, MODEV)                                                                      \
+    do {                                                                                             \
+        if (mq_lds > 48 * 1024)                                                                      \
+            QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_scan_mqg<KIND, QT, NGV, MODEV>,         \
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)mq_lds)); \
+        hipLaunchKernelGGL((k_scan_mqg<KIND, QT, NGV, MODEV>), dim3(p.G, (nq + MQ - 1) / MQ),        \
+                           dim3(SCAN_THREADS), mq_lds, s, qparams, nq, codes, n, ws, p.per_query,    \
+                           p.slots_off, p.gtab_off, p.cap_b, h.gtab_len, (uint32_t)h.qmax, gd);      \
+    } while (0)
+#define QADC_SCAN_ANY(NGV, MODEV)                                       \
+    do {                                                                \
+        if (mqg) QADC_MQG_GO(NGV, MODEV); else QADC_SCAN_GO(NGV, MODEV); \
+    } while (0)
+#undef QADC_SCAN_NG
+#define QADC_SCAN_NG(NGV)                                              \
+    do {                                                               \
+        if (KIND == SCAN_C5) {                                         \
+            if (mode == 2) QADC_SCAN_ANY(NGV, 2); else QADC_SCAN_ANY(NGV, 0); \
+        } else {                                                       \
+            if (mode == 1) QADC_SCAN_ANY(NGV, 1); else QADC_SCAN_ANY(NGV, 0); \
+        }                                                              \
+    } while (0)
         if (KIND == SCAN_W64 || KIND == SCAN_C5 || KIND == SCAN_W128) {
             switch (ngt) {
                 case 1: QADC_SCAN_NG(1); break;
@@ -617,6 +797,8 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
         } else {
             QADC_SCAN_GO(0, 0);
         }
+#undef QADC_MQG_GO
+#undef QADC_SCAN_ANY
 #undef QADC_SCAN_GO
 #undef QADC_SCAN_NG
         QADC_LAUNCH_CHECK("k_scan");

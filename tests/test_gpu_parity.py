@@ -203,6 +203,34 @@ def test_batch_sizes_give_identical_results(qb):
     idx.close()
 
 
+@pytest.mark.parametrize("nbits,d,acc", [
+    (synth.C3_BITS, 128, 16), (synth.C3_BITS, 128, 8), ([6, 6, 4] * 4, 128, 16), ([8] * 8, 64, 8),
+    ([6, 5, 5] * 4, 96, 16), ([8] * 16, 64, 16), ([6, 6, 4] * 8, 128, 8), ([7, 7, 7, 7, 4] * 2, 64, 16),
+    ([3, 7, 1, 2], 13, 8),
+])
+@pytest.mark.parametrize("n", [50_003, 6])
+def test_irregular_layouts_batched_equals_single_and_oracle(qb, nbits, d, acc, n):
+    """Batches of irregular-layout queries share passes over the codes four at a time; results
+    must not depend on the batching (11 = two full groups and a ragged one)."""
+    pr = synth.make_problem(n=n, nq=11, d=d, nbits=nbits, acc_bits=acc, dist="gamma_ints",
+                            seed=77 + len(nbits), train_n=min(n, 3000) if n > 300 else 300, kmeans_iters=2)
+    idx = make_index(qb, pr)
+    codes_d = pr.codes.to(dev())
+    qd = pr.queries.to(dev())
+    R = 20
+    full = gpu_search(qb, idx, qd, codes_d, R)
+    fused = qb.pq_search_topk(idx, qd, codes_d, T_CAL, R)
+    for q in (0, 3, 4, 10):
+        one = gpu_search(qb, idx, qd[q:q + 1].contiguous(), codes_d, R)
+        for a, b, c in zip(full[3:], one[3:], fused):
+            assert torch.equal(a[q:q + 1], b) and torch.equal(a[q], c[q])
+    pair = gpu_search(qb, idx, qd[5:7].contiguous(), codes_d, R)
+    for a, b in zip(full[3:], pair[3:]):
+        assert torch.equal(a[5:7], b)
+    check_against_oracle(qb, pr, R, queries=pr.queries[:5], stagewise=False)
+    idx.close()
+
+
 @pytest.mark.parametrize("name,n,R", [("C0", 60_001, 100), ("C2", 20_000, 1000), ("C3", 25_000, 10)])
 def test_fused_search_equals_three_calls_and_oracle(qb, name, n, R):
     pr = synth.build(synth.scaled(name, n=n, nq=5))
