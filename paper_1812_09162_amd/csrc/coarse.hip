@@ -12,21 +12,31 @@
 // them the ranking, are reproducible by a scalar fmaf loop.
 //
 //   k_cnorm    ||c||^2 per centroid
-//   k_scores   128 x 128 score tiles per block of four waves, each wave a 64 x 64 quarter as
-//              2 x 2 MFMA tiles; operands staged through LDS in chunks of 32 dimensions, the
-//              next chunk prefetched into registers while the current one is multiplied
+//   k_scores   128 x 256 (queries x cells) score tiles per block of four waves, each wave a
+//              64 x 128 part as 2 x 4 MFMA tiles; operands staged through LDS in chunks of 32
+//              dimensions, the next chunk prefetched into registers while the current one is
+//              multiplied
 //   k_select   one block per query: the cells in the low tail of the score range are gathered
 //              and ranked by (score, id); exact radix selection when that tail is crowded
+// For large K the score matrix is never written.  A pilot (the first P cells, through the two
+// kernels above) gives every query a bound: the nprobe-th smallest pilot score, which no result
+// can exceed.  k_scores then runs over all cells in its filtering form: a score within the bound
+// goes, as (ordered score << 32 | cell), to a short private list per (query, block of 256
+// cells); k_select_cand gathers a query's lists and ranks them.  If a list overflows (far more
+// near cells in one block than the pilot predicts), a flag sends the whole pass of queries
+// through the matrix form again, which is exact for any input.
 #include <math.h>
 #include <string.h>
 
-#include "qadc_device.h"
+#include "scan_device.h"
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-#define CS_TILE 128   // queries and centroids per block tile
+#define CS_TQ 128     // queries per block tile
+#define CS_TC 256     // cells per block tile
 #define CS_KC 32      // dimensions per LDS chunk
 #define CS_MAX_NPROBE 1024
+#define CS_SLOT 32    // candidate slots per (query, block of CS_TC cells) in the filtering form
 
 // --------------------------------------------------------------------- k_cnorm ---
 __global__ void __launch_bounds__(256)
@@ -42,15 +52,17 @@ k_cnorm(const float *__restrict__ centroids, int K, int d, float *__restrict__ c
 // -------------------------------------------------------------------- k_scores ---
 // scores[q][c] for q in [q0, q0 + nqc), c in [0, K); row stride ld (floats).
 // LDS: As[k][row], Bs[k][col], k-major so that the 32 lanes of an MFMA operand read 32
-// consecutive floats.
+// consecutive floats; rows of an odd number of floats ( so that the transposing stores spread over
+// the banks).  Global loads: eight adjacent lanes fetch the 128 contiguous bytes that one row
+// contributes to a chunk, so every cache line is requested once.
+template <int NI>  // rows rowb + 32 i, i < NI: a tile of 32 NI rows
 __device__ __forceinline__ void cs_load_chunk(const float *__restrict__ base, int rows_valid, int d,
-                                              int k0, bool vec, float4 (&r)[4]) {
-    // wave w, lane l: row = w*32 + l%32, float4 columns (l/32)*4 + i, i < 4
-    const int w = threadIdx.x / QADC_WAVE, l = threadIdx.x % QADC_WAVE;
-    const int row = w * 32 + (l & 31);
+                                              int k0, bool vec, float4 (&r)[NI]) {
+    const int piece = threadIdx.x & 7, rowb = threadIdx.x >> 3;
+    const int k = k0 + piece * 4;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int k = k0 + ((l >> 5) * 4 + i) * 4;
+    for (int i = 0; i < NI; ++i) {
+        const int row = rowb + 32 * i;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
         if (row < rows_valid) {
             const float *p = base + (size_t)row * d + k;
@@ -67,76 +79,121 @@ __device__ __forceinline__ void cs_load_chunk(const float *__restrict__ base, in
     }
 }
 
-__device__ __forceinline__ void cs_store_chunk(float *S, const float4 (&r)[4]) {
-    const int w = threadIdx.x / QADC_WAVE, l = threadIdx.x % QADC_WAVE;
-    const int row = w * 32 + (l & 31);
+template <int NI>
+__device__ __forceinline__ void cs_store_chunk(float *S, const float4 (&r)[NI]) {
+    constexpr int LD = 32 * NI + 1;
+    const int piece = threadIdx.x & 7, rowb = threadIdx.x >> 3;
+    const int k = piece * 4;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int k = ((l >> 5) * 4 + i) * 4;
-        S[(k + 0) * CS_TILE + row] = r[i].x;
-        S[(k + 1) * CS_TILE + row] = r[i].y;
-        S[(k + 2) * CS_TILE + row] = r[i].z;
-        S[(k + 3) * CS_TILE + row] = r[i].w;
+    for (int i = 0; i < NI; ++i) {
+        const int row = rowb + 32 * i;
+        S[(k + 0) * LD + row] = r[i].x;
+        S[(k + 1) * LD + row] = r[i].y;
+        S[(k + 2) * LD + row] = r[i].z;
+        S[(k + 3) * LD + row] = r[i].w;
     }
 }
 
-__global__ void __launch_bounds__(256)
+// FILTER: scores are not stored; those <= bound[query] (bound = pilot[q * pstride + koff]) are
+// appended to slots[(q * ncb + block) * CS_SLOT ...] and counted in counts[q * ncb + block].
+// guard: if non-null and *guard == 0 the kernel does nothing (the matrix form as a fallback).
+template <bool FILTER>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ centroids, int K,
-         int d, const float *__restrict__ cnorm, float *__restrict__ scores, size_t ld, int vec) {
-    __shared__ float As[CS_KC * CS_TILE];
-    __shared__ float Bs[CS_KC * CS_TILE];
-    const int c0 = blockIdx.x * CS_TILE, q0 = blockIdx.y * CS_TILE;
+         int d, const float *__restrict__ cnorm, float *__restrict__ scores, size_t ld, int vec,
+         const float *__restrict__ pilot, int pstride, int koff, uint64_t *__restrict__ slots,
+         uint32_t *__restrict__ counts, const int *__restrict__ guard, int gx, int gy) {
+    if (guard && *guard == 0) return;
+    constexpr int LDA = CS_TQ + 1, LDB = CS_TC + 1;
+    __shared__ float As[CS_KC * LDA];
+    __shared__ float Bs[CS_KC * LDB];
+    __shared__ __align__(16) float s_bound[FILTER ? CS_TQ : 4];
+    __shared__ uint32_t s_cnt[FILTER ? CS_TQ : 1];
     const int w = threadIdx.x / QADC_WAVE, l = threadIdx.x % QADC_WAVE;
-    const int wr = w >> 1, wc = w & 1;  // this wave's 64 x 64 quarter
-    const float *qa = queries + (size_t)q0 * d;
-    const float *cb = centroids + (size_t)c0 * d;
-    const int qv = nqc - q0 < CS_TILE ? nqc - q0 : CS_TILE;
-    const int cv = K - c0 < CS_TILE ? K - c0 : CS_TILE;
-
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    float4 ra[4], rb[4];
-    cs_load_chunk(qa, qv, d, 0, vec != 0, ra);
-    cs_load_chunk(cb, cv, d, 0, vec != 0, rb);
-    for (int k0 = 0; k0 < d; k0 += CS_KC) {
-        __syncthreads();  // the previous chunk has been consumed
-        cs_store_chunk(As, ra);
-        cs_store_chunk(Bs, rb);
-        __syncthreads();
-        if (k0 + CS_KC < d) {  // next chunk in flight during the multiplications
-            cs_load_chunk(qa, qv, d, k0 + CS_KC, vec != 0, ra);
-            cs_load_chunk(cb, cv, d, k0 + CS_KC, vec != 0, rb);
-        }
-#pragma unroll
-        for (int kk = 0; kk < CS_KC; kk += 2) {
-            const int kr = (kk + (l >> 5)) * CS_TILE + (l & 31);
-            const float a0 = As[kr + wr * 64], a1 = As[kr + wr * 64 + 32];
-            const float b0 = Bs[kr + wc * 64], b1 = Bs[kr + wc * 64 + 32];
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
-        }
-    }
-    // element r of a 32 x 32 result: row (r/4)*8 + (lane/32)*4 + r%4, column lane%32
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int col = c0 + wc * 64 + j * 32 + (l & 31);
-        if (col >= K) continue;
-        const float cn = cnorm[col];
+    const int wr = w >> 1, wc = w & 1;  // this wave's 64 x 128 part: 2 x 4 MFMA tiles
+    const int ncb = gx;
+    const int nch = (d + CS_KC - 1) / CS_KC;
+    float4 ra[CS_TQ / 32], rb[CS_TC / 32];
+    {
+        const int tile = blockIdx.x;  // cell block tile % gx, query block tile / gx
+        const int c0 = (tile % gx) * CS_TC, q0 = (tile / gx) * CS_TQ, cbx = tile % gx;
+        auto load = [&](int kc) {
+            cs_load_chunk<CS_TQ / 32>(queries + (size_t)q0 * d, nqc - q0 < CS_TQ ? nqc - q0 : CS_TQ, d,
+                                      kc * CS_KC, vec != 0, ra);
+            cs_load_chunk<CS_TC / 32>(centroids + (size_t)c0 * d, K - c0 < CS_TC ? K - c0 : CS_TC, d,
+                                      kc * CS_KC, vec != 0, rb);
+        };
+        load(0);
+        f32x16 acc[2][4];
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = q0 + wr * 64 + i * 32 + (r >> 2) * 8 + (l >> 5) * 4 + (r & 3);
-                if (row < nqc) scores[(size_t)row * ld + col] = __fmaf_rn(-2.0f, acc[i][j][r], cn);
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+        if (FILTER && threadIdx.x < CS_TQ) {  // visible after the barriers of the first chunk
+            const int row = q0 + (int)threadIdx.x;
+            s_bound[threadIdx.x] = row < nqc ? pilot[(size_t)row * pstride + koff] : -INFINITY;
+            s_cnt[threadIdx.x] = 0;
+        }
+        for (int kc = 0; kc < nch; ++kc) {
+            __syncthreads();  // the previous chunk has been consumed
+            cs_store_chunk<CS_TQ / 32>(As, ra);
+            cs_store_chunk<CS_TC / 32>(Bs, rb);
+            __syncthreads();
+            if (kc + 1 < nch) load(kc + 1);  // in flight during the multiplications
+#pragma unroll
+            for (int kk = 0; kk < CS_KC; kk += 2) {
+                const int ka = (kk + (l >> 5)) * LDA + (l & 31) + wr * 64;
+                const int kb = (kk + (l >> 5)) * LDB + (l & 31) + wc * 128;
+                const float a0 = As[ka], a1 = As[ka + 32];
+                float bv[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bv[j] = Bs[kb + 32 * j];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, bv[j], acc[0][j], 0, 0, 0);
+                    acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, bv[j], acc[1][j], 0, 0, 0);
+                }
             }
+        }
+        // element r of a 32 x 32 result: row (r/4)*8 + (lane/32)*4 + r%4, column lane%32
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = c0 + wc * 128 + j * 32 + (l & 31);
+            if (col >= K) continue;
+            const float cn = cnorm[col];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    // four consecutive rows: their bounds come as one 16-byte LDS read
+                    const int rl0 = wr * 64 + i * 32 + r4 * 8 + (l >> 5) * 4;
+                    float bnd[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (FILTER) {
+                        const float4 b4 = *(const float4 *)&s_bound[rl0];
+                        bnd[0] = b4.x; bnd[1] = b4.y; bnd[2] = b4.z; bnd[3] = b4.w;
+                    }
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        const int rl = rl0 + rr, row = q0 + rl;
+                        const float sc = __fmaf_rn(-2.0f, acc[i][j][4 * r4 + rr], cn);
+                        if (!FILTER) {
+                            if (row < nqc) scores[(size_t)row * ld + col] = sc;
+                        } else if (sc <= bnd[rr]) {  // rows past the end have bound -inf
+                            const uint32_t pos = atomicAdd(&s_cnt[rl], 1u);
+                            if (pos < CS_SLOT)
+                                slots[((size_t)row * ncb + cbx) * CS_SLOT + pos] =
+                                    ((uint64_t)qadc_f2ord(sc) << 32) | (uint32_t)col;
+                        }
+                    }
+                }
+        }
+        if (FILTER) {
+            __syncthreads();
+            if (threadIdx.x < CS_TQ && q0 + (int)threadIdx.x < nqc)
+                counts[(size_t)(q0 + threadIdx.x) * ncb + cbx] = s_cnt[threadIdx.x];  // uncapped
+        }
     }
 }
 
@@ -184,9 +241,13 @@ __device__ inline void cs_rank_and_write(const uint64_t *A, int na, int k, int n
     }
 }
 
+// guard: if non-null and *guard == 0 the kernel does nothing.  clear: if non-null, set to 0.
 __global__ void __launch_bounds__(1024)
 k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
-         int32_t *__restrict__ probe_ids, float *__restrict__ probe_scores) {
+         int32_t *__restrict__ probe_ids, float *__restrict__ probe_scores,
+         const int *__restrict__ guard, int *__restrict__ clear) {
+    if (guard && *guard == 0) return;
+    if (clear && blockIdx.x == 0 && threadIdx.x == 0) *clear = 0;
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sel[2];
     __shared__ uint64_t A[CS_CAND];
@@ -357,6 +418,57 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
 #undef CS_KEYM
 }
 
+// ---------------------------------------------------------------- k_select_cand ---
+// One block of 1024 threads per query: gather the query's candidate lists (one per block of 256
+// cells), keep those up to the bin of the k-th, rank by (score, id).  Bins: 256 equal steps of
+// the ordered score between the pilot's best score and the bound.  An overflowing list, or more
+// candidates than fit, raises *flag.
+__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4)))
+k_select_cand(const uint32_t *__restrict__ counts, const uint64_t *__restrict__ slots, int ncb,
+              const float *__restrict__ pilot, int pstride, int koff, int K, int nprobe, int logw,
+              int32_t *__restrict__ probe_ids, float *__restrict__ probe_scores, int *__restrict__ flag) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint64_t *A = (uint64_t *)smem;  // FINAL_CAP entries
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t whist[16][256];
+    __shared__ uint32_t sh[32];
+    __shared__ uint32_t wsum[16];
+    const size_t q = blockIdx.x;
+    const int k = nprobe < K ? nprobe : K;
+    const uint32_t lo = qadc_f2ord(pilot[q * pstride]);
+    const uint32_t hi = qadc_f2ord(pilot[q * pstride + koff]);
+    const uint32_t span = hi - lo;
+    const int shift = span < 256u ? 0 : 24 - __clz(span);
+    FinalShared S;
+    S.hist = hist;
+    S.whist = whist;
+    S.sh = sh;
+    S.wsum = wsum;
+    S.off = nullptr;
+    auto binf = [lo, shift](uint64_t c) {
+        const uint32_t key = (uint32_t)(c >> 32);
+        const uint32_t b = key <= lo ? 0u : (key - lo) >> shift;
+        return b > 255u ? 255u : b;
+    };
+    int na = 0;
+    const int per_batch = (ncb + (1024 >> logw) - 1) / (1024 >> logw);
+    bool slow;
+    const uint32_t *cq = counts + q * ncb;
+    const uint64_t *sq = slots + q * ncb * CS_SLOT;
+    if (per_batch <= 8)
+        slow = gather_select_rows<8>(cq, sq, ncb, CS_SLOT, k, logw, binf, A, S, na);
+    else if (per_batch <= 16)
+        slow = gather_select_rows<16>(cq, sq, ncb, CS_SLOT, k, logw, binf, A, S, na);
+    else
+        slow = gather_select_rows<32>(cq, sq, ncb, CS_SLOT, k, logw, binf, A, S, na);
+    if (slow) {
+        if (threadIdx.x == 0) atomicOr(flag, 1);
+        return;
+    }
+    cs_rank_and_write(A, na, k, nprobe, probe_ids + q * nprobe,
+                      probe_scores ? probe_scores + q * nprobe : nullptr);
+}
+
 // ------------------------------------------------------------------------ host ---
 static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -364,16 +476,37 @@ static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 static int coarse_chunk(int nq, int K) {
     const size_t ld = ((size_t)K + 31) & ~(size_t)31;
     size_t qc = ((size_t)256 << 20) / (ld * sizeof(float));
-    qc = qc / CS_TILE * CS_TILE;
-    if (qc < CS_TILE) qc = CS_TILE;
-    const size_t nqr = ((size_t)(nq > 0 ? nq : 1) + CS_TILE - 1) / CS_TILE * CS_TILE;
+    qc = qc / CS_TQ * CS_TQ;
+    if (qc < CS_TQ) qc = CS_TQ;
+    const size_t nqr = ((size_t)(nq > 0 ? nq : 1) + CS_TQ - 1) / CS_TQ * CS_TQ;
     return (int)(qc < nqr ? qc : nqr);
+}
+
+// one k_scores block per tile, cell blocks fastest
+static unsigned cs_grid(unsigned gx, unsigned gy) { return gx * gy; }
+
+// The filtering form: pilot size (0 = use the matrix form) and what it needs per pass of qc queries.
+static int coarse_pilot(int K, int nprobe) {
+    static const bool off = getenv("QADC_COARSE_MATRIX") != nullptr;
+    int64_t P = 64 * (int64_t)nprobe;
+    if (P < 4096) P = 4096;
+    P = (P + CS_TC - 1) / CS_TC * CS_TC;
+    const int64_t ncb = ((int64_t)K + CS_TC - 1) / CS_TC;
+    if (off || P > K / 4 || ncb > MAX_G) return 0;
+    return (int)P;
+}
+static size_t coarse_filter_bytes(int qc, int K, int nprobe) {
+    const size_t ncb = ((size_t)K + CS_TC - 1) / CS_TC;
+    return up256((size_t)qc * ncb * CS_SLOT * sizeof(uint64_t)) + up256((size_t)qc * ncb * sizeof(uint32_t)) +
+           up256((size_t)qc * nprobe * sizeof(int32_t)) + up256((size_t)qc * nprobe * sizeof(float)) + 256;
 }
 
 extern "C" size_t ivf_coarse_workspace_bytes(int nq, int K) {
     if (nq < 0 || K < 1) return 0;
     const size_t ld = ((size_t)K + 31) & ~(size_t)31;
-    return up256((size_t)K * sizeof(float)) + up256((size_t)coarse_chunk(nq, K) * ld * sizeof(float));
+    const int qc = coarse_chunk(nq, K);
+    return up256((size_t)K * sizeof(float)) + up256((size_t)qc * ld * sizeof(float)) +
+           coarse_filter_bytes(qc, K, CS_MAX_NPROBE);
 }
 
 extern "C" int ivf_coarse_search(const float *queries, int nq, const float *centroids, int K, int d,
@@ -407,15 +540,49 @@ extern "C" int ivf_coarse_search(const float *queries, int nq, const float *cent
     const int vec = (d % 4 == 0) && (((uintptr_t)queries | (uintptr_t)centroids) & 15u) == 0;
     hipLaunchKernelGGL(k_cnorm, dim3((K + 255) / 256), dim3(256), 0, s, centroids, K, d, cnorm);
     QADC_LAUNCH_CHECK("k_cnorm");
+    const int P = coarse_pilot(K, nprobe);
+    const int ncb = (K + CS_TC - 1) / CS_TC;
+    char *fb = (char *)scores + up256((size_t)qc * ld * sizeof(float));
+    uint64_t *slots = (uint64_t *)fb;
+    uint32_t *counts = (uint32_t *)(fb + up256((size_t)qc * ncb * CS_SLOT * sizeof(uint64_t)));
+    int32_t *pilot_ids = (int32_t *)((char *)counts + up256((size_t)qc * ncb * sizeof(uint32_t)));
+    float *pilot_sc = (float *)((char *)pilot_ids + up256((size_t)qc * nprobe * sizeof(int32_t)));
+    int *flag = (int *)((char *)pilot_sc + up256((size_t)qc * nprobe * sizeof(float)));
+    // expected candidates per list: CS_TC nprobe / P <= 4
+    const int logw = 3;
     for (int q0 = 0; q0 < nq; q0 += qc) {
         const int nqc = nq - q0 < qc ? nq - q0 : qc;
-        hipLaunchKernelGGL(k_scores, dim3((K + CS_TILE - 1) / CS_TILE, (nqc + CS_TILE - 1) / CS_TILE),
-                           dim3(256), 0, s, queries + (size_t)q0 * d, nqc, centroids, K, d, cnorm,
-                           scores, ld, vec);
-        QADC_LAUNCH_CHECK("k_scores");
+        const float *qp = queries + (size_t)q0 * d;
         int32_t *pid = probe_ids + (size_t)q0 * nprobe;
         float *psc = probe_scores ? probe_scores + (size_t)q0 * nprobe : nullptr;
-        hipLaunchKernelGGL(k_select, dim3(nqc), dim3(1024), 0, s, scores, ld, K, nprobe, pid, psc);
+        const dim3 gq((K + CS_TC - 1) / CS_TC, (nqc + CS_TQ - 1) / CS_TQ);
+        const int *guard = nullptr;
+        if (P > 0) {
+            // pilot: matrix form over the first P cells -> bound and best score per query
+            hipLaunchKernelGGL(k_scores<false>, dim3(cs_grid(P / CS_TC, gq.y)), dim3(256), 0, s, qp, nqc,
+                               centroids, P, d, cnorm, scores, (size_t)P, vec, (const float *)nullptr, 0, 0,
+                               (uint64_t *)nullptr, (uint32_t *)nullptr, (const int *)nullptr, P / CS_TC,
+                               (int)gq.y);
+            QADC_LAUNCH_CHECK("k_scores (pilot)");
+            hipLaunchKernelGGL(k_select, dim3(nqc), dim3(1024), 0, s, scores, (size_t)P, P, nprobe, pilot_ids,
+                               pilot_sc, (const int *)nullptr, flag);
+            QADC_LAUNCH_CHECK("k_select (pilot)");
+            hipLaunchKernelGGL(k_scores<true>, dim3(cs_grid(gq.x, gq.y)), dim3(256), 0, s, qp, nqc, centroids, K,
+                               d, cnorm, (float *)nullptr, ld, vec, (const float *)pilot_sc, nprobe, nprobe - 1,
+                               slots, counts, (const int *)nullptr, (int)gq.x, (int)gq.y);
+            QADC_LAUNCH_CHECK("k_scores (filter)");
+            hipLaunchKernelGGL(k_select_cand, dim3(nqc), dim3(1024), FINAL_CAP * sizeof(uint64_t), s,
+                               (const uint32_t *)counts, (const uint64_t *)slots, ncb, (const float *)pilot_sc,
+                               nprobe, nprobe - 1, K, nprobe, logw, pid, psc, flag);
+            QADC_LAUNCH_CHECK("k_select_cand");
+            guard = flag;  // the matrix form below only runs if a list overflowed
+        }
+        hipLaunchKernelGGL(k_scores<false>, dim3(cs_grid(gq.x, gq.y)), dim3(256), 0, s, qp, nqc, centroids, K, d,
+                           cnorm, scores, ld, vec, (const float *)nullptr, 0, 0, (uint64_t *)nullptr,
+                           (uint32_t *)nullptr, guard, (int)gq.x, (int)gq.y);
+        QADC_LAUNCH_CHECK("k_scores");
+        hipLaunchKernelGGL(k_select, dim3(nqc), dim3(1024), 0, s, scores, ld, K, nprobe, pid, psc, guard,
+                           (int *)nullptr);
         QADC_LAUNCH_CHECK("k_select");
     }
     return PQ_OK;

@@ -101,6 +101,34 @@ def test_coarse_search_full_k_sampled(qb):
     check(qb, cen, qs, 64, nq_oracle=12)
 
 
+@pytest.mark.parametrize("K,d,nq,nprobe,seed", [
+    (20_000, 96, 70, 64, 31), (16_511, 40, 130, 1, 32), (30_001, 128, 9, 20, 33), (17_000, 17, 257, 64, 34),
+])
+def test_coarse_search_filtering_form_bit_exact(qb, K, d, nq, nprobe, seed):
+    """K large enough for the form that never writes the score matrix (pilot bound, candidate
+    lists per block of 128 cells)."""
+    rng = np.random.default_rng(seed)
+    cen = rng.normal(size=(K, d)).astype(np.float32)
+    qs = rng.normal(size=(nq, d)).astype(np.float32)
+    check(qb, cen, qs, nprobe, nq_oracle=min(nq, 24))
+
+
+def test_coarse_search_filtering_form_overflow_falls_back(qb):
+    """Forty copies of one cell inside a single block of 128 overflow that block's candidate list
+    for the queries near it; the pass is then redone in the matrix form.  Also: all cells equal."""
+    rng = np.random.default_rng(41)
+    K, d = 20_000, 32
+    cen = rng.normal(size=(K, d)).astype(np.float32)
+    cen[12_800:12_840] = cen[12_800]
+    qs = rng.normal(size=(40, d)).astype(np.float32)
+    qs[:5] = cen[12_800] + 0.01 * rng.normal(size=(5, d)).astype(np.float32)
+    ids = check(qb, cen, qs, 64)
+    assert set(range(12_800, 12_840)) <= set(ids[0].tolist())
+    same = np.ones((18_000, 8), np.float32)
+    ids = check(qb, same, np.zeros((3, 8), np.float32), 100)
+    assert ids[2].tolist() == list(range(100))
+
+
 def test_coarse_search_errors(qb):
     cen = torch.zeros((10, 4), dtype=torch.float32, device=dev())
     qs = torch.zeros((2, 4), dtype=torch.float32, device=dev())
