@@ -132,7 +132,7 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sel[2];
-    __shared__ long long s_np;
+    __shared__ unsigned long long s_np;
     IvfLds l;
     unsigned char *rest = ivf_carve(L, smem, 2, l);
     uint32_t *ord = (uint32_t *)rest;  // [max(want, pilot_want)]
@@ -143,17 +143,22 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     const float *z = queries + q * L->d;
     const int m = L->m, cs = L->cs, qmax = L->qmax;
 
-    if (threadIdx.x == 0) {
+    // number of probed codes: one probe per thread (independent loads), then a block sum
+    if (threadIdx.x == 0) s_np = 0;
+    __syncthreads();
+    {
         long long np = 0;
-        for (int a = 0; a < nprobe; ++a) {
-            int c = probes[a];
+        for (int a = threadIdx.x; a < nprobe; a += blockDim.x) {
+            const int c = probes[a];
             if (c >= 0 && c < K) np += list_offsets[c + 1] - list_offsets[c];
         }
-        s_np = np;
+        for (int sft = QADC_WAVE / 2; sft > 0; sft >>= 1) np += __shfl_xor(np, sft, QADC_WAVE);
+        if (threadIdx.x % QADC_WAVE == 0 && np != 0)
+            atomicAdd((unsigned long long *)&s_np, (unsigned long long)np);
     }
     __syncthreads();
-    const int t_eff = (int)(s_np < (long long)want ? s_np : (long long)want);
-    const int pilot = (int)(s_np < (long long)pilot_want ? s_np : (long long)pilot_want);
+    const int t_eff = (int)((long long)s_np < (long long)want ? (long long)s_np : (long long)want);
+    const int pilot = (int)((long long)s_np < (long long)pilot_want ? (long long)s_np : (long long)pilot_want);
     const int k = R < t_eff ? R : t_eff;
     if (t_eff == 0) {
         if (threadIdx.x == 0) {

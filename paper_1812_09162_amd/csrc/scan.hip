@@ -26,7 +26,7 @@
 #define QADC_U8 2
 #endif
 #ifndef QADC_U5
-#define QADC_U5 2
+#define QADC_U5 1
 #endif
 constexpr int U8 = QADC_U8;  // 16-byte chunks per thread and tile, 8-byte codes
 constexpr int U5 = QADC_U5;  // 20-byte chunks per thread and tile, 5-byte codes
