@@ -138,3 +138,73 @@ def test_c4_full_size(qb):
     cfg = dict(synth.CONFIGS["C4"])
     cfg.update(nq=1024, kmeans_iters=3)
     run_ivf(qb, cfg, nq_oracle=64)
+
+
+def test_largest_n(qb):
+    """n = 2^31 - 1, the largest list the scan accepts (ids are int32): 17 GB of 8-byte codes.
+
+    Codebooks and queries are those of a small C1-shaped data set; the code bytes are uniform
+    random (so the best codes lie anywhere in the list), and for each query its best possible code
+    (every sub-quantizer at its table minimum) is planted at positions spread up to n - 1.  Quantized tables come from the oracle (it needs the first t codes only); the
+    expected top-R by (key, id) over all n codes is computed chunk by chunk with plain torch
+    indexing and top-k, and the float distances of those keys by the oracle.
+    """
+    n = 2 ** 31 - 1
+    R = 100
+    if torch.cuda.mem_get_info()[1] < 48e9:
+        pytest.skip("needs 17 GB for the code list plus temporaries")
+    pr = synth.build(synth.scaled("C1", n=100_000, nq=3), device=dev())
+    lay = pr.layout
+    assert lay.m == 16 and set(lay.nbits) == {4}
+    idx = qb.PqIndex(lay.d, lay.nbits, lay.dsub, pr.codebooks, lay.acc_bits)
+    g = torch.Generator(device=dev())
+    g.manual_seed(20_231)
+    codes = torch.empty((n, 8), dtype=torch.uint8, device=dev())
+    CH = 1 << 26
+    for a in range(0, n, CH):
+        b = min(n, a + CH)
+        codes[a:b] = torch.randint(0, 256, (b - a, 8), generator=g, device=dev(), dtype=torch.uint8)
+    cb = pr.codebooks.cpu().numpy()
+    qs = pr.queries.cpu().numpy()
+    nq = qs.shape[0]
+    ftab = [oracle.tables(lay.d, lay.nbits, lay.dsub, cb, qs[q]) for q in range(nq)]
+    planted = [n - 1, n - 2, n - 3 - 2, 2 ** 30 - 1, 2 ** 30, 2 ** 30 + 1, 2 ** 31 - 1024, 3 * 2 ** 29 + 7]
+    for q in range(nq):
+        arg = ftab[q].reshape(16, 16).argmin(axis=1)
+        best = np.array([arg[2 * i] | (arg[2 * i + 1] << 4) for i in range(8)], dtype=np.uint8)
+        for p in planted:
+            codes[p - 16 * q] = torch.from_numpy(best).to(dev())
+    head = codes[:4 * R + T_CAL].cpu().numpy()
+    quant = [oracle.quantize(lay.nbits, lay.acc_bits, ftab[q], head, T_CAL, R) for q in range(nq)]
+
+    def reference(q):
+        qt = torch.from_numpy(quant[q][0].astype(np.int32)).to(dev()).view(16, 16)
+        best = None
+        for a in range(0, n, CH):
+            c = codes[a:min(n, a + CH)]
+            key = torch.zeros(c.shape[0], dtype=torch.int32, device=dev())
+            for b in range(8):
+                byte = c[:, b].long()
+                key += qt[2 * b][byte & 15] + qt[2 * b + 1][byte >> 4]
+            key.clamp_(max=255)
+            comp = (key.long() << 32) | torch.arange(a, a + c.shape[0], device=dev(), dtype=torch.int64)
+            top = torch.topk(comp, R, largest=False).values
+            best = top if best is None else torch.topk(torch.cat([best, top]), R, largest=False).values
+            del key, comp, byte
+        best = torch.sort(best).values.cpu().numpy()
+        keys = (best >> 32).astype(np.uint16)
+        ids = (best & 0xffffffff).astype(np.int32)
+        _, _, dist = oracle.topk(lay.acc_bits, keys, R, quant[q][1], quant[q][2])
+        return ids, keys, dist
+
+    one = [qb.pq_search_topk(idx, pr.queries[q:q + 1].contiguous(), codes, T_CAL, R) for q in range(nq)]
+    many = qb.pq_search_topk(idx, pr.queries.contiguous(), codes, T_CAL, R)
+    torch.cuda.synchronize()
+    for q in range(nq):
+        ids, keys, dist = reference(q)
+        assert set(p - 16 * q for p in planted) <= set(ids.tolist()), "planted codes must be found"
+        for got in ([x[0] for x in one[q]], [x[q] for x in many]):
+            assert np.array_equal(got[0].cpu().numpy(), ids), (q, got[0][:12], ids[:12])
+            assert np.array_equal(got[1].cpu().numpy().astype(np.uint16), keys)
+            assert np.array_equal(got[2].cpu().numpy(), dist)
+    idx.close()
