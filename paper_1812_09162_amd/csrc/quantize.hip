@@ -282,6 +282,8 @@ PilotPlan qadc_pilot_plan(int nq, int64_t n, int t_eff, int R, bool have_scratch
     PilotPlan pp;
     const int pmax = have_scratch ? qadc_pilot_blocks_max(nq) : 1;
     int64_t want = pmax > 1 ? multi : single;
+    // the candidates the scan keeps grow with R / pilot: long result lists get a longer pilot
+    if (pmax > 1 && want < 512 * (int64_t)R) want = 512 * (int64_t)R;
     if (want > (int64_t)pmax * PILOT_BLOCK_MAX) want = (int64_t)pmax * PILOT_BLOCK_MAX;
     if (want < 64 * (int64_t)R) want = 64 * (int64_t)R;
     if (want < t_eff) want = t_eff;
