@@ -25,7 +25,6 @@ struct IvfLds {
     void *gtab;    // [gtab_len] of QT
     double *sc;    // {d_min, delta}
     int *flag;     // skip flag
-    uint8_t *esub; // [T] sub-quantizer of each table entry
 };
 
 __device__ inline size_t ivf_lds_bytes_dev(const DevLayout *L, size_t esz) {
@@ -48,7 +47,7 @@ __device__ inline unsigned char *ivf_carve(const DevLayout *L, unsigned char *ba
     l.pmin = (float *)p;     p += PQ_MAX_M * 4;
     l.gtab = (void *)p;      p += (((size_t)L->gtab_len * esz + 15) & ~(size_t)15);
     l.qt = (uint16_t *)p;    p += (size_t)L->T * 2;
-    l.esub = (uint8_t *)p;   p += (size_t)L->T * 2;  // T bytes used; keeps what follows 4-byte aligned
+    p += (size_t)L->T * 2;  // spare; keeps what follows 4-byte aligned
     return p;
 }
 
@@ -56,18 +55,18 @@ __device__ inline unsigned char *ivf_carve(const DevLayout *L, unsigned char *ba
 // also delta from dmax, the quantized table and (with `groups`) the group
 // tables.  Returns false when the list is skipped (d_min > d_max).
 template <int KIND, typename QT>
-__device__ inline bool ivf_setup(const DevLayout *L, const float *__restrict__ cb,
-                                 const float *__restrict__ z, const float *__restrict__ cen,
-                                 float dmax, bool quantize, bool groups, const IvfLds &l) {
+__device__ inline bool ivf_setup(const DevLayout *L, const EntryDesc *__restrict__ edesc,
+                                 const float *__restrict__ cb, const float *__restrict__ z,
+                                 const float *__restrict__ cen, float dmax, bool quantize,
+                                 bool groups, const IvfLds &l) {
     const int d = L->d, m = L->m, T = L->T, qmax = L->qmax;
     for (int i = threadIdx.x; i < d; i += blockDim.x) l.zres[i] = __fsub_rn(z[i], cen[i]);
     __syncthreads();
     for (int e = threadIdx.x; e < T; e += blockDim.x) {
-        const int j = l.esub[e];
-        const int i = e - L->toff[j];
-        const int ds = L->dsub[j];
-        const float *c = cb + L->cboff[j] + (size_t)i * ds;
-        const float *zz = l.zres + L->dimoff[j];
+        const EntryDesc ed = edesc[e];
+        const int ds = ed.ds;
+        const float *c = cb + ed.cb_off;
+        const float *zz = l.zres + ed.dim_off;
         float acc = 0.0f;
         for (int k = 0; k < ds; ++k) {
             float diff = __fsub_rn(zz[k], c[k]);
@@ -104,7 +103,7 @@ __device__ inline bool ivf_setup(const DevLayout *L, const float *__restrict__ c
     if (*l.flag) return false;
     const double delta = l.sc[1];
     for (int e = threadIdx.x; e < T; e += blockDim.x) {
-        const int j = l.esub[e];
+        const int j = edesc[e].j;
         uint32_t qv = 0;
         if (delta > 0.0) {
             double x = floor(((double)l.tab[e] - (double)l.pmin[j]) / delta);
@@ -123,8 +122,12 @@ __device__ __forceinline__ uint32_t dist_bin(float dist, float lo, float scale) 
 }
 
 // ------------------------------------------------------------ k_ivf_calib ---
+// NIB: 64-bit m x 4 codes (sub-code j is nibble j of the code).  Other layouts take the
+// sub-quantizers' table offset, bit offset and width from a small LDS array.
+template <bool NIB>
 __global__ void __launch_bounds__(256)
-k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
+k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
+            const float *__restrict__ cb,
             const float *__restrict__ coarse, const int64_t *__restrict__ list_offsets,
             const uint8_t *__restrict__ list_codes, const float *__restrict__ queries,
             const int32_t *__restrict__ probe_ids, int nprobe, int K, int want, int pilot_want,
@@ -133,10 +136,13 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sel[2];
     __shared__ unsigned long long s_np;
+    __shared__ uint32_t sdesc[PQ_MAX_M];  // table offset | bit offset << 12 | bits << 24
     IvfLds l;
     unsigned char *rest = ivf_carve(L, smem, 2, l);
     uint32_t *ord = (uint32_t *)rest;  // [max(want, pilot_want)]
-    qadc_build_entry_map(L, l.esub);
+    if (!NIB && (int)threadIdx.x < L->m)
+        sdesc[threadIdx.x] = (uint32_t)L->toff[threadIdx.x] | ((uint32_t)L->bitoff[threadIdx.x] << 12) |
+                             ((uint32_t)L->nbits[threadIdx.x] << 24);
     const size_t q = blockIdx.x;
     IvfState *st = (IvfState *)(ws + q * per_query);
     const int32_t *probes = probe_ids + q * nprobe;
@@ -176,16 +182,23 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         if (c < 0 || c >= K) continue;
         const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
         if (hi == lo) continue;
-        ivf_setup<SCAN_GENERIC, uint16_t>(L, cb, z, coarse + (size_t)c * L->d, 0.f, false, false, l);
+        ivf_setup<SCAN_GENERIC, uint16_t>(L, edesc, cb, z, coarse + (size_t)c * L->d, 0.f, false, false, l);
         const int take = (int)((hi - lo) < (int64_t)(t_eff - seen) ? (hi - lo) : (int64_t)(t_eff - seen));
         for (int p = threadIdx.x; p < take; p += blockDim.x) {
             const uint8_t *code = list_codes + (size_t)(lo + p) * cs;
             float s = 0.0f;
-            if (cs <= 16) {
+            if (NIB) {
+                const uint2 v = *(const uint2 *)code;
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    s = __fadd_rn(s, l.tab[16 * j + (((j < 8 ? v.x : v.y) >> (4 * (j & 7))) & 15u)]);
+            } else if (cs <= 16) {
                 uint32_t w[4];
                 qadc_load_code16(code, cs, w);
-                for (int j = 0; j < m; ++j)
-                    s = __fadd_rn(s, l.tab[L->toff[j] + qadc_extract_sub16(w, L->bitoff[j], L->nbits[j])]);
+                for (int j = 0; j < m; ++j) {
+                    const uint32_t ds = sdesc[j];
+                    s = __fadd_rn(s, l.tab[(ds & 0xfffu) + qadc_extract_sub16(w, (ds >> 12) & 0xfffu, ds >> 24)]);
+                }
             } else {
                 for (int j = 0; j < m; ++j)
                     s = __fadd_rn(s, l.tab[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])]);
@@ -203,7 +216,7 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         if (c < 0 || c >= K) continue;
         const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
         if (hi == lo) continue;
-        const bool ok = ivf_setup<SCAN_GENERIC, uint16_t>(L, cb, z, coarse + (size_t)c * L->d, dmax, true, false, l);
+        const bool ok = ivf_setup<SCAN_GENERIC, uint16_t>(L, edesc, cb, z, coarse + (size_t)c * L->d, dmax, true, false, l);
         const int take = (int)((hi - lo) < (int64_t)(pilot - seen) ? (hi - lo) : (int64_t)(pilot - seen));
         const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
         for (int p = threadIdx.x; p < take; p += blockDim.x) {
@@ -211,11 +224,18 @@ k_ivf_calib(const DevLayout *__restrict__ L, const float *__restrict__ cb,
             if (ok) {
                 const uint8_t *code = list_codes + (size_t)(lo + p) * cs;
                 uint32_t acc = 0;
-                if (cs <= 16) {
+                if (NIB) {
+                    const uint2 v = *(const uint2 *)code;
+#pragma unroll
+                    for (int j = 0; j < 16; ++j)
+                        acc += l.qt[16 * j + (((j < 8 ? v.x : v.y) >> (4 * (j & 7))) & 15u)];
+                } else if (cs <= 16) {
                     uint32_t w[4];
                     qadc_load_code16(code, cs, w);
-                    for (int j = 0; j < m; ++j)
-                        acc += l.qt[L->toff[j] + qadc_extract_sub16(w, L->bitoff[j], L->nbits[j])];
+                    for (int j = 0; j < m; ++j) {
+                        const uint32_t ds = sdesc[j];
+                        acc += l.qt[(ds & 0xfffu) + qadc_extract_sub16(w, (ds >> 12) & 0xfffu, ds >> 24)];
+                    }
                 } else {
                     for (int j = 0; j < m; ++j)
                         acc += l.qt[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])];
@@ -415,8 +435,7 @@ k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
             build_gtab<KIND, QT>(L, l.qt, (QT *)l.gtab);
         }
     } else {
-        qadc_build_entry_map(L, l.esub);
-        ok = ivf_setup<KIND, QT>(L, cb, queries + q * d, coarse + (size_t)c * d, dmax, true, true, l);
+        ok = ivf_setup<KIND, QT>(L, edesc, cb, queries + q * d, coarse + (size_t)c * d, dmax, true, true, l);
     }
     if (!ok) {
         if (threadIdx.x == 0) counts[a] = 0;
@@ -523,7 +542,8 @@ __device__ inline void ivf_rank_and_write(const uint64_t *A, int na, int R, int3
 // byte-wise radix selection of the R-th smallest 64-bit (distance, id) word,
 // regenerating the stream once per byte, then one collecting pass.
 template <int KIND, typename QT>
-__device__ inline int ivf_exact_select(const DevLayout *L, const float *cb, const float *coarse,
+__device__ inline int ivf_exact_select(const DevLayout *L, const EntryDesc *edesc, const float *cb,
+                                       const float *coarse,
                                        const int64_t *list_offsets, const uint8_t *list_codes,
                                        const int32_t *list_ids, const float *z,
                                        const int32_t *probes, int nprobe, int K, float dmax, int R,
@@ -540,7 +560,7 @@ __device__ inline int ivf_exact_select(const DevLayout *L, const float *cb, cons
             if (c < 0 || c >= K) continue;
             const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
             if (hi == lo) continue;
-            if (!ivf_setup<KIND, QT>(L, cb, z, coarse + (size_t)c * L->d, dmax, true, true, l)) continue;
+            if (!ivf_setup<KIND, QT>(L, edesc, cb, z, coarse + (size_t)c * L->d, dmax, true, true, l)) continue;
             const QT *gtab = (const QT *)l.gtab;
             const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
             for (int64_t p = lo + threadIdx.x; p < hi; p += blockDim.x) {
@@ -587,7 +607,8 @@ __device__ inline int ivf_exact_select(const DevLayout *L, const float *cb, cons
 
 template <int KIND, typename QT>
 __global__ void __launch_bounds__(1024)
-k_ivf_final(const DevLayout *__restrict__ L, const float *__restrict__ cb,
+k_ivf_final(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
+            const float *__restrict__ cb,
             const float *__restrict__ coarse, const int64_t *__restrict__ list_offsets,
             const uint8_t *__restrict__ list_codes, const int32_t *__restrict__ list_ids,
             const float *__restrict__ queries, const int32_t *__restrict__ probe_ids, int nprobe,
@@ -620,8 +641,7 @@ k_ivf_final(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     if (slow) {
         IvfLds l;
         ivf_carve(L, smem + FINAL_CAP * 8, sizeof(QT), l);
-        qadc_build_entry_map(L, l.esub);
-        na = ivf_exact_select<KIND, QT>(L, cb, coarse, list_offsets, list_codes, list_ids,
+        na = ivf_exact_select<KIND, QT>(L, edesc, cb, coarse, list_offsets, list_codes, list_ids,
                                         queries + q * L->d, probe_ids + q * nprobe, nprobe, K,
                                         st->dmax, R, l, A, hist, sh);
         __syncthreads();
@@ -649,14 +669,15 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     const size_t lds_scan = ivf_lds_bytes(idx->h, sizeof(QT));
     const size_t lds_final = FINAL_CAP * 8 + lds_scan;
     int rc;
-    if ((rc = allow_lds(k_ivf_calib, lds_calib)) != PQ_OK) return rc;
+    constexpr bool NIB = KIND == SCAN_NIB8;
+    if ((rc = allow_lds(k_ivf_calib<NIB>, lds_calib)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_scan<KIND, QT, 0>, lds_scan)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_scan<KIND, QT, 1>, lds_scan)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_scan<KIND, QT, 2>, lds_scan)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_scan<KIND, QT, 4>, lds_scan)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_final<KIND, QT>, lds_final)) != PQ_OK) return rc;
-    hipLaunchKernelGGL(k_ivf_calib, dim3(nq), dim3(256), lds_calib, s, idx->dev, idx->codebooks,
-                       coarse, list_offsets, list_codes, queries, probe_ids, nprobe, K, want, pilot_want, R, ws,
+    hipLaunchKernelGGL(k_ivf_calib<NIB>, dim3(nq), dim3(256), lds_calib, s, idx->dev, idx->edesc,
+                       idx->codebooks, coarse, list_offsets, list_codes, queries, probe_ids, nprobe, K, want, pilot_want, R, ws,
                        p.per_query);
     QADC_LAUNCH_CHECK("k_ivf_calib");
     static const int scan_threads = getenv("QADC_IVF_THREADS") ? atoi(getenv("QADC_IVF_THREADS")) : 128;
@@ -671,7 +692,7 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
 #undef QADC_IVF_SCAN
     QADC_LAUNCH_CHECK("k_ivf_scan");
     hipLaunchKernelGGL((k_ivf_final<KIND, QT>), dim3(nq), dim3(1024), lds_final, s, idx->dev,
-                       idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,
+                       idx->edesc, idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,
                        probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b,
                        out_ids, out_dist);
     QADC_LAUNCH_CHECK("k_ivf_final");

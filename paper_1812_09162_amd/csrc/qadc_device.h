@@ -121,28 +121,56 @@ __device__ inline void qadc_wave_select_bin(const uint32_t *hist, uint32_t kk, u
     }
 }
 
-// k-th smallest (k >= 1) of cnt uint32 values in LDS by most-significant-byte
-// radix selection over the bytes [0, nbytes).  All threads of the block call
-// it; `hist` is 256 words of LDS, `sel` two words.  Returns the value to every
-// thread.
+// k-th smallest (k >= 1, k <= cnt) of cnt > 0 uint32 values in LDS, by radix selection over
+// the bits in which the values differ at all: the bits above the highest differing one are
+// common to all values (ordered floats of similar size share their upper bytes, and counting
+// those would send every value to one histogram bin), the rest is taken eight bits at a time
+// from the top.  All threads of the block call it; `hist` is 256 words of LDS, `sel` two
+// words.  Returns the value to every thread.  (`nbytes` is kept for callers: the values'
+// width in bytes.)
 __device__ inline uint32_t qadc_block_kth_u32(const uint32_t *vals, int cnt, int k, int nbytes,
                                               uint32_t *hist, uint32_t *sel) {
-    uint32_t prefix = 0, mask = 0;
+    (void)nbytes;
+    uint32_t mn = 0xffffffffu, mxn = 0xffffffffu;  // minimum, and minimum of the complements
+    for (int i = threadIdx.x; i < cnt; i += blockDim.x) {
+        const uint32_t v = vals[i];
+        mn = v < mn ? v : mn;
+        mxn = ~v < mxn ? ~v : mxn;
+    }
+    mn = qadc_wave_min(mn);
+    mxn = qadc_wave_min(mxn);
+    if (threadIdx.x == 0) {
+        sel[0] = 0xffffffffu;
+        sel[1] = 0xffffffffu;
+    }
+    __syncthreads();
+    if (threadIdx.x % QADC_WAVE == 0) {
+        atomicMin(&sel[0], mn);
+        atomicMin(&sel[1], mxn);
+    }
+    __syncthreads();
+    mn = sel[0];
+    const uint32_t mx = ~sel[1];
+    __syncthreads();
+    if (mn == mx) return mn;
+    int rb = 32 - __clz((int)(mn ^ mx));  // the bits [0, rb) are undecided
+    uint32_t prefix = rb >= 32 ? 0u : (mn >> rb) << rb;
     int kk = k;
-    for (int pass = nbytes - 1; pass >= 0; --pass) {
-        int shift = pass * 8;
+    while (rb > 0) {
+        const int w = rb < 8 ? rb : 8, shift = rb - w;
         for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
         __syncthreads();
         for (int i = threadIdx.x; i < cnt; i += blockDim.x) {
-            uint32_t v = vals[i];
-            if ((v & mask) == prefix) atomicAdd(&hist[(v >> shift) & 255u], 1u);
+            const uint32_t v = vals[i];
+            const bool in = rb >= 32 || (v >> rb) == (prefix >> rb);
+            if (in) atomicAdd(&hist[(v >> shift) & ((1u << w) - 1u)], 1u);
         }
         __syncthreads();
         if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, (uint32_t)kk, 0u, sel);
         __syncthreads();
         prefix |= sel[0] << shift;
-        mask |= 255u << shift;
         kk -= (int)sel[1];
+        rb = shift;
         __syncthreads();
     }
     return prefix;
