@@ -156,14 +156,23 @@ __device__ inline uint32_t qadc_block_kth_u32(const uint32_t *vals, int cnt, int
     int rb = 32 - __clz((int)(mn ^ mx));  // the bits [0, rb) are undecided
     uint32_t prefix = rb >= 32 ? 0u : (mn >> rb) << rb;
     int kk = k;
+    // Equal values are common (a saturated key gives one distance per list), and LDS atomics of
+    // one wave to one word are served one lane at a time: every bin is kept as eight adjacent
+    // words (eight banks), lane l counting in word l % 8, and summed before the selection.
+    __shared__ __align__(16) uint32_t hist8[256 * 8];
     while (rb > 0) {
         const int w = rb < 8 ? rb : 8, shift = rb - w;
-        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+        for (int i = threadIdx.x; i < 256 * 8; i += blockDim.x) hist8[i] = 0;
         __syncthreads();
         for (int i = threadIdx.x; i < cnt; i += blockDim.x) {
             const uint32_t v = vals[i];
             const bool in = rb >= 32 || (v >> rb) == (prefix >> rb);
-            if (in) atomicAdd(&hist[(v >> shift) & ((1u << w) - 1u)], 1u);
+            if (in) atomicAdd(&hist8[(((v >> shift) & ((1u << w) - 1u)) << 3) + (threadIdx.x & 7u)], 1u);
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < 256; i += blockDim.x) {
+            const uint4 a = *(const uint4 *)&hist8[8 * i], b = *(const uint4 *)&hist8[8 * i + 4];
+            hist[i] = a.x + a.y + a.z + a.w + b.x + b.y + b.z + b.w;
         }
         __syncthreads();
         if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, (uint32_t)kk, 0u, sel);
