@@ -278,10 +278,14 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
 //   B  list bounds, centroid, codebook values of the entries (need A)
 //   C  the first codes of the list                           (need B; used after the set-up)
 // NE = table entries per thread (1, 2 or 4; 0 = the general set-up routine, no early loads).
+// DS > 0 fixes the shape at compile time: 16 sub-quantizers of 16 centroids over DS dimensions
+// each (T = 256, d = 16 DS) and blocks of 256 / NE threads, so that table entry e = thread +
+// k * threads is centroid e % 16 of sub-quantizer e / 16 at codebook offset e * DS, and the
+// set-up needs neither descriptors nor bounds tests.
 #ifndef QADC_IVF_PF
 #define QADC_IVF_PF 2
 #endif
-template <int KIND, typename QT, int NE>
+template <int KIND, typename QT, int NE, int DS = 0>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8, 8)))
 k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
            const float *__restrict__ cb, const float *__restrict__ coarse,
@@ -295,12 +299,14 @@ k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
     ivf_carve(L, smem, sizeof(QT), l);
     const size_t q = blockIdx.y;
     const int a = blockIdx.x;
-    const int bd = (int)blockDim.x;
+    constexpr bool FIX = DS > 0;
+    static_assert(!FIX || (KIND == SCAN_NIB8 && NE > 0 && DS <= 8 && 256 % NE == 0), "fixed shape");
+    const int bd = FIX ? 256 / (NE > 0 ? NE : 1) : (int)blockDim.x;
     char *wq = ws + q * per_query;
     const IvfState *st = (const IvfState *)wq;
     uint32_t *counts = (uint32_t *)(wq + counts_off);
     constexpr int MAXDS = 8;  // codebook values per entry held in registers
-    const int d = L->d, T = L->T, m = L->m, qmax = L->qmax;
+    const int d = FIX ? 16 * DS : L->d, T = FIX ? 256 : L->T, m = FIX ? 16 : L->m, qmax = L->qmax;
 
     // A
     const int c = probe_ids[q * nprobe + a];
@@ -310,7 +316,14 @@ k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
 #pragma unroll
         for (int k = 0; k < NE; ++k) {
             const int e = (int)threadIdx.x + k * bd;
-            ed[k] = edesc[e < T ? e : T - 1];
+            if (FIX) {
+                ed[k].j = e >> 4;
+                ed[k].cb_off = e * DS;
+                ed[k].dim_off = (e >> 4) * DS;
+                ed[k].ds = DS;
+            } else {
+                ed[k] = edesc[e < T ? e : T - 1];
+            }
         }
         for (int i = threadIdx.x; i < d; i += bd) l.zres[i] = queries[q * d + i];
     }
@@ -335,7 +348,7 @@ k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
         // B
         // sub-space width if all sub-quantizers share one (then a scalar, and nothing below
         // needs per-lane predicates), else 0
-        const int dsu = L->ds_uniform;
+        const int dsu = FIX ? DS : L->ds_uniform;
         float cv[NE > 0 ? NE : 1][MAXDS];
 #pragma unroll
         for (int k = 0; k < NE; ++k)
@@ -364,7 +377,7 @@ k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
 #pragma unroll
         for (int k = 0; k < NE; ++k) {
             const int e = (int)threadIdx.x + k * bd;
-            if (e < T) {
+            if (FIX || e < T) {
                 const float *zz = l.zres + ed[k].dim_off;
                 float acc = 0.0f;
 #pragma unroll
@@ -374,7 +387,7 @@ k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
                         acc = __fadd_rn(acc, __fmul_rn(diff, diff));
                     }
                 }
-                for (int t = MAXDS; t < ed[k].ds; ++t) {  // wider sub-spaces: the rest from memory
+                for (int t = MAXDS; !FIX && t < ed[k].ds; ++t) {  // wider sub-spaces: the rest from memory
                     const float diff = __fsub_rn(zz[t], cb[ed[k].cb_off + t]);
                     acc = __fadd_rn(acc, __fmul_rn(diff, diff));
                 }
@@ -386,13 +399,13 @@ k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
 #pragma unroll
             for (int k = 0; k < NE; ++k) {
                 const int e = (int)threadIdx.x + k * bd;
-                float mn = e < T ? l.tab[e] : INFINITY;  // own entry, just written by this thread
+                float mn = (FIX || e < T) ? l.tab[e] : INFINITY;  // own entry, just written by this thread
 #pragma unroll
                 for (int sft = 1; sft < 16; sft <<= 1) {
                     const float o = __shfl_xor(mn, sft, QADC_WAVE);
                     mn = o < mn ? o : mn;
                 }
-                if (e < T && (e & 15) == 0) l.pmin[e >> 4] = mn;
+                if ((FIX || e < T) && (e & 15) == 0) l.pmin[e >> 4] = mn;
             }
         } else {
             __syncthreads();
@@ -422,7 +435,7 @@ k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
 #pragma unroll
             for (int k = 0; k < NE; ++k) {
                 const int e = (int)threadIdx.x + k * bd;
-                if (e < T) {
+                if (FIX || e < T) {
                     uint32_t qv = 0;
                     if (delta > 0.0) {
                         double x = floor(((double)l.tab[e] - (double)l.pmin[ed[k].j]) / delta);
@@ -688,7 +701,22 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
                        idx->dev, idx->edesc, idx->codebooks, coarse, list_offsets, list_codes,     \
                        list_ids, queries, probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off,  \
                        p.slots_off, p.cap_b)
-    if (ne == 1) QADC_IVF_SCAN(1); else if (ne == 2) QADC_IVF_SCAN(2); else if (ne == 4) QADC_IVF_SCAN(4); else QADC_IVF_SCAN(0);
+    // 16 x 4 bits over equal sub-spaces with 8-bit tables, at the default block size: the
+    // fixed-shape set-up
+    const int dsf = (KIND == SCAN_NIB8 && sizeof(QT) == 1 && scan_threads == 128 && idx->h.m == 16 &&
+                     idx->h.T == 256 && idx->h.ds_uniform > 0 && idx->h.d == 16 * idx->h.ds_uniform)
+                        ? idx->h.ds_uniform : 0;
+#define QADC_IVF_SCAN_FIX(DSV)                                                                      \
+    hipLaunchKernelGGL((k_ivf_scan<SCAN_NIB8, uint8_t, 2, DSV>), dim3(nprobe, nq), dim3(128), lds_scan, s, \
+                       idx->dev, idx->edesc, idx->codebooks, coarse, list_offsets, list_codes,     \
+                       list_ids, queries, probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off,  \
+                       p.slots_off, p.cap_b)
+    if (dsf == 4 || dsf == 6 || dsf == 8) {
+        if (KIND == SCAN_NIB8 && sizeof(QT) == 1) {  // (the macro names the types itself)
+            if (dsf == 4) QADC_IVF_SCAN_FIX(4); else if (dsf == 6) QADC_IVF_SCAN_FIX(6); else QADC_IVF_SCAN_FIX(8);
+        }
+    } else if (ne == 1) QADC_IVF_SCAN(1); else if (ne == 2) QADC_IVF_SCAN(2); else if (ne == 4) QADC_IVF_SCAN(4); else QADC_IVF_SCAN(0);
+#undef QADC_IVF_SCAN_FIX
 #undef QADC_IVF_SCAN
     QADC_LAUNCH_CHECK("k_ivf_scan");
     hipLaunchKernelGGL((k_ivf_final<KIND, QT>), dim3(nq), dim3(1024), lds_final, s, idx->dev,
