@@ -632,7 +632,7 @@ k_ivf_final(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
     __shared__ uint32_t whist[16][256];
     __shared__ uint32_t sh[32];
     __shared__ uint32_t wsum[16];
-    __shared__ uint32_t off[MAX_G + 1];
+    __shared__ uint32_t off[1024 + 1];  // one slot list per probed cell, nprobe <= 1024
     uint64_t *A = (uint64_t *)smem;  // FINAL_CAP entries
     const size_t q = blockIdx.x;
     char *wq = ws + q * per_query;

@@ -395,7 +395,8 @@ __device__ inline bool gather_select(const uint32_t *__restrict__ counts,
                     uint32_t pos[FINAL_REG];
 #pragma unroll
                     for (int u = 0; u < FINAL_REG; ++u) pos[u] = 0;
-                    for (uint32_t s = MAX_G / 2; s >= 1; s >>= 1) {
+                    // first step: half the smallest power of two that is >= G
+                    for (uint32_t s = G > 1 ? 1u << (31 - __clz(G - 1)) : 1u; s >= 1; s >>= 1) {
 #pragma unroll
                         for (int u = 0; u < FINAL_REG; ++u) {
                             const uint32_t e = base + u * 1024 + threadIdx.x;
