@@ -46,7 +46,8 @@ __device__ inline bool qadc_arrive_last(unsigned long long *w, unsigned long lon
 // that is non-null); otherwise they are read from tables_in.
 template <int KIND, typename QT>
 __global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4)))
-k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
+k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
+           const float *__restrict__ cb,
            const float *__restrict__ queries, const float *__restrict__ tables_in,
            float *__restrict__ tables_out, const uint8_t *__restrict__ codes, int t_eff, int k,
            int pilot, int slice, int P, void *__restrict__ qtables,
@@ -90,13 +91,13 @@ k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     if (queries) {
         float *zs = (float *)ord;  // the query lives where the ADC sums go later
         for (int i = threadIdx.x; i < d; i += blockDim.x) zs[i] = queries[q * d + i];
-        qadc_build_entry_map(L, esub);
+        for (int e = threadIdx.x; e < T; e += blockDim.x) esub[e] = (uint8_t)edesc[e].j;
+        __syncthreads();
         for (int e = threadIdx.x; e < T; e += blockDim.x) {
-            const int j = esub[e];
-            const int i = e - L->toff[j];
-            const int ds = L->dsub[j];
-            const float *c = cb + L->cboff[j] + (size_t)i * ds;
-            const float *z = zs + L->dimoff[j];
+            const EntryDesc ed = edesc[e];
+            const int ds = ed.ds;
+            const float *c = cb + ed.cb_off;
+            const float *z = zs + ed.dim_off;
             float acc = 0.0f;
             for (int l = 0; l < ds; ++l) {
                 float diff = __fsub_rn(z[l], c[l]);
@@ -107,8 +108,11 @@ k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
         }
         __syncthreads();
     } else {
-        for (int e = threadIdx.x; e < T; e += blockDim.x) tab[e] = tables_in[q * T + e];
-        qadc_build_entry_map(L, esub);
+        for (int e = threadIdx.x; e < T; e += blockDim.x) {
+            tab[e] = tables_in[q * T + e];
+            esub[e] = (uint8_t)edesc[e].j;
+        }
+        __syncthreads();
     }
     if ((int)threadIdx.x < m) {
         const int j = threadIdx.x;
@@ -122,8 +126,15 @@ k_quantize(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     for (int pp = threadIdx.x; pp < t_eff; pp += blockDim.x) {
         const uint8_t *code = codes + (size_t)pp * cs;
         float s = 0.0f;
-        for (int j = 0; j < m; ++j)
-            s = __fadd_rn(s, tab[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])]);
+        if (KIND == SCAN_NIB8) {  // sub-code j is nibble j of the 8-byte code
+            const uint2 v = *(const uint2 *)code;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                s = __fadd_rn(s, tab[16 * j + (((j < 8 ? v.x : v.y) >> (4 * (j & 7))) & 15u)]);
+        } else {
+            for (int j = 0; j < m; ++j)
+                s = __fadd_rn(s, tab[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])]);
+        }
         ord[pp] = qadc_f2ord(s);
     }
     __syncthreads();
@@ -326,7 +337,7 @@ static int launch_quantize(const pq_index *idx, const float *queries, const floa
         QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_quantize<KIND, QT>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL((k_quantize<KIND, QT>), dim3((unsigned)nq * (unsigned)pp.P), dim3(1024), lds, s,
-                       idx->dev, idx->codebooks, queries, tables_in, tables_out, codes, t_eff, k,
+                       idx->dev, idx->edesc, idx->codebooks, queries, tables_in, tables_out, codes, t_eff, k,
                        pp.pilot, pp.slice, pp.P, qtables, qparams, gtab_out, gtab_stride, partial,
                        sync, pp.P > 1 ? scratch_tag(partial) : 0ull);
     QADC_LAUNCH_CHECK("k_quantize");
