@@ -360,6 +360,21 @@ def test_ivf_other_layouts(qb, nbits, d, acc):
     check_ivf(qb, ip, 50)
 
 
+@pytest.mark.parametrize("d", [64, 80, 128])
+def test_ivf_16x4_subspace_widths(qb, d):
+    """16 x 4 bits over sub-spaces of 4, 5 and 8 dimensions: widths 4, 6 and 8 take the scan kernel
+    whose shape is fixed at compile time, 5 the one that reads the entry descriptors."""
+    ip = synth.make_ivf_problem(n=50_000, nq=6, d=d, nbits=[4] * 16, acc_bits=8, dist="aniso_gauss",
+                                K=96, nprobe=12, seed=11 + d, train_n=8000, kmeans_iters=3)
+    check_ivf(qb, ip, 100)
+
+
+def test_ivf_largest_nprobe(qb):
+    """nprobe = 1024, the most the call accepts: one slot list per probed cell in the selection."""
+    ip = synth.build(synth.scaled("C4", n=300_000, nq=3, K=2048, nprobe=1024, train_n=40_000, kmeans_iters=2))
+    check_ivf(qb, ip, 100)
+
+
 def test_ivf_edge_probes_and_padding(qb):
     ip = synth.build(synth.scaled("C4", n=2_000, nq=4, K=64, nprobe=4))
     probe = ip.probe_ids.clone()
