@@ -261,6 +261,18 @@ int pq_copy_bytes(void *dst, const void *src, size_t nbytes, void *stream);
 /* Description of the last error on this thread ("" if none). */
 const char *pq_last_error(void);
 
+/*
+ * Tuning knobs, read from the environment once per process (results never depend on them):
+ *   QADC_G              scan blocks per query for one or a few queries (default 2048; fewer
+ *                       leave room on the chip for other streams' small kernels)
+ *   QADC_PILOT          pilot codes of the fused search when several blocks share it (262144)
+ *   QADC_PILOT1         pilot codes when one block per query counts them (65536)
+ *   QADC_PILOT_BLOCKS   most blocks per query that share a pilot (8)
+ *   QADC_IVF_THREADS    threads per (query, list) block of the inverted-list scan (128)
+ *   QADC_NO_MQ          if set, batches are scanned one query per pass
+ *   QADC_COARSE_MATRIX  if set, the coarse search always writes the full score matrix
+ */
+
 #ifdef __cplusplus
 }
 #endif
