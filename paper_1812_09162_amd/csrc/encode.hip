@@ -6,13 +6,37 @@
 // fp32, dimensions ascending, separate subtract / multiply / add.  Sub-code j is the index of
 // the smallest distance, the lowest index among equals.
 //
-// One block of 256 threads encodes 64 vectors: they are staged (minus the shift) in LDS, and so
-// are the codebooks when they fit; wave w takes the sub-quantizers w, w+4, ... and lane v the
-// vector v, so that centroid values are uniform across a wave (one LDS word broadcast to 64
-// lanes); a second step packs the sub-codes.
+// One block of 256 threads encodes 64 vectors, staged (minus the shift) in LDS; wave w takes the
+// sub-quantizers w, w+4, ... and lane v the vector v, so that centroid values are uniform across
+// a wave: codebooks of up to 16 KB are read from memory with scalar loads (they stay in the
+// scalar cache), larger ones are staged in LDS when they fit (one word broadcast to 64 lanes).
+// Sub-spaces of up to 8 dimensions are unrolled.  A second step packs the sub-codes.
 #include "qadc_device.h"
 
 #define ENC_VB 64  // vectors per block
+
+// Nearest of kj centroids of DS dimensions (rows of c) to the sub-vector xv: eq. (1) term by
+// term, the lowest index among equal distances.
+template <int DS>
+__device__ __forceinline__ void enc_nearest(const float *xv, const float *c, int kj, float &best,
+                                            int &besti) {
+    float xr[DS];
+#pragma unroll
+    for (int l = 0; l < DS; ++l) xr[l] = xv[l];
+#pragma unroll 4
+    for (int i = 0; i < kj; ++i) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int l = 0; l < DS; ++l) {
+            const float diff = __fsub_rn(xr[l], c[i * DS + l]);
+            acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+        }
+        if (i == 0 || acc < best) {
+            best = acc;
+            besti = i;
+        }
+    }
+}
 
 __global__ void __launch_bounds__(256)
 k_encode(const DevLayout *__restrict__ L, const float *__restrict__ cb,
@@ -36,46 +60,47 @@ k_encode(const DevLayout *__restrict__ L, const float *__restrict__ cb,
     for (int e = threadIdx.x; e < cb_floats; e += blockDim.x) cbs[e] = cb[e];
     __syncthreads();
 
-    const int v = threadIdx.x % ENC_VB, w = threadIdx.x / ENC_VB;
-    for (int j = w; j < m; j += 4) {
-        const int ds = L->dsub[j], kj = 1 << L->nbits[j];
-        const float *c = (cb_floats ? (const float *)cbs : cb) + L->cboff[j];
-        const float *xv = xs + v * ldx + L->dimoff[j];
-        float best = INFINITY;
-        int besti = 0;
-        if (ds <= 8) {
-            float xr[8];
-#pragma unroll
-            for (int l = 0; l < 8; ++l) xr[l] = l < ds ? xv[l] : 0.0f;
-            for (int i = 0; i < kj; ++i) {
-                float acc = 0.0f;
-#pragma unroll
-                for (int l = 0; l < 8; ++l) {
-                    if (l < ds) {
-                        const float diff = __fsub_rn(xr[l], c[i * ds + l]);
-                        acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+    // the wave index as a scalar: sub-quantizer, widths and codebook addresses are then uniform
+    // values, and codebook entries read from memory come through the scalar cache
+    const int v = threadIdx.x % ENC_VB, w = __builtin_amdgcn_readfirstlane(threadIdx.x / ENC_VB);
+    // `c0` = the codebooks, in LDS or in memory: one instance of the loop for each, so that the
+    // reads are plain LDS reads or (uniform addresses) scalar loads, not generic-pointer loads
+    auto assign = [&](const float *c0) {
+        for (int j = w; j < m; j += 4) {
+            const int ds = L->dsub[j], kj = 1 << L->nbits[j];
+            const float *c = c0 + L->cboff[j];
+            const float *xv = xs + v * ldx + L->dimoff[j];
+            float best = INFINITY;
+            int besti = 0;
+            switch (ds) {  // uniform over the wave; widths up to 8 are unrolled without predicates
+                case 1: enc_nearest<1>(xv, c, kj, best, besti); break;
+                case 2: enc_nearest<2>(xv, c, kj, best, besti); break;
+                case 3: enc_nearest<3>(xv, c, kj, best, besti); break;
+                case 4: enc_nearest<4>(xv, c, kj, best, besti); break;
+                case 5: enc_nearest<5>(xv, c, kj, best, besti); break;
+                case 6: enc_nearest<6>(xv, c, kj, best, besti); break;
+                case 7: enc_nearest<7>(xv, c, kj, best, besti); break;
+                case 8: enc_nearest<8>(xv, c, kj, best, besti); break;
+                default:
+                    for (int i = 0; i < kj; ++i) {
+                        float acc = 0.0f;
+                        for (int l = 0; l < ds; ++l) {
+                            const float diff = __fsub_rn(xv[l], c[i * ds + l]);
+                            acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                        }
+                        if (i == 0 || acc < best) {
+                            best = acc;
+                            besti = i;
+                        }
                     }
-                }
-                if (i == 0 || acc < best) {
-                    best = acc;
-                    besti = i;
-                }
             }
-        } else {
-            for (int i = 0; i < kj; ++i) {
-                float acc = 0.0f;
-                for (int l = 0; l < ds; ++l) {
-                    const float diff = __fsub_rn(xv[l], c[i * ds + l]);
-                    acc = __fadd_rn(acc, __fmul_rn(diff, diff));
-                }
-                if (i == 0 || acc < best) {
-                    best = acc;
-                    besti = i;
-                }
-            }
+            if (v < nv) sub[v * m + j] = (uint8_t)besti;
         }
-        if (v < nv) sub[v * m + j] = (uint8_t)besti;
-    }
+    };
+    if (cb_floats)
+        assign(cbs);
+    else
+        assign(cb);
     __syncthreads();
 
     // pack: one output byte per thread and round
@@ -110,6 +135,8 @@ extern "C" int pq_encode(const pq_index_t *idx, const float *vectors, int64_t n,
     for (int j = 0; j < h.m; ++j) cbf += ((size_t)1 << h.nbits[j]) * (size_t)h.dsub[j];
     const size_t base_lds = (size_t)ENC_VB * (size_t)(h.d | 1) * sizeof(float) + (size_t)ENC_VB * (size_t)h.m;
     if (cbf * sizeof(float) > 48 * 1024 || base_lds + cbf * sizeof(float) > 96 * 1024) cbf = 0;
+    // small codebooks are read through the scalar cache instead (faster than LDS reads)
+    if (cbf * sizeof(float) <= 16 * 1024) cbf = 0;
     const size_t lds = base_lds + cbf * sizeof(float);
     if (lds > 160 * 1024) {
         qadc_set_error("pq_encode: d=%d needs %zu bytes of LDS per block, more than 163840", h.d, lds);
