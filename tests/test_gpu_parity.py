@@ -360,11 +360,12 @@ def test_ivf_other_layouts(qb, nbits, d, acc):
     check_ivf(qb, ip, 50)
 
 
-@pytest.mark.parametrize("d", [64, 80, 128])
-def test_ivf_16x4_subspace_widths(qb, d):
-    """16 x 4 bits over sub-spaces of 4, 5 and 8 dimensions: widths 4, 6 and 8 take the scan kernel
-    whose shape is fixed at compile time, 5 the one that reads the entry descriptors."""
-    ip = synth.make_ivf_problem(n=50_000, nq=6, d=d, nbits=[4] * 16, acc_bits=8, dist="aniso_gauss",
+@pytest.mark.parametrize("d,acc", [(64, 8), (80, 8), (128, 8), (96, 16)])
+def test_ivf_16x4_subspace_widths(qb, d, acc):
+    """16 x 4 bits over sub-spaces of 4, 5 and 8 dimensions: widths 4, 6 and 8 with 8-bit tables
+    take the scan kernel whose shape is fixed at compile time; width 5, and 16-bit tables, the
+    one that reads the entry descriptors."""
+    ip = synth.make_ivf_problem(n=50_000, nq=6, d=d, nbits=[4] * 16, acc_bits=acc, dist="aniso_gauss",
                                 K=96, nprobe=12, seed=11 + d, train_n=8000, kmeans_iters=3)
     check_ivf(qb, ip, 100)
 
