@@ -258,14 +258,38 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
 // of a 16-bit field).  Code bytes are loaded and split into indices once for all four.
 // NG = groups per code (8: 64-bit codes, 16: 128-bit codes).
 #define MQ 4
+// Byte N of w, times 8 (the byte offset of an 8-byte table entry), as one instruction: a shift
+// whose operand is selected by sub-dword addressing.
+template <int N>
+__device__ __forceinline__ uint32_t mq_byte_x8(uint32_t w, uint32_t three) {
+    uint32_t r;
+    if (N == 0)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(three), "v"(w));
+    else if (N == 1)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(three), "v"(w));
+    else if (N == 2)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(three), "v"(w));
+    else
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(three), "v"(w));
+    return r;
+}
+// Entry `byte N of w` of group g of the interleaved tables, which start at LDS address 0 (the
+// kernel has no other LDS but what follows them): the read takes the shifted byte as its
+// address and g * 2048 as its immediate offset.
+typedef const unsigned long long __attribute__((address_space(3))) mq_lds_entry;
+template <int N>
+__device__ __forceinline__ uint2 mq_entry(int g, uint32_t w, uint32_t three) {
+    const unsigned long long e = *(mq_lds_entry *)(g * 2048u + mq_byte_x8<N>(w, three));
+    return make_uint2((uint32_t)e, (uint32_t)(e >> 32));
+}
 template <int NG>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__restrict__ codes,
           int64_t n, char *__restrict__ ws, size_t per_query, size_t slots_off, size_t gtab_off,
           int cap_b, uint32_t qmax) {
     extern __shared__ __align__(16) unsigned char smem[];
-    uint2 *tab = (uint2 *)smem;  // [NG][256]
-    __shared__ uint32_t s_count[MQ];
+    uint2 *tab = (uint2 *)smem;  // [NG][256], at LDS offset 0: entry offsets go into the reads as they are
+    uint32_t *s_count = (uint32_t *)(smem + NG * 256 * 8);  // [MQ]
     const int q0 = blockIdx.y * MQ;
     const int b = blockIdx.x, G = gridDim.x;
     uint32_t thr[MQ];
@@ -302,6 +326,7 @@ k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__res
     const int64_t nfull = NG == 8 ? (n >> 1) : n;
     const int64_t ntiles = (nfull + U * SCAN_THREADS - 1) / (U * SCAN_THREADS);
     const uint4 *__restrict__ p = (const uint4 *)codes;
+    const uint32_t three = 3;  // shift count of mq_byte_x8, held in a register
     for (int64_t tile = b; tile < ntiles; tile += G) {
         uint4 cur[U];
 #pragma unroll
@@ -319,12 +344,12 @@ k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__res
             for (int k = 0; k < CPC; ++k) {
                 uint32_t lo = 0, hi = 0;
 #pragma unroll
-                for (int g = 0; g < NG; ++g) {
+                for (int g = 0; g < NG; g += 4) {
                     const uint32_t word = w[(NG == 8 ? 2 * k : 0) + (g >> 2)];
-                    const uint32_t byte = (word >> (8 * (g & 3))) & 255u;
-                    const uint2 e = tab[g * 256 + byte];
-                    lo += e.x;
-                    hi += e.y;
+                    const uint2 e0 = mq_entry<0>(g, word, three), e1 = mq_entry<1>(g + 1, word, three);
+                    const uint2 e2 = mq_entry<2>(g + 2, word, three), e3 = mq_entry<3>(g + 3, word, three);
+                    lo += e0.x + e1.x + e2.x + e3.x;
+                    hi += e0.y + e1.y + e2.y + e3.y;
                 }
                 const int sidx = u * CPC + k;
                 sum[0][sidx] = lo & 0xffffu;
@@ -715,12 +740,24 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
     if ((what & 1) && sizeof(QT) == 1 && nq >= 2 && (KIND == SCAN_NIB8 || KIND == SCAN_NIB16) && !no_mq_nib) {
         // several queries: four of them share every pass over the codes
         const int groups = (nq + MQ - 1) / MQ;
+        // k_scan_mq addresses its tables from LDS address 0: it must have no static LDS
+        static const int mq_static_lds = [] {
+            hipFuncAttributes a8, a16;
+            if (hipFuncGetAttributes(&a8, (const void *)k_scan_mq<8>) != hipSuccess ||
+                hipFuncGetAttributes(&a16, (const void *)k_scan_mq<16>) != hipSuccess)
+                return -1;
+            return (int)(a8.sharedSizeBytes + a16.sharedSizeBytes);
+        }();
+        if (mq_static_lds != 0) {
+            qadc_set_error("k_scan_mq: static LDS of %d bytes (its tables must start at LDS address 0)", mq_static_lds);
+            return PQ_EHIP;
+        }
         if (KIND == SCAN_NIB8)
-            hipLaunchKernelGGL((k_scan_mq<8>), dim3(p.G, groups), dim3(SCAN_THREADS), 8 * 256 * 8, s,
+            hipLaunchKernelGGL((k_scan_mq<8>), dim3(p.G, groups), dim3(SCAN_THREADS), 8 * 256 * 8 + 16, s,
                                qparams, nq, codes, n, ws, p.per_query, p.slots_off, p.gtab_off,
                                p.cap_b, (uint32_t)h.qmax);
         else
-            hipLaunchKernelGGL((k_scan_mq<16>), dim3(p.G, groups), dim3(SCAN_THREADS), 16 * 256 * 8, s,
+            hipLaunchKernelGGL((k_scan_mq<16>), dim3(p.G, groups), dim3(SCAN_THREADS), 16 * 256 * 8 + 16, s,
                                qparams, nq, codes, n, ws, p.per_query, p.slots_off, p.gtab_off,
                                p.cap_b, (uint32_t)h.qmax);
         QADC_LAUNCH_CHECK("k_scan_mq");
