@@ -557,10 +557,13 @@ struct FinalOut {
 };
 
 // Rank the na candidates of A by (key, id) and write the first R, padding the rest.
-// `rank` is 512 words of LDS.  Few candidates: several threads share one candidate, each
-// counting over a part of A.
+// `rank` is 768 words of LDS, `order` na 16-bit words.  Few candidates: several threads share
+// one candidate, each counting over a part of A.  Many candidates (long result lists): they
+// are first grouped by key bin (key >> shift, at most 256 bins) with a counting sort of their
+// indices, and a candidate is then compared only with the others of its bin.
 __device__ inline void rank_and_write(const uint64_t *A, int na, int R, const pq_qparams_t &prm,
-                                      uint32_t qmax, const FinalOut &o, uint32_t *rank) {
+                                      uint32_t qmax, const FinalOut &o, uint32_t *rank, int shift,
+                                      uint16_t *order) {
     const float fdelta = (float)prm.delta, fdmin = (float)prm.d_min;
     if (na <= 512) {
         // 2^lt threads per candidate, each counting over its share of A
@@ -589,10 +592,39 @@ __device__ inline void rank_and_write(const uint64_t *A, int na, int R, const pq
             }
         }
     } else {
+        uint32_t *cnt = rank, *start = rank + 256, *fill = rank + 512;
+        for (int i = threadIdx.x; i < 768; i += blockDim.x) rank[i] = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < na; i += blockDim.x)
+            atomicAdd(&cnt[((uint32_t)(A[i] >> 32) >> shift) & 255u], 1u);
+        __syncthreads();
+        if (threadIdx.x < QADC_WAVE) {  // exclusive prefix of the 256 counts, four bins per lane
+            const int lane = threadIdx.x;
+            uint32_t c[4], sum = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                c[k] = cnt[4 * lane + k];
+                sum += c[k];
+            }
+            uint32_t run = qadc_wave_incl_scan(sum) - sum;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                start[4 * lane + k] = run;
+                run += c[k];
+            }
+        }
+        __syncthreads();
         for (int i = threadIdx.x; i < na; i += blockDim.x) {
-            const uint64_t mine = A[i];
-            int r = 0;
-            for (int j = 0; j < na; ++j) r += (A[j] < mine) ? 1 : 0;
+            const uint32_t b = ((uint32_t)(A[i] >> 32) >> shift) & 255u;
+            order[start[b] + atomicAdd(&fill[b], 1u)] = (uint16_t)i;
+        }
+        __syncthreads();
+        for (int p = threadIdx.x; p < na; p += blockDim.x) {
+            const uint64_t mine = A[order[p]];
+            const uint32_t b = ((uint32_t)(mine >> 32) >> shift) & 255u;
+            const int gs = (int)start[b], ge = gs + (int)cnt[b];
+            int r = gs;
+            for (int j = gs; j < ge; ++j) r += (A[order[j]] < mine) ? 1 : 0;
             if (r < R) {
                 const uint32_t key = (uint32_t)(mine >> 32);
                 o.ids[r] = (int32_t)(uint32_t)mine;
@@ -720,7 +752,8 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         __syncthreads();
         na = (int)sh[2];
     }
-    rank_and_write(A, na, R, prm, qmax, o, &whist[0][0]);
+    __syncthreads();  // the selection is done with `off`: its memory now holds the sort order
+    rank_and_write(A, na, R, prm, qmax, o, &whist[0][0], shift, (uint16_t *)off);
 }
 
 // ------------------------------------------------------------------ host ---
