@@ -69,6 +69,10 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
     __shared__ double s_dmin, s_delta;
     __shared__ float s_dmax;
     __shared__ int s_last;
+    __shared__ uint32_t sdesc[PQ_MAX_M];  // table offset | bit offset << 12 | bits << 24 of each sub-quantizer
+    if ((int)threadIdx.x < m)  // (read after the barriers of the table set-up)
+        sdesc[threadIdx.x] = (uint32_t)L->toff[threadIdx.x] | ((uint32_t)L->bitoff[threadIdx.x] << 12) |
+                             ((uint32_t)L->nbits[threadIdx.x] << 24);
 
     const size_t q = blockIdx.x / (unsigned)P;
     const int p = (int)(blockIdx.x % (unsigned)P);
@@ -131,6 +135,19 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
 #pragma unroll
             for (int j = 0; j < 16; ++j)
                 s = __fadd_rn(s, tab[16 * j + (((j < 8 ? v.x : v.y) >> (4 * (j & 7))) & 15u)]);
+        } else if (KIND == SCAN_NIB16) {  // ... of the 16-byte code
+            const uint4 v = *(const uint4 *)code;
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int j = 0; j < 32; ++j)
+                s = __fadd_rn(s, tab[16 * j + ((w[j >> 3] >> (4 * (j & 7))) & 15u)]);
+        } else if (cs <= 16) {  // the code in registers, the sub-quantizers' fields from LDS
+            uint32_t w[4];
+            qadc_load_code16(code, cs, w);
+            for (int j = 0; j < m; ++j) {
+                const uint32_t ds = sdesc[j];
+                s = __fadd_rn(s, tab[(ds & 0xfffu) + qadc_extract_sub16(w, (ds >> 12) & 0xfffu, ds >> 24)]);
+            }
         } else {
             for (int j = 0; j < m; ++j)
                 s = __fadd_rn(s, tab[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])]);
