@@ -272,8 +272,9 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
 }
 
 // ------------------------------------------------------------- k_ivf_scan ---
-// One block per (query, probed cell).  The block is latency bound (a few thousand codes
-// behind a chain of small dependent steps), so the set-up is ordered for few round trips:
+// One block per (query, probed cell).  A block is short (a few thousand codes behind a chain
+// of small dependent steps) and the kernel as a whole streams lists that are not cached, so
+// many blocks per CU matter (few registers) and the set-up is ordered for few round trips:
 //   A  probe id, query state, query, entry descriptors      (independent loads)
 //   B  list bounds, centroid, codebook values of the entries (need A)
 //   C  the first codes of the list                           (need B; used after the set-up)
