@@ -224,6 +224,61 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
                     count_key(id < hi ? (sm > (uint32_t)qmax ? (uint32_t)qmax : sm) : 0xffffffffu);
                 }
             }
+        } else if ((KIND == SCAN_W64 || KIND == SCAN_C5) && L->g32ok != 0 && L->ng <= QADC_MAXG_FAST) {
+            // group descriptors in registers; 8-byte codes one per load, 5-byte codes four per
+            // 20-byte chunk of five dwords (slices start on multiples of 1024 codes)
+            const GroupDesc gd = load_group_desc(L);
+            for (int base = lo; base < hi; base += step) {
+                if (KIND == SCAN_W64) {
+                    uint2 w[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        int id = base + u * (int)blockDim.x + (int)threadIdx.x;
+                        id = id < hi ? id : hi - 1;
+                        w[u] = *(const uint2 *)(codes + (size_t)id * 8);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int id = base + u * (int)blockDim.x + (int)threadIdx.x;
+                        const uint32_t sm = sum_groups_rt(gd, gtab, w[u].x, w[u].y);
+                        count_key(id < hi ? (sm > (uint32_t)qmax ? (uint32_t)qmax : sm) : 0xffffffffu);
+                    }
+                } else {
+                    uint32_t c5[2][5];
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const int id = base + 4 * (u * (int)blockDim.x + (int)threadIdx.x);
+#pragma unroll
+                        for (int i = 0; i < 5; ++i)  // a chunk not wholly inside is handled code by code
+                            c5[u][i] = id + 3 < hi ? ((const uint32_t *)(codes + (size_t)id * 5))[i] : 0u;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 2; ++u) {
+                        const int id = base + 4 * (u * (int)blockDim.x + (int)threadIdx.x);
+                        uint32_t k4[4];
+                        if (id + 3 < hi) {
+                            // code v = bits [40v, 40v+40) of the chunk, as (low dword, high byte)
+                            const uint32_t l4[4] = {c5[u][0], __builtin_amdgcn_alignbit(c5[u][2], c5[u][1], 8),
+                                                    __builtin_amdgcn_alignbit(c5[u][3], c5[u][2], 16),
+                                                    __builtin_amdgcn_alignbit(c5[u][4], c5[u][3], 24)};
+                            const uint32_t h4[4] = {c5[u][1] & 0xffu, (c5[u][2] >> 8) & 0xffu,
+                                                    (c5[u][3] >> 16) & 0xffu, c5[u][4] >> 24};
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) {
+                                const uint32_t sm = sum_groups_rt(gd, gtab, l4[v], h4[v]);
+                                k4[v] = sm > (uint32_t)qmax ? (uint32_t)qmax : sm;
+                            }
+                        } else {
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                k4[v] = id + v < hi ? key_at<KIND, QT>(L, gtab, codes, id + v) : 0xffffffffu;
+                        }
+                        // (count_key holds wave-wide operations: every lane calls it)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) count_key(k4[v]);
+                    }
+                }
+            }
         } else {
             for (int base = lo; base < hi; base += step) {
                 uint32_t key[8];

@@ -139,6 +139,19 @@ __device__ __forceinline__ GroupDesc load_group_desc(const DevLayout *L) {
     }
     return d;
 }
+// the same with the number of groups (at most QADC_MAXG_FAST) known only at run time
+template <typename QT>
+__device__ __forceinline__ uint32_t sum_groups_rt(const GroupDesc &d, const QT *gtab, uint32_t lo,
+                                                  uint32_t hi) {
+    uint32_t s = 0;
+#pragma unroll
+    for (int g = 0; g < QADC_MAXG_FAST; ++g)
+        if (g < d.ng) {
+            const uint32_t x = d.off[g] >= 32 ? hi : lo;
+            s += gtab[d.base[g] + __builtin_amdgcn_ubfe(x, (uint32_t)(d.off[g] & 31), (uint32_t)d.w[g])];
+        }
+    return s;
+}
 // code of at most 64 bits as two dwords, no group crossing the dword boundary; NG = number
 // of groups, fixed at compile time so that all lookups of a code are issued together
 // NLO >= 0: the first NLO groups lie in the low dword and the rest in the high one, known at
