@@ -391,3 +391,42 @@ def test_ivf_degenerate_identical_vectors(qb):
     ip = synth.build(synth.scaled("C4", n=60_000, nq=3, K=16, nprobe=4))
     ip.list_codes = ip.list_codes[:1].repeat(ip.list_codes.shape[0], 1).contiguous()
     check_ivf(qb, ip, 100)
+
+
+def test_concurrent_streams_and_repeats(qb):
+    """Calls that overlap on the GPU (eight streams, a workspace each) and repeated calls give the
+    bytes of a call alone on the default stream, which the oracle checks for the first queries.
+    (The result is defined as a sort, so nothing may depend on timing or on what a reused
+    workspace held.)"""
+    pr = synth.build(synth.scaled("C1", n=400_000, nq=24))
+    lay = pr.layout
+    idx = make_index(qb, pr)
+    codes = pr.codes.to(dev())
+    qs = pr.queries.to(dev())
+    R, nq, ns = 100, qs.shape[0], 8
+    alone = [qb.pq_search_topk(idx, qs[q:q + 1].contiguous(), codes, T_CAL, R) for q in range(nq)]
+    torch.cuda.synchronize()
+    cb, codes_np = pr.codebooks.numpy(), pr.codes.numpy()
+    for q in range(3):
+        oi, ok, od = oracle.search(lay.d, lay.nbits, lay.dsub, lay.acc_bits, cb, pr.queries[q].numpy(),
+                                   codes_np, T_CAL, R)
+        assert np.array_equal(alone[q][0][0].cpu().numpy(), oi)
+        assert np.array_equal(alone[q][1][0].cpu().numpy().astype(np.uint16), ok)
+        assert np.array_equal(alone[q][2][0].cpu().numpy(), od)
+    streams = [torch.cuda.Stream(device=dev()) for _ in range(ns)]
+    nbytes = qb.pq_search_workspace_bytes(idx, 1, codes.shape[0], R)
+    ws = [torch.empty(nbytes, dtype=torch.uint8, device=dev()) for _ in range(ns)]
+    for rep in range(3):
+        outs = []
+        for q in range(nq):
+            s = streams[q % ns]
+            if q >= ns:
+                s.synchronize()  # the stream's workspace and this slot's predecessor are done
+            with torch.cuda.stream(s):
+                outs.append(qb.pq_search_topk(idx, qs[q:q + 1].contiguous(), codes, T_CAL, R,
+                                              workspace=ws[q % ns], stream=s))
+        torch.cuda.synchronize()
+        for q in range(nq):
+            for a, b in zip(alone[q], outs[q]):
+                assert torch.equal(a, b), (rep, q)
+    idx.close()
