@@ -560,3 +560,25 @@ def test_encode_agrees_with_the_input_fabricator_on_exact_data():
     want = synth.pack_codes(synth.encode(torch.from_numpy(x), lay, torch.from_numpy(cb)), lay).numpy()
     # ties are possible with integer centroids: both break them towards the lowest index
     assert np.array_equal(oracle.encode(lay.d, lay.nbits, lay.dsub, cb, x), want)
+
+
+def test_oracle_clean_under_sanitizers(tmp_path):
+    """The oracle's C source, built with AddressSanitizer and UndefinedBehaviorSanitizer, runs a
+    driver over every entry point (regular and irregular layouts, empty and short lists, more
+    results than codes, empty and invalid inverted lists) without a report."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "oracle_sanitizer_driver")
+    build = subprocess.run(
+        ["gcc", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+         "-static-libasan", "-ffp-contract=off", os.path.join(root, "oracle", "adc_oracle.c"),
+         os.path.join(root, "tests", "oracle_sanitizer_driver.c"), "-lm", "-o", exe],
+        capture_output=True, text=True)
+    if build.returncode != 0:
+        pytest.skip("no sanitizer runtimes for gcc here: " + build.stderr[-300:])
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1",
+               UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+    run = subprocess.run([exe], env=env, capture_output=True, text=True, timeout=300)
+    assert run.returncode == 0, (run.stdout[-500:], run.stderr[-3000:])
+    assert "ok" in run.stdout
