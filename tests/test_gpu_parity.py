@@ -430,3 +430,26 @@ def test_concurrent_streams_and_repeats(qb):
             for a, b in zip(alone[q], outs[q]):
                 assert torch.equal(a, b), (rep, q)
     idx.close()
+
+
+def test_pipeline_coarse_search_then_ivf(qb):
+    """The two calls chained as a caller would: ivf_coarse_search picks the cells, its output
+    feeds ivf_adc_scan_topk; the oracle does the same two steps."""
+    ip = synth.build(synth.scaled("C4", n=80_000, nq=6, K=128, nprobe=8))
+    lay = ip.layout
+    idx = qb.PqIndex(lay.d, lay.nbits, lay.dsub, ip.codebooks.to(dev()), lay.acc_bits)
+    nprobe, R = 8, 50
+    qs, coarse = ip.queries.to(dev()), ip.coarse.to(dev())
+    probe, _ = qb.ivf_coarse_search(qs, coarse, nprobe)
+    gi, gd = qb.ivf_adc_scan_topk(idx, coarse, ip.list_offsets.to(dev()), ip.list_codes.to(dev()),
+                                  ip.list_ids.to(dev()), qs, probe, T_CAL, R)
+    torch.cuda.synchronize()
+    for q in range(qs.shape[0]):
+        opr, _ = oracle.coarse_search(ip.coarse.numpy(), ip.queries[q].numpy(), nprobe)
+        assert np.array_equal(probe[q].cpu().numpy(), opr)
+        oi, od, _ = oracle.search_ivf(lay.d, lay.nbits, lay.dsub, lay.acc_bits, ip.codebooks.numpy(),
+                                      ip.coarse.numpy(), ip.list_offsets.numpy(), ip.list_codes.numpy(),
+                                      ip.list_ids.numpy(), ip.queries[q].numpy(), opr, T_CAL, R)
+        assert np.array_equal(gi[q].cpu().numpy(), oi)
+        assert np.array_equal(gd[q].cpu().numpy(), od)
+    idx.close()
