@@ -388,7 +388,8 @@ def main_ivf(a):
     bs = min(bs, nq_all)
     sizes = ip.list_offsets[1:] - ip.list_offsets[:-1]
     probed = sizes[ip.probe_ids.long()].sum(dim=1)  # codes scanned per query
-    ws = torch.empty(qb.ivf_workspace_bytes(idx, bs, nprobe, a.R), dtype=torch.uint8, device=dev)
+    ws = torch.empty(qb.ivf_sorted_workspace_bytes(idx, bs, nprobe, a.R, ip.coarse.shape[0]), dtype=torch.uint8,
+                     device=dev)
     out = (torch.empty((bs, a.R), dtype=torch.int32, device=dev),
            torch.empty((bs, a.R), dtype=torch.float32, device=dev))
 
@@ -423,6 +424,12 @@ def main_ivf(a):
                    "codes_scanned_per_query": float(probed.float().mean().item())},
         "us_per_query": dt / steps / bs * 1e6,
         "list_bytes_per_s_gb": per_step * steps / dt * (cs + 0) / 1e9,
+        # bytes of list codes a step reads (every probed list once per query that probes it) and
+        # what it would read if each distinct probed list were read once per step
+        "list_bytes_per_step": {
+            "as_read": per_step * cs,
+            "distinct_lists_once": float(sizes[torch.unique(ip.probe_ids[:bs].long())].sum().item()) * cs,
+        },
     }
     print(json.dumps(out_d))
 

@@ -101,6 +101,11 @@ size_t pq_table_len(const pq_index_t *idx); /* T = sum_j 2^nbits[j] */
 size_t pq_workspace_bytes(const pq_index_t *idx, int nq, int64_t n, int R);
 /* Bytes of workspace ivf_adc_scan_topk needs for (nq queries, nprobe probes, R). */
 size_t ivf_workspace_bytes(const pq_index_t *idx, int nq, int nprobe, int R);
+/* The same plus room to order the (query, probe) pairs by probed cell (K cells): given that
+ * much, and at least K/4 pairs, ivf_adc_scan_topk scans the pairs of one cell close together
+ * in time, so that a list probed by several queries of the call is read from memory once
+ * (Section 2.1.3: queries of a batch probe overlapping cells).  Results are the same. */
+size_t ivf_sorted_workspace_bytes(const pq_index_t *idx, int nq, int nprobe, int R, int K);
 
 /*
  * Distance tables, eq. (1): tables[q][toff_j + i] = || z_q^j - C^j[i] ||^2.
@@ -202,6 +207,7 @@ int pq_search_topk(const pq_index_t *idx, const float *queries, int nq, const ui
  *                negative entries are ignored
  *   out_ids      [dev][nq][R] int32     out_dist [dev][nq][R] float32
  *   workspace    >= ivf_workspace_bytes(idx, nq, nprobe, R), 256-byte aligned
+ *                (ivf_sorted_workspace_bytes for the cell-ordered scan)
  * Requires 1 <= nprobe <= 1024 and the limits of pq_quantize_tables.
  */
 int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_centroids, int K,

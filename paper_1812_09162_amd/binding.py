@@ -23,7 +23,7 @@ QPARAMS_BYTES = 24
 
 EXPORTS = [
     "pq_index_create", "pq_index_destroy", "pq_code_size", "pq_table_len", "pq_workspace_bytes",
-    "ivf_workspace_bytes", "pq_compute_tables", "pq_quantize_tables", "pq_adc_scan_topk",
+    "ivf_workspace_bytes", "ivf_sorted_workspace_bytes", "pq_compute_tables", "pq_quantize_tables", "pq_adc_scan_topk",
     "ivf_adc_scan_topk", "pq_search_workspace_bytes", "pq_search_topk",
     "pq_adc_scan_candidates", "pq_adc_rescan_candidates", "pq_select_topk", "pq_copy_bytes", "pq_last_error",
     "ivf_coarse_workspace_bytes", "ivf_coarse_search", "pq_encode",
@@ -58,6 +58,8 @@ def load() -> ctypes.CDLL:
     lib.pq_workspace_bytes.restype = sz
     lib.ivf_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.ivf_workspace_bytes.restype = sz
+    lib.ivf_sorted_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
+    lib.ivf_sorted_workspace_bytes.restype = sz
     lib.pq_compute_tables.argtypes = [vp, vp, i32, vp, vp]
     lib.pq_compute_tables.restype = i32
     lib.pq_quantize_tables.argtypes = [vp, vp, i32, vp, i64, i32, i32, vp, vp, vp]
@@ -157,6 +159,10 @@ def ivf_workspace_bytes(idx: PqIndex, nq: int, nprobe: int, R: int) -> int:
     return int(load().ivf_workspace_bytes(idx.handle, nq, nprobe, R))
 
 
+def ivf_sorted_workspace_bytes(idx: PqIndex, nq: int, nprobe: int, R: int, K: int) -> int:
+    return int(load().ivf_sorted_workspace_bytes(idx.handle, nq, nprobe, R, K))
+
+
 def pq_compute_tables(idx: PqIndex, queries: torch.Tensor, tables: Optional[torch.Tensor] = None,
                       stream=None) -> torch.Tensor:
     _dev(queries, torch.float32)
@@ -240,8 +246,8 @@ def ivf_adc_scan_topk(idx: PqIndex, coarse: torch.Tensor, list_offsets: torch.Te
     nq, nprobe = probe_ids.shape
     dev = queries.device
     if workspace is None:
-        workspace = torch.empty(ivf_workspace_bytes(idx, nq, nprobe, R), dtype=torch.uint8,
-                                device=dev)
+        workspace = torch.empty(ivf_sorted_workspace_bytes(idx, nq, nprobe, R, coarse.shape[0]),
+                                dtype=torch.uint8, device=dev)
     if out is None:
         out = (torch.empty((nq, R), dtype=torch.int32, device=dev),
                torch.empty((nq, R), dtype=torch.float32, device=dev))

@@ -271,6 +271,73 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
     }
 }
 
+// ------------------------------------------------- (query, probe) pairs by cell ---
+// The scan kernel's blocks are handed out in the order of the probed cell, so that the blocks
+// that read one inverted list run close together and all but the first find it in the L2 /
+// last-level cache: a counting sort of the pair indices p = q * nprobe + a into NB <= 4096
+// buckets of consecutive cells (a bucket's few dozen blocks run within one filling of the chip,
+// which is close enough, and its lists are neighbours in memory).  Pairs without a list
+// (negative or out-of-range id, empty list) go to a bucket of their own at the end.  The order
+// within a bucket depends on timing; results do not (every pair owns its slots).
+#define IVF_SORT_BUCKETS 4096
+__global__ void __launch_bounds__(256)
+k_pair_zero(uint32_t *__restrict__ cnt, int nwords) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nwords) cnt[i] = 0;
+}
+
+__device__ __forceinline__ int ivf_pair_bucket(const int32_t *__restrict__ probe_ids,
+                                               const int64_t *__restrict__ list_offsets, int64_t p, int K,
+                                               int NB) {
+    const int c = probe_ids[p];
+    if (c < 0 || c >= K) return NB;
+    return list_offsets[c + 1] > list_offsets[c] ? (int)(((int64_t)c * NB) / K) : NB;
+}
+
+__global__ void __launch_bounds__(256)
+k_pair_count(const int32_t *__restrict__ probe_ids, const int64_t *__restrict__ list_offsets,
+             int64_t npairs, int K, int NB, uint32_t *__restrict__ cnt) {
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p < npairs) atomicAdd(&cnt[ivf_pair_bucket(probe_ids, list_offsets, p, K, NB)], 1u);
+}
+
+// one block: start[b] = number of pairs in buckets before b (b = 0 .. NB), and cnt cleared to
+// serve as the buckets' fill cursors
+__global__ void __launch_bounds__(1024)
+k_pair_scan(uint32_t *__restrict__ cnt, uint32_t *__restrict__ start, int nb) {
+    __shared__ uint32_t wsum[16];
+    __shared__ uint32_t carry;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
+    for (int base = 0; base < nb; base += 1024) {
+        const int i = base + (int)threadIdx.x;
+        const uint32_t v = i < nb ? cnt[i] : 0u;
+        const uint32_t incl = qadc_wave_incl_scan(v);
+        if (lane == QADC_WAVE - 1) wsum[wave] = incl;
+        __syncthreads();
+        uint32_t before = carry;
+        for (int w = 0; w < wave; ++w) before += wsum[w];
+        if (i < nb) {
+            start[i] = before + incl - v;
+            cnt[i] = 0;
+        }
+        __syncthreads();
+        if (threadIdx.x == 1023) carry = before + incl;
+        __syncthreads();
+    }
+}
+
+__global__ void __launch_bounds__(256)
+k_pair_fill(const int32_t *__restrict__ probe_ids, const int64_t *__restrict__ list_offsets,
+            int64_t npairs, int K, int NB, const uint32_t *__restrict__ start,
+            uint32_t *__restrict__ fill, uint32_t *__restrict__ order) {
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= npairs) return;
+    const int b = ivf_pair_bucket(probe_ids, list_offsets, p, K, NB);
+    order[start[b] + atomicAdd(&fill[b], 1u)] = (uint32_t)p;
+}
+
 // ------------------------------------------------------------- k_ivf_scan ---
 // One block per (query, probed cell).  A block is short (a few thousand codes behind a chain
 // of small dependent steps) and the kernel as a whole streams lists that are not cached, so
@@ -293,13 +360,17 @@ k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
            const int64_t *__restrict__ list_offsets, const uint8_t *__restrict__ list_codes,
            const int32_t *__restrict__ list_ids, const float *__restrict__ queries,
            const int32_t *__restrict__ probe_ids, int nprobe, int K, int R, char *__restrict__ ws,
-           size_t per_query, size_t counts_off, size_t slots_off, int cap_b) {
+           size_t per_query, size_t counts_off, size_t slots_off, int cap_b,
+           const uint32_t *__restrict__ order) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t s_count;
     IvfLds l;
     ivf_carve(L, smem, sizeof(QT), l);
-    const size_t q = blockIdx.y;
-    const int a = blockIdx.x;
+    // block -> (query, probe): in grid order, or in the order of the probed cells
+    const uint32_t lin = blockIdx.y * gridDim.x + blockIdx.x;
+    const uint32_t pair = order ? order[lin] : lin;
+    const size_t q = pair / (uint32_t)nprobe;
+    const int a = (int)(pair % (uint32_t)nprobe);
     constexpr bool FIX = DS > 0;
     static_assert(!FIX || (KIND == SCAN_NIB8 && NE > 0 && DS <= 8 && 256 % NE == 0), "fixed shape");
     const int bd = FIX ? 256 / (NE > 0 ? NE : 1) : (int)blockDim.x;
@@ -676,7 +747,27 @@ template <int KIND, typename QT>
 static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *list_offsets,
                       const uint8_t *list_codes, const int32_t *list_ids, const float *queries,
                       int nq, const int32_t *probe_ids, int nprobe, int K, int want, int R,
-                      int32_t *out_ids, float *out_dist, char *ws, const IvfPlan &p, hipStream_t s) {
+                      int32_t *out_ids, float *out_dist, char *ws, const IvfPlan &p, uint32_t *sortws,
+                      hipStream_t s) {
+    // blocks in the order of the probed cells (see k_pair_count):
+    // sortws = cnt[NB+1] | start[NB+1] | order[pairs]
+    const uint32_t *order = nullptr;
+    if (sortws) {
+        const int64_t npairs = (int64_t)nq * nprobe;
+        const int NB = K < IVF_SORT_BUCKETS ? K : IVF_SORT_BUCKETS;
+        uint32_t *cnt = sortws, *start = sortws + (NB + 1), *ord = sortws + 2 * (size_t)(NB + 1);
+        hipLaunchKernelGGL(k_pair_zero, dim3((NB + 1 + 255) / 256), dim3(256), 0, s, cnt, NB + 1);
+        QADC_LAUNCH_CHECK("k_pair_zero");
+        hipLaunchKernelGGL(k_pair_count, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, probe_ids,
+                           list_offsets, npairs, K, NB, cnt);
+        QADC_LAUNCH_CHECK("k_pair_count");
+        hipLaunchKernelGGL(k_pair_scan, dim3(1), dim3(1024), 0, s, cnt, start, NB + 1);
+        QADC_LAUNCH_CHECK("k_pair_scan");
+        hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, probe_ids,
+                           list_offsets, npairs, K, NB, (const uint32_t *)start, cnt, ord);
+        QADC_LAUNCH_CHECK("k_pair_fill");
+        order = ord;
+    }
     int pilot_want = 4096 > 32 * R ? 4096 : 32 * R;
     if (pilot_want < want) pilot_want = want;
     const size_t lds_calib = ivf_lds_bytes(idx->h, 2) + (size_t)pilot_want * 4;
@@ -701,7 +792,7 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     hipLaunchKernelGGL((k_ivf_scan<KIND, QT, NEV>), dim3(nprobe, nq), dim3(scan_threads), lds_scan, s, \
                        idx->dev, idx->edesc, idx->codebooks, coarse, list_offsets, list_codes,     \
                        list_ids, queries, probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off,  \
-                       p.slots_off, p.cap_b)
+                       p.slots_off, p.cap_b, order)
     // 16 x 4 bits over equal sub-spaces with 8-bit tables, at the default block size: the
     // fixed-shape set-up
     const int dsf = (KIND == SCAN_NIB8 && sizeof(QT) == 1 && scan_threads == 128 && idx->h.m == 16 &&
@@ -711,7 +802,7 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     hipLaunchKernelGGL((k_ivf_scan<SCAN_NIB8, uint8_t, 2, DSV>), dim3(nprobe, nq), dim3(128), lds_scan, s, \
                        idx->dev, idx->edesc, idx->codebooks, coarse, list_offsets, list_codes,     \
                        list_ids, queries, probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off,  \
-                       p.slots_off, p.cap_b)
+                       p.slots_off, p.cap_b, order)
     if (dsf == 4 || dsf == 6 || dsf == 8) {
         if (KIND == SCAN_NIB8 && sizeof(QT) == 1) {  // (the macro names the types itself)
             if (dsf == 4) QADC_IVF_SCAN_FIX(4); else if (dsf == 6) QADC_IVF_SCAN_FIX(6); else QADC_IVF_SCAN_FIX(8);
@@ -726,6 +817,17 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
                        out_ids, out_dist);
     QADC_LAUNCH_CHECK("k_ivf_final");
     return PQ_OK;
+}
+
+static size_t ivf_sort_bytes(int nq, int nprobe, int K) {
+    const size_t nb = K < IVF_SORT_BUCKETS ? (size_t)K : (size_t)IVF_SORT_BUCKETS;
+    return ((2 * (nb + 1) + (size_t)nq * (size_t)nprobe) * sizeof(uint32_t) + 255) & ~(size_t)255;
+}
+
+extern "C" size_t ivf_sorted_workspace_bytes(const pq_index_t *idx, int nq, int nprobe, int R, int K) {
+    if (!idx || nq < 0 || nprobe < 1 || R < 1 || K < 1) return 0;
+    const size_t base = (qadc_ivf_plan(idx, nq, nprobe, R).total + 255) & ~(size_t)255;
+    return base + ivf_sort_bytes(nq, nprobe, K) + 256;
 }
 
 extern "C" int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_centroids, int K,
@@ -768,10 +870,17 @@ extern "C" int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_cent
     }
     hipStream_t s = (hipStream_t)stream;
     char *ws = (char *)workspace;
+    // With the larger workspace of ivf_sorted_workspace_bytes, and enough (query, probe) pairs
+    // for cells to be probed more than once, the scan runs in the order of the probed cells.
+    const size_t base_bytes = (p.total + 255) & ~(size_t)255;
+    uint32_t *sortws = nullptr;
+    if ((int64_t)nq * nprobe * 4 >= (int64_t)K &&
+        workspace_bytes >= base_bytes + ivf_sort_bytes(nq, nprobe, K))
+        sortws = (uint32_t *)(ws + base_bytes);
     const bool u8 = idx->h.acc_bits == 8;
 #define QADC_GO(KIND, QT)                                                                          \
     return launch_ivf<KIND, QT>(idx, coarse_centroids, list_offsets, list_codes, list_ids, queries, \
-                                nq, probe_ids, nprobe, K, (int)want, R, out_ids, out_dist, ws, p, s)
+                                nq, probe_ids, nprobe, K, (int)want, R, out_ids, out_dist, ws, p, sortws, s)
     switch (idx->h.kind) {
         case SCAN_NIB8:
             if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);

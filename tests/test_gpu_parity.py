@@ -330,10 +330,14 @@ def check_ivf(qb, ip, R, t=T_CAL, probe=None):
     lay = ip.layout
     idx = qb.PqIndex(lay.d, lay.nbits, lay.dsub, ip.codebooks.to(dev()), lay.acc_bits)
     pids = ip.probe_ids if probe is None else probe
-    gi, gd = qb.ivf_adc_scan_topk(idx, ip.coarse.to(dev()), ip.list_offsets.to(dev()),
-                                  ip.list_codes.to(dev()), ip.list_ids.to(dev()),
-                                  ip.queries.to(dev()), pids.to(dev()), t, R)
+    args = (idx, ip.coarse.to(dev()), ip.list_offsets.to(dev()), ip.list_codes.to(dev()),
+            ip.list_ids.to(dev()), ip.queries.to(dev()), pids.to(dev()), t, R)
+    gi, gd = qb.ivf_adc_scan_topk(*args)   # default workspace: blocks in the order of the probed cells
+    small = torch.empty(qb.ivf_workspace_bytes(idx, pids.shape[0], pids.shape[1], R), dtype=torch.uint8,
+                        device=dev())
+    gi2, gd2 = qb.ivf_adc_scan_topk(*args, workspace=small)   # minimal workspace: blocks in grid order
     torch.cuda.synchronize()
+    assert torch.equal(gi, gi2) and torch.equal(gd, gd2)
     for q in range(ip.queries.shape[0]):
         oi, od, _ = oracle.search_ivf(lay.d, lay.nbits, lay.dsub, lay.acc_bits,
                                       ip.codebooks.numpy(), ip.coarse.numpy(),
