@@ -690,8 +690,11 @@ __device__ inline int ivf_exact_select(const DevLayout *L, const EntryDesc *edes
     return (int)(got < (uint32_t)R ? got : (uint32_t)R);
 }
 
-template <int KIND, typename QT>
-__global__ void __launch_bounds__(1024)
+// SMALL: blocks of 256 threads that can rank IVF_SMALL_CAP candidates (short result lists):
+// a quarter of the LDS and of the wave slots, so that several queries share a CU.
+#define IVF_SMALL_CAP 2048
+template <int KIND, typename QT, bool SMALL>
+__global__ void __launch_bounds__(SMALL ? 256 : 1024)
 k_ivf_final(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
             const float *__restrict__ cb,
             const float *__restrict__ coarse, const int64_t *__restrict__ list_offsets,
@@ -700,12 +703,13 @@ k_ivf_final(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
             int K, int R, char *__restrict__ ws, size_t per_query, size_t counts_off, size_t slots_off,
             int cap_b, int32_t *__restrict__ out_ids, float *__restrict__ out_dist) {
     extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int CAP = SMALL ? IVF_SMALL_CAP : FINAL_CAP;
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t whist[16][256];
+    __shared__ uint32_t whist[SMALL ? 4 : 16][256];  // one histogram per wave
     __shared__ uint32_t sh[32];
     __shared__ uint32_t wsum[16];
     __shared__ uint32_t off[1024 + 1];  // one slot list per probed cell, nprobe <= 1024
-    uint64_t *A = (uint64_t *)smem;  // FINAL_CAP entries
+    uint64_t *A = (uint64_t *)smem;  // CAP entries
     const size_t q = blockIdx.x;
     char *wq = ws + q * per_query;
     IvfState *st = (IvfState *)wq;
@@ -722,10 +726,10 @@ k_ivf_final(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
     const bool slow = gather_select(
         counts, slots, nprobe, cap_b, R,
         [blo, bscale](uint64_t c) { return dist_bin(qadc_ord2f((uint32_t)(c >> 32)), blo, bscale); }, A,
-        S, na);
+        CAP, S, na);
     if (slow) {
         IvfLds l;
-        ivf_carve(L, smem + FINAL_CAP * 8, sizeof(QT), l);
+        ivf_carve(L, smem + CAP * 8, sizeof(QT), l);
         na = ivf_exact_select<KIND, QT>(L, edesc, cb, coarse, list_offsets, list_codes, list_ids,
                                         queries + q * L->d, probe_ids + q * nprobe, nprobe, K,
                                         st->dmax, R, l, A, hist, sh);
@@ -772,7 +776,9 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     if (pilot_want < want) pilot_want = want;
     const size_t lds_calib = ivf_lds_bytes(idx->h, 2) + (size_t)pilot_want * 4;
     const size_t lds_scan = ivf_lds_bytes(idx->h, sizeof(QT));
-    const size_t lds_final = FINAL_CAP * 8 + lds_scan;
+    // short result lists: the small selection kernel (four lists per thread: nprobe <= 1024)
+    const bool small_final = R <= IVF_SMALL_CAP / 8;
+    const size_t lds_final = (small_final ? IVF_SMALL_CAP : FINAL_CAP) * 8 + lds_scan;
     int rc;
     constexpr bool NIB = KIND == SCAN_NIB8;
     if ((rc = allow_lds(k_ivf_calib<NIB>, lds_calib)) != PQ_OK) return rc;
@@ -780,7 +786,11 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     if ((rc = allow_lds(k_ivf_scan<KIND, QT, 1>, lds_scan)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_scan<KIND, QT, 2>, lds_scan)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_scan<KIND, QT, 4>, lds_scan)) != PQ_OK) return rc;
-    if ((rc = allow_lds(k_ivf_final<KIND, QT>, lds_final)) != PQ_OK) return rc;
+    if (small_final) {
+        if ((rc = allow_lds(k_ivf_final<KIND, QT, true>, lds_final)) != PQ_OK) return rc;
+    } else {
+        if ((rc = allow_lds(k_ivf_final<KIND, QT, false>, lds_final)) != PQ_OK) return rc;
+    }
     hipLaunchKernelGGL(k_ivf_calib<NIB>, dim3(nq), dim3(256), lds_calib, s, idx->dev, idx->edesc,
                        idx->codebooks, coarse, list_offsets, list_codes, queries, probe_ids, nprobe, K, want, pilot_want, R, ws,
                        p.per_query);
@@ -811,10 +821,16 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
 #undef QADC_IVF_SCAN_FIX
 #undef QADC_IVF_SCAN
     QADC_LAUNCH_CHECK("k_ivf_scan");
-    hipLaunchKernelGGL((k_ivf_final<KIND, QT>), dim3(nq), dim3(1024), lds_final, s, idx->dev,
-                       idx->edesc, idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,
-                       probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b,
-                       out_ids, out_dist);
+    if (small_final)
+        hipLaunchKernelGGL((k_ivf_final<KIND, QT, true>), dim3(nq), dim3(256), lds_final, s, idx->dev,
+                           idx->edesc, idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,
+                           probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b,
+                           out_ids, out_dist);
+    else
+        hipLaunchKernelGGL((k_ivf_final<KIND, QT, false>), dim3(nq), dim3(1024), lds_final, s, idx->dev,
+                           idx->edesc, idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,
+                           probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b,
+                           out_ids, out_dist);
     QADC_LAUNCH_CHECK("k_ivf_final");
     return PQ_OK;
 }

@@ -342,15 +342,17 @@ struct FinalShared {
     uint32_t *off;             // [MAX_G + 1] exclusive prefix of the list lengths
 };
 
-// Block-wide (1024 threads): gather the candidates of G slot lists (counts[], slots[][cap_b]),
-// find the bin of the R-th smallest by histogram (binf maps a candidate to a bin 0..255 that
-// is monotone in its sort key) and leave the candidates up to that bin in A (at most
-// FINAL_CAP).  Returns true if a list overflowed or A would overflow: the caller must then
+// Block-wide (256 to 1024 threads): gather the candidates of G slot lists (counts[],
+// slots[][cap_b]), find the bin of the R-th smallest by histogram (binf maps a candidate to a
+// bin 0..255 that is monotone in its sort key) and leave the candidates up to that bin in A (at
+// most cap_a).  Returns true if a list overflowed or A would overflow: the caller must then
 // select exactly by other means.  na = entries in A.
 template <class BinF>
 __device__ inline bool gather_select(const uint32_t *__restrict__ counts,
                                      const uint64_t *__restrict__ slots, int G, int cap_b, int R,
-                                     BinF binf, uint64_t *A, const FinalShared &S, int &na) {
+                                     BinF binf, uint64_t *A, int cap_a, const FinalShared &S, int &na) {
+    const uint32_t bd = blockDim.x;  // any multiple of 64 up to 1024 with FINAL_LPT * bd >= G
+    const int nwaves = (int)(bd / QADC_WAVE);
     const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
     // exclusive prefix sum of the G per-block counts: FINAL_LPT consecutive lists per thread
     uint32_t cnt[FINAL_LPT], mine = 0;
@@ -362,7 +364,7 @@ __device__ inline bool gather_select(const uint32_t *__restrict__ counts,
         over = over || cnt[l] > (uint32_t)cap_b;
         mine += cnt[l];
     }
-    for (int i = threadIdx.x; i < 16 * 256; i += blockDim.x) (&S.whist[0][0])[i] = 0;
+    for (int i = threadIdx.x; i < nwaves * 256; i += blockDim.x) (&S.whist[0][0])[i] = 0;
     const uint32_t incl = qadc_wave_incl_scan(mine);
     if (lane == QADC_WAVE - 1) S.wsum[wave] = incl;
     if (threadIdx.x == 0) {
@@ -398,10 +400,10 @@ __device__ inline bool gather_select(const uint32_t *__restrict__ counts,
         // pass 1: keep the candidates up to that bin.  When everything fits one batch
         // the second pass reuses the registers of the first.
         uint64_t c[FINAL_REG];
-        const bool single = E <= (uint32_t)(FINAL_REG * 1024);
+        const bool single = E <= (uint32_t)FINAL_REG * bd;
         uint32_t kbin = 255;
         for (int pass = 0; pass < 2; ++pass) {
-            for (uint32_t base = 0; base < E; base += FINAL_REG * 1024) {
+            for (uint32_t base = 0; base < E; base += FINAL_REG * bd) {
                 if (pass == 0 || !single) {
                     // list of each entry: largest index with S.off[list] <= e, by a branch-free
                     // binary search whose FINAL_REG chains run interleaved
@@ -412,7 +414,7 @@ __device__ inline bool gather_select(const uint32_t *__restrict__ counts,
                     for (uint32_t s = G > 1 ? 1u << (31 - __clz(G - 1)) : 1u; s >= 1; s >>= 1) {
 #pragma unroll
                         for (int u = 0; u < FINAL_REG; ++u) {
-                            const uint32_t e = base + u * 1024 + threadIdx.x;
+                            const uint32_t e = base + u * bd + threadIdx.x;
                             const uint32_t idx = pos[u] + s;
                             const uint32_t v = idx < (uint32_t)G ? S.off[idx] : 0xffffffffu;
                             pos[u] = v <= e ? idx : pos[u];
@@ -420,20 +422,20 @@ __device__ inline bool gather_select(const uint32_t *__restrict__ counts,
                     }
 #pragma unroll
                     for (int u = 0; u < FINAL_REG; ++u) {
-                        const uint32_t e = base + u * 1024 + threadIdx.x;
+                        const uint32_t e = base + u * bd + threadIdx.x;
                         c[u] = e < E ? slots[(size_t)pos[u] * cap_b + (e - S.off[pos[u]])] : ~0ull;
                     }
                 }
 #pragma unroll
                 for (int u = 0; u < FINAL_REG; ++u) {
-                    const uint32_t e = base + u * 1024 + threadIdx.x;
+                    const uint32_t e = base + u * bd + threadIdx.x;
                     if (e >= E) continue;
                     const uint32_t bin = binf(c[u]);
                     if (pass == 0) {
                         atomicAdd(&S.whist[wave][bin], 1u);
                     } else if (bin <= kbin) {
                         const uint32_t pos = atomicAdd(&S.sh[0], 1u);
-                        if (pos < FINAL_CAP) A[pos] = c[u]; else S.sh[1] = 1u;
+                        if (pos < (uint32_t)cap_a) A[pos] = c[u]; else S.sh[1] = 1u;
                     }
                 }
             }
@@ -442,7 +444,8 @@ __device__ inline bool gather_select(const uint32_t *__restrict__ counts,
                 if (threadIdx.x < 256) {
                     uint32_t t = 0;
 #pragma unroll
-                    for (int w = 0; w < 16; ++w) t += S.whist[w][threadIdx.x];
+                    for (int w = 0; w < 16; ++w)
+                        if (w < nwaves) t += S.whist[w][threadIdx.x];
                     S.hist[threadIdx.x] = t;
                 }
                 __syncthreads();
