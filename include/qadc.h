@@ -103,8 +103,8 @@ size_t pq_workspace_bytes(const pq_index_t *idx, int nq, int64_t n, int R);
 size_t ivf_workspace_bytes(const pq_index_t *idx, int nq, int nprobe, int R);
 /* The same plus room to order the (query, probe) pairs by probed cell (K cells): given that
  * much, and at least K/4 pairs, ivf_adc_scan_topk scans the pairs of one cell close together
- * in time, so that a list probed by several queries of the call is read from memory once
- * (Section 2.1.3: queries of a batch probe overlapping cells).  Results are the same. */
+ * in time, so that a list probed by several queries of the call is read from memory once.
+ * Results are the same. */
 size_t ivf_sorted_workspace_bytes(const pq_index_t *idx, int nq, int nprobe, int R, int K);
 
 /*
