@@ -242,7 +242,8 @@ __device__ inline void cs_rank_and_write(const uint64_t *A, int na, int k, int n
 }
 
 // guard: if non-null and *guard == 0 the kernel does nothing.  clear: if non-null, set to 0.
-__global__ void __launch_bounds__(1024)
+template <int BD>  // threads per block: 256 (a few thousand scores) or 1024
+__global__ void __launch_bounds__(BD)
 k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
          int32_t *__restrict__ probe_ids, float *__restrict__ probe_scores,
          const int *__restrict__ guard, int *__restrict__ clear) {
@@ -260,15 +261,15 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
     float *osc = probe_scores ? probe_scores + q * nprobe : nullptr;
     const int k = nprobe < K ? nprobe : K;
     const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
-    // 16-byte loads: thread t takes scores 4*(j*1024 + t) .. +3, UB loads in flight together.
+    // 16-byte loads: thread t takes scores 4*(j*BD + t) .. +3, UB loads in flight together.
     // Row starts are 128-byte aligned and padded to a multiple of 32 scores; what lies past K is
     // masked by index.
     constexpr int UB = 8;
-    const int nj = (K + 4095) / 4096;
+    const int nj = (K + 4 * BD - 1) / (4 * BD);
     auto load_keys = [&](int j0, uint32_t (&v)[UB][4]) {
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
-            const int i = ((j0 + u) * 1024 + (int)threadIdx.x) * 4;
+            const int i = ((j0 + u) * BD + (int)threadIdx.x) * 4;
             float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
             if (i < K) f = *(const float4 *)(s + i);
             v[u][0] = i + 0 < K ? qadc_f2ord(f.x) : 0xffffffffu;
@@ -287,7 +288,7 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
         for (int u = 0; u < UB; ++u)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                if (((j0 + u) * 1024 + (int)threadIdx.x) * 4 + c < K) {
+                if (((j0 + u) * BD + (int)threadIdx.x) * 4 + c < K) {
                     lo = v[u][c] < lo ? v[u][c] : lo;
                     hi = v[u][c] > hi ? v[u][c] : hi;
                 }
@@ -306,7 +307,7 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
     }
     __syncthreads();
 #pragma unroll
-    for (int w2 = 0; w2 < 16; ++w2) {
+    for (int w2 = 0; w2 < BD / QADC_WAVE; ++w2) {
         lo = s_lo[w2] < lo ? s_lo[w2] : lo;
         hi = s_hi[w2] > hi ? s_hi[w2] : hi;
     }
@@ -319,7 +320,7 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
         for (int u = 0; u < UB; ++u)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const bool in = ((j0 + u) * 1024 + (int)threadIdx.x) * 4 + c < K;
+                const bool in = ((j0 + u) * BD + (int)threadIdx.x) * 4 + c < K;
                 cs_hist_add(hist, in ? (v[u][c] - lo) >> shift : 0u, in);
             }
     }
@@ -336,7 +337,7 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
             for (int u = 0; u < UB; ++u)
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    const int i = ((j0 + u) * 1024 + (int)threadIdx.x) * 4 + c;
+                    const int i = ((j0 + u) * BD + (int)threadIdx.x) * 4 + c;
                     const bool take = i < K && ((v[u][c] - lo) >> shift) <= kbin;
                     const uint64_t m = __ballot(take);
                     if (m != 0) {
@@ -355,8 +356,8 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
     }
 
     // exact path: the keys are re-read from memory in every pass
-#define CS_KEYM(j) ((j) * 1024 + (int)threadIdx.x < K ? qadc_f2ord(s[(j) * 1024 + threadIdx.x]) : 0xffffffffu)
-    const int njm = (K + 1023) / 1024;
+#define CS_KEYM(j) ((j) * BD + (int)threadIdx.x < K ? qadc_f2ord(s[(j) * BD + threadIdx.x]) : 0xffffffffu)
+    const int njm = (K + BD - 1) / BD;
     __syncthreads();
     uint32_t prefix = 0, mask = 0, kk = (uint32_t)k;
     for (int pass = 3; pass >= 0; --pass) {
@@ -365,7 +366,7 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
         __syncthreads();
         for (int j = 0; j < njm; ++j) {
             const uint32_t v = CS_KEYM(j);
-            const bool in = j * 1024 + (int)threadIdx.x < K && (v & mask) == prefix;
+            const bool in = j * BD + (int)threadIdx.x < K && (v & mask) == prefix;
             cs_hist_add(hist, (v >> sh) & 255u, in);
         }
         __syncthreads();
@@ -380,7 +381,7 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
     const uint32_t kth = prefix, need = kk, below = (uint32_t)k - need;
     for (int j = 0; j < njm; ++j) {  // cells below the k-th key, in any order
         const uint32_t v = CS_KEYM(j);
-        const int i = j * 1024 + (int)threadIdx.x;
+        const int i = j * BD + (int)threadIdx.x;
         const bool lt = i < K && v < kth;
         const uint64_t m = __ballot(lt);
         if (m != 0) {
@@ -391,16 +392,16 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
         }
     }
     __syncthreads();
-    // cells equal to the k-th key: the `need` lowest ids.  Rounds of 1024 consecutive ids in
+    // cells equal to the k-th key: the `need` lowest ids.  Rounds of BD consecutive ids in
     // ascending order; within a round positions come from the wave counts.
     for (int j = 0; j < njm; ++j) {
-        const int i = j * 1024 + (int)threadIdx.x;
+        const int i = j * BD + (int)threadIdx.x;
         const bool eq = i < K && CS_KEYM(j) == kth;
         const uint64_t m = __ballot(eq);
         if (lane == 0) wcnt[wave] = (uint32_t)__popcll(m);
         __syncthreads();
         uint32_t before = s_ties, total = 0;
-        for (int w2 = 0; w2 < 16; ++w2) {
+        for (int w2 = 0; w2 < BD / QADC_WAVE; ++w2) {
             before += w2 < wave ? wcnt[w2] : 0u;
             total += wcnt[w2];
         }
@@ -564,7 +565,7 @@ extern "C" int ivf_coarse_search(const float *queries, int nq, const float *cent
                                (uint64_t *)nullptr, (uint32_t *)nullptr, (const int *)nullptr, P / CS_TC,
                                (int)gq.y);
             QADC_LAUNCH_CHECK("k_scores (pilot)");
-            hipLaunchKernelGGL(k_select, dim3(nqc), dim3(1024), 0, s, scores, (size_t)P, P, nprobe, pilot_ids,
+            hipLaunchKernelGGL(k_select<256>, dim3(nqc), dim3(256), 0, s, scores, (size_t)P, P, nprobe, pilot_ids,
                                pilot_sc, (const int *)nullptr, flag);
             QADC_LAUNCH_CHECK("k_select (pilot)");
             hipLaunchKernelGGL(k_scores<true>, dim3(cs_grid(gq.x, gq.y)), dim3(256), 0, s, qp, nqc, centroids, K,
@@ -581,7 +582,7 @@ extern "C" int ivf_coarse_search(const float *queries, int nq, const float *cent
                            cnorm, scores, ld, vec, (const float *)nullptr, 0, 0, (uint64_t *)nullptr,
                            (uint32_t *)nullptr, guard, (int)gq.x, (int)gq.y);
         QADC_LAUNCH_CHECK("k_scores");
-        hipLaunchKernelGGL(k_select, dim3(nqc), dim3(1024), 0, s, scores, ld, K, nprobe, pid, psc, guard,
+        hipLaunchKernelGGL(k_select<1024>, dim3(nqc), dim3(1024), 0, s, scores, ld, K, nprobe, pid, psc, guard,
                            (int *)nullptr);
         QADC_LAUNCH_CHECK("k_select");
     }
