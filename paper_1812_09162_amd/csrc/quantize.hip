@@ -347,6 +347,7 @@ int qadc_pilot_blocks_max(int nq) {
     static const int64_t cap = pilot_env("QADC_PILOT_BLOCKS", 8);
     int pmax = 256 / (nq > 0 ? nq : 1);
     pmax = pmax < 1 ? 1 : (pmax > 64 ? 64 : pmax);
+    if (nq > 16 && pmax > 4) pmax = 4;  // (32 queries per call: 4 blocks each measured 6 % faster than 8)
     return cap >= 1 && cap < pmax ? (int)cap : pmax;
 }
 
