@@ -206,40 +206,44 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
             slot_append(me && key <= thr, key, (uint32_t)id, slot, (uint32_t)cap_b, &s_count);
         }
     } else {
-        const int64_t ntiles = (n + 4 * SCAN_THREADS - 1) / (4 * SCAN_THREADS);
+        // one 16-byte code (or one code of the byte-wise kind) per thread and chunk, four chunks
+        // per tile; positions fit 32 bits unsigned (n < 2^31); loads past the end repeat the
+        // last code
+        const uint32_t un = (uint32_t)n;
+        const uint32_t ntiles = (un + 4 * SCAN_THREADS - 1) / (4 * SCAN_THREADS);
+        const uint4 *__restrict__ p = (const uint4 *)codes;
         uint4 cur[4];
-        int64_t tile = b;
-        auto load_tile = [&](int64_t t) {
+        uint32_t tile = b;
+        auto load_tile = [&](uint32_t t) {  // t < ntiles, hence n >= 1
             if (KIND != SCAN_NIB16 && KIND != SCAN_W128) return;  // others read byte by byte
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int64_t c = t * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
-                cur[u] = (t < ntiles && c < n) ? ((const uint4 *)codes)[c] : make_uint4(0, 0, 0, 0);
+                const uint32_t c = t * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                cur[u] = p[c < un ? c : un - 1];
             }
         };
-        load_tile(tile);  // the first tile is in flight while the tables are staged
+        if (tile < ntiles) load_tile(tile);  // the first tile is in flight while the tables are staged
         load_gtab<QT>(gsrc, gtab_len, gtab);
         while (tile < ntiles) {
             uint32_t s[4];
             bool pass[4], any = false;
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int64_t c = tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                const uint32_t c = tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
                 if (KIND == SCAN_NIB16)
                     s[u] = sum8(gtab, cur[u].x, cur[u].y) + sum8(gtab + 2048, cur[u].z, cur[u].w);
                 else if (KIND == SCAN_W128)
                     s[u] = sum_groups_desc<NG, NLO>(gd, gtab, cur[u].x, cur[u].y) +
                            sum_groups_desc<NG, NLO>(gd, gtab, cur[u].z, cur[u].w, true);
                 else
-                    s[u] = c < n ? key_generic(L, gtab, codes + c * L->cs) : 0u;
-                pass[u] = (c < n) && s[u] <= thr;
+                    s[u] = c < un ? key_generic(L, gtab, codes + (size_t)c * L->cs) : 0u;
+                pass[u] = (c < un) && s[u] <= thr;
                 any = any || pass[u];
             }
             if (__ballot(any) != 0) {
                 uint32_t id[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    id[u] = (uint32_t)(tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x);
+                for (int u = 0; u < 4; ++u) id[u] = tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
                 slot_append_multi<4>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
             }
             tile += G;
