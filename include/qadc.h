@@ -274,7 +274,8 @@ const char *pq_last_error(void);
  *   QADC_PILOT          pilot codes of the fused search when several blocks share it (262144)
  *   QADC_PILOT1         pilot codes when one block per query counts them (65536)
  *   QADC_PILOT_BLOCKS   most blocks per query that share a pilot (8)
- *   QADC_IVF_THREADS    threads per (query, list) block of the inverted-list scan (128)
+ *   QADC_IVF_THREADS    threads per (query, list) block of the inverted-list scan: 64, 128 or
+ *                       256, anything else means the default (128)
  *   QADC_NO_MQ          if set, batches are scanned one query per pass
  *   QADC_COARSE_MATRIX  if set, the coarse search always writes the full score matrix
  */

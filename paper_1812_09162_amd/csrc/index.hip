@@ -180,6 +180,7 @@ ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R) {
     if (gmax < 64) gmax = 64;
     if (gmax > g1) gmax = g1;
     if (gmax > 4096) gmax = 4096;
+    if (gmax < 1) gmax = 1;  // a zero or negative QADC_G
     int64_t G = tiles < 1 ? 1 : (tiles > gmax ? gmax : tiles);
     p.G = (int)G;
     // slots per block: four times the candidates expected when the bound comes from a
