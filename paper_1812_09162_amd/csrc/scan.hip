@@ -148,27 +148,29 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         // 20-byte chunks of four 5-byte codes: five dwords per lane, U5 chunks per thread and
         // tile; the last n % 4 codes are handled after the loop
         constexpr int U = U5;
-        const int64_t nfull = n >> 2;
-        const int64_t ntiles = (nfull + U * SCAN_THREADS - 1) / (U * SCAN_THREADS);
+        // (chunk and dword indices fit 32 bits: ids are int32, so n < 2^31 and 5 * (n / 4) < 2^32)
+        const uint32_t nfull = (uint32_t)(n >> 2);
+        const uint32_t ntiles = (nfull + U * SCAN_THREADS - 1) / (U * SCAN_THREADS);
         const uint32_t *__restrict__ p = (const uint32_t *)codes;
         uint32_t cur[U][5];
-        int64_t tile = b;
-        auto load_tile = [&](int64_t t) {
+        uint32_t tile = b;
+        auto load_tile = [&](uint32_t t) {  // t < ntiles, hence nfull >= 1; past the end: the last chunk again
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t c = t * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                const uint32_t c = t * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                const uint32_t *__restrict__ pc = p + (c < nfull ? c : nfull - 1) * 5u;
 #pragma unroll
-                for (int i = 0; i < 5; ++i) cur[u][i] = (t < ntiles && c < nfull) ? p[c * 5 + i] : 0u;
+                for (int i = 0; i < 5; ++i) cur[u][i] = pc[i];
             }
         };
-        load_tile(tile);  // the first tile is in flight while the tables are staged
+        if (tile < ntiles) load_tile(tile);  // the first tile is in flight while the tables are staged
         load_gtab<QT>(gsrc, gtab_len, gtab);
         while (tile < ntiles) {
             uint32_t s[4 * U];
             bool pass[4 * U], any = false;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                const uint32_t c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
                 // code v = bits [40v, 40v+40) of the 160-bit chunk, as (low dword, high byte)
                 uint32_t lo[4], hi[4];
                 lo[0] = cur[u][0];
@@ -191,8 +193,8 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 uint32_t id[4 * U];
 #pragma unroll
                 for (int u = 0; u < 4 * U; ++u) {
-                    const int64_t c = tile * (U * SCAN_THREADS) + (u >> 2) * SCAN_THREADS + threadIdx.x;
-                    id[u] = (uint32_t)(4 * c + (u & 3));
+                    const uint32_t c = tile * (U * SCAN_THREADS) + (u >> 2) * SCAN_THREADS + threadIdx.x;
+                    id[u] = 4u * c + (u & 3);
                 }
                 slot_append_multi<4 * U>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
             }
