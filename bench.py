@@ -33,8 +33,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 # known size); the summaries with the commands are under profiles/.  None = not profiled.
 MEASURED_TRAFFIC_BYTES = {
     ("C1", 1): (78202.0 + 232.6) * 1024,     # profiles/k_scan_C1_batch1.md
-    ("C2", 1): (312620.6 + 751.6) * 1024,    # profiles/k_scan_C2_batch1.md
-    ("C3", 1): (48987.1 + 220.8) * 1024,     # profiles/k_scan_C3_batch1.md
+    ("C2", 1): (312625.6 + 734.8) * 1024,    # profiles/k_scan_C2_batch1.md
+    ("C3", 1): (48980.1 + 219.4) * 1024,      # profiles/k_scan_C3_batch1.md
 }
 
 
