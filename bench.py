@@ -28,14 +28,65 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
-# HBM bytes per scan-kernel launch from hardware counters (rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE, one run each, scaled by the same counters over the library's copy kernel of
-# known size); the summaries with the commands are under profiles/.  None = not profiled.
-MEASURED_TRAFFIC_BYTES = {
-    ("C1", 1): (78202.0 + 232.6) * 1024,     # profiles/k_scan_C1_batch1.md
-    ("C2", 1): (312625.6 + 734.8) * 1024,    # profiles/k_scan_C2_batch1.md
-    ("C3", 1): (48980.1 + 219.4) * 1024,      # profiles/k_scan_C3_batch1.md
-}
+
+
+def measured_traffic_bytes(workload, batch):
+    """HBM bytes per scan-kernel launch from hardware counters, or None when this workload has
+    not been profiled.  Read from the line `traffic_bytes_per_launch: <bytes>` of the summary
+    profiles/k_scan_<workload>_batch<batch>.md, which `bench.py --summarize-pmc` writes from two
+    rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each scaled by the same counter over the
+    library's copy kernel of known size."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"k_scan_{workload}_batch{batch}.md")
+    try:
+        with open(path) as f:
+            m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", f.read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def summarize_pmc(fetch_dir, write_dir):
+    """Print the traffic summary of two rocprofv3 --pmc runs of this script (one with FETCH_SIZE,
+    one with WRITE_SIZE, both with --copy-calibration): mean counter value per dispatch of the
+    scan kernel's timing pass and of the copy kernel, the scale factors, and the line
+    `traffic_bytes_per_launch:` that measured_traffic_bytes() reads."""
+    import csv
+    import glob
+
+    def rows(d):
+        out = []
+        for fn in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
+            with open(fn, newline="") as f:
+                out += list(csv.DictReader(f))
+        return out
+
+    def per_kernel(d, counter):
+        by = {}
+        for r in rows(d):
+            if r.get("Counter_Name") != counter:
+                continue
+            name = r["Kernel_Name"]
+            key = "k_copy" if "k_copy" in name else ("k_scan" if "k_scan" in name else None)
+            if key:
+                by.setdefault(key, []).append((int(r["Dispatch_Id"]), float(r["Counter_Value"])))
+        return {k: [v for _, v in sorted(vs)] for k, vs in by.items()}
+
+    lines, scaled = [], {}
+    for counter, d in (("FETCH_SIZE", fetch_dir), ("WRITE_SIZE", write_dir)):
+        by = per_kernel(d, counter)
+        copy, scan = by.get("k_copy", []), by.get("k_scan", [])
+        if not copy or not scan:
+            raise SystemExit(f"{d}: no {counter} rows for k_copy / k_scan")
+        tail = scan[-min(len(scan), 1600):]          # the timing pass comes last
+        factor = 1048576.0 / (sum(copy) / len(copy))  # the copy moves 2^30 B = 1,048,576 KiB each way
+        mean = sum(tail) / len(tail)
+        scaled[counter] = mean * factor * 1024.0
+        lines.append(f"{counter}: k_copy {sum(copy) / len(copy):.1f} KiB/dispatch over {len(copy)} (factor "
+                     f"{factor:.4f}); k_scan timing pass {mean:.1f} KiB/dispatch over {len(tail)} "
+                     f"-> {scaled[counter] / 1e6:.3f} MB")
+    print("\n".join(lines))
+    print(f"traffic_bytes_per_launch: {scaled['FETCH_SIZE'] + scaled['WRITE_SIZE']:.0f}")
 
 
 def parse():

@@ -195,7 +195,7 @@ int pq_search_topk(const pq_index_t *idx, const float *queries, int nq, const ui
  * For every query: d_max from the float ADC of the first t_eff probed codes
  * (probe order, list order, each with its own cell's tables); per probed list
  * its own p_min / d_min / delta from that shared d_max; lists whose d_min
- * exceeds d_max are skipped; every code of the other probed lists gets
+ * is not below d_max are skipped (nothing in them is closer than d_max); every code of the other probed lists gets
  * dist = fmaf(key, (float)delta_l, (float)d_min_l); the R smallest
  * (dist, stored id) are returned.
  *   coarse       [dev][K][d] float32 cell centroids

@@ -35,8 +35,9 @@
  *   - Delta <= 0 or not finite: every q is 0 and Delta is reported as 0;
  *   - ties are broken by lowest id;
  *   - IVF: one d_max per query from the first t_eff probed codes, per-list
- *     p_min / d_min / Delta, lists with d_min > d_max skipped, candidates
- *     from different lists compared on the unquantized float.
+ *     p_min / d_min / Delta, lists with d_min >= d_max skipped (Section 3.4:
+ *     later candidates have to be closer than d_max), candidates from
+ *     different lists compared on the unquantized float.
  *
  * Sub-code extraction: a code is a little-endian bit stream; sub-code j sits in
  * bits [off_j, off_j + nbits[j]), off_j = sum_{i<j} nbits[i], bit 0 being the
@@ -363,7 +364,9 @@ void oracle_search_ivf(int d, int m, const int32_t *nbits, const int32_t *dsub, 
         if (hi == lo) continue;
         oracle_tables(d, m, nbits, dsub, codebooks, z, coarse + (size_t)probe[a] * d, table);
         double dmin = table_minima(&L, table, pmin);
-        if (dmin > (double)dmax) continue; /* nothing in this list can reach d_max */
+        /* Section 3.4: every candidate after calibration has to be closer than d_max, and no
+         * code of this list can be closer than the list's d_min */
+        if (dmin >= (double)dmax) continue;
         double delta = quantize_table(&L, table, pmin, dmin, dmax, qtable);
         for (int64_t p = lo; p < hi; ++p) {
             uint32_t key = adc_key(&L, qtable, list_codes + p * cs);

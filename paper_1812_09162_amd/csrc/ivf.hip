@@ -53,7 +53,8 @@ __device__ inline unsigned char *ivf_carve(const DevLayout *L, unsigned char *ba
 
 // Block-wide: residual, float tables (eq. (1)), p_min, d_min; with `quantize`
 // also delta from dmax, the quantized table and (with `groups`) the group
-// tables.  Returns false when the list is skipped (d_min > d_max).
+// tables.  Returns false when the list is skipped (d_min >= d_max: Section 3.4, later
+// candidates have to be closer than d_max).
 template <int KIND, typename QT>
 __device__ inline bool ivf_setup(const DevLayout *L, const EntryDesc *__restrict__ edesc,
                                  const float *__restrict__ cb, const float *__restrict__ z,
@@ -91,7 +92,7 @@ __device__ inline bool ivf_setup(const DevLayout *L, const EntryDesc *__restrict
         int skip = 0;
         double delta = 0.0;
         if (quantize) {
-            skip = dm > (double)dmax;
+            skip = dm >= (double)dmax;
             delta = ((double)dmax - dm) / (double)qmax;
             if (!((delta > 0.0) && isfinite(delta))) delta = 0.0;
         }
@@ -498,7 +499,7 @@ k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
             double delta = ((double)dmax - dm) / (double)qmax;
             if (!((delta > 0.0) && isfinite(delta))) delta = 0.0;
             l.sc[1] = delta;
-            *l.flag = dm > (double)dmax;
+            *l.flag = dm >= (double)dmax;
         }
         __syncthreads();
         ok = *l.flag == 0;
@@ -772,9 +773,20 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
         QADC_LAUNCH_CHECK("k_pair_fill");
         order = ord;
     }
+    // pilot: as many codes as fit the calibration block's LDS next to its tables (the kernel's
+    // own static arrays stay under 12 KB of the 160 KB), never fewer than the calibration codes;
+    // a shorter pilot only gives a weaker (still valid) pruning bound
     int pilot_want = 4096 > 32 * R ? 4096 : 32 * R;
+    const size_t lds_room = (size_t)(160 - 12) * 1024;
+    const size_t lds_tabs = ivf_lds_bytes(idx->h, 2);
+    if (lds_tabs + (size_t)want * 4 > lds_room) {
+        qadc_set_error("ivf_adc_scan_topk: tables of %zu bytes and %d calibration codes exceed the "
+                       "%zu bytes of LDS of the calibration kernel", lds_tabs, want, lds_room);
+        return PQ_EINVAL;
+    }
+    if ((size_t)pilot_want > (lds_room - lds_tabs) / 4) pilot_want = (int)((lds_room - lds_tabs) / 4);
     if (pilot_want < want) pilot_want = want;
-    const size_t lds_calib = ivf_lds_bytes(idx->h, 2) + (size_t)pilot_want * 4;
+    const size_t lds_calib = lds_tabs + (size_t)pilot_want * 4;
     const size_t lds_scan = ivf_lds_bytes(idx->h, sizeof(QT));
     // short result lists: the small selection kernel (four lists per thread: nprobe <= 1024)
     const bool small_final = R <= IVF_SMALL_CAP / 8;

@@ -75,8 +75,11 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     uint32_t *counts = (uint32_t *)wq;
     uint64_t *slot = (uint64_t *)(wq + slots_off) + (size_t)b * cap_b;
     const char *gsrc = wq + gtab_off;
+    // Sums are compared unsaturated.  A sum above q_max is the key q_max (Section 3.4), an
+    // ordinary largest key: with a bound below q_max such a code never passes, and with the
+    // bound at q_max every code does (the keys are saturated where they are stored).
     uint32_t thr = qparams[q].key_bound;
-    thr = thr > qmax ? qmax : thr;
+    thr = thr >= qmax ? 0xffffffffu : thr;
     if (threadIdx.x == 0) s_count = 0;
     constexpr bool g32 = NG > 0;
     constexpr int NLO = MODE == 1 ? NG / 2 : (MODE == 2 ? NG - 1 : -1);
@@ -126,6 +129,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 for (int u = 0; u < 2 * U; ++u) {
                     const int c = tile * (U * SCAN_THREADS) + (u >> 1) * SCAN_THREADS + (int)threadIdx.x;
                     id[u] = (uint32_t)(2 * c + (u & 1));
+                    s[u] = s[u] > qmax ? qmax : s[u];
                 }
                 slot_append_multi<2 * U>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
             }
@@ -141,7 +145,8 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                     key = KIND == SCAN_NIB8 ? sum8(gtab, w.x, w.y)
                                             : sum_groups64(L, gtab, ((uint64_t)w.y << 32) | w.x);
                 }
-                slot_append(me && key <= thr, key, (uint32_t)(n - 1), slot, (uint32_t)cap_b, &s_count);
+                slot_append(me && key <= thr, key > qmax ? qmax : key, (uint32_t)(n - 1), slot,
+                            (uint32_t)cap_b, &s_count);
             }
         }
     } else if (KIND == SCAN_C5) {
@@ -195,6 +200,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 for (int u = 0; u < 4 * U; ++u) {
                     const uint32_t c = tile * (U * SCAN_THREADS) + (u >> 2) * SCAN_THREADS + threadIdx.x;
                     id[u] = 4u * c + (u & 3);
+                    s[u] = s[u] > qmax ? qmax : s[u];
                 }
                 slot_append_multi<4 * U>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
             }
@@ -245,7 +251,10 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
             if (__ballot(any) != 0) {
                 uint32_t id[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) id[u] = tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                for (int u = 0; u < 4; ++u) {
+                    id[u] = tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
+                    s[u] = s[u] > qmax ? qmax : s[u];
+                }
                 slot_append_multi<4>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
             }
             tile += G;
@@ -305,7 +314,7 @@ k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__res
         const bool have = q0 + j < nq;
         const size_t q = have ? q0 + j : q0;
         uint32_t t = qparams[q].key_bound;
-        thr[j] = t > qmax ? qmax : t;
+        thr[j] = t >= qmax ? 0xffffffffu : t;  // sums are compared unsaturated (see k_scan)
         slot[j] = (uint64_t *)(ws + q * per_query + slots_off) + (size_t)b * cap_b;
     }
     if (threadIdx.x < MQ) s_count[threadIdx.x] = 0;
@@ -374,8 +383,11 @@ k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__res
                 pass[i] = ok[i] && sum[j][i] <= thr[j] && (q0 + j < nq);
                 any = any || pass[i];
             }
-            if (__ballot(any) != 0)
+            if (__ballot(any) != 0) {
+#pragma unroll
+                for (int i = 0; i < U * CPC; ++i) sum[j][i] = sum[j][i] > qmax ? qmax : sum[j][i];
                 slot_append_multi<U * CPC>(pass, sum[j], id, slot[j], (uint32_t)cap_b, &s_count[j]);
+            }
         }
     }
     if (NG == 8 && (n & 1) && b == 0 && threadIdx.x < QADC_WAVE) {  // the odd last 64-bit code
@@ -394,8 +406,8 @@ k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__res
         const uint32_t sj[MQ] = {lo & 0xffffu, lo >> 16, hi & 0xffffu, hi >> 16};
 #pragma unroll
         for (int j = 0; j < MQ; ++j)
-            slot_append(me && (q0 + j < nq) && sj[j] <= thr[j], sj[j], (uint32_t)(n - 1), slot[j],
-                        (uint32_t)cap_b, &s_count[j]);
+            slot_append(me && (q0 + j < nq) && sj[j] <= thr[j], sj[j] > qmax ? qmax : sj[j],
+                        (uint32_t)(n - 1), slot[j], (uint32_t)cap_b, &s_count[j]);
     }
     __syncthreads();
     if (threadIdx.x < MQ && q0 + (int)threadIdx.x < nq)

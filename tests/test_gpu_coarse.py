@@ -106,7 +106,7 @@ def test_coarse_search_full_k_sampled(qb):
 ])
 def test_coarse_search_filtering_form_bit_exact(qb, K, d, nq, nprobe, seed):
     """K large enough for the form that never writes the score matrix (pilot bound, candidate
-    lists per block of 128 cells)."""
+    lists per block of 256 cells)."""
     rng = np.random.default_rng(seed)
     cen = rng.normal(size=(K, d)).astype(np.float32)
     qs = rng.normal(size=(nq, d)).astype(np.float32)
@@ -114,7 +114,7 @@ def test_coarse_search_filtering_form_bit_exact(qb, K, d, nq, nprobe, seed):
 
 
 def test_coarse_search_filtering_form_overflow_falls_back(qb):
-    """Forty copies of one cell inside a single block of 128 overflow that block's candidate list
+    """Forty copies of one cell inside a single block of 256 overflow that block's candidate list
     for the queries near it; the pass is then redone in the matrix form.  Also: all cells equal."""
     rng = np.random.default_rng(41)
     K, d = 20_000, 32
@@ -127,6 +127,47 @@ def test_coarse_search_filtering_form_overflow_falls_back(qb):
     same = np.ones((18_000, 8), np.float32)
     ids = check(qb, same, np.zeros((3, 8), np.float32), 100)
     assert ids[2].tolist() == list(range(100))
+
+
+@pytest.mark.parametrize("K,d,nq,nprobe,seed,unit", [
+    (3000, 96, 40, 64, 51, False),      # matrix form
+    (20_000, 128, 70, 32, 52, False),   # filtering form
+    (65_536, 96, 48, 64, 53, True),     # the C4 shape: unit-norm centroids and queries
+    (513, 9, 130, 513, 54, False),      # every cell returned
+])
+def test_coarse_search_against_the_plain_definition_in_fp64(qb, K, d, nq, nprobe, seed, unit):
+    """Section 2.1.1 says only that a query goes to the cells whose centroids are nearest.  This
+    check does not use the oracle or its arithmetic: squared distances ||z - c||^2 by brute force
+    in fp64, and the GPU's answer must be a valid nearest-cell set up to the rounding of an fp32
+    evaluation of ||c||^2 - 2 z.c (d products and sums, each rounded once: |error| <=
+    (d + 2) 2^-23 (||c||^2 + 2 ||z|| ||c||))."""
+    rng = np.random.default_rng(seed)
+    cen = rng.normal(size=(K, d)).astype(np.float32)
+    qs = rng.normal(size=(nq, d)).astype(np.float32)
+    if unit:
+        cen /= np.linalg.norm(cen, axis=1, keepdims=True)
+        qs /= np.linalg.norm(qs, axis=1, keepdims=True)
+    ids, sc = qb.ivf_coarse_search(torch.from_numpy(qs).to(dev()), torch.from_numpy(cen).to(dev()), nprobe)
+    torch.cuda.synchronize()
+    ids, sc = ids.cpu().numpy(), sc.cpu().numpy().astype(np.float64)
+    c64, q64 = cen.astype(np.float64), qs.astype(np.float64)
+    cn = (c64 ** 2).sum(1)
+    cmax = np.sqrt(cn.max())
+    k = min(nprobe, K)
+    for q in range(nq):
+        true = ((c64 - q64[q][None, :]) ** 2).sum(1)              # ||z - c||^2 for every cell
+        zn = np.sqrt((q64[q] ** 2).sum())
+        tol = (d + 2) * 2.0 ** -23 * (cmax ** 2 + 2 * zn * cmax)
+        got = ids[q, :k]
+        assert np.all(ids[q, k:] == -1)
+        assert got.min() >= 0 and got.max() < K and len(set(got.tolist())) == k      # distinct cells
+        kth = np.partition(true, k - 1)[k - 1]
+        assert np.all(true[got] <= kth + 2 * tol)                  # nothing returned is farther
+        rest = np.ones(K, bool)
+        rest[got] = False
+        assert not rest.any() or true[rest].min() >= kth - 2 * tol  # nothing left out is nearer
+        assert np.all(np.diff(true[got]) >= -2 * tol)              # nearest first
+        assert np.all(np.abs(sc[q, :k] + (q64[q] ** 2).sum() - true[got]) <= tol)   # the scores themselves
 
 
 def test_coarse_search_errors(qb):

@@ -300,6 +300,52 @@ def test_caller_supplied_qparams_without_hint(qb):
     idx.close()
 
 
+@pytest.mark.parametrize("nbits,d,acc", [([4] * 16, 32, 8), ([4] * 32, 64, 8), (synth.C3_BITS, 128, 16),
+                                         ([8] * 8, 32, 8), ([8] * 16, 64, 16), ([3, 7, 1, 2], 13, 8),
+                                         ([4] * 16, 32, 16)])
+@pytest.mark.parametrize("n", [900, 50_001])
+@pytest.mark.parametrize("nq", [1, 5])
+def test_saturated_keys_are_ordinary_largest_keys(qb, nbits, d, acc, n, nq):
+    """Hand-made quantized tables whose sums mostly exceed q_max, scanned with key_bound = q_max
+    (the caller knows no bound): fewer than R codes stay below q_max, so the result must be
+    filled with saturated codes in id order (Section 3.4: sums saturate at q_max; q_max is an
+    ordinary largest key), whatever the batch size."""
+    pr = synth.make_problem(n=n, nq=nq, d=d, nbits=nbits, acc_bits=acc, dist="gamma_ints", seed=5,
+                            train_n=600, kmeans_iters=1)
+    lay = pr.layout
+    idx = make_index(qb, pr)
+    rng = np.random.default_rng(n + nq + len(nbits))
+    qmax, m, R = lay.q_max, lay.m, 100
+    T = sum(1 << b for b in nbits)
+    lo = 2 * qmax // m + 1                      # any two entries >= lo ... m of them exceed q_max
+    qtab = rng.integers(lo, min(qmax, 4 * lo) + 1, (nq, T)).astype(np.uint16)
+    # a few dozen codes (fewer than R) get sums below q_max: their sub-codes hit zero entries
+    toff = np.concatenate([[0], np.cumsum([1 << b for b in nbits])])[:-1]
+    sub = np.stack([rng.integers(1, 1 << b, n) for b in nbits], axis=1).astype(np.uint8)
+    qtab[:, toff] = 0                            # entry 0 of every sub-quantizer
+    few = rng.choice(n, 37, replace=False)
+    sub[few] = 0
+    sub[few[:20], 0] = 1                         # some with one non-zero addend: distinct small keys
+    codes = synth.pack_codes(torch.from_numpy(sub), lay)
+    rec = np.zeros(nq, np.dtype([("d_min", "<f8"), ("delta", "<f8"), ("d_max", "<f4"), ("kb", "<u4")]))
+    rec["d_min"], rec["delta"], rec["d_max"], rec["kb"] = 1.5, 0.25, 1.5 + 0.25 * qmax, qmax
+    qp = torch.from_numpy(rec.view(np.uint8).reshape(nq, -1).copy()).to(dev())
+    qt = torch.from_numpy(qtab.astype(np.uint8 if acc == 8 else np.uint16)).to(dev())
+    ids, keys, dist = qb.pq_adc_scan_topk(idx, qt, qp, codes.to(dev()), R)
+    torch.cuda.synchronize()
+    nsat = 0
+    for q in range(nq):
+        okeys = oracle.scan_keys(lay.nbits, acc, qtab[q], codes.numpy())
+        nsat += int((okeys[np.sort(few)] < qmax).sum())
+        oi, ok, od = oracle.topk(acc, okeys, R, 1.5, 0.25)
+        assert (okeys < qmax).sum() < R          # the case this test is about
+        assert np.array_equal(ids[q].cpu().numpy(), oi), (q, ids[q][:45], oi[:45])
+        assert np.array_equal(keys[q].cpu().numpy().astype(np.uint16), ok)
+        assert np.array_equal(dist[q].cpu().numpy(), od)
+    assert nsat > 0
+    idx.close()
+
+
 def test_error_paths_on_device(qb):
     pr = synth.build(synth.scaled("C0", n=3000, nq=2))
     idx = make_index(qb, pr)
@@ -378,6 +424,13 @@ def test_ivf_largest_nprobe(qb):
     """nprobe = 1024, the most the call accepts: one slot list per probed cell in the selection."""
     ip = synth.build(synth.scaled("C4", n=300_000, nq=3, K=2048, nprobe=1024, train_n=40_000, kmeans_iters=2))
     check_ivf(qb, ip, 100)
+
+
+def test_ivf_longest_result_list(qb):
+    """R = 2048, the most the call accepts: the pilot of the calibration kernel is cut to what
+    fits its LDS."""
+    ip = synth.build(synth.scaled("C4", n=120_000, nq=3, K=64, nprobe=16))
+    check_ivf(qb, ip, 2048)
 
 
 def test_ivf_edge_probes_and_padding(qb):

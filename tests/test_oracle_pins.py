@@ -416,6 +416,22 @@ def test_ivf_worked_example():
     assert dist.tolist() == [float(w) for w in want]
 
 
+def test_ivf_list_with_d_min_equal_to_d_max_is_skipped():
+    # Section 3.4: later candidates have to be closer than d_max, so a cell whose smallest
+    # representable distance equals d_max holds nothing to keep (hand-worked fixture)
+    g = json.load(open(os.path.join(GOLD, "ivf_skip_boundary_example.json")))
+    lay = synth.Layout(d=g["d"], nbits=g["nbits"], dsub=g["dsub"], acc_bits=g["acc_bits"])
+    codes = synth.pack_codes(torch.tensor(g["list_subcodes"], dtype=torch.uint8), lay).numpy()
+    ids, dist, dmax = oracle.search_ivf(
+        g["d"], g["nbits"], g["dsub"], g["acc_bits"], np.array(g["codebooks"], np.float32),
+        np.array(g["coarse"], np.float32), np.array(g["list_offsets"], np.int64), codes,
+        np.array(g["list_ids"], np.int32), np.array(g["query"], np.float32),
+        np.array(g["probe"], np.int32), g["t"], g["R"])
+    assert dmax == g["d_max"]
+    assert ids.tolist() == g["top_ids"]
+    assert dist.tolist() == g["top_dist"]
+
+
 # ---------------------------------------------------------------- O7: coarse-quantizer search
 def test_coarse_search_worked_example():
     g = json.load(open(os.path.join(GOLD, "coarse_worked_example.json")))
