@@ -27,6 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+LLC_BYTES = 256 << 20   # last-level (Infinity) cache
 
 
 
@@ -112,6 +113,11 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the batch-32/256 legs")
     ap.add_argument("--cpu-queries", type=int, default=24)
+    ap.add_argument("--reps", type=int, default=25,
+                    help="repetitions of the timed train of --steps steps; the headline is the median")
+    ap.add_argument("--summarize-pmc", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
+                    help="no benchmark: print the HBM-traffic summary of two rocprofv3 --pmc runs of "
+                         "this script (FETCH_SIZE, WRITE_SIZE; both with --copy-calibration)")
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="also run this many plain 1 GiB device copies (library kernel k_copy, "
                          "known traffic) so that hardware counters collected around this run "
@@ -173,17 +179,36 @@ class Runner:
         if rc != 0:
             raise RuntimeError("libqadc: " + lib.pq_last_error().decode())
 
-    def run(self, steps, warmup):
+    def prime(self, rounds=3):
+        """Use every stream set (and so every hardware queue) a few times: the first launches
+        on a stream create its queue and load code objects, which is not steady state."""
+        for _ in range(rounds):
+            for i in range(len(self.sets)):
+                self.step(i)
+        self.torch.cuda.synchronize()
+
+    def run(self, steps, warmup, reps=1):
+        """`warmup` untimed steps, then `reps` trains of exactly `steps` steps, each bracketed
+        by a device synchronisation on both sides.  Returns the list of train times (s)."""
         torch = self.torch
+        self.prime()
         for i in range(warmup):
             self.step(i)
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(steps):
-            self.step(warmup + i)
-        self.issue_s = time.perf_counter() - t0   # host time to enqueue the steps
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0
+        times, issue = [], []
+        k = warmup
+        for _ in range(max(1, reps)):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(steps):
+                self.step(k + i)
+            t1 = time.perf_counter()
+            torch.cuda.synchronize()
+            times.append(time.perf_counter() - t0)
+            issue.append(t1 - t0)             # host time to enqueue the steps
+            k += steps
+        self.issue_s = sorted(issue)[len(issue) // 2]
+        return times
 
     def result_of(self, q0):
         """Run the path for queries [q0, q0+batch) on stream set 0 and return numpy outputs."""
@@ -285,6 +310,8 @@ def cpu_baseline(pr, R, nq, t=400):
 
 def main():
     a = parse()
+    if a.summarize_pmc:
+        return summarize_pmc(*a.summarize_pmc)
     if a.gpus != 1:
         print("bench.py: this build is single-GPU; run with --gpus 1 (multi-GPU sharding is a "
               "design note only, no collective code exists)", file=sys.stderr)
@@ -328,9 +355,10 @@ def main():
         del src, dst
 
 
-    # headline: whole path, `batch` queries per step
+    # headline: whole path, `batch` queries per step; `reps` trains of exactly `steps` steps
     run = Runner(qb, idx, pr.queries, pr.codes, a.batch, a.R, streams=a.streams, fused=not a.unfused)
-    dt = run.run(a.steps, a.warmup)
+    trains = sorted(run.run(a.steps, a.warmup, a.reps))
+    dt = trains[len(trains) // 2]                      # median train
     ms_per_step = dt / a.steps * 1e3
     codes_per_s = a.batch * n * a.steps / dt
 
@@ -338,6 +366,22 @@ def main():
     k_avg_ms, k_cnt = scan_kernel_time(qb, idx, pr.queries, pr.codes, a.batch, a.R)
     alg_bytes = float(n) * cs  # every code byte is read once per launch, whatever the batch
     achieved = alg_bytes / (k_avg_ms * 1e-3) / 1e9
+    resident = n * cs <= LLC_BYTES
+    roofline = {"bound": "hbm", "kernel": "k_scan", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": measured_traffic_bytes(a.workload, a.batch),
+                "kernel_avg_ms": k_avg_ms, "launches": k_cnt,
+                "algorithmic_bytes_per_launch": alg_bytes,
+                "residency": (f"the {n * cs / 1e6:.0f} MB code array is rescanned back to back and stays in the "
+                              f"256 MB last-level cache: `frac` is a cache-resident figure, `frac_cold` the one "
+                              f"streamed from HBM" if resident else
+                              f"the {n * cs / 1e6:.0f} MB code array exceeds the 256 MB last-level cache")}
+    if n * cs <= (1 << 30) and not a.no_extras:
+        cold_ms = cold_scan_kernel_time(qb, idx, pr.queries, pr.codes, a.R)
+        roofline["achieved_cold"] = alg_bytes / cold_ms / 1e6
+        roofline["frac_cold"] = alg_bytes / cold_ms / 1e6 / HBM_PEAK_GBS
+        roofline["kernel_avg_ms_cold"] = cold_ms
+        roofline["cold_note"] = "5 separate copies of the code array scanned in turn (more than the last-level cache)"
 
     extras = {}
     if not a.no_extras:
@@ -345,16 +389,18 @@ def main():
         med, mn = isolated_latency(lat)
         extras["isolated_latency_ms"] = {"median": med, "min": mn,
                                          "note": "one step at a time, host-synchronised"}
-        if n * cs <= (1 << 30):
-            cold_ms = cold_scan_kernel_time(qb, idx, pr.queries, pr.codes, a.R)
-            extras["scan_kernel_cold"] = {"kernel_avg_ms": cold_ms, "gb_per_s": alg_bytes / cold_ms / 1e6,
-                                          "frac_of_peak": alg_bytes / cold_ms / 1e6 / HBM_PEAK_GBS,
-                                          "note": "5 copies of the code array scanned in turn"}
+        # query-batched passes: bound by LDS reads, not HBM.  Ceiling: one 8-byte table entry per
+        # lane, 16 lanes per CU and clock without bank conflicts (128 B/clk) = 256 CUs x 16 x 2.4 GHz
+        lds_ceiling = 256 * 16 * 2.4e9
         for bs, st in ((32, 60), (256, 12)):
             r2 = Runner(qb, idx, pr.queries, pr.codes, bs, a.R, streams=min(a.streams, 2),
                         fused=not a.unfused)
-            d2 = r2.run(st, 2)
+            d2 = sorted(r2.run(st, 2, 5))[2]
             kms, _ = scan_kernel_time(qb, idx, pr.queries, pr.codes, bs, a.R, nsamples=2, reps=5)
+            # one LDS read of an 8-byte entry serves four queries' lookups of one group
+            # (m x 4 layouts: a group is a code byte; irregular layouts: ng groups per code)
+            groups = lay.m // 2 if set(lay.nbits) == {4} else None
+            reads = ((bs + 3) // 4) * groups * float(n) if groups else None
             extras[f"batch{bs}"] = {
                 "ms_per_step": d2 / st * 1e3,
                 "gcodes_per_s": bs * n * st / d2 / 1e9,
@@ -362,6 +408,13 @@ def main():
                 "scan_kernel_ms": kms,
                 "scan_kernel_glookups_per_s": bs * n * lay.m / (kms * 1e-3) / 1e9,
             }
+            if reads:
+                extras[f"batch{bs}"]["roofline"] = {
+                    "bound": "lds", "kernel": "k_scan_mq", "unit": "G 8-byte LDS reads/s",
+                    "achieved": reads / (kms * 1e-3) / 1e9, "peak": lds_ceiling / 1e9,
+                    "frac": reads / (kms * 1e-3) / lds_ceiling, "lds_reads_per_launch": reads}
+        if a.workload == "C1" and a.batch == 1:
+            extras["C2_streaming"] = streaming_leg(qb, synth, dev, "C2", 100)
 
     entry = ("pq_compute_tables+pq_quantize_tables+pq_adc_scan_topk" if a.unfused
              else "pq_search_topk")
@@ -384,12 +437,16 @@ def main():
                                f"bits={sorted(set(lay.nbits))}, code_bytes={cs}, R={a.R}, t=400, "
                                f"batch={a.batch}, streams={a.streams}, hw_queues={a.hw_queues}, entry={entry}",
                    "seed": cfg["seed"], "dataset_build_s": round(t_build, 2)},
+        # `value` and `ms_per_step` are the median of `reps` trains of exactly `steps` steps, each
+        # train bracketed by a device synchronisation on both sides
+        "timing": {"reps": len(trains), "ms_per_step_median": ms_per_step,
+                   "ms_per_step_min": trains[0] / a.steps * 1e3,
+                   "ms_per_step_max": trains[-1] / a.steps * 1e3,
+                   "ms_per_step_mean": sum(trains) / len(trains) / a.steps * 1e3},
         "whole_path_hbm_gbs": codes_per_s * cs / 1e9,
+        "whole_path_frac_of_hbm_peak": codes_per_s * cs / 1e9 / HBM_PEAK_GBS,
         "host_issue_ms_per_step": run.issue_s / a.steps * 1e3,
-        "roofline": {"bound": "hbm", "kernel": "k_scan", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, a.batch)), "kernel_avg_ms": k_avg_ms, "launches": k_cnt,
-                     "algorithmic_bytes_per_launch": alg_bytes},
+        "roofline": roofline,
         "batched": extras,
         # the paper's own figure for this layout, another machine and size: context, not a baseline
         "paper_context": {"value": 1.89, "unit": "Gcodes/s",
@@ -399,10 +456,15 @@ def main():
 
     if not a.no_cpu_baseline:
         res, cdt, threads = cpu_baseline(pr, a.R, a.cpu_queries)
+        try:
+            usable = len(os.sched_getaffinity(0))
+        except AttributeError:
+            usable = os.cpu_count()
         out["cpu_baseline"] = {"value": a.cpu_queries * n / cdt / 1e9, "unit": "Gcodes/s",
                                "cores": threads, "kind": "oracle",
+                               "nproc": os.cpu_count(), "usable_cpus": usable,
                                "sample": f"{a.cpu_queries} queries x {n} codes (the full list), "
-                                         f"one query per thread, {cdt:.1f} s wall"}
+                                         f"one query per thread on {threads} threads, {cdt:.1f} s wall"}
         # parity of the timed configuration against the same oracle results
         ok = True
         for q0 in range(0, min(a.cpu_queries, run.nq_total), max(1, a.batch)):
@@ -413,6 +475,31 @@ def main():
                     keys[j].astype(np.uint16), okk) and np.array_equal(dist[j], od)
         out["parity_sample"] = {"queries": a.cpu_queries, "bit_exact": bool(ok)}
     print(json.dumps(out))
+
+
+def streaming_leg(qb, synth, dev, name, R):
+    """The scan kernel alone on another exhaustive configuration (C2: 320 MB of codes, more than
+    the last-level cache, so every launch streams from HBM), one query per launch."""
+    import torch
+    cfg = dict(synth.CONFIGS[name])
+    cfg["nq"] = 16
+    pr = synth.build(cfg, device=dev)
+    lay = pr.layout
+    n, cs = pr.codes.shape
+    idx = qb.PqIndex(lay.d, lay.nbits, lay.dsub, pr.codebooks, lay.acc_bits)
+    ms, cnt = scan_kernel_time(qb, idx, pr.queries, pr.codes, 1, R, nsamples=4, reps=50)
+    cold = cold_scan_kernel_time(qb, idx, pr.queries, pr.codes, R, copies=4, reps=10)
+    run = Runner(qb, idx, pr.queries, pr.codes, 1, R, streams=8)
+    trains = sorted(run.run(100, 16, 9))
+    torch.cuda.synchronize()
+    idx.close()
+    nb = float(n) * cs
+    return {"workload": f"{name}: N={n}, code_bytes={cs}, R={R}, batch=1",
+            "scan_kernel_ms": ms, "launches": cnt, "gb_per_s": nb / ms / 1e6,
+            "frac_of_hbm_peak": nb / ms / 1e6 / HBM_PEAK_GBS,
+            "scan_kernel_ms_cold": cold, "frac_of_hbm_peak_cold": nb / cold / 1e6 / HBM_PEAK_GBS,
+            "whole_path_ms_per_query": trains[len(trains) // 2] / 100 * 1e3,
+            "whole_path_frac_of_hbm_peak": nb / (trains[len(trains) // 2] / 100) / 1e9 / HBM_PEAK_GBS}
 
 
 def main_ivf(a):
