@@ -154,6 +154,23 @@ int pq_adc_scan_topk(const pq_index_t *idx, const void *qtables, const pq_qparam
                      size_t workspace_bytes, void *stream);
 
 /*
+ * pq_adc_scan_topk for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and error rules, minus the workspace: the scan's scratch memory is an
+ * array of PQ_STATIC_SCRATCH_BYTES bytes inside the library, one copy per GPU, held from the
+ * time the library is loaded until the process ends.  The call allocates nothing and frees
+ * nothing.  PQ_ENOMEM when pq_workspace_bytes(idx, nq, n, R) exceeds PQ_STATIC_SCRATCH_BYTES
+ * (the message says how much was needed).  All calls on one GPU share that GPU's array: two
+ * calls that overlap in time on one GPU (different streams, different threads) race and give
+ * undefined results; calls on one stream, or otherwise ordered, are fine.  Nothing in the array
+ * has to be cleared between calls.
+ */
+#define PQ_STATIC_SCRATCH_BYTES (16u << 20)
+int pq_adc_scan_topk_static(const pq_index_t *idx, const void *qtables, const pq_qparams_t *qparams,
+                            int nq, const uint8_t *codes, int64_t n, int R, int32_t *out_ids,
+                            uint16_t *out_keys, float *out_dist, void *stream);
+
+/*
  * The two halves of pq_adc_scan_topk as calls of their own (same arguments, same
  * workspace): pq_adc_scan_candidates prepares the query's lookup tables in the
  * workspace, streams the codes and leaves, per query, the codes whose key is

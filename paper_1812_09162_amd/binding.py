@@ -26,7 +26,7 @@ EXPORTS = [
     "ivf_workspace_bytes", "ivf_sorted_workspace_bytes", "pq_compute_tables", "pq_quantize_tables", "pq_adc_scan_topk",
     "ivf_adc_scan_topk", "pq_search_workspace_bytes", "pq_search_topk",
     "pq_adc_scan_candidates", "pq_adc_rescan_candidates", "pq_select_topk", "pq_copy_bytes", "pq_last_error",
-    "ivf_coarse_workspace_bytes", "ivf_coarse_search", "pq_encode",
+    "ivf_coarse_workspace_bytes", "ivf_coarse_search", "pq_encode", "pq_adc_scan_topk_static",
 ]
 
 
@@ -66,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.pq_quantize_tables.restype = i32
     lib.pq_adc_scan_topk.argtypes = [vp, vp, vp, i32, vp, i64, i32, vp, vp, vp, vp, sz, vp]
     lib.pq_adc_scan_topk.restype = i32
+    lib.pq_adc_scan_topk_static.argtypes = [vp, vp, vp, i32, vp, i64, i32, vp, vp, vp, vp]
+    lib.pq_adc_scan_topk_static.restype = i32
     lib.ivf_adc_scan_topk.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, vp, i32, i32, i32, vp, vp,
                                       vp, sz, vp]
     lib.ivf_adc_scan_topk.restype = i32
@@ -206,6 +208,17 @@ def pq_adc_scan_topk(idx: PqIndex, qtables: torch.Tensor, qparams: torch.Tensor,
     _check(load().pq_adc_scan_topk(idx.handle, _ptr(qtables), _ptr(qparams), nq, _ptr(codes), n, R,
                                    _ptr(ids), _ptr(keys), _ptr(dist), _ptr(workspace),
                                    workspace.numel(), _stream(stream)))
+    return ids, keys, dist
+
+
+def pq_adc_scan_topk_static(idx: PqIndex, qtables: torch.Tensor, qparams: torch.Tensor,
+                            codes: torch.Tensor, R: int, out, stream=None):
+    """The caller passes inputs and outputs; the library's own scratch array is the workspace."""
+    _dev(codes, torch.uint8)
+    ids, keys, dist = out
+    _check(load().pq_adc_scan_topk_static(idx.handle, _ptr(qtables), _ptr(qparams), qtables.shape[0],
+                                          _ptr(codes), codes.shape[0], R, _ptr(ids), _ptr(keys),
+                                          _ptr(dist), _stream(stream)))
     return ids, keys, dist
 
 

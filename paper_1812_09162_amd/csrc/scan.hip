@@ -17,6 +17,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "scan_device.h"
 
 #ifndef SCAN_THREADS
@@ -999,6 +1001,59 @@ extern "C" int pq_select_topk(const pq_index_t *idx, const void *qtables,
                               void *workspace, size_t workspace_bytes, void *stream) {
     return scan_entry("pq_select_topk", 2, idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys,
                       out_dist, workspace, workspace_bytes, stream);
+}
+
+// ------------------------------------------- entry point that allocates nothing ---
+// pq_adc_scan_topk with the workspace in a device array of this library instead of caller
+// memory.  Every GPU holds its own copy of the array at its own address: the address is asked
+// for once per device (with that device current) and kept; host code only ever uses that
+// address, never the array's name.
+static __device__ __align__(256) unsigned char scratch[PQ_STATIC_SCRATCH_BYTES];
+
+#define QADC_MAX_DEVICES 64
+static void *g_scratch_ptr[QADC_MAX_DEVICES];  // per device; null until first use there
+static std::mutex g_scratch_mutex;
+
+static int static_scratch(void **out) {
+    int dev = -1;
+    QADC_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= QADC_MAX_DEVICES) {
+        qadc_set_error("pq_adc_scan_topk_static: device %d out of range (0..%d)", dev, QADC_MAX_DEVICES - 1);
+        return PQ_EINVAL;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        QADC_HIP_TRY(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) {
+            qadc_set_error("pq_adc_scan_topk_static: no address for the scratch array on device %d", dev);
+            return PQ_EHIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PQ_OK;
+}
+
+extern "C" int pq_adc_scan_topk_static(const pq_index_t *idx, const void *qtables,
+                                       const pq_qparams_t *qparams, int nq, const uint8_t *codes,
+                                       int64_t n, int R, int32_t *out_ids, uint16_t *out_keys,
+                                       float *out_dist, void *stream) {
+    int rc = check_scan_args("pq_adc_scan_topk_static", idx, nq, n, R);
+    if (rc != PQ_OK) return rc;
+    if (nq == 0) return PQ_OK;
+    const size_t need = qadc_scan_plan(idx, nq, n, R).total;
+    if (need > (size_t)PQ_STATIC_SCRATCH_BYTES) {
+        qadc_set_error("pq_adc_scan_topk_static: nq=%d n=%lld R=%d need %zu bytes of scratch, the "
+                       "library's array holds %zu; use pq_adc_scan_topk with a workspace",
+                       nq, (long long)n, R, need, (size_t)PQ_STATIC_SCRATCH_BYTES);
+        return PQ_ENOMEM;
+    }
+    void *ptr = nullptr;
+    if ((rc = static_scratch(&ptr)) != PQ_OK) return rc;
+    // (the scan's workspace needs no initial contents: every word read was written by this call)
+    return scan_entry("pq_adc_scan_topk_static", 7, idx, qtables, qparams, nq, codes, n, R, out_ids,
+                      out_keys, out_dist, ptr, (size_t)PQ_STATIC_SCRATCH_BYTES, stream);
 }
 
 // ------------------------------------------------------- fused search call ---
