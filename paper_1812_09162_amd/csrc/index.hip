@@ -6,7 +6,7 @@
 
 #include <vector>
 
-#include "qadc_internal.h"
+#include "scan_device.h"
 
 static thread_local char g_err[512] = "";
 
@@ -183,36 +183,20 @@ ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R) {
     if (gmax < 1) gmax = 1;  // a zero or negative QADC_G
     int64_t G = tiles < 1 ? 1 : (tiles > gmax ? gmax : tiles);
     p.G = (int)G;
-    // slots per block: four times the candidates expected when the bound comes from a
-    // 65536-code pilot (the quantizer's default), plus slack for ties
-    const int64_t per_block = (n + G - 1) / G;
-    int64_t est = per_block * (int64_t)R / 65536 + 1;
-    int64_t cap = 128;
-    while (cap < 4 * est + 64 && cap < 65536) cap <<= 1;
-    if (cap > per_block + 2) {  // never more slots than codes the block sees
-        cap = 128;
-        while (cap < per_block + 2) cap <<= 1;
-    }
-    p.cap_b = (int)cap;
-    p.pilot_codes = 0;
-    p.state_off = 0;
-    p.counts_off = 0;
-    p.gtab_off = align_up((size_t)p.G * sizeof(uint32_t), 256);
-    p.slots_off = p.gtab_off + align_up((size_t)idx->h.gtab_len * (idx->h.acc_bits == 8 ? 1 : 2), 256);
-    p.per_query = p.slots_off + (size_t)p.G * (size_t)p.cap_b * sizeof(uint64_t);
-    p.per_query = align_up(p.per_query, 256);
+    // candidate lists (QADC_NSUB per query): together four times the candidates expected when
+    // the bound comes from a 65536-code pilot (the quantizer's smallest), plus slack for ties and
+    // for an uneven spread; never more entries than codes (a list that overflows only makes the
+    // selection take its slow exact path)
+    int64_t cap = (4 * (n / 65536 + 1) * (int64_t)R) / QADC_NSUB + 64;
+    if (cap > n + 8) cap = n + 8;
+    if (cap > ((int64_t)1 << 20)) cap = (int64_t)1 << 20;
+    cap = (cap + 7) & ~(int64_t)7;
+    p.cap = (uint32_t)cap;
+    p.gtab_off = align_up(sizeof(ScanHdr), 256);
+    p.cand_off = p.gtab_off + align_up((size_t)idx->h.gtab_len * (idx->h.acc_bits == 8 ? 1 : 2), 256);
+    p.per_query = align_up(p.cand_off + (size_t)QADC_NSUB * p.cap * sizeof(uint64_t), 256);
     p.total = p.per_query * (size_t)(nq > 0 ? nq : 0);
-    p.logw = qadc_rows_logw(n, p.G, R, 65536);
     return p;
-}
-
-// Slot-list entries the selection kernel reads per list and round (as a power of two): about
-// twice the candidates a scan block is expected to keep when the bound came from a pilot of
-// `pilot` codes, within [4, 32].
-int qadc_rows_logw(int64_t n, int G, int R, int64_t pilot) {
-    if (pilot < 1) pilot = 1;
-    const double est = (double)(n / (G > 0 ? G : 1) + 1) * (double)R / (double)pilot;
-    return est <= 1.5 ? 2 : (est <= 3.0 ? 3 : (est <= 7.0 ? 4 : 5));
 }
 
 IvfPlan qadc_ivf_plan(const pq_index *idx, int nq, int nprobe, int R) {

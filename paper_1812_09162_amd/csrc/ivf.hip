@@ -135,7 +135,8 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
             int R, char *__restrict__ ws, size_t per_query) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t sel[2];
+    __shared__ uint32_t sel[8];
+    __shared__ uint32_t kmem[QADC_KTH_MEM];
     __shared__ unsigned long long s_np;
     __shared__ uint32_t sdesc[PQ_MAX_M];  // table offset | bit offset << 12 | bits << 24
     IvfLds l;
@@ -209,7 +210,7 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
         seen += take;
         __syncthreads();
     }
-    const float dmax = qadc_ord2f(qadc_block_kth_u32(ord, t_eff, k, 4, hist, sel));
+    const float dmax = qadc_ord2f(qadc_block_kth_f32(ord, t_eff, k, hist, sel, kmem));
     // pass 2: quantized distances of the first `pilot` probed codes -> thr0 and the binning
     seen = 0;
     for (int a = 0; a < nprobe && seen < pilot; ++a) {

@@ -73,25 +73,35 @@ __device__ __forceinline__ float qadc_ord2f(uint32_t o) {
     return __uint_as_float(u);
 }
 
-// Wave-wide inclusive prefix sum (wave64).
+// Wave-wide operations (wave64) through data-parallel-primitive moves: shifts within rows of 16
+// lanes by 1, 2, 4, 8, then lane 15 of rows 0 and 2 broadcast to the next row, then lane 31 to
+// rows 2 and 3.  Lanes without a source take the neutral element.  (Six register moves; the
+// same through cross-lane shuffles takes six trips through the LDS crossbar.)
+#define QADC_DPP_STEP(OLD, V, CTRL, ROWS) (uint32_t)__builtin_amdgcn_update_dpp((int)(OLD), (int)(V), CTRL, ROWS, 0xf, false)
+
+// inclusive prefix sum
 __device__ __forceinline__ uint32_t qadc_wave_incl_scan(uint32_t v) {
-    int lane = __lane_id();
-#pragma unroll
-    for (int d = 1; d < QADC_WAVE; d <<= 1) {
-        uint32_t o = __shfl_up(v, d, QADC_WAVE);
-        if (lane >= d) v += o;
-    }
+    v += QADC_DPP_STEP(0u, v, 0x111, 0xf);
+    v += QADC_DPP_STEP(0u, v, 0x112, 0xf);
+    v += QADC_DPP_STEP(0u, v, 0x114, 0xf);
+    v += QADC_DPP_STEP(0u, v, 0x118, 0xf);
+    v += QADC_DPP_STEP(0u, v, 0x142, 0xa);
+    v += QADC_DPP_STEP(0u, v, 0x143, 0xc);
     return v;
 }
 
+// minimum / maximum over the wave, returned to every lane
 __device__ __forceinline__ uint32_t qadc_wave_min(uint32_t v) {
-#pragma unroll
-    for (int d = QADC_WAVE / 2; d >= 1; d >>= 1) {
-        uint32_t o = __shfl_xor(v, d, QADC_WAVE);
-        v = o < v ? o : v;
-    }
-    return v;
+    uint32_t t;
+    t = QADC_DPP_STEP(0xffffffffu, v, 0x111, 0xf); v = t < v ? t : v;
+    t = QADC_DPP_STEP(0xffffffffu, v, 0x112, 0xf); v = t < v ? t : v;
+    t = QADC_DPP_STEP(0xffffffffu, v, 0x114, 0xf); v = t < v ? t : v;
+    t = QADC_DPP_STEP(0xffffffffu, v, 0x118, 0xf); v = t < v ? t : v;
+    t = QADC_DPP_STEP(0xffffffffu, v, 0x142, 0xa); v = t < v ? t : v;
+    t = QADC_DPP_STEP(0xffffffffu, v, 0x143, 0xc); v = t < v ? t : v;
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
+__device__ __forceinline__ uint32_t qadc_wave_max(uint32_t v) { return ~qadc_wave_min(~v); }
 
 // Over 256 bins: the smallest bin b with base + hist[0..b] >= kk (bin 255 if
 // none), and base + hist[0..b-1].  Called by one full wave; the result goes to
@@ -185,3 +195,81 @@ __device__ inline uint32_t qadc_block_kth_u32(const uint32_t *vals, int cnt, int
     return prefix;
 }
 
+
+// k-th smallest (1 <= k <= cnt) of cnt > 0 finite floats held in LDS as ordered words
+// (qadc_f2ord), for the common case of values that are spread out: 256 equal bins over
+// [min, max] (subtraction, multiplication by a positive factor and truncation are all monotone
+// under rounding, so a lower bin never holds a larger value), the bin that holds the k-th, and
+// an exact pick among that bin's few members by counting.  Five short steps with a barrier
+// each instead of the radix selection's four passes; a crowded bin (many equal values) or a
+// degenerate range falls back to qadc_block_kth_u32.  All threads of the block call it; `hist`
+// is 256 words of LDS, `sel` eight, `mem` QADC_KTH_MEM.  Returns the value to every thread.
+#define QADC_KTH_MEM 256
+__device__ inline uint32_t qadc_block_kth_f32(const uint32_t *vals, int cnt, int k, uint32_t *hist,
+                                              uint32_t *sel, uint32_t *mem) {
+    uint32_t mn = 0xffffffffu, mx = 0u;
+    for (int i = threadIdx.x; i < cnt; i += blockDim.x) {
+        const uint32_t v = vals[i];
+        mn = v < mn ? v : mn;
+        mx = v > mx ? v : mx;
+    }
+    mn = qadc_wave_min(mn);
+    mx = qadc_wave_max(mx);
+    if (threadIdx.x == 0) {
+        sel[0] = 0xffffffffu;
+        sel[1] = 0u;
+        sel[2] = 0u;  // members gathered
+    }
+    for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+    __syncthreads();
+    if (threadIdx.x % QADC_WAVE == 0) {
+        atomicMin(&sel[0], mn);
+        atomicMax(&sel[1], mx);
+    }
+    __syncthreads();
+    mn = sel[0];
+    mx = sel[1];
+    if (mn == mx) {
+        __syncthreads();
+        return mn;
+    }
+    const float fmn = qadc_ord2f(mn);
+    const float scale = 256.0f / (qadc_ord2f(mx) - fmn);
+    const bool usable = scale > 0.0f && scale <= 3.0e38f;  // (block-uniform)
+    auto bin_of = [fmn, scale](uint32_t v) {
+        const float x = (qadc_ord2f(v) - fmn) * scale;  // >= 0
+        return x >= 255.0f ? 255u : (uint32_t)x;
+    };
+    if (usable) {
+        for (int i = threadIdx.x; i < cnt; i += blockDim.x) atomicAdd(&hist[bin_of(vals[i])], 1u);
+        __syncthreads();
+        if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, (uint32_t)k, 0u, sel + 4);
+        __syncthreads();
+    }
+    const uint32_t b = usable ? sel[4] : 0u, below = usable ? sel[5] : 0u;
+    const uint32_t nm = usable ? hist[b] : 0xffffffffu;
+    if (nm > QADC_KTH_MEM) {
+        __syncthreads();
+        return qadc_block_kth_u32(vals, cnt, k, 4, hist, sel);
+    }
+    for (int i = threadIdx.x; i < cnt; i += blockDim.x) {
+        const uint32_t v = vals[i];
+        if (bin_of(v) == b) mem[atomicAdd(&sel[2], 1u)] = v;
+    }
+    __syncthreads();
+    const uint32_t r = (uint32_t)k - below;  // 1-based rank among the nm members
+    for (uint32_t i = threadIdx.x; i < nm; i += blockDim.x) {
+        const uint32_t mine = mem[i];
+        uint32_t lt = 0, le = 0;
+        for (uint32_t j = 0; j < nm; ++j) {
+            const uint32_t o = mem[j];
+            lt += o < mine ? 1u : 0u;
+            le += o <= mine ? 1u : 0u;
+        }
+        if (lt < r && r <= le) sel[3] = mine;  // (equal values may all write: the same word)
+    }
+    __syncthreads();
+    const uint32_t res = sel[3];
+    __syncthreads();
+    return res;
+}

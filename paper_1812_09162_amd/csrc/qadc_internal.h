@@ -73,19 +73,16 @@ struct IvfPlan {
 IvfPlan qadc_ivf_plan(const pq_index *idx, int nq, int nprobe, int R);
 
 struct ScanPlan {
-    int G;        // blocks per query in the scan kernel
-    int cap_b;    // candidate slots per block
-    int64_t pilot_codes;
-    size_t per_query;  // bytes per query
-    size_t state_off, counts_off, slots_off;
+    int G;             // blocks per query in the scan kernel
+    uint32_t cap;      // entries of each of a query's candidate lists
+    size_t per_query;  // bytes per query: header | prepared group tables | candidate lists
     size_t gtab_off;   // prepared group tables of the query (gtab_len entries)
+    size_t cand_off;   // candidate lists (QADC_NSUB x cap 64-bit entries)
     size_t total;
-    int logw;     // log2 of the slot-list entries the selection kernel reads per round
 };
 
 void qadc_set_error(const char *fmt, ...);
 ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R);
-int qadc_rows_logw(int64_t n, int G, int R, int64_t pilot);
 
 // Pilot of the distance quantizer: `pilot` codes, counted by P blocks per query, `slice` each.
 struct PilotPlan {
@@ -96,12 +93,13 @@ size_t qadc_pilot_scratch_bytes(int nq);
 PilotPlan qadc_pilot_plan(int nq, int64_t n, int t_eff, int R, bool have_scratch);
 
 // gtab_out: if non-null, query q's group tables are also written to gtab_out + q*gtab_stride bytes.
+// hdr_out: if non-null, the scan header at hdr_out + q*gtab_stride is cleared (an empty candidate list).
 // scratch: null, or qadc_pilot_scratch_bytes(nq) bytes (256-byte aligned, any contents) that let
-// several blocks share a query's pilot.  pilot_used: if non-null, receives the pilot size.
+// several blocks share a query's pilot (they leave their records there).  plan_used: if non-null, receives the pilot plan.
 int qadc_quantize_launch(const pq_index *idx, const float *queries, const float *tables_in,
                          float *tables_out, int nq, const uint8_t *codes, int64_t n, int t, int R,
                          void *qtables, pq_qparams_t *qparams, char *gtab_out, size_t gtab_stride,
-                         char *scratch, int *pilot_used, hipStream_t s);
+                         char *hdr_out, char *scratch, PilotPlan *plan_used, hipStream_t s);
 
 
 #define QADC_HIP_TRY(expr)                                                        \

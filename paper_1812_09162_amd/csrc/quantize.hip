@@ -1,31 +1,9 @@
 // pq_quantize_tables: the query-time distance quantizer of Section 3.4.
 #include <math.h>
 #include <stdlib.h>
-#include <time.h>
-#include <unistd.h>
 
 
 #include "scan_device.h"
-
-// Last-arrival test for the P blocks that work on one query.  `w` is a 64-bit word of
-// caller-provided scratch: its upper 48 bits hold a tag derived from the scratch address, the
-// lower 16 the number of blocks that have arrived.  Normally the word reads (tag, 0), left by
-// the previous call, and arriving is one atomic add.  A word with any other tag (memory used
-// for the first time) is re-tagged by compare-and-swap and the arrival repeated; a failed
-// swap means that another block changed the word, so every block gets through after at most
-// P + 1 rounds.  The block that arrives last must leave (tag, 0) behind when it is done.
-__device__ inline bool qadc_arrive_last(unsigned long long *w, unsigned long long tag, uint32_t P) {
-    unsigned long long old = atomicAdd(w, 1ull);
-    while ((old >> 16) != tag) {
-        unsigned long long cur = __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((cur >> 16) != tag) {
-            atomicCAS(w, cur, tag << 16);
-            cur = __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if ((cur >> 16) == tag) old = atomicAdd(w, 1ull);
-    }
-    return (uint32_t)(old & 0xffffull) + 1u == P;
-}
 
 // P blocks per query (grid = nq * P, block q*P + p).  Every block of a query computes
 //   0. (fused form only) the float table from the query, eq. (1)
@@ -39,9 +17,12 @@ __device__ inline bool qadc_arrive_last(unsigned long long *w, unsigned long lon
 //      codes (pilot >= t_eff), from a 256-bin histogram of the keys (of their high bytes for
 //      16-bit keys).  It bounds the R-th best key of the whole list from above and lets the
 //      scan drop almost every code with one compare.
-// Block p counts the codes [p*slice, (p+1)*slice) of the pilot; with P > 1 the histograms
-// meet in `partial` and the block that arrives last adds them up.  Block 0 of a query stores
-// the tables, that last block the parameters.
+// Block p counts the codes [p*slice, (p+1)*slice) of the pilot.  With P == 1 the block selects
+// the bound itself and stores it in the query's parameters.  With P > 1 no block waits for
+// another: each leaves a record of 64 cumulative counts (how many of its codes have a key in
+// coarse bin t or below, a coarse bin being four bins of the 256-bin histogram) in `bound_rec`,
+// and the scan kernel adds the P records up (scan_bound_from_records); the parameters then
+// carry q_max as the bound.  Block 0 of a query stores the tables and the parameters.
 // `queries` non-null: tables are computed here (and stored to tables_out if
 // that is non-null); otherwise they are read from tables_in.
 template <int KIND, typename QT>
@@ -52,8 +33,7 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
            float *__restrict__ tables_out, const uint8_t *__restrict__ codes, int t_eff, int k,
            int pilot, int slice, int P, void *__restrict__ qtables,
            pq_qparams_t *__restrict__ qparams, char *__restrict__ gtab_out, size_t gtab_stride,
-           uint32_t *__restrict__ partial, unsigned long long *__restrict__ sync,
-           unsigned long long tag) {
+           char *__restrict__ hdr_out, uint16_t *__restrict__ bound_rec) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int T = L->T, m = L->m, cs = L->cs, qmax = L->qmax, d = L->d;
     float *tab = (float *)smem;
@@ -64,11 +44,11 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
     uint8_t *esub = (uint8_t *)(qt + T);
     QT *gtab = (QT *)(smem + (((size_t)T * 4 + (size_t)nord * 4 + PQ_MAX_M * 4 + (size_t)T * 3 + 15) &
                               ~(size_t)15));
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t sel[2];
+    __shared__ __align__(16) uint32_t hist[256];
+    __shared__ uint32_t sel[8];
+    __shared__ uint32_t kmem[QADC_KTH_MEM];
     __shared__ double s_dmin, s_delta;
     __shared__ float s_dmax;
-    __shared__ int s_last;
     __shared__ uint32_t sdesc[PQ_MAX_M];  // table offset | bit offset << 12 | bits << 24 of each sub-quantizer
     if ((int)threadIdx.x < m)  // (read after the barriers of the table set-up)
         sdesc[threadIdx.x] = (uint32_t)L->toff[threadIdx.x] | ((uint32_t)L->bitoff[threadIdx.x] << 12) |
@@ -92,13 +72,22 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
         }
     }
 
+    // The calibration code of this thread (at most one per thread in the common case) and the
+    // descriptor of its table entry are requested now as well: they do not depend on anything.
+    const bool cal_one = t_eff <= (int)blockDim.x && cs <= 16;
+    uint32_t cw[4] = {0u, 0u, 0u, 0u};
+    if (cal_one && (int)threadIdx.x < t_eff) qadc_load_code16(codes + (size_t)threadIdx.x * cs, cs, cw);
+    EntryDesc ed0 = {0, 0, 0, 0};
+    if ((int)threadIdx.x < T) ed0 = edesc[threadIdx.x];
+
     if (queries) {
         float *zs = (float *)ord;  // the query lives where the ADC sums go later
         for (int i = threadIdx.x; i < d; i += blockDim.x) zs[i] = queries[q * d + i];
-        for (int e = threadIdx.x; e < T; e += blockDim.x) esub[e] = (uint8_t)edesc[e].j;
+        for (int e = threadIdx.x; e < T; e += blockDim.x)
+            esub[e] = (uint8_t)(e == (int)threadIdx.x ? ed0.j : edesc[e].j);
         __syncthreads();
         for (int e = threadIdx.x; e < T; e += blockDim.x) {
-            const EntryDesc ed = edesc[e];
+            const EntryDesc ed = e == (int)threadIdx.x ? ed0 : edesc[e];
             const int ds = ed.ds;
             const float *c = cb + ed.cb_off;
             const float *z = zs + ed.dim_off;
@@ -114,7 +103,7 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
     } else {
         for (int e = threadIdx.x; e < T; e += blockDim.x) {
             tab[e] = tables_in[q * T + e];
-            esub[e] = (uint8_t)edesc[e].j;
+            esub[e] = (uint8_t)(e == (int)threadIdx.x ? ed0.j : edesc[e].j);
         }
         __syncthreads();
     }
@@ -131,19 +120,23 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
         const uint8_t *code = codes + (size_t)pp * cs;
         float s = 0.0f;
         if (KIND == SCAN_NIB8) {  // sub-code j is nibble j of the 8-byte code
-            const uint2 v = *(const uint2 *)code;
+            const uint2 v = cal_one ? make_uint2(cw[0], cw[1]) : *(const uint2 *)code;
 #pragma unroll
             for (int j = 0; j < 16; ++j)
                 s = __fadd_rn(s, tab[16 * j + (((j < 8 ? v.x : v.y) >> (4 * (j & 7))) & 15u)]);
         } else if (KIND == SCAN_NIB16) {  // ... of the 16-byte code
-            const uint4 v = *(const uint4 *)code;
+            const uint4 v = cal_one ? make_uint4(cw[0], cw[1], cw[2], cw[3]) : *(const uint4 *)code;
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int j = 0; j < 32; ++j)
                 s = __fadd_rn(s, tab[16 * j + ((w[j >> 3] >> (4 * (j & 7))) & 15u)]);
         } else if (cs <= 16) {  // the code in registers, the sub-quantizers' fields from LDS
             uint32_t w[4];
-            qadc_load_code16(code, cs, w);
+            if (cal_one) {
+                w[0] = cw[0]; w[1] = cw[1]; w[2] = cw[2]; w[3] = cw[3];
+            } else {
+                qadc_load_code16(code, cs, w);
+            }
             for (int j = 0; j < m; ++j) {
                 const uint32_t ds = sdesc[j];
                 s = __fadd_rn(s, tab[(ds & 0xfffu) + qadc_extract_sub16(w, (ds >> 12) & 0xfffu, ds >> 24)]);
@@ -161,7 +154,7 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
         s_dmin = dm;
     }
     float dmax = INFINITY;
-    if (t_eff > 0) dmax = qadc_ord2f(qadc_block_kth_u32(ord, t_eff, k, 4, hist, sel));
+    if (t_eff > 0) dmax = qadc_ord2f(qadc_block_kth_f32(ord, t_eff, k, hist, sel, kmem));
     __syncthreads();
     if (threadIdx.x == 0) {
         double delta = ((double)dmax - s_dmin) / (double)qmax;
@@ -195,6 +188,7 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
             for (int e = threadIdx.x; e < L->gtab_len; e += blockDim.x) dst[e] = gtab[e];
         }
     }
+    if (hdr_out && first) scan_hdr_clear((ScanHdr *)(hdr_out + q * gtab_stride));  // empty candidate lists
     if (pilot > 0) {
         const int shift = sizeof(QT) == 1 ? 0 : 8;
         for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
@@ -290,39 +284,21 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
         }
         __syncthreads();
         if (P > 1) {
-            uint32_t *mine = partial + ((size_t)q * P + p) * 256;
-            if (threadIdx.x < 256) {
-                mine[threadIdx.x] = hist[threadIdx.x];
-                __threadfence();
+            // this block's record: cumulative counts over 64 coarse bins, one lane per bin
+            if (threadIdx.x < QADC_WAVE) {
+                const uint4 h4 = *(const uint4 *)&hist[4 * threadIdx.x];
+                const uint32_t c4 = h4.x + h4.y + h4.z + h4.w;
+                const uint32_t cum = qadc_wave_incl_scan(c4);
+                bound_rec[((size_t)q * QADC_REC_BINS + threadIdx.x) * QADC_REC_SLOTS + p] =
+                    (uint16_t)(cum > 65535u ? 65535u : cum);
             }
+        } else {
+            if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, (uint32_t)k, 0u, sel);
             __syncthreads();
-            if (threadIdx.x == 0) s_last = qadc_arrive_last(sync + q, tag, (uint32_t)P) ? 1 : 0;
-            __syncthreads();
-            if (!s_last) return;
-            // The partial histograms are read with device-scope atomic loads, which see what
-            // the other blocks released before they arrived; all loads are issued together.
-            for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
-            __syncthreads();
-            const uint32_t *all = partial + (size_t)q * P * 256;
-            uint32_t v[16];  // P <= 64 blocks of 256 bins over 1024 threads
-#pragma unroll
-            for (int it = 0; it < 16; ++it) {
-                const int i = it * 1024 + (int)threadIdx.x;
-                v[it] = i < P * 256
-                            ? __hip_atomic_load(all + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                            : 0u;
-            }
-#pragma unroll
-            for (int it = 0; it < 16; ++it)
-                if (v[it]) atomicAdd(&hist[threadIdx.x & 255], v[it]);
-            __syncthreads();
-            if (threadIdx.x == 0)  // ready for the next call on this scratch
-                __hip_atomic_store(sync + q, tag << 16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            bound = sizeof(QT) == 1 ? sel[0] : ((sel[0] << 8) | 255u);
         }
-        if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, (uint32_t)k, 0u, sel);
-        __syncthreads();
-        bound = sizeof(QT) == 1 ? sel[0] : ((sel[0] << 8) | 255u);
     }
+    if (!first) return;
     if (threadIdx.x == 0) {
         pq_qparams_t prm;
         prm.d_min = s_dmin;
@@ -344,7 +320,7 @@ static int64_t pilot_env(const char *name, int64_t dflt) {
 #define PILOT_BLOCK_MAX 65536
 
 int qadc_pilot_blocks_max(int nq) {
-    static const int64_t cap = pilot_env("QADC_PILOT_BLOCKS", 8);
+    static const int64_t cap = pilot_env("QADC_PILOT_BLOCKS", 32);
     int pmax = 256 / (nq > 0 ? nq : 1);
     pmax = pmax < 1 ? 1 : (pmax > 64 ? 64 : pmax);
     if (nq > 16 && pmax > 4) pmax = 4;  // (32 queries per call: 4 blocks each measured 6 % faster than 8)
@@ -352,9 +328,7 @@ int qadc_pilot_blocks_max(int nq) {
 }
 
 size_t qadc_pilot_scratch_bytes(int nq) {
-    const size_t part = (size_t)(nq > 0 ? nq : 0) * (size_t)qadc_pilot_blocks_max(nq) * 256 * sizeof(uint32_t);
-    const size_t sync = ((size_t)(nq > 0 ? nq : 0) * sizeof(unsigned long long) + 255) & ~(size_t)255;
-    return part + sync;
+    return (size_t)(nq > 0 ? nq : 0) * QADC_REC_BINS * QADC_REC_SLOTS * sizeof(uint16_t);
 }
 
 // The pilot of a call: how many codes, split over how many blocks per query.  With scratch
@@ -384,15 +358,6 @@ PilotPlan qadc_pilot_plan(int nq, int64_t n, int t_eff, int R, bool have_scratch
     return pp;
 }
 
-// Tag of a scratch area: its address mixed with a per-process value, 48 bits, never zero.
-static unsigned long long scratch_tag(const void *scratch) {
-    static const unsigned long long salt =
-        (((unsigned long long)time(nullptr) << 24) ^ ((unsigned long long)getpid() << 4)) * 0x9E3779B97F4A7C15ull;
-    unsigned long long t = (((unsigned long long)(uintptr_t)scratch >> 8) * 0xD6E8FEB86659FD93ull) ^ salt;
-    t = (t >> 16) & 0xffffffffffffull;
-    return t ? t : 1ull;
-}
-
 static size_t quantize_lds(const DevLayout &h, int t_eff, size_t esz) {
     const size_t nord = (size_t)((t_eff > h.d ? t_eff : h.d) > 0 ? (t_eff > h.d ? t_eff : h.d) : 1);
     return (((size_t)h.T * 4 + nord * 4 + PQ_MAX_M * 4 + (size_t)h.T * 3 + 15) & ~(size_t)15) +
@@ -403,16 +368,14 @@ template <int KIND, typename QT>
 static int launch_quantize(const pq_index *idx, const float *queries, const float *tables_in,
                            float *tables_out, int nq, const uint8_t *codes, int t_eff, int k,
                            const PilotPlan &pp, void *qtables, pq_qparams_t *qparams, char *gtab_out,
-                           size_t gtab_stride, uint32_t *partial, unsigned long long *sync,
-                           hipStream_t s) {
+                           size_t gtab_stride, char *hdr_out, uint16_t *bound_rec, hipStream_t s) {
     const size_t lds = quantize_lds(idx->h, t_eff, sizeof(QT));
     if (lds > 48 * 1024)
         QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_quantize<KIND, QT>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL((k_quantize<KIND, QT>), dim3((unsigned)nq * (unsigned)pp.P), dim3(1024), lds, s,
                        idx->dev, idx->edesc, idx->codebooks, queries, tables_in, tables_out, codes, t_eff, k,
-                       pp.pilot, pp.slice, pp.P, qtables, qparams, gtab_out, gtab_stride, partial,
-                       sync, pp.P > 1 ? scratch_tag(partial) : 0ull);
+                       pp.pilot, pp.slice, pp.P, qtables, qparams, gtab_out, gtab_stride, hdr_out, bound_rec);
     QADC_LAUNCH_CHECK("k_quantize");
     return PQ_OK;
 }
@@ -423,21 +386,17 @@ static int launch_quantize(const pq_index *idx, const float *queries, const floa
 int qadc_quantize_launch(const pq_index *idx, const float *queries, const float *tables_in,
                          float *tables_out, int nq, const uint8_t *codes, int64_t n, int t, int R,
                          void *qtables, pq_qparams_t *qparams, char *gtab_out, size_t gtab_stride,
-                         char *scratch, int *pilot_used, hipStream_t s) {
+                         char *hdr_out, char *scratch, PilotPlan *plan_used, hipStream_t s) {
     const int64_t want = t > 4 * (int64_t)R ? t : 4 * (int64_t)R;
     const int t_eff = (int)(n < want ? n : want);
     const int k = R < t_eff ? R : t_eff;
     const PilotPlan pp = qadc_pilot_plan(nq, n, t_eff, R, scratch != nullptr);
-    if (pilot_used) *pilot_used = pp.pilot;
-    uint32_t *partial = (uint32_t *)scratch;
-    unsigned long long *sync = nullptr;
-    if (scratch)
-        sync = (unsigned long long *)(scratch + (size_t)nq * (size_t)qadc_pilot_blocks_max(nq) * 256 *
-                                                    sizeof(uint32_t));
+    if (plan_used) *plan_used = pp;
+    uint16_t *bound_rec = (uint16_t *)scratch;
     const bool u8 = idx->h.acc_bits == 8;
 #define QADC_GO(KIND, QT)                                                                       \
     return launch_quantize<KIND, QT>(idx, queries, tables_in, tables_out, nq, codes, t_eff, k, \
-                                     pp, qtables, qparams, gtab_out, gtab_stride, partial, sync, s)
+                                     pp, qtables, qparams, gtab_out, gtab_stride, hdr_out, bound_rec, s)
     switch (idx->h.kind) {
         case SCAN_NIB8:
             if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);
@@ -481,5 +440,5 @@ extern "C" int pq_quantize_tables(const pq_index_t *idx, const float *tables, in
         return PQ_EINVAL;
     }
     return qadc_quantize_launch(idx, nullptr, tables, nullptr, nq, codes, n, t, R, qtables, qparams,
-                                nullptr, 0, nullptr, nullptr, (hipStream_t)stream);
+                                nullptr, 0, nullptr, nullptr, nullptr, (hipStream_t)stream);
 }

@@ -1,18 +1,16 @@
 // pq_adc_scan_topk: scan of packed codes with quantized tables (eq. (2),
 // Section 3.4 saturating sums, Section 3.5) and exact top-R by (key, id).
 //
-// Two kernels per call, no atomics on global memory, no state to initialise:
-//   k_scan   G blocks per query stream the codes once.  A code is kept when its
-//            key is <= qparams.key_bound (an upper bound on the R-th best key, so
-//            nothing that can be a result is dropped) and appended to the block's
-//            private slot array; the block finally stores how many it saw.
-//   k_final  one block per query gathers the kept candidates, finds the R-th
-//            key by histogram, ranks the few candidates up to it by (key, id) and
-//            writes the R best.  If a slot array overflowed (huge tie classes, or
-//            a caller that supplied no bound) it runs an exact two-pass selection
-//            over all codes instead.
-// The result is defined as a sort by (key, id), so it does not depend on the
-// order in which blocks run.
+//   k_scan   G blocks per query stream the codes once.  A code is kept when its key is <=
+//            the query's bound (an upper bound on the R-th best key, so nothing that can be
+//            a result is dropped) and appended to the query's candidate list in the
+//            workspace (one atomic add per wave that holds candidates).
+//   k_final  one block per query reads the list, finds the R-th key by histogram, ranks the
+//            few candidates up to it by (key, id) and writes the R best.  If the list
+//            overflowed (huge tie classes, or a caller that supplied no bound) it runs an
+//            exact two-pass selection over all codes instead.
+// The result is defined as a sort by (key, id), so it does not depend on the order in which
+// blocks run or candidates arrive.
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
@@ -47,6 +45,7 @@ k_prepare(const DevLayout *__restrict__ L, const void *__restrict__ qtables, cha
     build_gtab<KIND, QT>(L, qs, gtab);
     QT *dst = (QT *)(ws + q * per_query + gtab_off);
     for (int e = threadIdx.x; e < L->gtab_len; e += blockDim.x) dst[e] = gtab[e];
+    scan_hdr_clear((ScanHdr *)(ws + q * per_query));  // empty candidate lists for the scan that follows
 }
 
 // Copy prepared group tables (a multiple of 16 bytes is allocated for them) into LDS.
@@ -57,32 +56,213 @@ __device__ __forceinline__ void load_gtab(const char *__restrict__ src, int gtab
     __syncthreads();
 }
 
+// -------------------------------------------------------------- selection ---
+struct FinalOut {
+    int32_t *ids;
+    uint16_t *keys;
+    float *dist;
+};
+
+// Rank the na candidates of S.A by (key, id) and write the first R, padding the rest.  The
+// candidates are first grouped by key bin (key >> shift, at most 256 bins) with a counting
+// sort of their indices; a candidate's rank is the number of candidates in lower bins plus
+// the number of smaller ones within its bin.  Block of NT threads.
+template <int NT, int ACAP>
+__device__ inline void rank_and_write(SelectLds<NT, ACAP> &S, int na, int R, const pq_qparams_t &prm,
+                                      uint32_t qmax, const FinalOut &o, int shift) {
+    const float fdelta = (float)prm.delta, fdmin = (float)prm.d_min;
+    const uint64_t *A = S.A;
+    if (na <= 2 * NT) {
+        // few candidates (the usual case): every candidate counts the smaller ones; all lanes
+        // read the same entry at a time
+        for (int i = threadIdx.x; i < na; i += NT) {
+            const uint64_t mine = A[i];
+            int r = 0;
+            for (int j = 0; j < na; ++j) r += (A[j] < mine) ? 1 : 0;
+            if (r < R) {
+                const uint32_t key = (uint32_t)(mine >> 32);
+                o.ids[r] = (int32_t)(uint32_t)mine;
+                o.keys[r] = (uint16_t)key;
+                o.dist[r] = fmaf((float)key, fdelta, fdmin);
+            }
+        }
+    } else {
+        uint32_t *cnt = &S.whist[0][0], *start = cnt + 256, *fill = cnt + 512;  // (NT >= 256: 1024 words there)
+        for (int i = threadIdx.x; i < 768; i += NT) cnt[i] = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < na; i += NT) atomicAdd(&cnt[((uint32_t)(A[i] >> 32) >> shift) & 255u], 1u);
+        __syncthreads();
+        if (threadIdx.x < QADC_WAVE) {  // exclusive prefix of the 256 counts, four bins per lane
+            const int lane = threadIdx.x;
+            uint32_t c[4], sum = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                c[k] = cnt[4 * lane + k];
+                sum += c[k];
+            }
+            uint32_t run = qadc_wave_incl_scan(sum) - sum;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                start[4 * lane + k] = run;
+                run += c[k];
+            }
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < na; i += NT) {
+            const uint32_t b = ((uint32_t)(A[i] >> 32) >> shift) & 255u;
+            S.order[start[b] + atomicAdd(&fill[b], 1u)] = (uint16_t)i;
+        }
+        __syncthreads();
+        for (int p = threadIdx.x; p < na; p += NT) {
+            const uint64_t mine = A[S.order[p]];
+            const uint32_t b = ((uint32_t)(mine >> 32) >> shift) & 255u;
+            const int gs = (int)start[b], ge = gs + (int)cnt[b];
+            int r = gs;
+            if (gs < R) {  // (a whole bin at or beyond rank R cannot hold a result)
+                for (int j = gs; j < ge; ++j) r += (A[S.order[j]] < mine) ? 1 : 0;
+                if (r < R) {
+                    const uint32_t key = (uint32_t)(mine >> 32);
+                    o.ids[r] = (int32_t)(uint32_t)mine;
+                    o.keys[r] = (uint16_t)key;
+                    o.dist[r] = fmaf((float)key, fdelta, fdmin);
+                }
+            }
+        }
+    }
+    for (int r = (na < R ? na : R) + threadIdx.x; r < R; r += NT) {
+        o.ids[r] = -1;
+        o.keys[r] = (uint16_t)qmax;
+        o.dist[r] = INFINITY;
+    }
+}
+
+// Exact selection over all n codes by one block: histogram of key bins (two
+// levels for 16-bit keys) gives the R-th key k*; a second pass in id order keeps
+// every code below k* and the first (R - count_below) codes equal to k*.  A receives
+// min(R, n) entries; their number is left in sh[2].
+template <int KIND, typename QT>
+__device__ inline void exact_select(const DevLayout *L, const QT *gtab,
+                                    const uint8_t *__restrict__ codes, int64_t n, int R,
+                                    uint64_t *A, uint32_t *hist, uint32_t *sh) {
+    const int Rn = (int64_t)R < n ? R : (int)n;
+    const bool wide = L->acc_bits != 8;
+    uint32_t kstar = 0, below = 0;
+    for (int level = 0; level < (wide ? 2 : 1); ++level) {
+        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+        __syncthreads();
+        for (int64_t id = threadIdx.x; id < n; id += blockDim.x) {
+            uint32_t key = key_at<KIND, QT>(L, gtab, codes, id);
+            if (!wide)
+                atomicAdd(&hist[key], 1u);
+            else if (level == 0)
+                atomicAdd(&hist[key >> 8], 1u);
+            else if ((key >> 8) == kstar)
+                atomicAdd(&hist[key & 255u], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, (uint32_t)Rn, below, sh);
+        __syncthreads();
+        kstar = (level == 0) ? sh[0] : ((kstar << 8) | sh[0]);
+        below = sh[1];
+        __syncthreads();
+    }
+    const uint32_t need = (uint32_t)Rn - below;  // ties to keep, lowest ids first
+    if (threadIdx.x == 0) sh[2] = 0;             // entries written to A
+    uint32_t tie_base = 0;
+    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
+    const int nwaves = blockDim.x / QADC_WAVE;
+    uint32_t *wtot = sh + 8;  // nwaves words
+    __syncthreads();
+    for (int64_t base = 0; base < n; base += blockDim.x) {
+        const int64_t id = base + threadIdx.x;
+        const bool valid = id < n;
+        const uint32_t key = valid ? key_at<KIND, QT>(L, gtab, codes, id) : 0xffffffffu;
+        const bool lt = valid && key < kstar, eq = valid && key == kstar;
+        const uint64_t m = __ballot(eq);
+        if (lane == 0) wtot[wave] = (uint32_t)__popcll(m);
+        __syncthreads();
+        uint32_t woff = 0, tot = 0;
+        for (int w = 0; w < nwaves; ++w) {
+            uint32_t c = wtot[w];
+            woff += (w < wave) ? c : 0;
+            tot += c;
+        }
+        const uint32_t tie_rank = tie_base + woff + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+        if (lt || (eq && tie_rank < need)) {
+            uint32_t pos = atomicAdd(&sh[2], 1u);
+            A[pos] = ((uint64_t)key << 32) | (uint64_t)(uint32_t)id;
+        }
+        tie_base += tot;
+        __syncthreads();
+    }
+}
+
+// The selection of one query by a block of NT threads: from the candidate list, or from the
+// codes when the list overflowed.  gtab: the query's group tables in LDS if the caller has
+// them there already, else null (they are then staged from gsrc on the slow path only, into
+// gtab_room).  COHERENT: see select_from_list.
+template <int KIND, typename QT, int NT, int ACAP, bool COHERENT>
+__device__ inline void select_query(const DevLayout *L, const char *__restrict__ wq, size_t cand_off,
+                                    size_t gtab_off, uint32_t cap, const uint8_t *__restrict__ codes,
+                                    int64_t n, int R, const pq_qparams_t &prm, const FinalOut &o,
+                                    SelectLds<NT, ACAP> &S, const QT *gtab, QT *gtab_room) {
+    const int shift = L->acc_bits == 8 ? 0 : 8;
+    const uint32_t qmax = (uint32_t)L->qmax;
+    int na = select_from_lists<NT, ACAP, COHERENT>((const ScanHdr *)wq, (const uint64_t *)(wq + cand_off), cap,
+                                                   R, shift, S);
+    if (na < 0) {
+        if (!gtab) {
+            const int n16 = (L->gtab_len * (int)sizeof(QT) + 15) >> 4;
+            for (int i = threadIdx.x; i < n16; i += NT) ((uint4 *)gtab_room)[i] = ((const uint4 *)(wq + gtab_off))[i];
+            __syncthreads();
+            gtab = gtab_room;
+        }
+        exact_select<KIND, QT>(L, gtab, codes, n, R, S.A, S.hist, S.sh);
+        __syncthreads();
+        na = (int)S.sh[2];
+        __syncthreads();
+    }
+    rank_and_write<NT, ACAP>(S, na, R, prm, qmax, o, shift);
+}
+
 // ---------------------------------------------------------------- k_scan ---
 // NG > 0: the layout has NG groups (per 64-bit half for 16-byte irregular codes), none
 // crossing a dword boundary of the code; NG == 0: group descriptors are read from the layout.
 // MODE says where the groups lie: 0 = decided per group at run time, 1 = the first NG/2 in the
 // low dword, 2 = all but the last in the low dword.
+// (Eight waves per SIMD, i.e. at most 64 vector registers: the streaming loop needs a fraction
+// of that, and the selection at the end, which runs in one block per query, must not cost the
+// loop its occupancy.)
 template <int KIND, typename QT, int NG, int MODE>
-__global__ void __launch_bounds__(SCAN_THREADS)
+__global__ void __launch_bounds__(SCAN_THREADS) __attribute__((amdgpu_waves_per_eu(8, 8)))
 k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
        const pq_qparams_t *__restrict__ qparams, const uint8_t *__restrict__ codes, int64_t n,
-       char *__restrict__ ws, size_t per_query, size_t slots_off, size_t gtab_off, int cap_b,
-       int gtab_len, uint32_t qmax, GroupDesc gd) {
+       char *__restrict__ ws, size_t per_query, size_t cand_off, size_t gtab_off, uint32_t cap,
+       int gtab_len, uint32_t qmax, GroupDesc gd, int fuse, int R, int32_t *__restrict__ out_ids,
+       uint16_t *__restrict__ out_keys, float *__restrict__ out_dist,
+       const uint16_t *__restrict__ bound_rec, int recP, uint32_t reck) {
     extern __shared__ __align__(16) unsigned char smem[];
     QT *gtab = (QT *)smem;
-    __shared__ uint32_t s_count;
+    __shared__ uint32_t s_last, s_thr;
     const size_t q = blockIdx.y;
     const int b = blockIdx.x, G = gridDim.x;
     char *wq = ws + q * per_query;
-    uint32_t *counts = (uint32_t *)wq;
-    uint64_t *slot = (uint64_t *)(wq + slots_off) + (size_t)b * cap_b;
+    const int sl = b % QADC_NSUB;  // this block's candidate list
+    uint32_t *count = &((ScanHdr *)wq)->count[sl][0];
+    uint64_t *cand = (uint64_t *)(wq + cand_off) + (size_t)sl * cap;
     const char *gsrc = wq + gtab_off;
     // Sums are compared unsaturated.  A sum above q_max is the key q_max (Section 3.4), an
     // ordinary largest key: with a bound below q_max such a code never passes, and with the
     // bound at q_max every code does (the keys are saturated where they are stored).
+    // The bound: from the query's parameters, or (bound_rec) added up by the first wave from the
+    // records the quantizer's pilot blocks left; it reaches the other waves through LDS behind
+    // the barrier that ends the staging of the tables.
     uint32_t thr = qparams[q].key_bound;
-    thr = thr >= qmax ? 0xffffffffu : thr;
-    if (threadIdx.x == 0) s_count = 0;
+    if (bound_rec && threadIdx.x < QADC_WAVE) {
+        const uint32_t t = scan_bound_from_records(bound_rec + q * (QADC_REC_BINS * QADC_REC_SLOTS), recP, reck,
+                                                   sizeof(QT) == 1 ? 0 : 8, qmax);
+        if (threadIdx.x == 0) s_thr = t;
+    }
     constexpr bool g32 = NG > 0;
     constexpr int NLO = MODE == 1 ? NG / 2 : (MODE == 2 ? NG - 1 : -1);
 
@@ -105,6 +285,8 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         };
         if (tile < ntiles) load_tile(tile);  // in flight while the tables are staged
         load_gtab<QT>(gsrc, gtab_len, gtab);
+        if (bound_rec) thr = s_thr;
+        thr = thr >= qmax ? 0xffffffffu : thr;
         while (tile < ntiles) {
             uint32_t s[2 * U];
             bool pass[2 * U], any = false;
@@ -133,7 +315,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                     id[u] = (uint32_t)(2 * c + (u & 1));
                     s[u] = s[u] > qmax ? qmax : s[u];
                 }
-                slot_append_multi<2 * U>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
+                cand_append_multi<2 * U>(pass, s, id, cand, cap, count);
             }
             tile += G;
             if (tile < ntiles) load_tile(tile);
@@ -147,8 +329,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                     key = KIND == SCAN_NIB8 ? sum8(gtab, w.x, w.y)
                                             : sum_groups64(L, gtab, ((uint64_t)w.y << 32) | w.x);
                 }
-                slot_append(me && key <= thr, key > qmax ? qmax : key, (uint32_t)(n - 1), slot,
-                            (uint32_t)cap_b, &s_count);
+                cand_append(me && key <= thr, key > qmax ? qmax : key, (uint32_t)(n - 1), cand, cap, count);
             }
         }
     } else if (KIND == SCAN_C5) {
@@ -172,6 +353,8 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         };
         if (tile < ntiles) load_tile(tile);  // the first tile is in flight while the tables are staged
         load_gtab<QT>(gsrc, gtab_len, gtab);
+        if (bound_rec) thr = s_thr;
+        thr = thr >= qmax ? 0xffffffffu : thr;
         while (tile < ntiles) {
             uint32_t s[4 * U];
             bool pass[4 * U], any = false;
@@ -204,7 +387,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                     id[u] = 4u * c + (u & 3);
                     s[u] = s[u] > qmax ? qmax : s[u];
                 }
-                slot_append_multi<4 * U>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
+                cand_append_multi<4 * U>(pass, s, id, cand, cap, count);
             }
             tile += G;
             if (tile < ntiles) load_tile(tile);
@@ -213,7 +396,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
             const int64_t id = (nfull << 2) + threadIdx.x;
             const bool me = id < n;
             uint32_t key = me ? key_at<KIND, QT>(L, gtab, codes, id) : 0u;
-            slot_append(me && key <= thr, key, (uint32_t)id, slot, (uint32_t)cap_b, &s_count);
+            cand_append(me && key <= thr, key, (uint32_t)id, cand, cap, count);
         }
     } else {
         // one 16-byte code (or one code of the byte-wise kind) per thread and chunk, four chunks
@@ -234,6 +417,8 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         };
         if (tile < ntiles) load_tile(tile);  // the first tile is in flight while the tables are staged
         load_gtab<QT>(gsrc, gtab_len, gtab);
+        if (bound_rec) thr = s_thr;
+        thr = thr >= qmax ? 0xffffffffu : thr;
         while (tile < ntiles) {
             uint32_t s[4];
             bool pass[4], any = false;
@@ -257,14 +442,43 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                     id[u] = tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
                     s[u] = s[u] > qmax ? qmax : s[u];
                 }
-                slot_append_multi<4>(pass, s, id, slot, (uint32_t)cap_b, &s_count);
+                cand_append_multi<4>(pass, s, id, cand, cap, count);
             }
             tile += G;
             if (tile < ntiles) load_tile(tile);
         }
     }
+    if (!fuse) return;
+    // Selection by the block that finishes last.  Candidates were stored and counted with
+    // device-scope operations; every thread waits until its own have completed, then the block
+    // counts itself in, and the block that completes the count reads all lists with
+    // device-scope loads and turns them into the result.  (No cache write-back or invalidation
+    // is involved: a release fence in each of the 2048 blocks made the kernel fifteen times
+    // slower.)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (threadIdx.x == 0) counts[b] = s_count;  // uncapped: > cap_b tells k_final about the overflow
+    if (threadIdx.x == 0) {
+        // two levels, because atomic adds to one address are served one by one (about 10 ns
+        // each): first among the blocks of this block's list, then among the lists
+        ScanHdr *hd = (ScanHdr *)wq;
+        const uint32_t in_list = (uint32_t)(G - sl + QADC_NSUB - 1) / QADC_NSUB;
+        const uint32_t lists = (uint32_t)(G < QADC_NSUB ? G : QADC_NSUB);
+        uint32_t last = 0;
+        if (__hip_atomic_fetch_add(&hd->count[sl][1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u == in_list)
+            last = __hip_atomic_fetch_add(&hd->arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u == lists;
+        s_last = last;
+    }
+    __syncthreads();
+    if (s_last == 0) return;
+    typedef SelectLds<SCAN_THREADS, FUSED_CAP> Lds;
+    Lds &S = *(Lds *)(smem + (((size_t)gtab_len * sizeof(QT) + 15) & ~(size_t)15));
+    FinalOut o;
+    o.ids = out_ids + q * R;
+    o.keys = out_keys + q * R;
+    o.dist = out_dist + q * R;
+    const pq_qparams_t prm = qparams[q];
+    select_query<KIND, QT, SCAN_THREADS, FUSED_CAP, true>(L, wq, cand_off, gtab_off, cap, codes, n, R, prm, o, S,
+                                                          (const QT *)gtab, (QT *)nullptr);
 }
 
 // -------------------------------------------------------------- k_scan_mq ---
@@ -302,24 +516,31 @@ __device__ __forceinline__ uint2 mq_entry(int g, uint32_t w, uint32_t three) {
 template <int NG>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__restrict__ codes,
-          int64_t n, char *__restrict__ ws, size_t per_query, size_t slots_off, size_t gtab_off,
-          int cap_b, uint32_t qmax) {
+          int64_t n, char *__restrict__ ws, size_t per_query, size_t cand_off, size_t gtab_off,
+          uint32_t cap, uint32_t qmax, const uint16_t *__restrict__ bound_rec, int recP, uint32_t reck) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint2 *tab = (uint2 *)smem;  // [NG][256], at LDS offset 0: entry offsets go into the reads as they are
-    uint32_t *s_count = (uint32_t *)(smem + NG * 256 * 8);  // [MQ]
+    uint32_t *s_thr = (uint32_t *)(smem + NG * 256 * 8);  // [MQ] bounds added up from the pilot's records
+    if (bound_rec) {  // wave j adds up the records of query q0 + j (SCAN_THREADS / 64 == MQ)
+        const int j = threadIdx.x / QADC_WAVE;
+        const size_t q = (blockIdx.y * MQ + j < nq) ? blockIdx.y * MQ + j : blockIdx.y * MQ;
+        const uint32_t t = scan_bound_from_records(bound_rec + q * (QADC_REC_BINS * QADC_REC_SLOTS), recP, reck, 0, qmax);
+        if (threadIdx.x % QADC_WAVE == 0) s_thr[j] = t;
+    }
     const int q0 = blockIdx.y * MQ;
     const int b = blockIdx.x, G = gridDim.x;
     uint32_t thr[MQ];
-    uint64_t *slot[MQ];
+    uint64_t *cand[MQ];
+    uint32_t *count[MQ];
 #pragma unroll
     for (int j = 0; j < MQ; ++j) {
         const bool have = q0 + j < nq;
         const size_t q = have ? q0 + j : q0;
         uint32_t t = qparams[q].key_bound;
         thr[j] = t >= qmax ? 0xffffffffu : t;  // sums are compared unsaturated (see k_scan)
-        slot[j] = (uint64_t *)(ws + q * per_query + slots_off) + (size_t)b * cap_b;
+        cand[j] = (uint64_t *)(ws + q * per_query + cand_off) + (size_t)(b % QADC_NSUB) * cap;
+        count[j] = &((ScanHdr *)(ws + q * per_query))->count[b % QADC_NSUB][0];
     }
-    if (threadIdx.x < MQ) s_count[threadIdx.x] = 0;
     // interleave the four prepared tables: thread handles 4 consecutive entries at a time
     for (int w = threadIdx.x; w < NG * 64; w += SCAN_THREADS) {
         uint32_t v[MQ];
@@ -337,6 +558,10 @@ k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__res
         }
     }
     __syncthreads();
+    if (bound_rec) {
+#pragma unroll
+        for (int j = 0; j < MQ; ++j) thr[j] = s_thr[j] >= qmax ? 0xffffffffu : s_thr[j];
+    }
 
     constexpr int CPC = NG == 8 ? 2 : 1;  // codes per 16-byte chunk
     constexpr int U = 2;                  // chunks per thread and tile
@@ -388,7 +613,7 @@ k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__res
             if (__ballot(any) != 0) {
 #pragma unroll
                 for (int i = 0; i < U * CPC; ++i) sum[j][i] = sum[j][i] > qmax ? qmax : sum[j][i];
-                slot_append_multi<U * CPC>(pass, sum[j], id, slot[j], (uint32_t)cap_b, &s_count[j]);
+                cand_append_multi<U * CPC>(pass, sum[j], id, cand[j], cap, count[j]);
             }
         }
     }
@@ -408,12 +633,9 @@ k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__res
         const uint32_t sj[MQ] = {lo & 0xffffu, lo >> 16, hi & 0xffffu, hi >> 16};
 #pragma unroll
         for (int j = 0; j < MQ; ++j)
-            slot_append(me && (q0 + j < nq) && sj[j] <= thr[j], sj[j] > qmax ? qmax : sj[j],
-                        (uint32_t)(n - 1), slot[j], (uint32_t)cap_b, &s_count[j]);
+            cand_append(me && (q0 + j < nq) && sj[j] <= thr[j], sj[j] > qmax ? qmax : sj[j],
+                        (uint32_t)(n - 1), cand[j], cap, count[j]);
     }
-    __syncthreads();
-    if (threadIdx.x < MQ && q0 + (int)threadIdx.x < nq)
-        ((uint32_t *)(ws + (size_t)(q0 + threadIdx.x) * per_query))[b] = s_count[threadIdx.x];
 }
 
 // ------------------------------------------------------------- k_scan_mqg ---
@@ -462,27 +684,36 @@ __device__ __forceinline__ void mq_add_groups(const GroupDesc &d, const uint2 *t
 template <int KIND, typename QT, int NG, int MODE>
 __global__ void __launch_bounds__(SCAN_THREADS)
 k_scan_mqg(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__restrict__ codes,
-           int64_t n, char *__restrict__ ws, size_t per_query, size_t slots_off, size_t gtab_off,
-           int cap_b, int gtab_len, uint32_t qmax, GroupDesc gd) {
+           int64_t n, char *__restrict__ ws, size_t per_query, size_t cand_off, size_t gtab_off,
+           uint32_t cap, int gtab_len, uint32_t qmax, GroupDesc gd, const uint16_t *__restrict__ bound_rec,
+           int recP, uint32_t reck) {
     extern __shared__ __align__(16) unsigned char smem[];
     uint2 *tab = (uint2 *)smem;  // [gtab_len]
-    __shared__ uint32_t s_count[MQ];
+    __shared__ uint32_t s_thr[MQ];
+    if (bound_rec) {  // wave j adds up the records of query q0 + j (SCAN_THREADS / 64 == MQ)
+        const int j = threadIdx.x / QADC_WAVE;
+        const size_t q = (blockIdx.y * MQ + j < nq) ? blockIdx.y * MQ + j : blockIdx.y * MQ;
+        const uint32_t t = scan_bound_from_records(bound_rec + q * (QADC_REC_BINS * QADC_REC_SLOTS), recP, reck,
+                                                   sizeof(QT) == 1 ? 0 : 8, qmax);
+        if (threadIdx.x % QADC_WAVE == 0) s_thr[j] = t;
+    }
     constexpr int NLO = MODE == 1 ? NG / 2 : (MODE == 2 ? NG - 1 : -1);
     constexpr int NC = KIND == SCAN_W128 ? 2 : 4;  // codes per thread and tile
     const int q0 = blockIdx.y * MQ;
     const int b = blockIdx.x, G = gridDim.x;
     uint32_t thr[MQ];
-    uint64_t *slot[MQ];
+    uint64_t *cand[MQ];
+    uint32_t *count[MQ];
     const QT *src[MQ];
 #pragma unroll
     for (int j = 0; j < MQ; ++j) {
         const size_t q = (q0 + j < nq) ? q0 + j : q0;
         uint32_t t = qparams[q].key_bound;
         thr[j] = t > qmax ? qmax : t;
-        slot[j] = (uint64_t *)(ws + q * per_query + slots_off) + (size_t)b * cap_b;
+        cand[j] = (uint64_t *)(ws + q * per_query + cand_off) + (size_t)(b % QADC_NSUB) * cap;
+        count[j] = &((ScanHdr *)(ws + q * per_query))->count[b % QADC_NSUB][0];
         src[j] = (const QT *)(ws + q * per_query + gtab_off);
     }
-    if (threadIdx.x < MQ) s_count[threadIdx.x] = 0;
     for (int e = threadIdx.x; e < gtab_len; e += SCAN_THREADS) {
         uint2 v;
         v.x = (uint32_t)src[0][e] | ((uint32_t)src[1][e] << 16);
@@ -490,6 +721,10 @@ k_scan_mqg(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__re
         tab[e] = v;
     }
     __syncthreads();
+    if (bound_rec) {
+#pragma unroll
+        for (int j = 0; j < MQ; ++j) thr[j] = s_thr[j];
+    }
 
     // tiles of NC * SCAN_THREADS codes; thread t takes the codes NC*t .. NC*t+NC-1 of a tile
     const int ntiles = (int)((n + NC * SCAN_THREADS - 1) / (NC * SCAN_THREADS));
@@ -561,219 +796,32 @@ k_scan_mqg(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__re
                 any = any || pass[i];
             }
             if (__ballot(any) != 0)
-                slot_append_multi<NC>(pass, key, id, slot[j], (uint32_t)cap_b, &s_count[j]);
+                cand_append_multi<NC>(pass, key, id, cand[j], cap, count[j]);
         }
     }
-    __syncthreads();
-    if (threadIdx.x < MQ && q0 + (int)threadIdx.x < nq)
-        ((uint32_t *)(ws + (size_t)(q0 + threadIdx.x) * per_query))[b] = s_count[threadIdx.x];
 }
 
 // --------------------------------------------------------------- k_final ---
-struct FinalOut {
-    int32_t *ids;
-    uint16_t *keys;
-    float *dist;
-};
-
-// Rank the na candidates of A by (key, id) and write the first R, padding the rest.
-// `rank` is 768 words of LDS, `order` na 16-bit words.  Few candidates: several threads share
-// one candidate, each counting over a part of A.  Many candidates (long result lists): they
-// are first grouped by key bin (key >> shift, at most 256 bins) with a counting sort of their
-// indices, and a candidate is then compared only with the others of its bin.
-__device__ inline void rank_and_write(const uint64_t *A, int na, int R, const pq_qparams_t &prm,
-                                      uint32_t qmax, const FinalOut &o, uint32_t *rank, int shift,
-                                      uint16_t *order) {
-    const float fdelta = (float)prm.delta, fdmin = (float)prm.d_min;
-    if (na <= 512) {
-        // 2^lt threads per candidate, each counting over its share of A
-        int lt = 1;
-        while (lt < 4 && (na << (lt + 1)) <= 1024) ++lt;
-        if ((int)threadIdx.x < na) rank[threadIdx.x] = 0;
-        __syncthreads();
-        const int i = threadIdx.x >> lt, part = threadIdx.x & ((1 << lt) - 1);
-        if (i < na) {
-            const uint64_t mine = A[i];
-            const int per = (na + (1 << lt) - 1) >> lt;
-            const int j1 = (part + 1) * per < na ? (part + 1) * per : na;
-            uint32_t r = 0;
-            for (int j = part * per; j < j1; ++j) r += (A[j] < mine) ? 1u : 0u;
-            if (r) atomicAdd(&rank[i], r);
-        }
-        __syncthreads();
-        if ((int)threadIdx.x < na) {
-            const int r = (int)rank[threadIdx.x];
-            if (r < R) {
-                const uint64_t mine = A[threadIdx.x];
-                const uint32_t key = (uint32_t)(mine >> 32);
-                o.ids[r] = (int32_t)(uint32_t)mine;
-                o.keys[r] = (uint16_t)key;
-                o.dist[r] = fmaf((float)key, fdelta, fdmin);
-            }
-        }
-    } else {
-        uint32_t *cnt = rank, *start = rank + 256, *fill = rank + 512;
-        for (int i = threadIdx.x; i < 768; i += blockDim.x) rank[i] = 0;
-        __syncthreads();
-        for (int i = threadIdx.x; i < na; i += blockDim.x)
-            atomicAdd(&cnt[((uint32_t)(A[i] >> 32) >> shift) & 255u], 1u);
-        __syncthreads();
-        if (threadIdx.x < QADC_WAVE) {  // exclusive prefix of the 256 counts, four bins per lane
-            const int lane = threadIdx.x;
-            uint32_t c[4], sum = 0;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                c[k] = cnt[4 * lane + k];
-                sum += c[k];
-            }
-            uint32_t run = qadc_wave_incl_scan(sum) - sum;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                start[4 * lane + k] = run;
-                run += c[k];
-            }
-        }
-        __syncthreads();
-        for (int i = threadIdx.x; i < na; i += blockDim.x) {
-            const uint32_t b = ((uint32_t)(A[i] >> 32) >> shift) & 255u;
-            order[start[b] + atomicAdd(&fill[b], 1u)] = (uint16_t)i;
-        }
-        __syncthreads();
-        for (int p = threadIdx.x; p < na; p += blockDim.x) {
-            const uint64_t mine = A[order[p]];
-            const uint32_t b = ((uint32_t)(mine >> 32) >> shift) & 255u;
-            const int gs = (int)start[b], ge = gs + (int)cnt[b];
-            int r = gs;
-            for (int j = gs; j < ge; ++j) r += (A[order[j]] < mine) ? 1 : 0;
-            if (r < R) {
-                const uint32_t key = (uint32_t)(mine >> 32);
-                o.ids[r] = (int32_t)(uint32_t)mine;
-                o.keys[r] = (uint16_t)key;
-                o.dist[r] = fmaf((float)key, fdelta, fdmin);
-            }
-        }
-    }
-    for (int r = (na < R ? na : R) + threadIdx.x; r < R; r += blockDim.x) {
-        o.ids[r] = -1;
-        o.keys[r] = (uint16_t)qmax;
-        o.dist[r] = INFINITY;
-    }
-}
-
-// Exact selection over all n codes by one block: histogram of key bins (two
-// levels for 16-bit keys) gives the R-th key k*; a second pass in id order keeps
-// every code below k* and the first (R - count_below) codes equal to k*.
-template <int KIND, typename QT>
-__device__ inline void exact_select(const DevLayout *L, const QT *gtab,
-                                    const uint8_t *__restrict__ codes, int64_t n, int R,
-                                    uint64_t *A, uint32_t *hist, uint32_t *sh) {
-    const int Rn = (int64_t)R < n ? R : (int)n;
-    const bool wide = L->acc_bits != 8;
-    uint32_t kstar = 0, below = 0;
-    for (int level = 0; level < (wide ? 2 : 1); ++level) {
-        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
-        __syncthreads();
-        for (int64_t id = threadIdx.x; id < n; id += blockDim.x) {
-            uint32_t key = key_at<KIND, QT>(L, gtab, codes, id);
-            if (!wide)
-                atomicAdd(&hist[key], 1u);
-            else if (level == 0)
-                atomicAdd(&hist[key >> 8], 1u);
-            else if ((key >> 8) == kstar)
-                atomicAdd(&hist[key & 255u], 1u);
-        }
-        __syncthreads();
-        if (threadIdx.x < QADC_WAVE) qadc_wave_select_bin(hist, (uint32_t)Rn, below, sh);
-        __syncthreads();
-        kstar = (level == 0) ? sh[0] : ((kstar << 8) | sh[0]);
-        below = sh[1];
-        __syncthreads();
-    }
-    const uint32_t need = (uint32_t)Rn - below;  // ties to keep, lowest ids first
-    if (threadIdx.x == 0) sh[2] = 0;             // entries written to A
-    uint32_t tie_base = 0;
-    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
-    const int nwaves = blockDim.x / QADC_WAVE;
-    uint32_t *wtot = sh + 8;  // nwaves words
-    __syncthreads();
-    for (int64_t base = 0; base < n; base += blockDim.x) {
-        const int64_t id = base + threadIdx.x;
-        const bool valid = id < n;
-        const uint32_t key = valid ? key_at<KIND, QT>(L, gtab, codes, id) : 0xffffffffu;
-        const bool lt = valid && key < kstar, eq = valid && key == kstar;
-        const uint64_t m = __ballot(eq);
-        if (lane == 0) wtot[wave] = (uint32_t)__popcll(m);
-        __syncthreads();
-        uint32_t woff = 0, tot = 0;
-        for (int w = 0; w < nwaves; ++w) {
-            uint32_t c = wtot[w];
-            woff += (w < wave) ? c : 0;
-            tot += c;
-        }
-        const uint32_t tie_rank = tie_base + woff + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-        if (lt || (eq && tie_rank < need)) {
-            uint32_t pos = atomicAdd(&sh[2], 1u);
-            A[pos] = ((uint64_t)key << 32) | (uint64_t)(uint32_t)id;
-        }
-        tie_base += tot;
-        __syncthreads();
-    }
-}
-
-template <int KIND, typename QT>
-__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4)))
-k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
-        const pq_qparams_t *__restrict__ qparams, const uint8_t *__restrict__ codes, int64_t n,
-        int R, const char *__restrict__ ws, size_t per_query, size_t slots_off, int cap_b, int G,
-        int logw, int32_t *__restrict__ out_ids, uint16_t *__restrict__ out_keys,
-        float *__restrict__ out_dist) {
+// NT threads per query; ACAP = candidates it can rank in LDS.
+template <int KIND, typename QT, int NT, int ACAP>
+__global__ void __launch_bounds__(NT)
+k_final(const DevLayout *__restrict__ L, const pq_qparams_t *__restrict__ qparams,
+        const uint8_t *__restrict__ codes, int64_t n, int R, char *__restrict__ ws, size_t per_query,
+        size_t cand_off, size_t gtab_off, uint32_t cap, int32_t *__restrict__ out_ids,
+        uint16_t *__restrict__ out_keys, float *__restrict__ out_dist) {
     extern __shared__ __align__(16) unsigned char smem[];
-    uint64_t *A = (uint64_t *)smem;                // FINAL_CAP entries
-    QT *gtab = (QT *)(smem + FINAL_CAP * 8);       // only built on the slow path
-    uint16_t *qs = (uint16_t *)(smem + FINAL_CAP * 8 +
-                                (((size_t)L->gtab_len * sizeof(QT) + 15) & ~(size_t)15));
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t whist[16][256];            // per-wave histograms: candidate keys share few bins
-    __shared__ uint32_t sh[32];
-    __shared__ uint32_t wsum[16];
-    __shared__ uint32_t off[MAX_G + 1];            // exclusive prefix of the per-block counts
+    typedef SelectLds<NT, ACAP> Lds;
+    Lds &S = *(Lds *)smem;
+    QT *gtab_room = (QT *)(smem + sizeof(Lds));  // only filled on the slow path
     const size_t q = blockIdx.x;
-    const char *wq = ws + q * per_query;
-    const uint32_t *counts = (const uint32_t *)wq;
-    const uint64_t *slots = (const uint64_t *)(wq + slots_off);
-    const int shift = L->acc_bits == 8 ? 0 : 8;
-    const uint32_t qmax = (uint32_t)L->qmax;
+    char *wq = ws + q * per_query;
     FinalOut o;
     o.ids = out_ids + q * R;
     o.keys = out_keys + q * R;
     o.dist = out_dist + q * R;
     const pq_qparams_t prm = qparams[q];
-
-    FinalShared S;
-    S.hist = hist;
-    S.whist = whist;
-    S.sh = sh;
-    S.wsum = wsum;
-    S.off = off;
-    int na = 0;
-    auto binf = [shift](uint64_t c) { return ((uint32_t)(c >> 32)) >> shift; };
-    const int per_batch = (G + (1024 >> logw) - 1) / (1024 >> logw);  // lists per thread
-    bool slow;
-    if (per_batch <= 8)
-        slow = gather_select_rows<8>(counts, slots, G, cap_b, R, logw, binf, A, S, na);
-    else if (per_batch <= 16)
-        slow = gather_select_rows<16>(counts, slots, G, cap_b, R, logw, binf, A, S, na);
-    else
-        slow = gather_select_rows<32>(counts, slots, G, cap_b, R, logw, binf, A, S, na);
-    if (slow) {
-        stage_qtable<QT>((const QT *)qtables + q * L->T, L->T, qs);
-        build_gtab<KIND, QT>(L, qs, gtab);
-        exact_select<KIND, QT>(L, gtab, codes, n, R, A, hist, sh);
-        __syncthreads();
-        na = (int)sh[2];
-    }
-    __syncthreads();  // the selection is done with `off`: its memory now holds the sort order
-    rank_and_write(A, na, R, prm, qmax, o, &whist[0][0], shift, (uint16_t *)off);
+    select_query<KIND, QT, NT, ACAP, false>(L, wq, cand_off, gtab_off, cap, codes, n, R, prm, o, S,
+                                            (const QT *)nullptr, gtab_room);
 }
 
 // ------------------------------------------------------------------ host ---
@@ -781,7 +829,8 @@ k_final(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
 template <int KIND, typename QT>
 static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparams_t *qparams, int nq,
                        const uint8_t *codes, int64_t n, int R, int32_t *out_ids, uint16_t *out_keys,
-                       float *out_dist, char *ws, const ScanPlan &p, hipStream_t s, int what) {
+                       float *out_dist, char *ws, const ScanPlan &p, hipStream_t s, int what,
+                       const uint16_t *bound_rec, int recP, uint32_t reck) {
     const DevLayout &h = idx->h;
     const size_t gtab_bytes = ((size_t)h.gtab_len * sizeof(QT) + 15) & ~(size_t)15;
     if (what & 4) {
@@ -789,8 +838,9 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
                            idx->dev, qtables, ws, p.per_query, p.gtab_off);
         QADC_LAUNCH_CHECK("k_prepare");
     }
-    static const bool no_mq_nib = getenv("QADC_NO_MQ") != nullptr;
-    if ((what & 1) && sizeof(QT) == 1 && nq >= 2 && (KIND == SCAN_NIB8 || KIND == SCAN_NIB16) && !no_mq_nib) {
+    static const bool no_mq = getenv("QADC_NO_MQ") != nullptr;
+    bool fused = false;  // the scan kernel's last block does the selection
+    if ((what & 1) && sizeof(QT) == 1 && nq >= 2 && (KIND == SCAN_NIB8 || KIND == SCAN_NIB16) && !no_mq) {
         // several queries: four of them share every pass over the codes
         const int groups = (nq + MQ - 1) / MQ;
         // k_scan_mq addresses its tables from LDS address 0: it must have no static LDS
@@ -807,12 +857,12 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
         }
         if (KIND == SCAN_NIB8)
             hipLaunchKernelGGL((k_scan_mq<8>), dim3(p.G, groups), dim3(SCAN_THREADS), 8 * 256 * 8 + 16, s,
-                               qparams, nq, codes, n, ws, p.per_query, p.slots_off, p.gtab_off,
-                               p.cap_b, (uint32_t)h.qmax);
+                               qparams, nq, codes, n, ws, p.per_query, p.cand_off, p.gtab_off,
+                               p.cap, (uint32_t)h.qmax, bound_rec, recP, reck);
         else
             hipLaunchKernelGGL((k_scan_mq<16>), dim3(p.G, groups), dim3(SCAN_THREADS), 16 * 256 * 8 + 16, s,
-                               qparams, nq, codes, n, ws, p.per_query, p.slots_off, p.gtab_off,
-                               p.cap_b, (uint32_t)h.qmax);
+                               qparams, nq, codes, n, ws, p.per_query, p.cand_off, p.gtab_off,
+                               p.cap, (uint32_t)h.qmax, bound_rec, recP, reck);
         QADC_LAUNCH_CHECK("k_scan_mq");
     } else if (what & 1) {
         GroupDesc gd;
@@ -825,6 +875,7 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
         }
         if (KIND == SCAN_W128)  // NG = groups per 64-bit half
             for (int g = 0; g < h.ng / 2; ++g) gd.base2[g] = h.gbase[g + h.ng / 2];
+        constexpr bool desc_kind = KIND == SCAN_W64 || KIND == SCAN_C5 || KIND == SCAN_W128;
         const bool fast = (KIND == SCAN_W64 || KIND == SCAN_C5) && h.g32ok != 0 && h.ng >= 1 &&
                           h.ng <= QADC_MAXG_FAST;
         const int ngt = KIND == SCAN_W128 ? h.ng / 2 : (fast ? h.ng : 0);
@@ -833,23 +884,21 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
         const int gper = KIND == SCAN_W128 ? h.ng / 2 : h.ng;
         for (int g = 0; g < gper; ++g) nlo += h.goff[g] < 32 ? 1 : 0;
         const int mode = (ngt > 0 && ngt % 2 == 0 && nlo == ngt / 2) ? 1 : ((ngt > 1 && nlo == ngt - 1) ? 2 : 0);
-#define QADC_SCAN_GO(NGV, MODEV)                                                                       \
-    hipLaunchKernelGGL((k_scan<KIND, QT, NGV, MODEV>), dim3(p.G, nq), dim3(SCAN_THREADS), gtab_bytes, \
-                       s, idx->dev, qtables, qparams, codes, n, ws, p.per_query, p.slots_off,         \
-                       p.gtab_off, p.cap_b, h.gtab_len, (uint32_t)h.qmax, gd)
-#define QADC_SCAN_NG(NGV)                                            \
-    do {                                                             \
-        if (KIND == SCAN_C5) {                                       \
-            if (mode == 2) QADC_SCAN_GO(NGV, 2); else QADC_SCAN_GO(NGV, 0); \
-        } else {                                                     \
-            if (mode == 1) QADC_SCAN_GO(NGV, 1); else QADC_SCAN_GO(NGV, 0); \
-        }                                                            \
-    } while (0)
         // several queries over an irregular layout: four of them share every pass over the codes
-        static const bool no_mq = getenv("QADC_NO_MQ") != nullptr;
         const size_t mq_lds = (size_t)h.gtab_len * sizeof(uint2);
-        const bool mqg = nq >= 2 && ngt > 0 && mq_lds <= 96 * 1024 && !no_mq &&
-                         (KIND == SCAN_W64 || KIND == SCAN_C5 || KIND == SCAN_W128);
+        const bool mqg = desc_kind && nq >= 2 && ngt > 0 && mq_lds <= 96 * 1024 && !no_mq;
+        // one query (or a few) per pass, a short result list, scan and selection asked for
+        // together: the block of the scan kernel that finishes last does the selection, which
+        // saves a dependent launch; the selection's LDS is then part of every scan block's
+        const size_t lds_fused = gtab_bytes + sizeof(SelectLds<SCAN_THREADS, FUSED_CAP>);
+        fused = !mqg && (what & 2) && R <= FUSED_R && lds_fused <= 20 * 1024;
+        const size_t lds_scan = fused ? lds_fused : gtab_bytes;
+        const int fuse = fused ? 1 : 0;
+#define QADC_SCAN_GO(NGV, MODEV)                                                                     \
+    hipLaunchKernelGGL((k_scan<KIND, QT, NGV, MODEV>), dim3(p.G, nq), dim3(SCAN_THREADS), lds_scan, \
+                       s, idx->dev, qtables, qparams, codes, n, ws, p.per_query, p.cand_off,        \
+                       p.gtab_off, p.cap, h.gtab_len, (uint32_t)h.qmax, gd, fuse, R, out_ids,       \
+                       out_keys, out_dist, bound_rec, recP, reck)
 #define QADC_MQG_GO(NGV, MODEV)                                                                      \
     do {                                                                                             \
         if (mq_lds > 48 * 1024)                                                                      \
@@ -857,13 +906,13 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)mq_lds)); \
         hipLaunchKernelGGL((k_scan_mqg<KIND, QT, NGV, MODEV>), dim3(p.G, (nq + MQ - 1) / MQ),        \
                            dim3(SCAN_THREADS), mq_lds, s, qparams, nq, codes, n, ws, p.per_query,    \
-                           p.slots_off, p.gtab_off, p.cap_b, h.gtab_len, (uint32_t)h.qmax, gd);      \
+                           p.cand_off, p.gtab_off, p.cap, h.gtab_len, (uint32_t)h.qmax, gd,         \
+                           bound_rec, recP, reck);                                                   \
     } while (0)
 #define QADC_SCAN_ANY(NGV, MODEV)                                       \
     do {                                                                \
         if (mqg) QADC_MQG_GO(NGV, MODEV); else QADC_SCAN_GO(NGV, MODEV); \
     } while (0)
-#undef QADC_SCAN_NG
 #define QADC_SCAN_NG(NGV)                                              \
     do {                                                               \
         if (KIND == SCAN_C5) {                                         \
@@ -872,7 +921,7 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
             if (mode == 1) QADC_SCAN_ANY(NGV, 1); else QADC_SCAN_ANY(NGV, 0); \
         }                                                              \
     } while (0)
-        if (KIND == SCAN_W64 || KIND == SCAN_C5 || KIND == SCAN_W128) {
+        if constexpr (desc_kind) {
             switch (ngt) {
                 case 1: QADC_SCAN_NG(1); break;
                 case 2: QADC_SCAN_NG(2); break;
@@ -893,14 +942,24 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
 #undef QADC_SCAN_NG
         QADC_LAUNCH_CHECK("k_scan");
     }
-    if (!(what & 2)) return PQ_OK;
-    const size_t lds_final = FINAL_CAP * 8 + gtab_bytes + (size_t)h.T * 2;
-    if (lds_final > 48 * 1024)
-        QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_final<KIND, QT>,
+    if (!(what & 2) || fused) return PQ_OK;
+    // short result lists: a small block (cheap barriers, little LDS); long ones: 1024 threads
+    if (R <= FINAL_SMALL_R) {
+        const size_t lds_final = sizeof(SelectLds<256, FINAL_SMALL_CAP>) + gtab_bytes;
+        if (lds_final > 48 * 1024)
+            QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_final<KIND, QT, 256, FINAL_SMALL_CAP>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_final));
+        hipLaunchKernelGGL((k_final<KIND, QT, 256, FINAL_SMALL_CAP>), dim3(nq), dim3(256), lds_final, s,
+                           idx->dev, qparams, codes, n, R, ws, p.per_query, p.cand_off, p.gtab_off, p.cap,
+                           out_ids, out_keys, out_dist);
+    } else {
+        const size_t lds_final = sizeof(SelectLds<1024, FINAL_CAP>) + gtab_bytes;
+        QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_final<KIND, QT, 1024, FINAL_CAP>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_final));
-    hipLaunchKernelGGL((k_final<KIND, QT>), dim3(nq), dim3(1024), lds_final, s, idx->dev, qtables,
-                       qparams, codes, n, R, ws, p.per_query, p.slots_off, p.cap_b, p.G, p.logw,
-                       out_ids, out_keys, out_dist);
+        hipLaunchKernelGGL((k_final<KIND, QT, 1024, FINAL_CAP>), dim3(nq), dim3(1024), lds_final, s,
+                           idx->dev, qparams, codes, n, R, ws, p.per_query, p.cand_off, p.gtab_off, p.cap,
+                           out_ids, out_keys, out_dist);
+    }
     QADC_LAUNCH_CHECK("k_final");
     return PQ_OK;
 }
@@ -908,10 +967,12 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
 static int scan_dispatch(const pq_index *idx, const void *qtables, const pq_qparams_t *qparams,
                          int nq, const uint8_t *codes, int64_t n, int R, int32_t *out_ids,
                          uint16_t *out_keys, float *out_dist, char *ws, const ScanPlan &p,
-                         hipStream_t s, int what) {
+                         hipStream_t s, int what, const uint16_t *bound_rec = nullptr, int recP = 0,
+                         uint32_t reck = 0) {
     const bool u8 = idx->h.acc_bits == 8;
 #define QADC_GO(KIND, QT) \
-    return launch_scan<KIND, QT>(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s, what)
+    return launch_scan<KIND, QT>(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s, what, \
+                                 bound_rec, recP, reck)
     switch (idx->h.kind) {
         case SCAN_NIB8:
             if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);
@@ -1097,12 +1158,15 @@ extern "C" int pq_search_topk(const pq_index_t *idx, const float *queries, int n
     void *qtables = w + up256((size_t)nq * sizeof(pq_qparams_t));
     char *ws = (char *)qtables + up256((size_t)nq * idx->h.T * esz);
     hipStream_t s = (hipStream_t)stream;
-    ScanPlan p = qadc_scan_plan(idx, nq, n, R);
+    const ScanPlan p = qadc_scan_plan(idx, nq, n, R);
     char *scratch = ws + up256(p.total);
-    int pilot = 0;
+    PilotPlan pp;
     rc = qadc_quantize_launch(idx, queries, nullptr, nullptr, nq, codes, n, t, R, qtables, qparams,
-                              ws + p.gtab_off, p.per_query, scratch, &pilot, s);
+                              ws + p.gtab_off, p.per_query, ws, scratch, &pp, s);
     if (rc != PQ_OK) return rc;
-    p.logw = qadc_rows_logw(n, p.G, R, pilot);
-    return scan_dispatch(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s, 3);
+    // several pilot blocks per query: the scan adds their records up; one: the bound is in qparams
+    const uint16_t *rec = pp.P > 1 ? (const uint16_t *)scratch : nullptr;
+    const uint32_t reck = (uint32_t)(R < pp.pilot ? R : pp.pilot);
+    return scan_dispatch(idx, qtables, qparams, nq, codes, n, R, out_ids, out_keys, out_dist, ws, p, s, 3, rec,
+                         pp.P, reck);
 }

@@ -4,7 +4,11 @@
 
 #include "qadc_device.h"
 
-#define FINAL_CAP 5120  // candidates a final kernel can rank in LDS
+#define FINAL_CAP 5120        // candidates a selection block of 1024 threads can rank in LDS
+#define FINAL_SMALL_CAP 2048  // ... a block of 256 threads, used for result lists up to FINAL_SMALL_R
+#define FINAL_SMALL_R 256
+#define FUSED_CAP 1024        // ... the last block of the scan kernel itself, for result lists up to FUSED_R
+#define FUSED_R 128
 
 // ------------------------------------------------------------ group tables --
 // gtab[gbase[g] + e] = min(q_max, sum of the quantized entries of the
@@ -333,6 +337,221 @@ __device__ __forceinline__ void slot_append_multi(const bool *pass, const uint32
     }
 }
 
+
+// ------------------------------------------------------- candidate lists ---
+// The exhaustive scan keeps QADC_NSUB candidate lists per query in the workspace, each with its
+// own counter on a cache line of its own: entries `key << 32 | id`, appended by whichever wave
+// finds candidates (a block appends to list blockIdx.x % QADC_NSUB), in no particular order
+// (the result is defined as a sort).  A wave reserves room with one atomic add for all the
+// candidates its lanes hold.  (One list per query would be simpler, but atomic adds to one
+// address are served one by one, about 10 ns each: 3000 of them per query took longer than
+// the scan itself.)  Entries beyond a list's capacity are not stored, and a count above the
+// capacity tells the selection that it must work from the codes themselves.
+#define QADC_NSUB 64
+struct ScanHdr {                      // first bytes of a query's workspace
+    uint32_t arrive;                  // lists whose blocks have all finished (fused selection only)
+    uint32_t pad[31];
+    uint32_t count[QADC_NSUB][32];    // count[l][0] = candidates appended to list l (may exceed the capacity)
+                                      // count[l][1] = blocks of list l that have finished (fused selection only)
+};
+
+// Zero a query's header: an empty set of candidate lists.  Block-wide, any block size.
+__device__ __forceinline__ void scan_hdr_clear(ScanHdr *h) {
+    for (int l = threadIdx.x; l < QADC_NSUB; l += blockDim.x) {
+        h->count[l][0] = 0;
+        h->count[l][1] = 0;
+    }
+    if (threadIdx.x == 0) h->arrive = 0;
+}
+
+// Append the (lane, slot) pairs with pass[u] set, NS slots per lane.  Wave-uniform call.
+template <int NS>
+__device__ __forceinline__ void cand_append_multi(const bool *pass, const uint32_t *key,
+                                                  const uint32_t *id, uint64_t *cand, uint32_t cap,
+                                                  uint32_t *count) {
+    uint64_t m[NS];
+    uint32_t total = 0;
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+        m[u] = __ballot(pass[u]);
+        total += (uint32_t)__popcll(m[u]);
+    }
+    if (total == 0) return;
+    const int lane = __lane_id();
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(count, total);
+    base = __builtin_amdgcn_readfirstlane(base);
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+        const uint32_t pos = base + (uint32_t)__popcll(m[u] & ((1ull << lane) - 1ull));
+        // (a device-scope store: written through to where every compute unit of the chip reads
+        // it, so that the block which finishes last can pick it up within this same kernel)
+        if (pass[u] && pos < cap)
+            __hip_atomic_store((unsigned long long *)cand + pos, ((unsigned long long)key[u] << 32) | id[u],
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        base += (uint32_t)__popcll(m[u]);
+    }
+}
+__device__ __forceinline__ void cand_append(bool pass, uint32_t key, uint32_t id, uint64_t *cand,
+                                            uint32_t cap, uint32_t *count) {
+    cand_append_multi<1>(&pass, &key, &id, cand, cap, count);
+}
+
+// ------------------------------------------------- pruning bound from records ---
+// The quantizer's pilot may be counted by several blocks that never meet: block p of query q
+// leaves, for each of QADC_REC_BINS coarse key bins t (a coarse bin = four bins of the 256-bin
+// key histogram, i.e. keys >> shift >> 2), how many of its pilot codes have a key in bin t or
+// below: rec[q][t][p], 16-bit, saturating.  The sum over p is the number of pilot codes up to
+// bin t; the first bin where it reaches k (the k-th smallest pilot key lies in it) gives an
+// upper bound on the k-th smallest key of the whole list: the bin's largest key.
+#define QADC_REC_BINS 64
+#define QADC_REC_SLOTS 64
+// Called by one full wave (lane t adds up bin t); returns the bound to every lane.
+__device__ __forceinline__ uint32_t scan_bound_from_records(const uint16_t *__restrict__ rec, int P,
+                                                            uint32_t k, int shift, uint32_t qmax) {
+    const int t = __lane_id();
+    const uint4 *row = (const uint4 *)(rec + (size_t)t * QADC_REC_SLOTS);  // 128 bytes: 8 chunks of 8 slots
+    uint4 v[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) v[c] = c * 8 < P ? row[c] : make_uint4(0u, 0u, 0u, 0u);
+    uint32_t s = 0;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        const uint32_t w[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (c * 8 + 2 * i < P) s += w[i] & 0xffffu;
+            if (c * 8 + 2 * i + 1 < P) s += w[i] >> 16;
+        }
+    }
+    const uint64_t reached = __ballot(s >= k);
+    if (reached == 0) return qmax;  // (fewer than k pilot codes in all: no bound)
+    const uint32_t bin = (uint32_t)(__ffsll((unsigned long long)reached) - 1);
+    const uint32_t bound = (((bin << 2) | 3u) << shift) | ((1u << shift) - 1u);
+    return bound > qmax ? qmax : bound;
+}
+
+// LDS of a selection block of NT threads that can rank ACAP candidates.
+template <int NT, int ACAP>
+struct SelectLds {
+    uint64_t A[ACAP];                 // candidates up to the bin of the R-th
+    uint32_t whist[NT / 64][256];     // one key-bin histogram per wave; later: counts / starts / cursors
+    uint32_t hist[256];
+    uint32_t sh[32];
+    uint16_t order[ACAP];
+};
+
+// Block-wide (NT threads): from the QADC_NSUB candidate lists of a query (list l: min(count_l,
+// cap) entries at cand + l * cap), find the key bin (key >> shift) of the kk-th smallest
+// candidate, kk = min(R, all of them), and leave every candidate up to that bin in S.A.
+// NT / QADC_NSUB adjacent threads share a list, REG entries each per round, all loads of a
+// round in flight together.  COHERENT: the lists were written by other blocks of this same
+// kernel (they are read with device-scope loads).  Returns the number kept, or -1 when a list
+// overflowed or the kept ones exceed ACAP.
+template <int NT, int ACAP, bool COHERENT>
+__device__ inline int select_from_lists(const ScanHdr *__restrict__ h, const uint64_t *__restrict__ cand,
+                                        uint32_t cap, int R, int shift, SelectLds<NT, ACAP> &S) {
+#ifndef QADC_SEL_REG
+#define QADC_SEL_REG 16
+#endif
+    constexpr int REG = QADC_SEL_REG;
+    constexpr int W = NT / QADC_NSUB;  // threads per list
+    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
+    const int l = threadIdx.x / W, sub = threadIdx.x % W;
+    const uint64_t *mine = cand + (size_t)l * cap;
+    auto load = [&](uint32_t e) -> uint64_t {
+        if (COHERENT)
+            return __hip_atomic_load((const unsigned long long *)mine + e, __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_AGENT);
+        return mine[e];
+    };
+    // the list's length and its first W * REG entries are requested together (entries beyond
+    // the length are read and ignored; none beyond the capacity), before anything else
+    uint32_t cnt = COHERENT ? __hip_atomic_load(&h->count[l][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                            : h->count[l][0];
+    uint64_t c[REG];
+#pragma unroll
+    for (int u = 0; u < REG; ++u) {
+        const uint32_t e = u * W + sub;
+        c[u] = e < cap ? load(e) : ~0ull;
+    }
+    for (int i = threadIdx.x; i < (NT / 64) * 256; i += NT) (&S.whist[0][0])[i] = 0;
+    if (threadIdx.x < 8) S.sh[threadIdx.x] = 0;  // 0: kept, 1: overflow flag, 2: all candidates, 3: longest list
+    __syncthreads();
+    if (sub == 0) {
+        if (cnt > cap) S.sh[1] = 1u;
+        atomicAdd(&S.sh[2], cnt);
+        atomicMax(&S.sh[3], cnt);
+    }
+    // first round of the histogram from the registers
+#pragma unroll
+    for (int u = 0; u < REG; ++u)
+        if ((uint32_t)(u * W + sub) < cnt && (uint32_t)(u * W + sub) < cap)
+            atomicAdd(&S.whist[wave][((uint32_t)(c[u] >> 32) >> shift) & 255u], 1u);
+    __syncthreads();
+    if (S.sh[1] != 0) {
+        __syncthreads();
+        return -1;
+    }
+    const uint32_t E = S.sh[2], longest = S.sh[3];
+    const bool single = longest <= (uint32_t)(W * REG);  // the second pass reuses the registers
+    uint32_t kbin = 255;
+    for (int pass = 0; pass < 2; ++pass) {
+        for (uint32_t base = (pass == 0 ? W * REG : 0); base < longest; base += W * REG) {
+            if (pass == 0 || !single) {
+#pragma unroll
+                for (int u = 0; u < REG; ++u) {
+                    const uint32_t e = base + u * W + sub;
+                    c[u] = e < cnt ? load(e) : ~0ull;
+                }
+            }
+            if (pass == 0) {
+#pragma unroll
+                for (int u = 0; u < REG; ++u)
+                    if (base + u * W + sub < cnt)
+                        atomicAdd(&S.whist[wave][((uint32_t)(c[u] >> 32) >> shift) & 255u], 1u);
+            } else {
+                // (few candidates reach this point -- about R of some thousands -- so each takes
+                // its place with an LDS atomic of its own)
+#pragma unroll
+                for (int u = 0; u < REG; ++u) {
+                    if (base + u * W + sub < cnt && (((uint32_t)(c[u] >> 32) >> shift) & 255u) <= kbin) {
+                        const uint32_t pos = atomicAdd(&S.sh[0], 1u);
+                        if (pos < (uint32_t)ACAP) S.A[pos] = c[u]; else S.sh[1] = 1u;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (pass == 0) {
+            // the bin of the kk-th smallest: wave 0 adds up the waves' histograms, four bins per lane
+            if (threadIdx.x < QADC_WAVE) {
+                uint32_t hb[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int w = 0; w < NT / 64; ++w) {
+                    const uint4 x = *(const uint4 *)&S.whist[w][4 * lane];
+                    hb[0] += x.x; hb[1] += x.y; hb[2] += x.z; hb[3] += x.w;
+                }
+                const uint32_t kk = E < (uint32_t)R ? E : (uint32_t)R;
+                const uint32_t s4 = hb[0] + hb[1] + hb[2] + hb[3];
+                uint32_t run = qadc_wave_incl_scan(s4) - s4;
+                uint32_t my = 0xffffffffu;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (my == 0xffffffffu && (run + hb[i] >= kk || 4 * lane + i == 255)) my = (uint32_t)(4 * lane + i);
+                    run += hb[i];
+                }
+                const uint32_t best = qadc_wave_min(my);
+                if (lane == 0) S.sh[4] = best;
+            }
+            __syncthreads();
+            kbin = S.sh[4];
+        }
+    }
+    const int na = S.sh[1] != 0 ? -1 : (int)S.sh[0];
+    __syncthreads();
+    return na;
+}
 
 struct FinalShared {
     uint32_t *hist;            // [256]

@@ -47,12 +47,12 @@ def test_static_scratch_entry_equals_workspace_entry_twice(qb, name):
         for a, b in zip(want, got):
             assert torch.equal(a, b), (name, nq, n)
     # beyond the array: a clear error, nothing launched
-    nq_big = 64
+    nq_big, r_big = 64, 2048
     tables = qb.pq_compute_tables(idx, qs[:1].repeat(nq_big, 1).contiguous())
-    qt, qp = qb.pq_quantize_tables(idx, tables, codes, 400, R)
-    assert qb.pq_workspace_bytes(idx, nq_big, codes.shape[0], R) > 16 << 20
+    qt, qp = qb.pq_quantize_tables(idx, tables, codes, 400, r_big)
+    assert qb.pq_workspace_bytes(idx, nq_big, codes.shape[0], r_big) > 16 << 20
     with pytest.raises(qb.QadcError) as e:
-        qb.pq_adc_scan_topk_static(idx, qt, qp, codes, R, empty_out(nq_big, R, -5))
+        qb.pq_adc_scan_topk_static(idx, qt, qp, codes, r_big, empty_out(nq_big, r_big, -5))
     assert e.value.code == qb.PQ_ENOMEM and "scratch" in str(e.value)
     torch.cuda.synchronize()
     idx.close()
