@@ -25,8 +25,11 @@
 // carry q_max as the bound.  Block 0 of a query stores the tables and the parameters.
 // `queries` non-null: tables are computed here (and stored to tables_out if
 // that is non-null); otherwise they are read from tables_in.
+#ifndef QUANT_THREADS
+#define QUANT_THREADS 256
+#endif
 template <int KIND, typename QT>
-__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4)))
+__global__ void __launch_bounds__(QUANT_THREADS)
 k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
            const float *__restrict__ cb,
            const float *__restrict__ queries, const float *__restrict__ tables_in,
@@ -316,11 +319,11 @@ static int64_t pilot_env(const char *name, int64_t dflt) {
 }
 
 // Codes one pilot block counts per batch (eight per thread) and at most in total.
-#define PILOT_BATCH 8192
+#define PILOT_BATCH (8 * QUANT_THREADS)
 #define PILOT_BLOCK_MAX 65536
 
 int qadc_pilot_blocks_max(int nq) {
-    static const int64_t cap = pilot_env("QADC_PILOT_BLOCKS", 32);
+    static const int64_t cap = pilot_env("QADC_PILOT_BLOCKS", 64);
     int pmax = 256 / (nq > 0 ? nq : 1);
     pmax = pmax < 1 ? 1 : (pmax > 64 ? 64 : pmax);
     if (nq > 16 && pmax > 4) pmax = 4;  // (32 queries per call: 4 blocks each measured 6 % faster than 8)
@@ -373,7 +376,7 @@ static int launch_quantize(const pq_index *idx, const float *queries, const floa
     if (lds > 48 * 1024)
         QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_quantize<KIND, QT>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL((k_quantize<KIND, QT>), dim3((unsigned)nq * (unsigned)pp.P), dim3(1024), lds, s,
+    hipLaunchKernelGGL((k_quantize<KIND, QT>), dim3((unsigned)nq * (unsigned)pp.P), dim3(QUANT_THREADS), lds, s,
                        idx->dev, idx->edesc, idx->codebooks, queries, tables_in, tables_out, codes, t_eff, k,
                        pp.pilot, pp.slice, pp.P, qtables, qparams, gtab_out, gtab_stride, hdr_out, bound_rec);
     QADC_LAUNCH_CHECK("k_quantize");

@@ -208,8 +208,9 @@ __device__ inline void select_query(const DevLayout *L, const char *__restrict__
                                     SelectLds<NT, ACAP> &S, const QT *gtab, QT *gtab_room) {
     const int shift = L->acc_bits == 8 ? 0 : 8;
     const uint32_t qmax = (uint32_t)L->qmax;
-    int na = select_from_lists<NT, ACAP, COHERENT>((const ScanHdr *)wq, (const uint64_t *)(wq + cand_off), cap,
-                                                   R, shift, S);
+    // (inside the scan kernel, whose register budget is small, half as many entries per round)
+    int na = select_from_lists<NT, ACAP, COHERENT, COHERENT ? 8 : 16>((const ScanHdr *)wq,
+                                                                      (const uint64_t *)(wq + cand_off), cap, R, shift, S);
     if (na < 0) {
         if (!gtab) {
             const int n16 = (L->gtab_len * (int)sizeof(QT) + 15) >> 4;
@@ -243,7 +244,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
        const uint16_t *__restrict__ bound_rec, int recP, uint32_t reck) {
     extern __shared__ __align__(16) unsigned char smem[];
     QT *gtab = (QT *)smem;
-    __shared__ uint32_t s_last, s_thr;
+    __shared__ uint32_t s_last, s_bin[SCAN_THREADS / QADC_WAVE];
     const size_t q = blockIdx.y;
     const int b = blockIdx.x, G = gridDim.x;
     char *wq = ws + q * per_query;
@@ -254,15 +255,11 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     // Sums are compared unsaturated.  A sum above q_max is the key q_max (Section 3.4), an
     // ordinary largest key: with a bound below q_max such a code never passes, and with the
     // bound at q_max every code does (the keys are saturated where they are stored).
-    // The bound: from the query's parameters, or (bound_rec) added up by the first wave from the
-    // records the quantizer's pilot blocks left; it reaches the other waves through LDS behind
-    // the barrier that ends the staging of the tables.
+    // The bound: from the query's parameters, or (bound_rec) added up from the records the
+    // quantizer's pilot blocks left; the waves' parts meet in LDS behind the barrier that ends
+    // the staging of the tables.
     uint32_t thr = qparams[q].key_bound;
-    if (bound_rec && threadIdx.x < QADC_WAVE) {
-        const uint32_t t = scan_bound_from_records(bound_rec + q * (QADC_REC_BINS * QADC_REC_SLOTS), recP, reck,
-                                                   sizeof(QT) == 1 ? 0 : 8, qmax);
-        if (threadIdx.x == 0) s_thr = t;
-    }
+    if (bound_rec) scan_bound_bins_256(bound_rec + q * (QADC_REC_BINS * QADC_REC_SLOTS), recP, reck, s_bin);
     constexpr bool g32 = NG > 0;
     constexpr int NLO = MODE == 1 ? NG / 2 : (MODE == 2 ? NG - 1 : -1);
 
@@ -285,7 +282,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         };
         if (tile < ntiles) load_tile(tile);  // in flight while the tables are staged
         load_gtab<QT>(gsrc, gtab_len, gtab);
-        if (bound_rec) thr = s_thr;
+        if (bound_rec) thr = scan_bound_of_bin(min(min(s_bin[0], s_bin[1]), min(s_bin[2], s_bin[3])), sizeof(QT) == 1 ? 0 : 8, qmax);
         thr = thr >= qmax ? 0xffffffffu : thr;
         while (tile < ntiles) {
             uint32_t s[2 * U];
@@ -353,7 +350,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         };
         if (tile < ntiles) load_tile(tile);  // the first tile is in flight while the tables are staged
         load_gtab<QT>(gsrc, gtab_len, gtab);
-        if (bound_rec) thr = s_thr;
+        if (bound_rec) thr = scan_bound_of_bin(min(min(s_bin[0], s_bin[1]), min(s_bin[2], s_bin[3])), sizeof(QT) == 1 ? 0 : 8, qmax);
         thr = thr >= qmax ? 0xffffffffu : thr;
         while (tile < ntiles) {
             uint32_t s[4 * U];
@@ -417,7 +414,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         };
         if (tile < ntiles) load_tile(tile);  // the first tile is in flight while the tables are staged
         load_gtab<QT>(gsrc, gtab_len, gtab);
-        if (bound_rec) thr = s_thr;
+        if (bound_rec) thr = scan_bound_of_bin(min(min(s_bin[0], s_bin[1]), min(s_bin[2], s_bin[3])), sizeof(QT) == 1 ? 0 : 8, qmax);
         thr = thr >= qmax ? 0xffffffffu : thr;
         while (tile < ntiles) {
             uint32_t s[4];

@@ -406,29 +406,51 @@ __device__ __forceinline__ void cand_append(bool pass, uint32_t key, uint32_t id
 // upper bound on the k-th smallest key of the whole list: the bin's largest key.
 #define QADC_REC_BINS 64
 #define QADC_REC_SLOTS 64
+// Sum of the first P 16-bit slots of a record row, chunks [c0, c1) of 8 slots (16 bytes) each.
+__device__ __forceinline__ uint32_t scan_rec_row_sum(const uint16_t *__restrict__ row, int P, int c0, int c1) {
+    uint32_t s = 0;
+    for (int c = c0; c < c1; c += 4) {  // four 16-byte loads in flight at a time
+        uint4 v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            v[i] = (c + i < c1 && (c + i) * 8 < P) ? ((const uint4 *)row)[c + i] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t w[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                if ((c + i) * 8 + 2 * h < P) s += w[h] & 0xffffu;
+                if ((c + i) * 8 + 2 * h + 1 < P) s += w[h] >> 16;
+            }
+        }
+    }
+    return s;
+}
+__device__ __forceinline__ uint32_t scan_bound_of_bin(uint32_t bin, int shift, uint32_t qmax) {
+    if (bin >= QADC_REC_BINS) return qmax;  // (fewer than k pilot codes in all: no bound)
+    const uint32_t bound = (((bin << 2) | 3u) << shift) | ((1u << shift) - 1u);
+    return bound > qmax ? qmax : bound;
+}
 // Called by one full wave (lane t adds up bin t); returns the bound to every lane.
 __device__ __forceinline__ uint32_t scan_bound_from_records(const uint16_t *__restrict__ rec, int P,
                                                             uint32_t k, int shift, uint32_t qmax) {
-    const int t = __lane_id();
-    const uint4 *row = (const uint4 *)(rec + (size_t)t * QADC_REC_SLOTS);  // 128 bytes: 8 chunks of 8 slots
-    uint4 v[8];
-#pragma unroll
-    for (int c = 0; c < 8; ++c) v[c] = c * 8 < P ? row[c] : make_uint4(0u, 0u, 0u, 0u);
-    uint32_t s = 0;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-        const uint32_t w[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if (c * 8 + 2 * i < P) s += w[i] & 0xffffu;
-            if (c * 8 + 2 * i + 1 < P) s += w[i] >> 16;
-        }
-    }
+    const uint32_t s = scan_rec_row_sum(rec + (size_t)__lane_id() * QADC_REC_SLOTS, P, 0, QADC_REC_SLOTS / 8);
     const uint64_t reached = __ballot(s >= k);
-    if (reached == 0) return qmax;  // (fewer than k pilot codes in all: no bound)
-    const uint32_t bin = (uint32_t)(__ffsll((unsigned long long)reached) - 1);
-    const uint32_t bound = (((bin << 2) | 3u) << shift) | ((1u << shift) - 1u);
-    return bound > qmax ? qmax : bound;
+    return scan_bound_of_bin(reached ? (uint32_t)(__ffsll((unsigned long long)reached) - 1) : 0xffffffffu, shift, qmax);
+}
+// The same by a block of 256 threads with few registers each: four adjacent lanes share a bin
+// (two chunks each), so every wave covers 16 bins; the wave's first bin that reaches k (or
+// 0xffffffff) goes to first_bin[wave], and after the block's next barrier the bound is
+// scan_bound_of_bin(min of the four).  All 256 threads call it.
+__device__ __forceinline__ void scan_bound_bins_256(const uint16_t *__restrict__ rec, int P, uint32_t k,
+                                                    uint32_t *first_bin) {
+    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
+    const int bin = wave * 16 + lane / 4, part = lane % 4;
+    uint32_t s = scan_rec_row_sum(rec + (size_t)bin * QADC_REC_SLOTS, P, 2 * part, 2 * part + 2);
+    s += QADC_DPP_STEP(0u, s, 0xB1, 0xf);  // quad_perm [1,0,3,2]
+    s += QADC_DPP_STEP(0u, s, 0x4E, 0xf);  // quad_perm [2,3,0,1]
+    const uint64_t reached = __ballot(s >= k);
+    if (lane == 0) first_bin[wave] = reached ? (uint32_t)(wave * 16 + (__ffsll((unsigned long long)reached) - 1) / 4) : 0xffffffffu;
 }
 
 // LDS of a selection block of NT threads that can rank ACAP candidates.
@@ -444,17 +466,13 @@ struct SelectLds {
 // Block-wide (NT threads): from the QADC_NSUB candidate lists of a query (list l: min(count_l,
 // cap) entries at cand + l * cap), find the key bin (key >> shift) of the kk-th smallest
 // candidate, kk = min(R, all of them), and leave every candidate up to that bin in S.A.
-// NT / QADC_NSUB adjacent threads share a list, REG entries each per round, all loads of a
-// round in flight together.  COHERENT: the lists were written by other blocks of this same
+// NT / QADC_NSUB adjacent threads share a list, REG entries each per round (held in
+// registers), all loads of a round in flight together.  COHERENT: the lists were written by other blocks of this same
 // kernel (they are read with device-scope loads).  Returns the number kept, or -1 when a list
 // overflowed or the kept ones exceed ACAP.
-template <int NT, int ACAP, bool COHERENT>
+template <int NT, int ACAP, bool COHERENT, int REG>
 __device__ inline int select_from_lists(const ScanHdr *__restrict__ h, const uint64_t *__restrict__ cand,
                                         uint32_t cap, int R, int shift, SelectLds<NT, ACAP> &S) {
-#ifndef QADC_SEL_REG
-#define QADC_SEL_REG 16
-#endif
-    constexpr int REG = QADC_SEL_REG;
     constexpr int W = NT / QADC_NSUB;  // threads per list
     const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
     const int l = threadIdx.x / W, sub = threadIdx.x % W;
