@@ -28,9 +28,16 @@
 #ifndef QUANT_THREADS
 #define QUANT_THREADS 256
 #endif
+// The few layout numbers the kernel needs before anything else, as kernel arguments (reading
+// them through the layout pointer would be a memory round trip ahead of every other load).
+struct QuantShape {
+    int T, m, cs, qmax, d;
+};
+// NIB8 pilot codes a thread holds in registers per batch
+#define PILOT_PER_THREAD 16
 template <int KIND, typename QT>
 __global__ void __launch_bounds__(QUANT_THREADS)
-k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
+k_quantize(const DevLayout *__restrict__ L, const QuantShape shape, const EntryDesc *__restrict__ edesc,
            const float *__restrict__ cb,
            const float *__restrict__ queries, const float *__restrict__ tables_in,
            float *__restrict__ tables_out, const uint8_t *__restrict__ codes, int t_eff, int k,
@@ -38,7 +45,7 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
            pq_qparams_t *__restrict__ qparams, char *__restrict__ gtab_out, size_t gtab_stride,
            char *__restrict__ hdr_out, uint16_t *__restrict__ bound_rec) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const int T = L->T, m = L->m, cs = L->cs, qmax = L->qmax, d = L->d;
+    const int T = shape.T, m = shape.m, cs = shape.cs, qmax = shape.qmax, d = shape.d;
     float *tab = (float *)smem;
     uint32_t *ord = (uint32_t *)(tab + T);                    // max(t_eff, d) words
     const int nord = (t_eff > d ? t_eff : d) > 0 ? (t_eff > d ? t_eff : d) : 1;
@@ -53,22 +60,26 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
     __shared__ double s_dmin, s_delta;
     __shared__ float s_dmax;
     __shared__ uint32_t sdesc[PQ_MAX_M];  // table offset | bit offset << 12 | bits << 24 of each sub-quantizer
-    if ((int)threadIdx.x < m)  // (read after the barriers of the table set-up)
+    __shared__ uint32_t pmin_ord[PQ_MAX_M];  // table minima as ordered words (qadc_f2ord), by LDS atomic min
+    if ((int)threadIdx.x < m) {  // (read after the barriers of the table set-up)
         sdesc[threadIdx.x] = (uint32_t)L->toff[threadIdx.x] | ((uint32_t)L->bitoff[threadIdx.x] << 12) |
                              ((uint32_t)L->nbits[threadIdx.x] << 24);
+        pmin_ord[threadIdx.x] = 0xffffffffu;
+    }
 
     const size_t q = blockIdx.x / (unsigned)P;
     const int p = (int)(blockIdx.x % (unsigned)P);
     const bool first = p == 0;
     const int lo = (int64_t)p * slice < pilot ? p * slice : pilot;
     const int hi = (int64_t)lo + slice < pilot ? lo + slice : pilot;
-    const int step = 8 * (int)blockDim.x;
+    constexpr int PPT = KIND == SCAN_NIB8 ? PILOT_PER_THREAD : 8;  // pilot codes per thread and batch
+    const int step = PPT * (int)blockDim.x;
 
     // The first batch of this block's pilot codes is requested now and used at the very end.
-    uint2 pc[8];
+    uint2 pc[PPT];
     if (KIND == SCAN_NIB8 && hi > lo) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < PPT; ++u) {
             int id = lo + u * (int)blockDim.x + (int)threadIdx.x;
             id = id < hi ? id : hi - 1;
             pc[u] = *(const uint2 *)(codes + (size_t)id * 8);
@@ -77,9 +88,15 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
 
     // The calibration code of this thread (at most one per thread in the common case) and the
     // descriptor of its table entry are requested now as well: they do not depend on anything.
-    const bool cal_one = t_eff <= (int)blockDim.x && cs <= 16;
-    uint32_t cw[4] = {0u, 0u, 0u, 0u};
-    if (cal_one && (int)threadIdx.x < t_eff) qadc_load_code16(codes + (size_t)threadIdx.x * cs, cs, cw);
+    const bool cal_pre = t_eff <= 2 * (int)blockDim.x && cs <= 16;  // up to two per thread
+    uint32_t cw[2][4] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+    if (cal_pre) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int pp = r * (int)blockDim.x + (int)threadIdx.x;
+            if (pp < t_eff) qadc_load_code16(codes + (size_t)pp * cs, cs, cw[r]);
+        }
+    }
     EntryDesc ed0 = {0, 0, 0, 0};
     if ((int)threadIdx.x < T) ed0 = edesc[threadIdx.x];
 
@@ -88,55 +105,68 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
         for (int i = threadIdx.x; i < d; i += blockDim.x) zs[i] = queries[q * d + i];
         for (int e = threadIdx.x; e < T; e += blockDim.x)
             esub[e] = (uint8_t)(e == (int)threadIdx.x ? ed0.j : edesc[e].j);
+        // the first eight codebook values of this thread's own entry: requested before the
+        // barrier, so that they travel while the query settles in LDS
+        float c0[8];
+#pragma unroll
+        for (int l = 0; l < 8; ++l) c0[l] = ((int)threadIdx.x < T && l < ed0.ds) ? cb[ed0.cb_off + l] : 0.0f;
         __syncthreads();
         for (int e = threadIdx.x; e < T; e += blockDim.x) {
-            const EntryDesc ed = e == (int)threadIdx.x ? ed0 : edesc[e];
+            const bool own = e == (int)threadIdx.x;
+            const EntryDesc ed = own ? ed0 : edesc[e];
             const int ds = ed.ds;
             const float *c = cb + ed.cb_off;
             const float *z = zs + ed.dim_off;
             float acc = 0.0f;
-            for (int l = 0; l < ds; ++l) {
+            if (own) {
+#pragma unroll
+                for (int l = 0; l < 8; ++l)
+                    if (l < ds) {
+                        float diff = __fsub_rn(z[l], c0[l]);
+                        acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                    }
+            }
+            for (int l = own ? 8 : 0; l < ds; ++l) {
                 float diff = __fsub_rn(z[l], c[l]);
                 acc = __fadd_rn(acc, __fmul_rn(diff, diff));
             }
             tab[e] = acc;
+            atomicMin(&pmin_ord[ed.j], qadc_f2ord(acc));
             if (tables_out && first) tables_out[q * T + e] = acc;
         }
         __syncthreads();
     } else {
+        __syncthreads();  // pmin_ord is set up
         for (int e = threadIdx.x; e < T; e += blockDim.x) {
-            tab[e] = tables_in[q * T + e];
-            esub[e] = (uint8_t)(e == (int)threadIdx.x ? ed0.j : edesc[e].j);
+            const float v = tables_in[q * T + e];
+            const int j = e == (int)threadIdx.x ? ed0.j : edesc[e].j;
+            tab[e] = v;
+            esub[e] = (uint8_t)j;
+            atomicMin(&pmin_ord[j], qadc_f2ord(v));
         }
         __syncthreads();
     }
-    if ((int)threadIdx.x < m) {
-        const int j = threadIdx.x;
-        const int kj = 1 << L->nbits[j];
-        const float *tj = tab + L->toff[j];
-        float mn = tj[0];
-        for (int i = 1; i < kj; ++i) mn = tj[i] < mn ? tj[i] : mn;
-        pmin[j] = mn;
-    }
+    if ((int)threadIdx.x < m) pmin[threadIdx.x] = qadc_ord2f(pmin_ord[threadIdx.x]);
     // float ADC of the calibration codes
-    for (int pp = threadIdx.x; pp < t_eff; pp += blockDim.x) {
+    for (int pp = threadIdx.x, r = 0; pp < t_eff; pp += blockDim.x, ++r) {
         const uint8_t *code = codes + (size_t)pp * cs;
         float s = 0.0f;
+        const uint32_t *cwr = cw[r & 1];  // (r < 2 whenever cal_pre)
         if (KIND == SCAN_NIB8) {  // sub-code j is nibble j of the 8-byte code
-            const uint2 v = cal_one ? make_uint2(cw[0], cw[1]) : *(const uint2 *)code;
+            const uint2 v = cal_pre ? make_uint2(cwr[0], cwr[1]) : *(const uint2 *)code;
 #pragma unroll
             for (int j = 0; j < 16; ++j)
                 s = __fadd_rn(s, tab[16 * j + (((j < 8 ? v.x : v.y) >> (4 * (j & 7))) & 15u)]);
         } else if (KIND == SCAN_NIB16) {  // ... of the 16-byte code
-            const uint4 v = cal_one ? make_uint4(cw[0], cw[1], cw[2], cw[3]) : *(const uint4 *)code;
+            const uint4 v = cal_pre ? make_uint4(cwr[0], cwr[1], cwr[2], cwr[3]) : *(const uint4 *)code;
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int j = 0; j < 32; ++j)
                 s = __fadd_rn(s, tab[16 * j + ((w[j >> 3] >> (4 * (j & 7))) & 15u)]);
         } else if (cs <= 16) {  // the code in registers, the sub-quantizers' fields from LDS
             uint32_t w[4];
-            if (cal_one) {
-                w[0] = cw[0]; w[1] = cw[1]; w[2] = cw[2]; w[3] = cw[3];
+            if (cal_pre) {
+                w[0] = cwr[0]; w[1] = cwr[1]; w[2] = cwr[2]; w[3] = cwr[3];
             } else {
                 qadc_load_code16(code, cs, w);
             }
@@ -151,10 +181,16 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
         ord[pp] = qadc_f2ord(s);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (threadIdx.x < QADC_WAVE) {  // d_min = sum of the minima in fp64, ascending j (m <= 64: one per lane)
+        const double mine = (int)threadIdx.x < m ? (double)pmin[threadIdx.x] : 0.0;
+        const unsigned long long bits = (unsigned long long)__double_as_longlong(mine);
         double dm = 0.0;
-        for (int j = 0; j < m; ++j) dm = dm + (double)pmin[j];
-        s_dmin = dm;
+        for (int j = 0; j < m; ++j) {  // (lane reads: no memory involved)
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bits, j);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(bits >> 32), j);
+            dm = dm + __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+        }
+        if (threadIdx.x == 0) s_dmin = dm;
     }
     float dmax = INFINITY;
     if (t_eff > 0) dmax = qadc_ord2f(qadc_block_kth_f32(ord, t_eff, k, hist, sel, kmem));
@@ -208,14 +244,14 @@ k_quantize(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
             for (int base = lo; base < hi; base += step) {
                 if (base != lo) {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) {
+                    for (int u = 0; u < PPT; ++u) {
                         int id = base + u * (int)blockDim.x + (int)threadIdx.x;
                         id = id < hi ? id : hi - 1;
                         pc[u] = *(const uint2 *)(codes + (size_t)id * 8);
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
+                for (int u = 0; u < PPT; ++u) {
                     const int id = base + u * (int)blockDim.x + (int)threadIdx.x;
                     const uint32_t sm = sum8(gtab, pc[u].x, pc[u].y);
                     count_key(id < hi ? (sm > (uint32_t)qmax ? (uint32_t)qmax : sm) : 0xffffffffu);
@@ -377,7 +413,8 @@ static int launch_quantize(const pq_index *idx, const float *queries, const floa
         QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_quantize<KIND, QT>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL((k_quantize<KIND, QT>), dim3((unsigned)nq * (unsigned)pp.P), dim3(QUANT_THREADS), lds, s,
-                       idx->dev, idx->edesc, idx->codebooks, queries, tables_in, tables_out, codes, t_eff, k,
+                       idx->dev, QuantShape{idx->h.T, idx->h.m, idx->h.cs, idx->h.qmax, idx->h.d}, idx->edesc,
+                       idx->codebooks, queries, tables_in, tables_out, codes, t_eff, k,
                        pp.pilot, pp.slice, pp.P, qtables, qparams, gtab_out, gtab_stride, hdr_out, bound_rec);
     QADC_LAUNCH_CHECK("k_quantize");
     return PQ_OK;

@@ -208,7 +208,8 @@ __device__ inline void select_query(const DevLayout *L, const char *__restrict__
                                     SelectLds<NT, ACAP> &S, const QT *gtab, QT *gtab_room) {
     const int shift = L->acc_bits == 8 ? 0 : 8;
     const uint32_t qmax = (uint32_t)L->qmax;
-    // (inside the scan kernel, whose register budget is small, half as many entries per round)
+    // (inside the scan kernel, whose register budget is small, half as many entries per round:
+    // sixteen made the compiler reserve per-lane scratch memory for every scan block)
     int na = select_from_lists<NT, ACAP, COHERENT, COHERENT ? 8 : 16>((const ScanHdr *)wq,
                                                                       (const uint64_t *)(wq + cand_off), cap, R, shift, S);
     if (na < 0) {
@@ -258,7 +259,8 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     // The bound: from the query's parameters, or (bound_rec) added up from the records the
     // quantizer's pilot blocks left; the waves' parts meet in LDS behind the barrier that ends
     // the staging of the tables.
-    uint32_t thr = qparams[q].key_bound;
+    const pq_qparams_t prm = qparams[q];  // (delta and d_min are used by the selection at the very end)
+    uint32_t thr = prm.key_bound;
     if (bound_rec) scan_bound_bins_256(bound_rec + q * (QADC_REC_BINS * QADC_REC_SLOTS), recP, reck, s_bin);
     constexpr bool g32 = NG > 0;
     constexpr int NLO = MODE == 1 ? NG / 2 : (MODE == 2 ? NG - 1 : -1);
@@ -473,7 +475,6 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     o.ids = out_ids + q * R;
     o.keys = out_keys + q * R;
     o.dist = out_dist + q * R;
-    const pq_qparams_t prm = qparams[q];
     select_query<KIND, QT, SCAN_THREADS, FUSED_CAP, true>(L, wq, cand_off, gtab_off, cap, codes, n, R, prm, o, S,
                                                           (const QT *)gtab, (QT *)nullptr);
 }
