@@ -7,9 +7,9 @@ headline workload is the PQ 16x4, R=100 exhaustive scan over N = 10,000,000
 codes (d = 96), one query per step.  Inputs are seeded synthetic data resident in
 HBM before the timed region.  Prints ONE JSON line.
 
-Steps are issued round-robin on a few HIP streams (independent requests in
-flight), each with private buffers, so that the small per-query kernels of one
-step can overlap the scan of another.  The roofline figure is for the scan
+Steps are issued round-robin on four HIP streams (independent requests in
+flight), each with private buffers, so that the quantizer kernel of one step can
+run beside the scan of another.  The roofline figure is for the scan
 kernel alone: it is launched back to back through pq_adc_rescan_candidates between
 two HIP events on its stream, and the elapsed time is divided by the launches.
 """
@@ -96,7 +96,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=4000)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--batch", type=int, default=1, help="queries per step")
-    ap.add_argument("--streams", type=int, default=32, help="HIP streams the steps rotate over")
+    ap.add_argument("--streams", type=int, default=4, help="HIP streams the steps rotate over")
     ap.add_argument("--hw-queues", type=int, default=16,
                     help="hardware queues the HIP runtime may use for this process "
                          "(GPU_MAX_HW_QUEUES); streams beyond it share queues")

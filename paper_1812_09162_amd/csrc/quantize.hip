@@ -360,9 +360,8 @@ static int64_t pilot_env(const char *name, int64_t dflt) {
 
 int qadc_pilot_blocks_max(int nq) {
     static const int64_t cap = pilot_env("QADC_PILOT_BLOCKS", 64);
-    int pmax = 256 / (nq > 0 ? nq : 1);
-    pmax = pmax < 1 ? 1 : (pmax > 64 ? 64 : pmax);
-    if (nq > 16 && pmax > 4) pmax = 4;  // (32 queries per call: 4 blocks each measured 6 % faster than 8)
+    int pmax = 2048 / (nq > 0 ? nq : 1);  // (blocks of 256 threads: a few thousand fill the chip)
+    pmax = pmax < 1 ? 1 : (pmax > QADC_REC_SLOTS ? QADC_REC_SLOTS : pmax);
     return cap >= 1 && cap < pmax ? (int)cap : pmax;
 }
 

@@ -253,6 +253,11 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
     uint32_t *count = &((ScanHdr *)wq)->count[sl][0];
     uint64_t *cand = (uint64_t *)(wq + cand_off) + (size_t)sl * cap;
     const char *gsrc = wq + gtab_off;
+    // this wave's staging buffer for candidates, behind the tables (the selection at the end
+    // reuses the room: every wave has emptied its buffer by then)
+    uint64_t *wbuf = (uint64_t *)(smem + (((size_t)gtab_len * sizeof(QT) + 15) & ~(size_t)15)) +
+                     (threadIdx.x / QADC_WAVE) * QADC_WSTAGE;
+    uint32_t nbuf = 0;
     // Sums are compared unsaturated.  A sum above q_max is the key q_max (Section 3.4), an
     // ordinary largest key: with a bound below q_max such a code never passes, and with the
     // bound at q_max every code does (the keys are saturated where they are stored).
@@ -314,7 +319,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                     id[u] = (uint32_t)(2 * c + (u & 1));
                     s[u] = s[u] > qmax ? qmax : s[u];
                 }
-                cand_append_multi<2 * U>(pass, s, id, cand, cap, count);
+                stage_append_multi<2 * U>(pass, s, id, wbuf, nbuf, cand, cap, count);
             }
             tile += G;
             if (tile < ntiles) load_tile(tile);
@@ -328,7 +333,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                     key = KIND == SCAN_NIB8 ? sum8(gtab, w.x, w.y)
                                             : sum_groups64(L, gtab, ((uint64_t)w.y << 32) | w.x);
                 }
-                cand_append(me && key <= thr, key > qmax ? qmax : key, (uint32_t)(n - 1), cand, cap, count);
+                stage_append(me && key <= thr, key > qmax ? qmax : key, (uint32_t)(n - 1), wbuf, nbuf, cand, cap, count);
             }
         }
     } else if (KIND == SCAN_C5) {
@@ -386,7 +391,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                     id[u] = 4u * c + (u & 3);
                     s[u] = s[u] > qmax ? qmax : s[u];
                 }
-                cand_append_multi<4 * U>(pass, s, id, cand, cap, count);
+                stage_append_multi<4 * U>(pass, s, id, wbuf, nbuf, cand, cap, count);
             }
             tile += G;
             if (tile < ntiles) load_tile(tile);
@@ -395,7 +400,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
             const int64_t id = (nfull << 2) + threadIdx.x;
             const bool me = id < n;
             uint32_t key = me ? key_at<KIND, QT>(L, gtab, codes, id) : 0u;
-            cand_append(me && key <= thr, key, (uint32_t)id, cand, cap, count);
+            stage_append(me && key <= thr, key, (uint32_t)id, wbuf, nbuf, cand, cap, count);
         }
     } else {
         // one 16-byte code (or one code of the byte-wise kind) per thread and chunk, four chunks
@@ -441,12 +446,13 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                     id[u] = tile * (4 * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
                     s[u] = s[u] > qmax ? qmax : s[u];
                 }
-                cand_append_multi<4>(pass, s, id, cand, cap, count);
+                stage_append_multi<4>(pass, s, id, wbuf, nbuf, cand, cap, count);
             }
             tile += G;
             if (tile < ntiles) load_tile(tile);
         }
     }
+    stage_flush(wbuf, nbuf, cand, cap, count);
     if (!fuse) return;
     // Selection by the block that finishes last.  Candidates were stored and counted with
     // device-scope operations; every thread waits until its own have completed, then the block
@@ -487,6 +493,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
 // of a 16-bit field).  Code bytes are loaded and split into indices once for all four.
 // NG = groups per code (8: 64-bit codes, 16: 128-bit codes).
 #define MQ 4
+#define MQ_STAGE_BYTES ((SCAN_THREADS / QADC_WAVE) * MQ * QADC_WSTAGE * 8)
 // Byte N of w, times 8 (the byte offset of an 8-byte table entry), as one instruction: a shift
 // whose operand is selected by sub-dword addressing.
 template <int N>
@@ -519,6 +526,9 @@ k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__res
     extern __shared__ __align__(16) unsigned char smem[];
     uint2 *tab = (uint2 *)smem;  // [NG][256], at LDS offset 0: entry offsets go into the reads as they are
     uint32_t *s_thr = (uint32_t *)(smem + NG * 256 * 8);  // [MQ] bounds added up from the pilot's records
+    // this wave's staging buffers for candidates, one per query
+    uint64_t *wbuf = (uint64_t *)(smem + NG * 256 * 8 + 16) + (threadIdx.x / QADC_WAVE) * (MQ * QADC_WSTAGE);
+    uint32_t nbuf[MQ] = {0u, 0u, 0u, 0u};
     if (bound_rec) {  // wave j adds up the records of query q0 + j (SCAN_THREADS / 64 == MQ)
         const int j = threadIdx.x / QADC_WAVE;
         const size_t q = (blockIdx.y * MQ + j < nq) ? blockIdx.y * MQ + j : blockIdx.y * MQ;
@@ -611,7 +621,7 @@ k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__res
             if (__ballot(any) != 0) {
 #pragma unroll
                 for (int i = 0; i < U * CPC; ++i) sum[j][i] = sum[j][i] > qmax ? qmax : sum[j][i];
-                cand_append_multi<U * CPC>(pass, sum[j], id, cand[j], cap, count[j]);
+                stage_append_multi<U * CPC>(pass, sum[j], id, wbuf + j * QADC_WSTAGE, nbuf[j], cand[j], cap, count[j]);
             }
         }
     }
@@ -631,9 +641,11 @@ k_scan_mq(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__res
         const uint32_t sj[MQ] = {lo & 0xffffu, lo >> 16, hi & 0xffffu, hi >> 16};
 #pragma unroll
         for (int j = 0; j < MQ; ++j)
-            cand_append(me && (q0 + j < nq) && sj[j] <= thr[j], sj[j] > qmax ? qmax : sj[j],
-                        (uint32_t)(n - 1), cand[j], cap, count[j]);
+            stage_append(me && (q0 + j < nq) && sj[j] <= thr[j], sj[j] > qmax ? qmax : sj[j],
+                         (uint32_t)(n - 1), wbuf + j * QADC_WSTAGE, nbuf[j], cand[j], cap, count[j]);
     }
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) stage_flush(wbuf + j * QADC_WSTAGE, nbuf[j], cand[j], cap, count[j]);
 }
 
 // ------------------------------------------------------------- k_scan_mqg ---
@@ -688,6 +700,9 @@ k_scan_mqg(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__re
     extern __shared__ __align__(16) unsigned char smem[];
     uint2 *tab = (uint2 *)smem;  // [gtab_len]
     __shared__ uint32_t s_thr[MQ];
+    __shared__ uint64_t s_stage[SCAN_THREADS / QADC_WAVE][MQ][QADC_WSTAGE];  // per wave and query
+    uint64_t *wbuf = &s_stage[threadIdx.x / QADC_WAVE][0][0];
+    uint32_t nbuf[MQ] = {0u, 0u, 0u, 0u};
     if (bound_rec) {  // wave j adds up the records of query q0 + j (SCAN_THREADS / 64 == MQ)
         const int j = threadIdx.x / QADC_WAVE;
         const size_t q = (blockIdx.y * MQ + j < nq) ? blockIdx.y * MQ + j : blockIdx.y * MQ;
@@ -794,9 +809,11 @@ k_scan_mqg(const pq_qparams_t *__restrict__ qparams, int nq, const uint8_t *__re
                 any = any || pass[i];
             }
             if (__ballot(any) != 0)
-                cand_append_multi<NC>(pass, key, id, cand[j], cap, count[j]);
+                stage_append_multi<NC>(pass, key, id, wbuf + j * QADC_WSTAGE, nbuf[j], cand[j], cap, count[j]);
         }
     }
+#pragma unroll
+    for (int j = 0; j < MQ; ++j) stage_flush(wbuf + j * QADC_WSTAGE, nbuf[j], cand[j], cap, count[j]);
 }
 
 // --------------------------------------------------------------- k_final ---
@@ -854,11 +871,11 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
             return PQ_EHIP;
         }
         if (KIND == SCAN_NIB8)
-            hipLaunchKernelGGL((k_scan_mq<8>), dim3(p.G, groups), dim3(SCAN_THREADS), 8 * 256 * 8 + 16, s,
+            hipLaunchKernelGGL((k_scan_mq<8>), dim3(p.G, groups), dim3(SCAN_THREADS), 8 * 256 * 8 + 16 + MQ_STAGE_BYTES, s,
                                qparams, nq, codes, n, ws, p.per_query, p.cand_off, p.gtab_off,
                                p.cap, (uint32_t)h.qmax, bound_rec, recP, reck);
         else
-            hipLaunchKernelGGL((k_scan_mq<16>), dim3(p.G, groups), dim3(SCAN_THREADS), 16 * 256 * 8 + 16, s,
+            hipLaunchKernelGGL((k_scan_mq<16>), dim3(p.G, groups), dim3(SCAN_THREADS), 16 * 256 * 8 + 16 + MQ_STAGE_BYTES, s,
                                qparams, nq, codes, n, ws, p.per_query, p.cand_off, p.gtab_off,
                                p.cap, (uint32_t)h.qmax, bound_rec, recP, reck);
         QADC_LAUNCH_CHECK("k_scan_mq");
@@ -890,7 +907,7 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
         // saves a dependent launch; the selection's LDS is then part of every scan block's
         const size_t lds_fused = gtab_bytes + sizeof(SelectLds<SCAN_THREADS, FUSED_CAP>);
         fused = !mqg && (what & 2) && R <= FUSED_R && lds_fused <= 20 * 1024;
-        const size_t lds_scan = fused ? lds_fused : gtab_bytes;
+        const size_t lds_scan = fused ? lds_fused : gtab_bytes + (SCAN_THREADS / QADC_WAVE) * QADC_WSTAGE * sizeof(uint64_t);
         const int fuse = fused ? 1 : 0;
 #define QADC_SCAN_GO(NGV, MODEV)                                                                     \
     hipLaunchKernelGGL((k_scan<KIND, QT, NGV, MODEV>), dim3(p.G, nq), dim3(SCAN_THREADS), lds_scan, \

@@ -397,6 +397,56 @@ __device__ __forceinline__ void cand_append(bool pass, uint32_t key, uint32_t id
     cand_append_multi<1>(&pass, &key, &id, cand, cap, count);
 }
 
+// Candidates on their way to the lists are staged per wave in LDS (QADC_WSTAGE entries), so that
+// the streaming loop issues no global atomic: a wave adds what it holds to its list when its
+// buffer would overflow and when it is done.  `nbuf` (entries staged) is wave-uniform.
+#define QADC_WSTAGE 32
+__device__ __forceinline__ void stage_flush(uint64_t *wbuf, uint32_t &nbuf, uint64_t *cand, uint32_t cap,
+                                            uint32_t *count) {
+    if (nbuf == 0) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the lanes' LDS writes before other lanes' reads
+    const uint32_t lane = __lane_id();
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(count, nbuf);
+    base = __builtin_amdgcn_readfirstlane(base);
+    if (lane < nbuf && base + lane < cap)
+        __hip_atomic_store((unsigned long long *)cand + base + lane, (unsigned long long)wbuf[lane],
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // ... and the reads before the buffer is reused
+    nbuf = 0;
+}
+template <int NS>
+__device__ __forceinline__ void stage_append_multi(const bool *pass, const uint32_t *key, const uint32_t *id,
+                                                   uint64_t *wbuf, uint32_t &nbuf, uint64_t *cand,
+                                                   uint32_t cap, uint32_t *count) {
+    uint64_t m[NS];
+    uint32_t total = 0;
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+        m[u] = __ballot(pass[u]);
+        total += (uint32_t)__popcll(m[u]);
+    }
+    if (total == 0) return;
+    if (nbuf + total > QADC_WSTAGE) stage_flush(wbuf, nbuf, cand, cap, count);
+    if (total > QADC_WSTAGE) {  // more than the buffer holds (a crowd of ties): straight to the list
+        cand_append_multi<NS>(pass, key, id, cand, cap, count);
+        return;
+    }
+    const int lane = __lane_id();
+    uint32_t base = nbuf;
+#pragma unroll
+    for (int u = 0; u < NS; ++u) {
+        if (pass[u])
+            wbuf[base + (uint32_t)__popcll(m[u] & ((1ull << lane) - 1ull))] = ((uint64_t)key[u] << 32) | (uint64_t)id[u];
+        base += (uint32_t)__popcll(m[u]);
+    }
+    nbuf = base;
+}
+__device__ __forceinline__ void stage_append(bool pass, uint32_t key, uint32_t id, uint64_t *wbuf, uint32_t &nbuf,
+                                             uint64_t *cand, uint32_t cap, uint32_t *count) {
+    stage_append_multi<1>(&pass, &key, &id, wbuf, nbuf, cand, cap, count);
+}
+
 // ------------------------------------------------- pruning bound from records ---
 // The quantizer's pilot may be counted by several blocks that never meet: block p of query q
 // leaves, for each of QADC_REC_BINS coarse key bins t (a coarse bin = four bins of the 256-bin
