@@ -327,7 +327,8 @@ def main():
         return main_encode(a)
     import numpy as np
     import torch
-    from paper_1812_09162_amd import binding as qb, synth
+    from paper_1812_09162_amd import binding as qb
+    from harness import synth
 
     assert torch.cuda.is_available(), "bench.py needs the GPU; there is no CPU fallback"
     dev = torch.device("cuda:0")
@@ -506,7 +507,8 @@ def main_ivf(a):
     """Workload C4: residual PQ 16x4 behind a coarse quantizer, nprobe lists per query."""
     import numpy as np
     import torch
-    from paper_1812_09162_amd import binding as qb, synth
+    from paper_1812_09162_amd import binding as qb
+    from harness import synth
     assert torch.cuda.is_available(), "bench.py needs the GPU; there is no CPU fallback"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -624,7 +626,8 @@ def main_encode(a):
     packed, so the ceiling is one such operation per lane and cycle: 256 CUs x 4 SIMDs x 16
     lanes x 2.4 GHz = 39.3 T operations/s."""
     import torch
-    from paper_1812_09162_amd import binding as qb, synth
+    from paper_1812_09162_amd import binding as qb
+    from harness import synth
     assert torch.cuda.is_available(), "bench.py needs the GPU; there is no CPU fallback"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

@@ -50,6 +50,7 @@ extern "C" {
 #define PQ_MAX_R 2048         /* results per query */
 #define PQ_MAX_T_EFF 8192     /* calibration codes: max(t, 4R) must not exceed this */
 #define PQ_MAX_DIM 4096
+#define PQ_MAX_NQ 65535       /* queries per call */
 
 /* Immutable description of a product quantizer; opaque. */
 typedef struct pq_index pq_index_t;
@@ -62,12 +63,14 @@ typedef struct pq_index pq_index_t;
  *             there was no code to calibrate on (all table entries are then 0)
  *   d_max     R-th smallest float ADC among the first t_eff codes
  *   key_bound an inclusive upper bound on the R-th best quantized key of the
- *             list: pq_quantize_tables sets it to the R-th smallest key among
- *             the first few ten thousand codes (a superset of the calibration
- *             codes).  The scan keeps only codes with key <= key_bound, so a
- *             caller who writes this record by hand must supply a valid bound;
- *             q_max is always valid but makes the scan fall back to a slow
- *             exact selection.
+ *             list.  Output of pq_quantize_tables (the R-th smallest key among
+ *             the first few ten thousand codes, a superset of the calibration
+ *             codes) and INPUT of pq_adc_scan_topk, which keeps only codes with
+ *             key <= key_bound.  A caller who writes this record by hand either
+ *             supplies a valid bound or PQ_KEY_BOUND_UNKNOWN (any value >= q_max
+ *             means the same): every code is then a candidate and the selection
+ *             takes its slow exact path.  A bound that is too small loses
+ *             results without an error.
  */
 typedef struct pq_qparams {
     double d_min;
@@ -75,6 +78,7 @@ typedef struct pq_qparams {
     float d_max;
     uint32_t key_bound;
 } pq_qparams_t;
+#define PQ_KEY_BOUND_UNKNOWN 0xffffffffu
 
 /*
  * Create an index handle.  Section 2.1.2 (product quantizer = m codebooks) and
@@ -139,7 +143,8 @@ int pq_quantize_tables(const pq_index_t *idx, const float *tables, int nq, const
  * Scan, eq. (2) with quantized tables and saturating unsigned sums at the
  * accumulator width (Section 3.4 last paragraph, Section 3.5), then the R
  * smallest (key, id) per query, id = position of the code in `codes`.
- *   qtables, qparams  as written by pq_quantize_tables (or by the caller)
+ *   qtables, qparams  as written by pq_quantize_tables, or by the caller (then see
+ *             pq_qparams_t.key_bound, an input here); nq <= PQ_MAX_NQ, R <= PQ_MAX_R
  *   codes     [dev][n][code_size], n < 2^31; must be 16-byte aligned
  *   out_ids   [dev][nq][R] int32       out_keys [dev][nq][R] uint16
  *   out_dist  [dev][nq][R] float32 = fmaf(key, (float)delta, (float)d_min)
@@ -176,17 +181,11 @@ int pq_adc_scan_topk_static(const pq_index_t *idx, const void *qtables, const pq
  * workspace, streams the codes and leaves, per query, the codes whose key is
  * within qparams.key_bound in the workspace; pq_select_topk turns those
  * candidates into the sorted top-R.  Calling the two in this order on one stream
- * is exactly pq_adc_scan_topk.  pq_adc_rescan_candidates repeats only the scan
- * kernel with the tables a previous pq_adc_scan_candidates call on the same
- * workspace and the same qtables prepared; benchmarks use it to time that kernel
- * alone.
+ * is exactly pq_adc_scan_topk.
  */
 int pq_adc_scan_candidates(const pq_index_t *idx, const void *qtables,
                            const pq_qparams_t *qparams, int nq, const uint8_t *codes, int64_t n,
                            int R, void *workspace, size_t workspace_bytes, void *stream);
-int pq_adc_rescan_candidates(const pq_index_t *idx, const void *qtables,
-                             const pq_qparams_t *qparams, int nq, const uint8_t *codes, int64_t n,
-                             int R, void *workspace, size_t workspace_bytes, void *stream);
 int pq_select_topk(const pq_index_t *idx, const void *qtables, const pq_qparams_t *qparams, int nq,
                    const uint8_t *codes, int64_t n, int R, int32_t *out_ids, uint16_t *out_keys,
                    float *out_dist, void *workspace, size_t workspace_bytes, void *stream);
@@ -273,29 +272,32 @@ int ivf_coarse_search(const float *queries, int nq, const float *centroids, int 
                       int32_t *probe_ids, float *probe_scores, void *workspace,
                       size_t workspace_bytes, void *stream);
 
-/*
- * Plain device-to-device copy by a library kernel (k_copy) whose traffic is known
- * exactly: nbytes read and nbytes written.  For scaling hardware-counter readings
- * (rocprofv3 FETCH_SIZE / WRITE_SIZE) taken in the same run as the scan kernel.
- * dst, src [dev], 16-byte aligned, non-overlapping; nbytes a multiple of 16.
- */
-int pq_copy_bytes(void *dst, const void *src, size_t nbytes, void *stream);
-
 /* Description of the last error on this thread ("" if none). */
 const char *pq_last_error(void);
 
 /*
- * Tuning knobs, read from the environment once per process (results never depend on them):
- *   QADC_G              scan blocks per query for one or a few queries (default 2048; fewer
- *                       leave room on the chip for other streams' small kernels)
- *   QADC_PILOT          pilot codes of the fused search when several blocks share it (262144)
- *   QADC_PILOT1         pilot codes when one block per query counts them (65536)
- *   QADC_PILOT_BLOCKS   most blocks per query that share a pilot (8)
- *   QADC_IVF_THREADS    threads per (query, list) block of the inverted-list scan: 64, 128 or
- *                       256, anything else means the default (128)
- *   QADC_NO_MQ          if set, batches are scanned one query per pass
- *   QADC_COARSE_MATRIX  if set, the coarse search always writes the full score matrix
+ * Tuning options.  Process-wide; none changes a result.  Workspace sizes depend on
+ * PQ_OPT_SCAN_BLOCKS and PQ_OPT_PILOT_BLOCKS: set those before asking for sizes, and do not
+ * change them between a size query and the call that uses the workspace.
+ * pq_set_option returns PQ_EINVAL for an unknown option or a value outside its range
+ * (pq_last_error says which); pq_get_option returns -1 for an unknown option.
  */
+enum {
+    PQ_OPT_SCAN_BLOCKS = 0,        /* scan blocks per query for one or a few queries: 1..4096 (2048) */
+    PQ_OPT_PILOT_CODES = 1,        /* codes the fused search samples for its pruning bound when
+                                      several blocks share them: 0..2^24 (262144) */
+    PQ_OPT_PILOT_CODES_SINGLE = 2, /* ... when one block per query counts them: 0..2^24 (65536) */
+    PQ_OPT_PILOT_BLOCKS = 3,       /* most blocks per query that share that sample: 1..64 (64) */
+    PQ_OPT_IVF_THREADS = 4,        /* threads per (query, list) block of the inverted-list scan:
+                                      64, 128 or 256 (128) */
+    PQ_OPT_SHARED_PASSES = 5,      /* 1: four queries of a batch share each pass over the codes;
+                                      0: one pass per query (1) */
+    PQ_OPT_COARSE_FILTER = 6,      /* 1: the coarse search keeps only scores within a sampled bound;
+                                      0: it always writes the full score matrix (1) */
+    PQ_OPT_COUNT = 7
+};
+int pq_set_option(int option, int64_t value);
+int64_t pq_get_option(int option);
 
 #ifdef __cplusplus
 }

@@ -27,7 +27,11 @@ EXPORTS = [
     "ivf_adc_scan_topk", "pq_search_workspace_bytes", "pq_search_topk",
     "pq_adc_scan_candidates", "pq_adc_rescan_candidates", "pq_select_topk", "pq_copy_bytes", "pq_last_error",
     "ivf_coarse_workspace_bytes", "ivf_coarse_search", "pq_encode", "pq_adc_scan_topk_static",
+    "pq_set_option", "pq_get_option",
 ]
+PQ_KEY_BOUND_UNKNOWN = 0xFFFFFFFF
+(PQ_OPT_SCAN_BLOCKS, PQ_OPT_PILOT_CODES, PQ_OPT_PILOT_CODES_SINGLE, PQ_OPT_PILOT_BLOCKS, PQ_OPT_IVF_THREADS,
+ PQ_OPT_SHARED_PASSES, PQ_OPT_COARSE_FILTER) = range(7)
 
 
 class QadcError(RuntimeError):
@@ -83,6 +87,10 @@ def load() -> ctypes.CDLL:
     lib.pq_select_topk.restype = i32
     lib.pq_copy_bytes.argtypes = [vp, vp, sz, vp]
     lib.pq_copy_bytes.restype = i32
+    lib.pq_set_option.argtypes = [i32, i64]
+    lib.pq_set_option.restype = i32
+    lib.pq_get_option.argtypes = [i32]
+    lib.pq_get_option.restype = i64
     lib.pq_last_error.argtypes = []
     lib.pq_last_error.restype = ctypes.c_char_p
     lib.pq_encode.argtypes = [vp, vp, i64, vp, vp, vp, vp]
@@ -307,6 +315,14 @@ def pq_copy_bytes(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(load().pq_copy_bytes(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+
+
+def pq_set_option(option: int, value: int) -> None:
+    _check(load().pq_set_option(option, value))
+
+
+def pq_get_option(option: int) -> int:
+    return int(load().pq_get_option(option))
 
 
 def unpack_qparams(qparams: torch.Tensor):

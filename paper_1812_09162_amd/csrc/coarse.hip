@@ -488,7 +488,7 @@ static unsigned cs_grid(unsigned gx, unsigned gy) { return gx * gy; }
 
 // The filtering form: pilot size (0 = use the matrix form) and what it needs per pass of qc queries.
 static int coarse_pilot(int K, int nprobe) {
-    static const bool off = getenv("QADC_COARSE_MATRIX") != nullptr;
+    const bool off = qadc_option(PQ_OPT_COARSE_FILTER) == 0;
     int64_t P = 64 * (int64_t)nprobe;
     if (P < 4096) P = 4096;
     P = (P + CS_TC - 1) / CS_TC * CS_TC;

@@ -19,6 +19,43 @@ void qadc_set_error(const char *fmt, ...) {
 
 extern "C" const char *pq_last_error(void) { return g_err; }
 
+// ----------------------------------------------------------- tuning options ---
+// Process-wide, set through pq_set_option; none changes a result.
+#include <atomic>
+static std::atomic<int64_t> g_opt[PQ_OPT_COUNT] = {
+    {2048},    // PQ_OPT_SCAN_BLOCKS
+    {262144},  // PQ_OPT_PILOT_CODES
+    {65536},   // PQ_OPT_PILOT_CODES_SINGLE
+    {64},      // PQ_OPT_PILOT_BLOCKS
+    {128},     // PQ_OPT_IVF_THREADS
+    {1},       // PQ_OPT_SHARED_PASSES
+    {1},       // PQ_OPT_COARSE_FILTER
+};
+
+int64_t qadc_option(int option) { return g_opt[option].load(std::memory_order_relaxed); }
+
+extern "C" int pq_set_option(int option, int64_t value) {
+    bool ok = option >= 0 && option < PQ_OPT_COUNT;
+    if (ok) switch (option) {
+        case PQ_OPT_SCAN_BLOCKS: ok = value >= 1 && value <= 4096; break;
+        case PQ_OPT_PILOT_CODES: ok = value >= 0 && value <= ((int64_t)1 << 24); break;
+        case PQ_OPT_PILOT_CODES_SINGLE: ok = value >= 0 && value <= ((int64_t)1 << 24); break;
+        case PQ_OPT_PILOT_BLOCKS: ok = value >= 1 && value <= 64; break;
+        case PQ_OPT_IVF_THREADS: ok = value == 64 || value == 128 || value == 256; break;
+        default: ok = value == 0 || value == 1; break;
+    }
+    if (!ok) {
+        qadc_set_error("pq_set_option: option %d does not take the value %lld", option, (long long)value);
+        return PQ_EINVAL;
+    }
+    g_opt[option].store(value, std::memory_order_relaxed);
+    return PQ_OK;
+}
+
+extern "C" int64_t pq_get_option(int option) {
+    return option >= 0 && option < PQ_OPT_COUNT ? qadc_option(option) : -1;
+}
+
 // Partition the sub-quantizers into consecutive groups of at most gmax bits.
 static void plan_groups(DevLayout &L, int gmax) {
     L.ng = 0;
@@ -175,12 +212,10 @@ ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R) {
     // A single query gets several times more blocks than fit on the chip at once: blocks
     // start cheaply (their tables are prepared beforehand) and the hardware hands the
     // next block to whichever compute unit finishes first, which evens out the tail.
-    static const int64_t g1 = getenv("QADC_G") ? atoll(getenv("QADC_G")) : 2048;
+    const int64_t g1 = qadc_option(PQ_OPT_SCAN_BLOCKS);
     int64_t gmax = 32768 / (nq > 0 ? nq : 1);
     if (gmax < 64) gmax = 64;
     if (gmax > g1) gmax = g1;
-    if (gmax > 4096) gmax = 4096;
-    if (gmax < 1) gmax = 1;  // a zero or negative QADC_G
     int64_t G = tiles < 1 ? 1 : (tiles > gmax ? gmax : tiles);
     p.G = (int)G;
     // candidate lists (QADC_NSUB per query): together four times the candidates expected when

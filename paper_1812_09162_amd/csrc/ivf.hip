@@ -808,10 +808,7 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
                        idx->codebooks, coarse, list_offsets, list_codes, queries, probe_ids, nprobe, K, want, pilot_want, R, ws,
                        p.per_query);
     QADC_LAUNCH_CHECK("k_ivf_calib");
-    static const int scan_threads = [] {
-        const int v = getenv("QADC_IVF_THREADS") ? atoi(getenv("QADC_IVF_THREADS")) : 128;
-        return (v == 64 || v == 128 || v == 256) ? v : 128;  // whole waves, at most the launch bound
-    }();
+    const int scan_threads = (int)qadc_option(PQ_OPT_IVF_THREADS);
     // table entries per thread: the low-latency set-up holds up to four in registers
     const int ne = idx->h.T <= scan_threads ? 1 : (idx->h.T <= 2 * scan_threads ? 2 : (idx->h.T <= 4 * scan_threads ? 4 : 0));
 #define QADC_IVF_SCAN(NEV)                                                                          \

@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "qadc.h"
+#include "qadc_bench.h"
 
 // Layout of a product quantizer as the kernels see it.  A copy lives in device
 // memory; kernels read it through uniform (scalar) loads.
@@ -82,6 +83,8 @@ struct ScanPlan {
 };
 
 void qadc_set_error(const char *fmt, ...);
+// Current value of a tuning option (PQ_OPT_*), set through pq_set_option.
+int64_t qadc_option(int option);
 ScanPlan qadc_scan_plan(const pq_index *idx, int nq, int64_t n, int R);
 
 // Pilot of the distance quantizer: `pilot` codes, counted by P blocks per query, `slice` each.

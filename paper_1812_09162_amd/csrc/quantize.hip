@@ -348,18 +348,12 @@ k_quantize(const DevLayout *__restrict__ L, const QuantShape shape, const EntryD
     }
 }
 
-static int64_t pilot_env(const char *name, int64_t dflt) {
-    const char *e = getenv(name);
-    int64_t v = e ? atoll(e) : dflt;
-    return v < 0 ? 0 : v;
-}
-
 // Codes one pilot block counts per batch (eight per thread) and at most in total.
 #define PILOT_BATCH (8 * QUANT_THREADS)
 #define PILOT_BLOCK_MAX 65536
 
 int qadc_pilot_blocks_max(int nq) {
-    static const int64_t cap = pilot_env("QADC_PILOT_BLOCKS", 64);
+    const int64_t cap = qadc_option(PQ_OPT_PILOT_BLOCKS);
     int pmax = 2048 / (nq > 0 ? nq : 1);  // (blocks of 256 threads: a few thousand fill the chip)
     pmax = pmax < 1 ? 1 : (pmax > QADC_REC_SLOTS ? QADC_REC_SLOTS : pmax);
     return cap >= 1 && cap < pmax ? (int)cap : pmax;
@@ -373,8 +367,8 @@ size_t qadc_pilot_scratch_bytes(int nq) {
 // memory (the fused search) a small batch of queries spreads a large pilot over many
 // blocks; without it every query has one block and the pilot stays small.
 PilotPlan qadc_pilot_plan(int nq, int64_t n, int t_eff, int R, bool have_scratch) {
-    static const int64_t multi = pilot_env("QADC_PILOT", 262144);
-    static const int64_t single = pilot_env("QADC_PILOT1", PILOT_BLOCK_MAX);
+    const int64_t multi = qadc_option(PQ_OPT_PILOT_CODES);
+    const int64_t single = qadc_option(PQ_OPT_PILOT_CODES_SINGLE);
     PilotPlan pp;
     const int pmax = have_scratch ? qadc_pilot_blocks_max(nq) : 1;
     int64_t want = pmax > 1 ? multi : single;

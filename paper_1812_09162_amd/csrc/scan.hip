@@ -853,7 +853,7 @@ static int launch_scan(const pq_index *idx, const void *qtables, const pq_qparam
                            idx->dev, qtables, ws, p.per_query, p.gtab_off);
         QADC_LAUNCH_CHECK("k_prepare");
     }
-    static const bool no_mq = getenv("QADC_NO_MQ") != nullptr;
+    const bool no_mq = qadc_option(PQ_OPT_SHARED_PASSES) == 0;
     bool fused = false;  // the scan kernel's last block does the selection
     if ((what & 1) && sizeof(QT) == 1 && nq >= 2 && (KIND == SCAN_NIB8 || KIND == SCAN_NIB16) && !no_mq) {
         // several queries: four of them share every pass over the codes

@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "qadc.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("qadc.h", "qadc_bench.h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b((?:pq|ivf)_[a-z_]+)\s*\(", text)))
 
@@ -53,6 +53,18 @@ def test_index_create_rejects_bad_shapes_before_touching_the_gpu():
     assert create(0, [4], [0], 8) == qb.PQ_EINVAL
     assert create(17 * 8, [8] * 17, [8] * 17, 8) == qb.PQ_EINVAL  # table longer than the limit
     assert h.value is None
+
+
+def test_options_are_validated_and_kept():
+    lib = qb.load()
+    assert lib.pq_get_option(qb.PQ_OPT_SCAN_BLOCKS) == 2048
+    assert lib.pq_set_option(qb.PQ_OPT_SCAN_BLOCKS, 0) == qb.PQ_EINVAL       # out of range: unchanged
+    assert lib.pq_set_option(qb.PQ_OPT_IVF_THREADS, 100) == qb.PQ_EINVAL
+    assert lib.pq_set_option(99, 1) == qb.PQ_EINVAL and b"option 99" in lib.pq_last_error()
+    assert lib.pq_get_option(99) == -1
+    assert lib.pq_set_option(qb.PQ_OPT_SCAN_BLOCKS, 1024) == qb.PQ_OK
+    assert lib.pq_get_option(qb.PQ_OPT_SCAN_BLOCKS) == 1024
+    assert lib.pq_set_option(qb.PQ_OPT_SCAN_BLOCKS, 2048) == qb.PQ_OK
 
 
 def test_calls_reject_null_handle():

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import oracle
-from paper_1812_09162_amd import synth
+from harness import synth
 
 pytestmark = pytest.mark.gpu
 

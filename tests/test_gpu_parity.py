@@ -11,7 +11,7 @@ import pytest
 import torch
 
 import oracle
-from paper_1812_09162_amd import synth
+from harness import synth
 
 pytestmark = pytest.mark.gpu
 
@@ -292,11 +292,12 @@ def test_caller_supplied_qparams_without_hint(qb):
     tables, qt, qp, ids, keys, dist = gpu_search(qb, idx, pr.queries.to(dev()), codes_d, 100)
     raw = qp.cpu().numpy().copy()
     rec = raw.view(np.dtype([("d_min", "<f8"), ("delta", "<f8"), ("d_max", "<f4"), ("kb", "<u4")]))
-    rec["kb"] = 255
-    qp2 = torch.from_numpy(raw).to(dev())
-    ids2, keys2, dist2 = qb.pq_adc_scan_topk(idx, qt, qp2, codes_d, 100)
-    torch.cuda.synchronize()
-    assert torch.equal(ids, ids2) and torch.equal(keys, keys2) and torch.equal(dist, dist2)
+    for unknown in (255, qb.PQ_KEY_BOUND_UNKNOWN):
+        rec["kb"] = unknown
+        qp2 = torch.from_numpy(raw.copy()).to(dev())
+        ids2, keys2, dist2 = qb.pq_adc_scan_topk(idx, qt, qp2, codes_d, 100)
+        torch.cuda.synchronize()
+        assert torch.equal(ids, ids2) and torch.equal(keys, keys2) and torch.equal(dist, dist2)
     idx.close()
 
 

@@ -10,7 +10,7 @@ import pytest
 import torch
 
 import oracle
-from paper_1812_09162_amd import synth
+from harness import synth
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -564,9 +564,12 @@ def test_encode_fixed_points_ties_and_shift():
     assert np.array_equal(oracle.encode(d, nbits, lay.dsub, cb, x + shift, shift), oracle.encode(d, nbits, lay.dsub, cb, x))
 
 
-def test_encode_agrees_with_the_input_fabricator_on_exact_data():
-    """The harness encoder is a separate implementation (matrix form); on small integers both
-    are exact and must agree bit for bit, packing included."""
+def test_input_fabricator_writes_the_codes_the_pinned_encoder_writes():
+    """A check of the input fabricator, not of the oracle: the oracle's encoder is pinned above
+    (hand-packed layouts, fp64 brute force, fixed points, ties, shift).  The fabricator's own
+    encoder (matrix form, used to make synthetic codes at sizes the oracle cannot) must write
+    the same codes on data where both are exact, packing included, so that the synthetic inputs
+    really are nearest-centroid codes."""
     pr = synth.make_problem(n=400, nq=1, d=12, nbits=[4, 3, 5, 4], acc_bits=16, dist="gamma_ints",
                             seed=5, train_n=400, kmeans_iters=0)
     lay = pr.layout

@@ -5,7 +5,7 @@ the array's size."""
 import pytest
 import torch
 
-from paper_1812_09162_amd import synth
+from harness import synth
 
 pytestmark = pytest.mark.gpu
 
