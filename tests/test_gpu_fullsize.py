@@ -1,6 +1,7 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
-(fused pq_search_topk, one query per call, and a 32-query batch): a sample of queries is
-compared bit for bit with the CPU oracle, and all batch sizes must agree with each other.
+(fused pq_search_topk, one query per call): every configured query is run in batches of 1, 32
+and 256, which must agree byte for byte, and a sample of queries is compared bit for bit with
+the CPU oracle.
 
 Data sets are fabricated on the GPU (seconds); the oracle runs one query per host thread.
 The 10^8-vector IVF configuration is fabricated with 3 Lloyd iterations for its 65,536-cell
@@ -44,35 +45,52 @@ def oracle_many(pr, qsel, R, codes_np):
         return list(ex.map(one, range(len(qsel))))
 
 
-def run_flat(qb, name, Rs, nq_oracle, nq_gpu=64):
+def run_flat(qb, name, Rs, nq_oracle, nq_gpu=None):
+    """nq_gpu = None: every query the configuration has (10,000 for C1, 1,000 for C2 and C3)."""
     cfg = dict(synth.CONFIGS[name])
-    cfg["nq"] = nq_gpu
+    if nq_gpu is not None:
+        cfg["nq"] = nq_gpu
     pr = synth.build(cfg, device=dev())
     lay = pr.layout
     idx = qb.PqIndex(lay.d, lay.nbits, lay.dsub, pr.codebooks, lay.acc_bits)
     codes_np = pr.codes.cpu().numpy()
+    nq, n = pr.queries.shape[0], pr.codes.shape[0]
     qsel = list(range(nq_oracle))
     for R in Rs:
-        # the configuration bench.py times: one query per fused call
-        singles = [qb.pq_search_topk(idx, pr.queries[q:q + 1].contiguous(), pr.codes, T_CAL, R)
-                   for q in qsel]
-        batch = qb.pq_search_topk(idx, pr.queries[:32].contiguous(), pr.codes, T_CAL, R)
-        torch.cuda.synchronize()
+        def outputs():
+            return (torch.full((nq, R), -7, dtype=torch.int32, device=dev()),
+                    torch.full((nq, R), 9, dtype=torch.uint16, device=dev()),
+                    torch.full((nq, R), -1.0, dtype=torch.float32, device=dev()))
+
+        # every query in batches of 1 (the configuration bench.py times), 32 and 256: the result
+        # is defined as a sort, so the three must agree byte for byte
+        by_batch = {}
+        for bs in (1, 32, 256):
+            out = outputs()
+            ws = torch.empty(qb.pq_search_workspace_bytes(idx, bs, n, R), dtype=torch.uint8, device=dev())
+            for lo in range(0, nq, bs):
+                hi = min(nq, lo + bs)
+                qb.pq_search_topk(idx, pr.queries[lo:hi], pr.codes, T_CAL, R, workspace=ws,
+                                  out=tuple(o[lo:hi] for o in out))
+            torch.cuda.synchronize()
+            by_batch[bs] = out
+        for bs in (32, 256):
+            for a, b in zip(by_batch[1], by_batch[bs]):
+                assert torch.equal(a, b), (name, R, bs, int((a != b).any(dim=1).nonzero()[0]))
+        # a sample of them against the oracle
         ref = oracle_many(pr, qsel, R, codes_np)
         for q in qsel:
             oi, ok, od = ref[q]
-            gi, gk, gd = (x[0].cpu().numpy() for x in singles[q])
+            gi, gk, gd = (x[q].cpu().numpy() for x in by_batch[1])
             assert np.array_equal(gi, oi), (name, R, q, gi[:8], oi[:8])
             assert np.array_equal(gk.astype(np.uint16), ok)
             assert np.array_equal(gd, od)
-            for a, b in zip(singles[q], batch):
-                assert torch.equal(a[0], b[q])
         # property that holds at any size: keys ascending, ids ascending within equal keys, all valid
-        k = batch[1].cpu().numpy().astype(np.int64)
-        i = batch[0].cpu().numpy().astype(np.int64)
+        k = by_batch[1][1].cpu().numpy().astype(np.int64)
+        i = by_batch[1][0].cpu().numpy().astype(np.int64)
         assert np.all(np.diff(k, axis=1) >= 0)
         assert np.all((np.diff(k, axis=1) > 0) | (np.diff(i, axis=1) > 0))
-        assert i.min() >= 0 and i.max() < pr.codes.shape[0]
+        assert i.min() >= 0 and i.max() < n
     idx.close()
 
 
@@ -88,19 +106,26 @@ def test_c3_full_size(qb):
     run_flat(qb, "C3", [100], nq_oracle=4)
 
 
-@pytest.mark.parametrize("name", ["L8x8", "L664", "L16x8", "L664x2"])
+@pytest.mark.parametrize("name", ["L8x8", "L664", "L655", "L16x8", "L664x2"])
 def test_further_layouts_full_size(qb, name):
     """The 64- and 128-bit layouts bench.py offers as workloads, at their 10^7 codes."""
-    run_flat(qb, name, [100], nq_oracle=2, nq_gpu=32)
+    run_flat(qb, name, [100], nq_oracle=2, nq_gpu=300)
 
 
 def run_ivf(qb, cfg, nq_oracle, R=100):
     ip = synth.build(cfg, device=dev())
     lay = ip.layout
     idx = qb.PqIndex(lay.d, lay.nbits, lay.dsub, ip.codebooks, lay.acc_bits)
+    # the default workspace (blocks in the order of the probed cells) and the minimal one (grid order)
     gi, gd = qb.ivf_adc_scan_topk(idx, ip.coarse, ip.list_offsets, ip.list_codes, ip.list_ids,
                                   ip.queries, ip.probe_ids, T_CAL, R)
+    small = torch.empty(qb.ivf_workspace_bytes(idx, ip.probe_ids.shape[0], ip.probe_ids.shape[1], R),
+                        dtype=torch.uint8, device=dev())
+    gi2, gd2 = qb.ivf_adc_scan_topk(idx, ip.coarse, ip.list_offsets, ip.list_codes, ip.list_ids,
+                                    ip.queries, ip.probe_ids, T_CAL, R, workspace=small)
     torch.cuda.synchronize()
+    assert torch.equal(gi, gi2) and torch.equal(gd, gd2)
+    del small, gi2, gd2
     host = dict(cb=ip.codebooks.cpu().numpy(), coarse=ip.coarse.cpu().numpy(),
                 off=ip.list_offsets.cpu().numpy(), codes=ip.list_codes.cpu().numpy(),
                 ids=ip.list_ids.cpu().numpy(), q=ip.queries.cpu().numpy(),
