@@ -158,6 +158,23 @@ def search_ivf(d, nbits, dsub, acc_bits, codebooks, coarse, list_offsets, list_c
     return ids, od, float(dmax[0])
 
 
+def search_ivf_tightening(d, nbits, dsub, acc_bits, codebooks, coarse, list_offsets, list_codes, list_ids,
+                          z, probe, t, R):
+    """O6b for one query: (ids[R], dist[R], d_max, bounds[nprobe])."""
+    nb, ds, cb, z = _i32(nbits), _i32(dsub), _f32(codebooks), _f32(z)
+    coarse = _f32(coarse)
+    lo = np.ascontiguousarray(np.asarray(list_offsets, dtype=np.int64))
+    lc, li, pr = _u8(list_codes), _i32(list_ids), _i32(probe)
+    ids = np.empty(R, dtype=np.int32)
+    od = np.empty(R, dtype=np.float32)
+    dmax = np.empty(1, dtype=np.float32)
+    bounds = np.empty(pr.shape[0], dtype=np.float32)
+    _load().oracle_search_ivf_tightening(int(d), len(nb), _p(nb), _p(ds), int(acc_bits), _p(cb), _p(coarse),
+                                         _p(lo), _p(lc), _p(li), _p(z), _p(pr), int(pr.shape[0]), int(t),
+                                         int(R), _p(ids), _p(od), _p(dmax), _p(bounds))
+    return ids, od, float(dmax[0]), bounds
+
+
 def coarse_search(centroids, z, nprobe):
     """O7 for one query: (ids[nprobe], scores[nprobe]) of the nearest cells."""
     cen, z = _f32(centroids), _f32(z)

@@ -17,6 +17,8 @@
  *                                  Section 3.4, d = (sum q) Delta + d_min
  *   O6  inverted-list search       Section 2.1.1 (residuals), Section 2.1.3
  *                                  (one table set per probed cell)
+ *   O6b the same with a bound that tightens from list to list (optional mode)
+ *                                  Sections 3.4, 3.5
  *   O7  coarse-quantizer search    Section 2.1.1 (the cells a query is routed to)
  *   O8  encoding and packing       Sections 2.1.2, 2.1.1, 3.3
  *
@@ -386,6 +388,102 @@ void oracle_search_ivf(int d, int m, const int32_t *nbits, const int32_t *dsub, 
         }
     }
     free(cand);
+    free(table);
+    free(qtable);
+    free(pmin);
+}
+
+/*
+ * O6b: the inverted-list search with a bound that tightens from list to list (optional mode).
+ * Section 3.5: a scanned vector is compared with the worst of the R candidates held and kept
+ * when it is closer; Section 3.4: the distance of the R-th candidate is the largest distance
+ * the quantizer has to represent.  Read together for several lists visited one after the
+ * other: the lists are scanned in probe order, and list l is quantized against
+ *     cur_l = min(d_max, R-th smallest unquantized distance among all codes of the unskipped
+ *                        lists before l)           (the second term only once R codes were seen)
+ * with d_max the calibration bound of O6.  A list with d_min >= cur_l is skipped.  A code of
+ * the other lists whose sum saturates (key = q_max, the value Section 3.4 reserves for a
+ * distance that is too large) is not a candidate: unlike in O6, where the bound is fixed and
+ * generous, a saturated code here is one that is not closer than the worst candidate held.
+ * Every other code gets dist = fmaf(key, (float)Delta_l, (float)d_min_l) with the list's own
+ * Delta_l = (cur_l - d_min_l)/q_max; the R smallest (dist, stored id) are returned, fewer (the
+ * rest padded) if fewer codes stayed below their bounds.  cur_l never grows, so later lists
+ * are quantized more finely than in O6; the result depends on the probe order by construction.  out_bounds[a] receives cur for probe a (the value its list was,
+ * or would have been, quantized against); may be NULL.
+ */
+void oracle_search_ivf_tightening(int d, int m, const int32_t *nbits, const int32_t *dsub, int acc_bits,
+                                  const float *codebooks, const float *coarse,
+                                  const int64_t *list_offsets, const uint8_t *list_codes,
+                                  const int32_t *list_ids, const float *z, const int32_t *probe,
+                                  int nprobe, int t, int R, int32_t *out_ids, float *out_dist,
+                                  float *out_dmax, float *out_bounds) {
+    layout_t L = {d, m, nbits, dsub, acc_bits};
+    int T = table_len(&L), cs = code_size(&L);
+    float *table = (float *)malloc(sizeof(float) * (size_t)T);
+    uint16_t *qtable = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)T);
+    float *pmin = (float *)malloc(sizeof(float) * (size_t)m);
+
+    int64_t nprobed = 0;
+    for (int a = 0; a < nprobe; ++a)
+        if (probe[a] >= 0) nprobed += list_offsets[probe[a] + 1] - list_offsets[probe[a]];
+    int64_t te = oracle_t_eff(nprobed, t, R);
+
+    /* calibration exactly as in O6 */
+    float dmax = INFINITY;
+    if (te > 0) {
+        float *s = (float *)malloc(sizeof(float) * (size_t)te);
+        int64_t seen = 0;
+        for (int a = 0; a < nprobe && seen < te; ++a) {
+            if (probe[a] < 0) continue;
+            int64_t lo = list_offsets[probe[a]], hi = list_offsets[probe[a] + 1];
+            if (hi == lo) continue;
+            oracle_tables(d, m, nbits, dsub, codebooks, z, coarse + (size_t)probe[a] * d, table);
+            for (int64_t p = lo; p < hi && seen < te; ++p)
+                s[seen++] = adc_float(&L, table, list_codes + p * cs);
+        }
+        dmax = kth_smallest(s, te, R < te ? R : te);
+        free(s);
+    }
+    *out_dmax = dmax;
+
+    fid_t *cand = (fid_t *)malloc(sizeof(fid_t) * (size_t)(nprobed > 0 ? nprobed : 1));
+    float *dists = (float *)malloc(sizeof(float) * (size_t)(nprobed > 0 ? nprobed : 1));
+    int64_t nc = 0;
+    float cur = dmax;
+    for (int a = 0; a < nprobe; ++a) {
+        if (out_bounds) out_bounds[a] = cur;
+        if (probe[a] < 0) continue;
+        int64_t lo = list_offsets[probe[a]], hi = list_offsets[probe[a] + 1];
+        if (hi == lo) continue;
+        oracle_tables(d, m, nbits, dsub, codebooks, z, coarse + (size_t)probe[a] * d, table);
+        double dmin = table_minima(&L, table, pmin);
+        if (dmin >= (double)cur) continue; /* nothing in this list is closer than the bound */
+        double delta = quantize_table(&L, table, pmin, dmin, cur, qtable);
+        for (int64_t p = lo; p < hi; ++p) {
+            uint32_t key = adc_key(&L, qtable, list_codes + p * cs);
+            if (key == q_max_of(&L)) continue; /* saturated: not closer than the bound */
+            cand[nc].dist = fmaf((float)key, (float)delta, (float)dmin);
+            cand[nc].id = list_ids[p];
+            dists[nc] = cand[nc].dist;
+            ++nc;
+        }
+        if (nc >= R) { /* the worst of the R best seen so far */
+            float worst = kth_smallest(dists, nc, R);
+            if (worst < cur) cur = worst;
+        }
+    }
+    qsort(cand, (size_t)nc, sizeof(fid_t), cmp_fid);
+    for (int r = 0; r < R; ++r) {
+        if (r < nc) {
+            out_ids[r] = cand[r].id;
+            out_dist[r] = cand[r].dist;
+        } else {
+            out_ids[r] = -1;
+            out_dist[r] = INFINITY;
+        }
+    }
+    free(cand);
+    free(dists);
     free(table);
     free(qtable);
     free(pmin);

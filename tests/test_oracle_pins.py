@@ -366,6 +366,7 @@ def test_ivf_against_reconstruction_brute_force(acc_bits, nbits, d, R):
         te = oracle.t_eff(len(probed_pos), 400, R)
         assert dmax == pytest.approx(np.sort(true[probed_pos[:te]])[min(R, te) - 1], rel=1e-4)
         # results come from probed lists only, ordered by (dist, id)
+        assert np.all(ids >= 0)
         assert np.all(np.isin(cell_of[pos_of_id[ids]], probe))
         assert np.all((np.diff(dist) > 0) | ((np.diff(dist) == 0) & (np.diff(ids) > 0)))
         # unquantized distance is within (d - m*Delta_l, d] of the true residual distance,
@@ -430,6 +431,84 @@ def test_ivf_list_with_d_min_equal_to_d_max_is_skipped():
     assert dmax == g["d_max"]
     assert ids.tolist() == g["top_ids"]
     assert dist.tolist() == g["top_dist"]
+
+
+def ivf_tight_call(pr, q, R, t=400, probe=None):
+    lay = pr.layout
+    return oracle.search_ivf_tightening(lay.d, lay.nbits, lay.dsub, lay.acc_bits, pr.codebooks.numpy(),
+                                        pr.coarse.numpy(), pr.list_offsets.numpy(), pr.list_codes.numpy(),
+                                        pr.list_ids.numpy(), pr.queries[q].numpy(),
+                                        pr.probe_ids[q].numpy() if probe is None else probe, t, R)
+
+
+def test_ivf_tightening_worked_example():
+    g = json.load(open(os.path.join(GOLD, "ivf_tightening_example.json")))
+    lay = synth.Layout(d=g["d"], nbits=g["nbits"], dsub=g["dsub"], acc_bits=g["acc_bits"])
+    codes = synth.pack_codes(torch.tensor(g["list_subcodes"], dtype=torch.uint8), lay).numpy()
+    args = (g["d"], g["nbits"], g["dsub"], g["acc_bits"], np.array(g["codebooks"], np.float32),
+            np.array(g["coarse"], np.float32), np.array(g["list_offsets"], np.int64), codes,
+            np.array(g["list_ids"], np.int32), np.array(g["query"], np.float32),
+            np.array(g["probe"], np.int32), g["t"], g["R"])
+    ids, dist, dmax, bounds = oracle.search_ivf_tightening(*args)
+    assert dmax == g["d_max"]
+    assert ids.tolist() == g["top_ids_tightening"] and dist.tolist() == g["top_dist_tightening"]
+    assert bounds[0] == g["d_max"]
+    # 3 steps of float(272/255): the fp32 product, as the unquantize formula gives it
+    step32 = np.float32(np.float64(g["d_max"]) / 255.0)
+    assert bounds[1] == np.float32(np.float64(3.0) * np.float64(step32))
+    assert bounds[1] == pytest.approx(g["bound_after_first_list_num"] / g["bound_after_first_list_den"], rel=1e-6)
+    ids0, _, _ = oracle.search_ivf(*args)
+    assert ids0.tolist() == g["top_ids_fixed_bound"]
+    # a code that saturates against the tightened bound is no candidate
+    rows = g["saturated_variant_rows"]
+    var = list(args)
+    var[6] = np.array(g["saturated_variant_list_offsets"], np.int64)
+    var[7], var[8] = codes[rows], np.array(g["list_ids"], np.int32)[rows]
+    ids, dist, _, bounds = oracle.search_ivf_tightening(*var)
+    assert ids.tolist() == g["saturated_variant_top_ids"] and dist[0] == bounds[1]
+
+
+@pytest.mark.parametrize("acc_bits,nbits,d,R", [(8, None, 32, 15), (16, None, 32, 15), (8, [6, 6, 4], 8, 60)])
+def test_ivf_tightening_properties(acc_bits, nbits, d, R):
+    pr = small_ivf(acc_bits=acc_bits, nbits=nbits, d=d, n=6000, K=12, nprobe=6)
+    lay = pr.layout
+    sub = oracle.unpack(lay.nbits, pr.list_codes.numpy())
+    dec = decode(lay, pr.codebooks.numpy(), sub)
+    offs = pr.list_offsets.numpy()
+    cell_of = np.repeat(np.arange(len(offs) - 1), np.diff(offs))
+    recon = dec + pr.coarse.numpy().astype(np.float64)[cell_of]
+    pos_of_id = np.empty(len(cell_of), np.int64)
+    pos_of_id[pr.list_ids.numpy()] = np.arange(len(cell_of))
+    tightened = 0
+    for q in range(pr.queries.shape[0]):
+        z = pr.queries[q].numpy().astype(np.float64)
+        probe = pr.probe_ids[q].numpy()
+        ids, dist, dmax, bounds = ivf_tight_call(pr, q, R)
+        ids0, dist0, dmax0 = ivf_call(pr, q, R)
+        assert dmax == dmax0                                   # same calibration
+        assert bounds[0] == np.float32(dmax)
+        assert np.all(np.diff(bounds) <= 0)                    # the bound never grows
+        tightened += int(bounds[-1] < bounds[0])
+        # one probed list: nothing to tighten, the fixed-bound search exactly
+        one = probe[:1]
+        a = ivf_tight_call(pr, q, R, probe=one)
+        b = ivf_call(pr, q, R, probe=one)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+        # results: probed lists only, ordered by (dist, id), and as good as the quantizer allows:
+        # unquantized distance within (true - m * Delta, true], Delta <= d_max / q_max
+        true = ((recon - z[None, :]) ** 2).sum(1)
+        probed_pos = np.concatenate([np.arange(offs[c], offs[c + 1]) for c in probe])
+        assert np.all(np.isin(cell_of[pos_of_id[ids]], probe))
+        assert np.all((np.diff(dist) > 0) | ((np.diff(dist) == 0) & (np.diff(ids) > 0)))
+        step = lay.m * dmax / lay.q_max
+        t_ids = true[pos_of_id[ids]]
+        assert np.all(dist <= t_ids + 1e-4 * t_ids)
+        assert np.all(dist > t_ids - step - 1e-4 * t_ids)
+        kth = np.sort(true[probed_pos])[R - 1]
+        assert t_ids.max() <= kth + step + 1e-4 * kth
+        # a finer quantizer cannot make the R-th result worse than the fixed bound's by more than a step
+        assert dist[-1] <= dist0[-1] + step
+    assert tightened >= pr.queries.shape[0] // 2                 # the mode really is exercised
 
 
 # ---------------------------------------------------------------- O7: coarse-quantizer search
