@@ -233,6 +233,32 @@ int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_centroids, int 
                       float *out_dist, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Inverted-list search with a bound that tightens from list to list (optional
+ * mode).  Section 3.5: a scanned vector is kept when it is closer than the worst
+ * of the R candidates held; Section 3.4: that worst distance is the largest
+ * distance the quantizer has to represent.  For every query the probed lists are
+ * visited in probe order, and list l is quantized against
+ *     cur_l = min(d_max, R-th smallest dist among the candidates of the lists
+ *                        visited before l)     (the second term once R are held)
+ * with d_max the calibration bound of ivf_adc_scan_topk: p_min / d_min as there,
+ * delta_l = (cur_l - d_min_l) / q_max; a list with d_min_l >= cur_l is skipped;
+ * a code whose sum saturates (key = q_max) is no candidate; every other code
+ * gets dist = fmaf(key, (float)delta_l, (float)d_min_l).  The R smallest
+ * (dist, stored id) are returned, fewer (ids -1, dist +inf) if fewer codes stayed
+ * below their bounds.  Later lists are quantized more finely than with the fixed
+ * bound; the result depends on the probe order by construction.
+ * Arguments, workspace size (ivf_workspace_bytes), limits and errors as for
+ * ivf_adc_scan_topk.  One block of 256 threads serves a query: the call needs a
+ * few hundred queries to fill the chip.
+ */
+int ivf_adc_scan_topk_tightening(const pq_index_t *idx, const float *coarse_centroids, int K,
+                                 const int64_t *list_offsets, const uint8_t *list_codes,
+                                 const int32_t *list_ids, const float *queries, int nq,
+                                 const int32_t *probe_ids, int nprobe, int t, int R,
+                                 int32_t *out_ids, float *out_dist, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+
+/*
  * Encode vectors (Section 2.1.2: every sub-vector is replaced by the index of its
  * nearest centroid; Section 2.1.1: behind an inverted index the residual
  * x - centroid is encoded; Section 3.3: sub-codes are packed as a little-endian

@@ -408,8 +408,9 @@ void oracle_search_ivf(int d, int m, const int32_t *nbits, const int32_t *dsub, 
  * Every other code gets dist = fmaf(key, (float)Delta_l, (float)d_min_l) with the list's own
  * Delta_l = (cur_l - d_min_l)/q_max; the R smallest (dist, stored id) are returned, fewer (the
  * rest padded) if fewer codes stayed below their bounds.  cur_l never grows, so later lists
- * are quantized more finely than in O6; the result depends on the probe order by construction.  out_bounds[a] receives cur for probe a (the value its list was,
- * or would have been, quantized against); may be NULL.
+ * are quantized more finely than in O6; the result depends on the probe order by construction.
+ * out_bounds[a] receives cur for probe a (the value its list was, or would have been,
+ * quantized against); may be NULL.
  */
 void oracle_search_ivf_tightening(int d, int m, const int32_t *nbits, const int32_t *dsub, int acc_bits,
                                   const float *codebooks, const float *coarse,

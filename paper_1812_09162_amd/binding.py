@@ -27,7 +27,7 @@ EXPORTS = [
     "ivf_adc_scan_topk", "pq_search_workspace_bytes", "pq_search_topk",
     "pq_adc_scan_candidates", "pq_adc_rescan_candidates", "pq_select_topk", "pq_copy_bytes", "pq_last_error",
     "ivf_coarse_workspace_bytes", "ivf_coarse_search", "pq_encode", "pq_adc_scan_topk_static",
-    "pq_set_option", "pq_get_option",
+    "pq_set_option", "pq_get_option", "ivf_adc_scan_topk_tightening",
 ]
 PQ_KEY_BOUND_UNKNOWN = 0xFFFFFFFF
 (PQ_OPT_SCAN_BLOCKS, PQ_OPT_PILOT_CODES, PQ_OPT_PILOT_CODES_SINGLE, PQ_OPT_PILOT_BLOCKS, PQ_OPT_IVF_THREADS,
@@ -75,6 +75,8 @@ def load() -> ctypes.CDLL:
     lib.ivf_adc_scan_topk.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, vp, i32, i32, i32, vp, vp,
                                       vp, sz, vp]
     lib.ivf_adc_scan_topk.restype = i32
+    lib.ivf_adc_scan_topk_tightening.argtypes = lib.ivf_adc_scan_topk.argtypes
+    lib.ivf_adc_scan_topk_tightening.restype = i32
     lib.pq_search_workspace_bytes.argtypes = [vp, i32, i64, i32]
     lib.pq_search_workspace_bytes.restype = sz
     lib.pq_search_topk.argtypes = [vp, vp, i32, vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
@@ -277,6 +279,31 @@ def ivf_adc_scan_topk(idx: PqIndex, coarse: torch.Tensor, list_offsets: torch.Te
                                     _ptr(list_codes), _ptr(list_ids), _ptr(queries), nq,
                                     _ptr(probe_ids), nprobe, t, R, _ptr(ids), _ptr(dist),
                                     _ptr(workspace), workspace.numel(), _stream(stream)))
+    return ids, dist
+
+
+def ivf_adc_scan_topk_tightening(idx: PqIndex, coarse: torch.Tensor, list_offsets: torch.Tensor,
+                                 list_codes: torch.Tensor, list_ids: torch.Tensor, queries: torch.Tensor,
+                                 probe_ids: torch.Tensor, t: int, R: int,
+                                 workspace: Optional[torch.Tensor] = None, out=None, stream=None):
+    _dev(coarse, torch.float32)
+    _dev(list_offsets, torch.int64)
+    _dev(list_codes, torch.uint8)
+    _dev(list_ids, torch.int32)
+    _dev(queries, torch.float32)
+    _dev(probe_ids, torch.int32)
+    nq, nprobe = probe_ids.shape
+    dev = queries.device
+    if workspace is None:
+        workspace = torch.empty(ivf_workspace_bytes(idx, nq, nprobe, R), dtype=torch.uint8, device=dev)
+    if out is None:
+        out = (torch.empty((nq, R), dtype=torch.int32, device=dev),
+               torch.empty((nq, R), dtype=torch.float32, device=dev))
+    ids, dist = out
+    _check(load().ivf_adc_scan_topk_tightening(idx.handle, _ptr(coarse), coarse.shape[0], _ptr(list_offsets),
+                                               _ptr(list_codes), _ptr(list_ids), _ptr(queries), nq,
+                                               _ptr(probe_ids), nprobe, t, R, _ptr(ids), _ptr(dist),
+                                               _ptr(workspace), workspace.numel(), _stream(stream)))
     return ids, dist
 
 

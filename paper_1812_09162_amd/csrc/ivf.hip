@@ -740,6 +740,158 @@ k_ivf_final(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
     ivf_rank_and_write(A, na, R, out_ids + q * R, out_dist + q * R);
 }
 
+// ------------------------------------------------------------ k_ivf_tight ---
+// The search with a bound that tightens from list to list (Section 3.5: a scanned vector is
+// kept when it is closer than the worst of the R candidates held; Section 3.4: that worst
+// distance is the largest the quantizer has to represent).  One block per query walks the
+// probed lists in probe order; list l is quantized against
+//     cur = min(d_max, R-th smallest distance among the candidates of the lists before l),
+// a list whose d_min is not below cur is skipped, and a code whose sum saturates is no
+// candidate.  The block holds the candidates as (ordered float distance << 32 | stored id) in
+// LDS; whenever the buffer runs full, and at the end of every list that added to it, the R
+// smallest are kept and the rest dropped: a dropped word is above R held ones, so it can
+// neither be a result nor move a later R-th smallest.
+#define TIGHT_CAP 4096
+#define TIGHT_U 4  // codes per thread between two looks at the fill level
+
+// k-th smallest (k = 1..na) of the different 64-bit words A[0..na), byte by byte from the top.
+__device__ inline uint64_t tight_kth(const uint64_t *A, int na, int k, uint32_t *hist, uint32_t *sh) {
+    uint64_t prefix = 0, mask = 0;
+    uint32_t kk = (uint32_t)k;
+    for (int pass = 7; pass >= 0; --pass) {
+        for (int i = threadIdx.x; i < 256; i += blockDim.x) hist[i] = 0;
+        __syncthreads();
+        for (int i = threadIdx.x; i < na; i += blockDim.x) {
+            const uint64_t w = A[i];
+            if ((w & mask) == prefix) atomicAdd(&hist[(uint32_t)(w >> (8 * pass)) & 255u], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x < QADC_WAVE) {
+            // lane l owns bins 4l .. 4l+3; the bin of the kk-th lies in the first lane whose
+            // running total reaches kk (the total over all lanes is at least kk)
+            const uint4 h = *(const uint4 *)&hist[4 * threadIdx.x];
+            const uint32_t sum = h.x + h.y + h.z + h.w;
+            const uint32_t incl = qadc_wave_incl_scan(sum);
+            const unsigned long long reach = __ballot(incl >= kk);
+            if (reach != 0 && (int)threadIdx.x == __ffsll(reach) - 1) {
+                uint32_t run = incl - sum, b = 4 * threadIdx.x;
+                if (run + h.x < kk) {
+                    run += h.x, ++b;
+                    if (run + h.y < kk) {
+                        run += h.y, ++b;
+                        if (run + h.z < kk) run += h.z, ++b;
+                    }
+                }
+                sh[0] = b;
+                sh[1] = kk - run;
+            }
+        }
+        __syncthreads();
+        prefix |= (uint64_t)sh[0] << (8 * pass);
+        mask |= (uint64_t)255u << (8 * pass);
+        kk = sh[1];
+        __syncthreads();
+    }
+    return prefix;
+}
+
+// Keep the R smallest of A[0..na), na > R; returns the R-th smallest.  *count becomes R.
+__device__ inline uint64_t tight_keep(uint64_t *A, int na, int R, uint32_t *hist, uint32_t *sh,
+                                      uint32_t *count) {
+    const uint64_t thr = tight_kth(A, na, R, hist, sh);
+    constexpr int PER = TIGHT_CAP / 256;
+    uint64_t mine[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const int i = (int)threadIdx.x + u * 256;
+        mine[u] = i < na ? A[i] : ~0ull;
+    }
+    if (threadIdx.x == 0) *count = 0;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < PER; ++u)
+        if (mine[u] <= thr) {
+            const uint32_t pos = atomicAdd(count, 1u);
+            if (pos < TIGHT_CAP) A[pos] = mine[u];
+        }
+    __syncthreads();
+    return thr;
+}
+
+template <int KIND, typename QT>
+__global__ void __launch_bounds__(256)
+k_ivf_tight(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
+            const float *__restrict__ cb, const float *__restrict__ coarse,
+            const int64_t *__restrict__ list_offsets, const uint8_t *__restrict__ list_codes,
+            const int32_t *__restrict__ list_ids, const float *__restrict__ queries,
+            const int32_t *__restrict__ probe_ids, int nprobe, int K, int R,
+            const char *__restrict__ ws, size_t per_query, int32_t *__restrict__ out_ids,
+            float *__restrict__ out_dist) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ __align__(16) uint32_t hist[256];
+    __shared__ uint32_t sh[8];
+    __shared__ uint32_t s_na;
+    uint64_t *A = (uint64_t *)smem;  // TIGHT_CAP words
+    IvfLds l;
+    ivf_carve(L, smem + TIGHT_CAP * 8, sizeof(QT), l);
+    const size_t q = blockIdx.x;
+    const IvfState *st = (const IvfState *)(ws + q * per_query);
+    const int32_t *probes = probe_ids + q * nprobe;
+    const int bd = 256;
+    const uint32_t qmax = (uint32_t)L->qmax;
+    float cur = st->dmax;
+    uint64_t pthr = ~0ull;  // words above it are beyond R held candidates
+    int na = 0;
+    if (threadIdx.x == 0) s_na = 0;
+    __syncthreads();
+    for (int a = 0; a < nprobe; ++a) {
+        const int c = probes[a];
+        if (c < 0 || c >= K) continue;
+        const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
+        if (hi == lo) continue;
+        if (!ivf_setup<KIND, QT>(L, edesc, cb, queries + q * L->d, coarse + (size_t)c * L->d, cur, true,
+                                 true, l))
+            continue;
+        const QT *gtab = (const QT *)l.gtab;
+        const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
+        const int na_before = na;
+        for (int64_t base = lo; base < hi; base += TIGHT_U * bd) {
+            if (na + TIGHT_U * bd > TIGHT_CAP) {  // na > R here: R <= TIGHT_CAP - TIGHT_U * 256
+                pthr = tight_keep(A, na, R, hist, sh, &s_na);
+                na = R;
+            }
+            uint32_t key[TIGHT_U];
+            keys_batch<KIND, QT, TIGHT_U>(L, gtab, list_codes, base + threadIdx.x, bd, hi, key);
+#pragma unroll
+            for (int u = 0; u < TIGHT_U; ++u) {
+                if (key[u] == 0xffffffffu || key[u] >= qmax) continue;  // past the end, or saturated
+                const uint32_t o = qadc_f2ord(fmaf((float)key[u], fdelta, fdmin));
+                if (o > (uint32_t)(pthr >> 32)) continue;
+                const int64_t p = base + (int64_t)u * bd + threadIdx.x;
+                const uint64_t w = ((uint64_t)o << 32) | (uint64_t)(uint32_t)list_ids[p];
+                if (w <= pthr) {
+                    const uint32_t pos = atomicAdd(&s_na, 1u);
+                    if (pos < TIGHT_CAP) A[pos] = w;  // always, unless stored ids repeat
+                }
+            }
+            __syncthreads();
+            na = (int)(s_na < TIGHT_CAP ? s_na : TIGHT_CAP);
+            __syncthreads();  // every thread has read the fill level before the next batch adds to it
+        }
+        if (na != na_before && na >= R) {
+            if (na > R) {
+                pthr = tight_keep(A, na, R, hist, sh, &s_na);
+                na = R;
+            } else {
+                pthr = tight_kth(A, na, R, hist, sh);
+            }
+            const float worst = qadc_ord2f((uint32_t)(pthr >> 32));
+            cur = worst < cur ? worst : cur;
+        }
+    }
+    ivf_rank_and_write(A, na, R, out_ids + q * R, out_dist + q * R);
+}
+
 // ------------------------------------------------------------------ host ---
 template <typename K>
 static int allow_lds(K kernel, size_t bytes) {
@@ -754,7 +906,7 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
                       const uint8_t *list_codes, const int32_t *list_ids, const float *queries,
                       int nq, const int32_t *probe_ids, int nprobe, int K, int want, int R,
                       int32_t *out_ids, float *out_dist, char *ws, const IvfPlan &p, uint32_t *sortws,
-                      hipStream_t s) {
+                      bool tighten, hipStream_t s) {
     // blocks in the order of the probed cells (see k_pair_count):
     // sortws = cnt[NB+1] | start[NB+1] | order[pairs]
     const uint32_t *order = nullptr;
@@ -808,6 +960,16 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
                        idx->codebooks, coarse, list_offsets, list_codes, queries, probe_ids, nprobe, K, want, pilot_want, R, ws,
                        p.per_query);
     QADC_LAUNCH_CHECK("k_ivf_calib");
+    if (tighten) {
+        static_assert(PQ_MAX_R + TIGHT_U * 256 <= TIGHT_CAP, "room for one batch above R candidates");
+        const size_t lds_tight = (size_t)TIGHT_CAP * 8 + lds_scan;
+        if ((rc = allow_lds(k_ivf_tight<KIND, QT>, lds_tight)) != PQ_OK) return rc;
+        hipLaunchKernelGGL((k_ivf_tight<KIND, QT>), dim3(nq), dim3(256), lds_tight, s, idx->dev, idx->edesc,
+                           idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries, probe_ids,
+                           nprobe, K, R, (const char *)ws, p.per_query, out_ids, out_dist);
+        QADC_LAUNCH_CHECK("k_ivf_tight");
+        return PQ_OK;
+    }
     const int scan_threads = (int)qadc_option(PQ_OPT_IVF_THREADS);
     // table entries per thread: the low-latency set-up holds up to four in registers
     const int ne = idx->h.T <= scan_threads ? 1 : (idx->h.T <= 2 * scan_threads ? 2 : (idx->h.T <= 4 * scan_threads ? 4 : 0));
@@ -859,42 +1021,41 @@ extern "C" size_t ivf_sorted_workspace_bytes(const pq_index_t *idx, int nq, int 
     return base + ivf_sort_bytes(nq, nprobe, K) + 256;
 }
 
-extern "C" int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_centroids, int K,
-                                 const int64_t *list_offsets, const uint8_t *list_codes,
-                                 const int32_t *list_ids, const float *queries, int nq,
-                                 const int32_t *probe_ids, int nprobe, int t, int R,
-                                 int32_t *out_ids, float *out_dist, void *workspace,
-                                 size_t workspace_bytes, void *stream) {
+static int ivf_search(const char *name, bool tighten, const pq_index_t *idx, const float *coarse_centroids,
+                      int K, const int64_t *list_offsets, const uint8_t *list_codes,
+                      const int32_t *list_ids, const float *queries, int nq, const int32_t *probe_ids,
+                      int nprobe, int t, int R, int32_t *out_ids, float *out_dist, void *workspace,
+                      size_t workspace_bytes, void *stream) {
     if (!idx || nq < 0 || K < 1 || nprobe < 1 || nprobe > 1024) {
-        qadc_set_error("ivf_adc_scan_topk: bad handle, nq, K or nprobe (1..1024)");
+        qadc_set_error("%s: bad handle, nq, K or nprobe (1..1024)", name);
         return PQ_EINVAL;
     }
     if (R < 1 || R > PQ_MAX_R || t < 1) {
-        qadc_set_error("ivf_adc_scan_topk: need 1<=R<=%d and t>=1 (got R=%d t=%d)", PQ_MAX_R, R, t);
+        qadc_set_error("%s: need 1<=R<=%d and t>=1 (got R=%d t=%d)", name, PQ_MAX_R, R, t);
         return PQ_EINVAL;
     }
     const int64_t want = t > 4 * (int64_t)R ? t : 4 * (int64_t)R;
     if (want > PQ_MAX_T_EFF) {
-        qadc_set_error("ivf_adc_scan_topk: max(t,4R)=%lld exceeds %d", (long long)want, PQ_MAX_T_EFF);
+        qadc_set_error("%s: max(t,4R)=%lld exceeds %d", name, (long long)want, PQ_MAX_T_EFF);
         return PQ_EINVAL;
     }
     if (nq == 0) return PQ_OK;
     if (nq > 65535) {
-        qadc_set_error("ivf_adc_scan_topk: at most 65535 queries per call (got %d)", nq);
+        qadc_set_error("%s: at most 65535 queries per call (got %d)", name, nq);
         return PQ_EINVAL;
     }
     if (!coarse_centroids || !list_offsets || !list_codes || !list_ids || !queries || !probe_ids ||
         !out_ids || !out_dist || !workspace) {
-        qadc_set_error("ivf_adc_scan_topk: null pointer");
+        qadc_set_error("%s: null pointer", name);
         return PQ_EINVAL;
     }
     if (((uintptr_t)list_codes & 15u) != 0 || ((uintptr_t)workspace & 255u) != 0) {
-        qadc_set_error("ivf_adc_scan_topk: list_codes must be 16-byte and workspace 256-byte aligned");
+        qadc_set_error("%s: list_codes must be 16-byte and workspace 256-byte aligned", name);
         return PQ_EINVAL;
     }
     const IvfPlan p = qadc_ivf_plan(idx, nq, nprobe, R);
     if (workspace_bytes < p.total) {
-        qadc_set_error("ivf_adc_scan_topk: workspace of %zu bytes, need %zu", workspace_bytes, p.total);
+        qadc_set_error("%s: workspace of %zu bytes, need %zu", name, workspace_bytes, p.total);
         return PQ_ENOMEM;
     }
     hipStream_t s = (hipStream_t)stream;
@@ -903,13 +1064,13 @@ extern "C" int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_cent
     // for cells to be probed more than once, the scan runs in the order of the probed cells.
     const size_t base_bytes = (p.total + 255) & ~(size_t)255;
     uint32_t *sortws = nullptr;
-    if ((int64_t)nq * nprobe * 4 >= (int64_t)K &&
+    if (!tighten && (int64_t)nq * nprobe * 4 >= (int64_t)K &&
         workspace_bytes >= base_bytes + ivf_sort_bytes(nq, nprobe, K))
         sortws = (uint32_t *)(ws + base_bytes);
     const bool u8 = idx->h.acc_bits == 8;
 #define QADC_GO(KIND, QT)                                                                          \
     return launch_ivf<KIND, QT>(idx, coarse_centroids, list_offsets, list_codes, list_ids, queries, \
-                                nq, probe_ids, nprobe, K, (int)want, R, out_ids, out_dist, ws, p, sortws, s)
+                                nq, probe_ids, nprobe, K, (int)want, R, out_ids, out_dist, ws, p, sortws, tighten, s)
     switch (idx->h.kind) {
         case SCAN_NIB8:
             if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);
@@ -925,4 +1086,26 @@ extern "C" int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_cent
             if (u8) QADC_GO(SCAN_GENERIC, uint8_t); else QADC_GO(SCAN_GENERIC, uint16_t);
     }
 #undef QADC_GO
+}
+
+extern "C" int ivf_adc_scan_topk(const pq_index_t *idx, const float *coarse_centroids, int K,
+                                 const int64_t *list_offsets, const uint8_t *list_codes,
+                                 const int32_t *list_ids, const float *queries, int nq,
+                                 const int32_t *probe_ids, int nprobe, int t, int R,
+                                 int32_t *out_ids, float *out_dist, void *workspace,
+                                 size_t workspace_bytes, void *stream) {
+    return ivf_search("ivf_adc_scan_topk", false, idx, coarse_centroids, K, list_offsets, list_codes,
+                      list_ids, queries, nq, probe_ids, nprobe, t, R, out_ids, out_dist, workspace,
+                      workspace_bytes, stream);
+}
+
+extern "C" int ivf_adc_scan_topk_tightening(const pq_index_t *idx, const float *coarse_centroids, int K,
+                                            const int64_t *list_offsets, const uint8_t *list_codes,
+                                            const int32_t *list_ids, const float *queries, int nq,
+                                            const int32_t *probe_ids, int nprobe, int t, int R,
+                                            int32_t *out_ids, float *out_dist, void *workspace,
+                                            size_t workspace_bytes, void *stream) {
+    return ivf_search("ivf_adc_scan_topk_tightening", true, idx, coarse_centroids, K, list_offsets,
+                      list_codes, list_ids, queries, nq, probe_ids, nprobe, t, R, out_ids, out_dist,
+                      workspace, workspace_bytes, stream);
 }

@@ -75,6 +75,9 @@ def test_calls_reject_null_handle():
                                 None) == qb.PQ_EINVAL
     assert lib.ivf_adc_scan_topk(None, None, 1, None, None, None, None, 1, None, 1, 400, 10, None,
                                  None, None, 0, None) == qb.PQ_EINVAL
+    assert lib.ivf_adc_scan_topk_tightening(None, None, 1, None, None, None, None, 1, None, 1, 400, 10,
+                                            None, None, None, 0, None) == qb.PQ_EINVAL
+    assert b"ivf_adc_scan_topk_tightening" in lib.pq_last_error()
     assert lib.pq_code_size(None) == 0 and lib.pq_table_len(None) == 0
     assert lib.pq_workspace_bytes(None, 1, 10, 10) == 0
     lib.pq_index_destroy(None)

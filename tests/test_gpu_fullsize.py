@@ -123,6 +123,8 @@ def run_ivf(qb, cfg, nq_oracle, R=100):
                         dtype=torch.uint8, device=dev())
     gi2, gd2 = qb.ivf_adc_scan_topk(idx, ip.coarse, ip.list_offsets, ip.list_codes, ip.list_ids,
                                     ip.queries, ip.probe_ids, T_CAL, R, workspace=small)
+    ti, td = qb.ivf_adc_scan_topk_tightening(idx, ip.coarse, ip.list_offsets, ip.list_codes, ip.list_ids,
+                                             ip.queries, ip.probe_ids, T_CAL, R, workspace=small)
     torch.cuda.synchronize()
     assert torch.equal(gi, gi2) and torch.equal(gd, gd2)
     del small, gi2, gd2
@@ -136,12 +138,21 @@ def run_ivf(qb, cfg, nq_oracle, R=100):
                                  host["off"], host["codes"], host["ids"], host["q"][q],
                                  host["probe"][q], T_CAL, R)
 
+    def one_tightening(q):
+        return oracle.search_ivf_tightening(lay.d, lay.nbits, lay.dsub, lay.acc_bits, host["cb"],
+                                            host["coarse"], host["off"], host["codes"], host["ids"],
+                                            host["q"][q], host["probe"][q], T_CAL, R)
+
     with ThreadPoolExecutor(max_workers=8) as ex:
         ref = list(ex.map(one, range(nq_oracle)))
+        ref_t = list(ex.map(one_tightening, range(nq_oracle)))
     gi_np, gd_np = gi.cpu().numpy(), gd.cpu().numpy()
+    ti_np, td_np = ti.cpu().numpy(), td.cpu().numpy()
     for q in range(nq_oracle):
         assert np.array_equal(gi_np[q], ref[q][0]), (q, gi_np[q][:8], ref[q][0][:8])
         assert np.array_equal(gd_np[q], ref[q][1])
+        assert np.array_equal(ti_np[q], ref_t[q][0]), ("tightening", q, ti_np[q][:8], ref_t[q][0][:8])
+        assert np.array_equal(td_np[q], ref_t[q][1])
     # any-size properties on all queries: sorted by (dist, id), ids come from probed lists
     assert np.all(np.diff(gd_np, axis=1) >= 0)
     sizes = np.diff(host["off"])

@@ -383,16 +383,18 @@ def check_ivf(qb, ip, R, t=T_CAL, probe=None):
     small = torch.empty(qb.ivf_workspace_bytes(idx, pids.shape[0], pids.shape[1], R), dtype=torch.uint8,
                         device=dev())
     gi2, gd2 = qb.ivf_adc_scan_topk(*args, workspace=small)   # minimal workspace: blocks in grid order
+    ti, td = qb.ivf_adc_scan_topk_tightening(*args)           # the bound tightened list by list
     torch.cuda.synchronize()
     assert torch.equal(gi, gi2) and torch.equal(gd, gd2)
+    host = (lay.d, lay.nbits, lay.dsub, lay.acc_bits, ip.codebooks.numpy(), ip.coarse.numpy(),
+            ip.list_offsets.numpy(), ip.list_codes.numpy(), ip.list_ids.numpy())
     for q in range(ip.queries.shape[0]):
-        oi, od, _ = oracle.search_ivf(lay.d, lay.nbits, lay.dsub, lay.acc_bits,
-                                      ip.codebooks.numpy(), ip.coarse.numpy(),
-                                      ip.list_offsets.numpy(), ip.list_codes.numpy(),
-                                      ip.list_ids.numpy(), ip.queries[q].numpy(),
-                                      pids[q].numpy(), t, R)
+        oi, od, _ = oracle.search_ivf(*host, ip.queries[q].numpy(), pids[q].numpy(), t, R)
         assert np.array_equal(gi[q].cpu().numpy(), oi), (q, gi[q][:8], oi[:8])
         assert np.array_equal(gd[q].cpu().numpy(), od)
+        oi, od, _, _ = oracle.search_ivf_tightening(*host, ip.queries[q].numpy(), pids[q].numpy(), t, R)
+        assert np.array_equal(ti[q].cpu().numpy(), oi), ("tightening", q, ti[q][:8], oi[:8])
+        assert np.array_equal(td[q].cpu().numpy(), od)
     idx.close()
 
 
