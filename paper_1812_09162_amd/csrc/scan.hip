@@ -294,18 +294,25 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         while (tile < ntiles) {
             uint32_t s[2 * U];
             bool pass[2 * U], any = false;
+            // 64-bit irregular codes: the next tile is requested before this one is looked up (their
+            // look-ups take longer than the m x 4 kind's, for which the later request measured faster)
+            constexpr bool EARLY = KIND != SCAN_NIB8;
+            uint4 w[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) w[u] = cur[u];
+            if (EARLY && tile + G < ntiles) load_tile(tile + G);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + (int)threadIdx.x;
                 if (KIND == SCAN_NIB8) {
-                    s[2 * u] = sum8(gtab, cur[u].x, cur[u].y);
-                    s[2 * u + 1] = sum8(gtab, cur[u].z, cur[u].w);
+                    s[2 * u] = sum8(gtab, w[u].x, w[u].y);
+                    s[2 * u + 1] = sum8(gtab, w[u].z, w[u].w);
                 } else if (g32) {
-                    s[2 * u] = sum_groups_desc<NG, NLO>(gd, gtab, cur[u].x, cur[u].y);
-                    s[2 * u + 1] = sum_groups_desc<NG, NLO>(gd, gtab, cur[u].z, cur[u].w);
+                    s[2 * u] = sum_groups_desc<NG, NLO>(gd, gtab, w[u].x, w[u].y);
+                    s[2 * u + 1] = sum_groups_desc<NG, NLO>(gd, gtab, w[u].z, w[u].w);
                 } else {
-                    s[2 * u] = sum_groups64(L, gtab, ((uint64_t)cur[u].y << 32) | cur[u].x);
-                    s[2 * u + 1] = sum_groups64(L, gtab, ((uint64_t)cur[u].w << 32) | cur[u].z);
+                    s[2 * u] = sum_groups64(L, gtab, ((uint64_t)w[u].y << 32) | w[u].x);
+                    s[2 * u + 1] = sum_groups64(L, gtab, ((uint64_t)w[u].w << 32) | w[u].z);
                 }
                 pass[2 * u] = (c < nfull) && s[2 * u] <= thr;
                 pass[2 * u + 1] = (c < nfull) && s[2 * u + 1] <= thr;
@@ -322,7 +329,7 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 stage_append_multi<2 * U>(pass, s, id, wbuf, nbuf, cand, cap, count);
             }
             tile += G;
-            if (tile < ntiles) load_tile(tile);
+            if (!EARLY && tile < ntiles) load_tile(tile);
         }
         if ((n & 1) && b == 0) {  // the odd last code, by one wave of block 0
             if (threadIdx.x < QADC_WAVE) {
@@ -362,19 +369,26 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
         while (tile < ntiles) {
             uint32_t s[4 * U];
             bool pass[4 * U], any = false;
+            // the next tile is requested before this one is looked up
+            uint32_t w[U][5];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int i = 0; i < 5; ++i) w[u][i] = cur[u][i];
+            if (tile + G < ntiles) load_tile(tile + G);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const uint32_t c = tile * (U * SCAN_THREADS) + u * SCAN_THREADS + threadIdx.x;
                 // code v = bits [40v, 40v+40) of the 160-bit chunk, as (low dword, high byte)
                 uint32_t lo[4], hi[4];
-                lo[0] = cur[u][0];
-                hi[0] = cur[u][1] & 0xffu;
-                lo[1] = __builtin_amdgcn_alignbit(cur[u][2], cur[u][1], 8);
-                hi[1] = (cur[u][2] >> 8) & 0xffu;
-                lo[2] = __builtin_amdgcn_alignbit(cur[u][3], cur[u][2], 16);
-                hi[2] = (cur[u][3] >> 16) & 0xffu;
-                lo[3] = __builtin_amdgcn_alignbit(cur[u][4], cur[u][3], 24);
-                hi[3] = cur[u][4] >> 24;
+                lo[0] = w[u][0];
+                hi[0] = w[u][1] & 0xffu;
+                lo[1] = __builtin_amdgcn_alignbit(w[u][2], w[u][1], 8);
+                hi[1] = (w[u][2] >> 8) & 0xffu;
+                lo[2] = __builtin_amdgcn_alignbit(w[u][3], w[u][2], 16);
+                hi[2] = (w[u][3] >> 16) & 0xffu;
+                lo[3] = __builtin_amdgcn_alignbit(w[u][4], w[u][3], 24);
+                hi[3] = w[u][4] >> 24;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     s[4 * u + v] = g32 ? sum_groups_desc<NG, NLO>(gd, gtab, lo[v], hi[v])
@@ -394,7 +408,6 @@ k_scan(const DevLayout *__restrict__ L, const void *__restrict__ qtables,
                 stage_append_multi<4 * U>(pass, s, id, wbuf, nbuf, cand, cap, count);
             }
             tile += G;
-            if (tile < ntiles) load_tile(tile);
         }
         if ((n & 3) && b == 0 && threadIdx.x < QADC_WAVE) {  // the last n % 4 codes
             const int64_t id = (nfull << 2) + threadIdx.x;
