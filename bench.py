@@ -393,6 +393,21 @@ def main():
         # query-batched passes: bound by LDS reads, not HBM.  Ceiling: one 8-byte table entry per
         # lane, 16 lanes per CU and clock without bank conflicts (128 B/clk) = 256 CUs x 16 x 2.4 GHz
         lds_ceiling = 256 * 16 * 2.4e9
+        # the same read measured on this GPU for the kernel's own address pattern (every lane an
+        # independent entry of a 2 KB table: bank conflicts included) and for a conflict-free one
+        lds_measured = {}
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        for name, pat in (("conflict_free", qb.PQ_LDS_LINEAR), ("random_2kb_table", qb.PQ_LDS_RANDOM_2K)):
+            best = None
+            for _ in range(4):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                nreads = qb.pq_lds_read_probe(pat, 2048, sink)
+                e1.record()
+                e1.synchronize()
+                rate = nreads / (e0.elapsed_time(e1) * 1e-3)
+                best = rate if best is None or rate > best else best
+            lds_measured[name] = best
         for bs, st in ((32, 60), (256, 12)):
             r2 = Runner(qb, idx, pr.queries, pr.codes, bs, a.R, streams=min(a.streams, 2),
                         fused=not a.unfused)
@@ -413,7 +428,10 @@ def main():
                 extras[f"batch{bs}"]["roofline"] = {
                     "bound": "lds", "kernel": "k_scan_mq", "unit": "G 8-byte LDS reads/s",
                     "achieved": reads / (kms * 1e-3) / 1e9, "peak": lds_ceiling / 1e9,
-                    "frac": reads / (kms * 1e-3) / lds_ceiling, "lds_reads_per_launch": reads}
+                    "frac": reads / (kms * 1e-3) / lds_ceiling, "lds_reads_per_launch": reads,
+                    "peak_measured_conflict_free": lds_measured["conflict_free"] / 1e9,
+                    "peak_measured_random_2kb_table": lds_measured["random_2kb_table"] / 1e9,
+                    "frac_of_measured_random": reads / (kms * 1e-3) / lds_measured["random_2kb_table"]}
         if a.workload == "C1" and a.batch == 1:
             extras["C2_streaming"] = streaming_leg(qb, synth, dev, "C2", 100)
 

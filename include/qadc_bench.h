@@ -31,6 +31,19 @@ int pq_adc_rescan_candidates(const pq_index_t *idx, const void *qtables,
  */
 int pq_copy_bytes(void *dst, const void *src, size_t nbytes, void *stream);
 
+/*
+ * The rate at which this GPU serves 8-byte LDS reads (ds_read_b64) for an address pattern:
+ * launches PQ_LDS_PROBE_BLOCKS blocks of 256 threads in which every lane reads 8 * iters entries
+ * of eight 2 KB tables (the shape of the interleaved group tables of the batched scan, Section
+ * 3.4 tables for four queries side by side).  The caller times the launch; the number of lane
+ * reads is PQ_LDS_PROBE_BLOCKS * 256 * 8 * iters.  PQ_LDS_RANDOM_2K is the batched scan's own
+ * pattern (every lane an independent entry of a 256-entry table), PQ_LDS_LINEAR is free of bank
+ * conflicts.  sink: [dev] one 32-bit word the kernel may write.
+ */
+enum { PQ_LDS_UNIFORM = 0, PQ_LDS_LINEAR = 1, PQ_LDS_RANDOM_2K = 2, PQ_LDS_RANDOM_128 = 3 };
+#define PQ_LDS_PROBE_BLOCKS 2048
+int pq_lds_read_probe(int pattern, int iters, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

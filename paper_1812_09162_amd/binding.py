@@ -27,7 +27,7 @@ EXPORTS = [
     "ivf_adc_scan_topk", "pq_search_workspace_bytes", "pq_search_topk",
     "pq_adc_scan_candidates", "pq_adc_rescan_candidates", "pq_select_topk", "pq_copy_bytes", "pq_last_error",
     "ivf_coarse_workspace_bytes", "ivf_coarse_search", "pq_encode", "pq_adc_scan_topk_static",
-    "pq_set_option", "pq_get_option", "ivf_adc_scan_topk_tightening",
+    "pq_set_option", "pq_get_option", "ivf_adc_scan_topk_tightening", "pq_lds_read_probe",
 ]
 PQ_KEY_BOUND_UNKNOWN = 0xFFFFFFFF
 (PQ_OPT_SCAN_BLOCKS, PQ_OPT_PILOT_CODES, PQ_OPT_PILOT_CODES_SINGLE, PQ_OPT_PILOT_BLOCKS, PQ_OPT_IVF_THREADS,
@@ -77,6 +77,8 @@ def load() -> ctypes.CDLL:
     lib.ivf_adc_scan_topk.restype = i32
     lib.ivf_adc_scan_topk_tightening.argtypes = lib.ivf_adc_scan_topk.argtypes
     lib.ivf_adc_scan_topk_tightening.restype = i32
+    lib.pq_lds_read_probe.argtypes = [i32, i32, vp, vp]
+    lib.pq_lds_read_probe.restype = i32
     lib.pq_search_workspace_bytes.argtypes = [vp, i32, i64, i32]
     lib.pq_search_workspace_bytes.restype = sz
     lib.pq_search_topk.argtypes = [vp, vp, i32, vp, i64, i32, i32, vp, vp, vp, vp, sz, vp]
@@ -342,6 +344,17 @@ def pq_copy_bytes(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(load().pq_copy_bytes(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+
+
+PQ_LDS_UNIFORM, PQ_LDS_LINEAR, PQ_LDS_RANDOM_2K, PQ_LDS_RANDOM_128 = range(4)
+PQ_LDS_PROBE_BLOCKS = 2048
+
+
+def pq_lds_read_probe(pattern: int, iters: int, sink: torch.Tensor, stream=None) -> int:
+    """Launches the probe; returns the number of 8-byte lane reads it performs."""
+    _dev(sink, torch.int32)
+    _check(load().pq_lds_read_probe(pattern, iters, _ptr(sink), _stream(stream)))
+    return PQ_LDS_PROBE_BLOCKS * 256 * 8 * iters
 
 
 def pq_set_option(option: int, value: int) -> None:

@@ -280,3 +280,52 @@ extern "C" int pq_copy_bytes(void *dst, const void *src, size_t nbytes, void *st
     QADC_LAUNCH_CHECK("k_copy");
     return PQ_OK;
 }
+
+// 8-byte LDS reads at the rate the hardware sustains for a given address pattern: every lane
+// reads 8 * iters entries of eight 2 KB tables (256 entries of 8 bytes each, the shape of the
+// batched scan's interleaved group tables).  The addresses change from read to read by an
+// exclusive-or with a wave-uniform value, which keeps each pattern's bank behaviour.
+template <int PATTERN>
+__global__ void __launch_bounds__(256) k_lds_read_probe(int iters, uint32_t *__restrict__ sink) {
+    __shared__ unsigned long long t[8 * 256];
+    for (int i = threadIdx.x; i < 8 * 256; i += 256) t[i] = (unsigned long long)i * 0x9e3779b97f4a7c15ull;
+    __syncthreads();
+    uint32_t r[8];
+    uint32_t x = threadIdx.x * 2654435761u + blockIdx.x;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) {
+        x = x * 1664525u + 1013904223u;
+        r[g] = PATTERN == PQ_LDS_UNIFORM ? 0u
+               : (PATTERN == PQ_LDS_LINEAR ? (threadIdx.x & 63u) * 8u
+                                           : ((x >> 20) & (PATTERN == PQ_LDS_RANDOM_2K ? 0x7f8u : 0x78u)));
+    }
+    const uint32_t mask = PATTERN == PQ_LDS_LINEAR ? 0x1f8u : (PATTERN == PQ_LDS_RANDOM_128 ? 0x78u : 0x7f8u);
+    uint32_t acc = 0;
+    const char *tb = (const char *)t;
+    for (int it = 0; it < iters; ++it) {
+        const uint32_t s = (uint32_t)it * 0x9e3779b8u;  // wave-uniform multiple of 8
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            const unsigned long long v = *(const unsigned long long *)(tb + g * 2048 + ((r[g] ^ s) & mask));
+            acc ^= (uint32_t)v ^ (uint32_t)(v >> 32);
+        }
+    }
+    if (acc == 0x1234567u) sink[0] = acc;  // (keeps the reads alive; practically never taken)
+}
+
+extern "C" int pq_lds_read_probe(int pattern, int iters, void *sink, void *stream) {
+    if (pattern < 0 || pattern > PQ_LDS_RANDOM_128 || iters < 1 || !sink) {
+        qadc_set_error("pq_lds_read_probe: pattern 0..%d, iters >= 1 and a device word to write to", PQ_LDS_RANDOM_128);
+        return PQ_EINVAL;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const dim3 grid(PQ_LDS_PROBE_BLOCKS), block(256);
+    switch (pattern) {
+        case PQ_LDS_UNIFORM: hipLaunchKernelGGL(k_lds_read_probe<PQ_LDS_UNIFORM>, grid, block, 0, s, iters, (uint32_t *)sink); break;
+        case PQ_LDS_LINEAR: hipLaunchKernelGGL(k_lds_read_probe<PQ_LDS_LINEAR>, grid, block, 0, s, iters, (uint32_t *)sink); break;
+        case PQ_LDS_RANDOM_2K: hipLaunchKernelGGL(k_lds_read_probe<PQ_LDS_RANDOM_2K>, grid, block, 0, s, iters, (uint32_t *)sink); break;
+        default: hipLaunchKernelGGL(k_lds_read_probe<PQ_LDS_RANDOM_128>, grid, block, 0, s, iters, (uint32_t *)sink); break;
+    }
+    QADC_LAUNCH_CHECK("k_lds_read_probe");
+    return PQ_OK;
+}
