@@ -41,7 +41,7 @@ def measured_traffic_bytes(workload, batch):
     path = os.path.join(ROOT, "profiles", f"k_scan_{workload}_batch{batch}.md")
     try:
         with open(path) as f:
-            m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", f.read(), re.M)
+            m = re.search(r"^\s*traffic_bytes_per_launch:\s*([0-9.eE+]+)", f.read(), re.M)
         return float(m.group(1)) if m else None
     except OSError:
         return None
