@@ -31,7 +31,7 @@ EXPORTS = [
 ]
 PQ_KEY_BOUND_UNKNOWN = 0xFFFFFFFF
 (PQ_OPT_SCAN_BLOCKS, PQ_OPT_PILOT_CODES, PQ_OPT_PILOT_CODES_SINGLE, PQ_OPT_PILOT_BLOCKS, PQ_OPT_IVF_THREADS,
- PQ_OPT_SHARED_PASSES, PQ_OPT_COARSE_FILTER) = range(7)
+ PQ_OPT_SHARED_PASSES, PQ_OPT_COARSE_FILTER, PQ_OPT_IVF_SHARED_LISTS) = range(8)
 
 
 class QadcError(RuntimeError):

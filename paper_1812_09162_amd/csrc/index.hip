@@ -30,6 +30,7 @@ static std::atomic<int64_t> g_opt[PQ_OPT_COUNT] = {
     {128},     // PQ_OPT_IVF_THREADS
     {1},       // PQ_OPT_SHARED_PASSES
     {1},       // PQ_OPT_COARSE_FILTER
+    {1},       // PQ_OPT_IVF_SHARED_LISTS
 };
 
 int64_t qadc_option(int option) { return g_opt[option].load(std::memory_order_relaxed); }
@@ -42,6 +43,7 @@ extern "C" int pq_set_option(int option, int64_t value) {
         case PQ_OPT_PILOT_CODES_SINGLE: ok = value >= 0 && value <= ((int64_t)1 << 24); break;
         case PQ_OPT_PILOT_BLOCKS: ok = value >= 1 && value <= 64; break;
         case PQ_OPT_IVF_THREADS: ok = value == 64 || value == 128 || value == 256; break;
+        case PQ_OPT_IVF_SHARED_LISTS: ok = value >= 0 && value <= 2; break;
         default: ok = value == 0 || value == 1; break;
     }
     if (!ok) {

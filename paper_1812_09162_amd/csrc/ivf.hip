@@ -606,6 +606,319 @@ k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
     if (threadIdx.x == 0) counts[a] = s_count;  // uncapped: > cap_b tells k_ivf_final about the overflow
 }
 
+// --------------------------------------------------------- k_ivf_scan_mq ---
+// One pass over a list for up to four of the queries that probe it (Section 2.1.3: every
+// (query, cell) pair has its own tables, but the codes of the cell are the same for all).
+// For calls with several (query, probe) pairs per cell, 16 x 4-bit codes over equal sub-spaces
+// and 8-bit tables.  The pairs are sorted by cell exactly (one bucket per cell), the pairs of a
+// cell are cut into groups of at most four, and a block of four waves serves one group: wave w
+// builds the residual tables and the quantizer of the group's w-th pair exactly as k_ivf_scan
+// does, writes its byte-indexed group tables as field w of 8-byte entries {u16 q0..q3} in LDS,
+// and then all four waves scan the list once: one 8-byte read per code byte serves the four
+// pairs.  Every pair keeps its own slot list and count, so the selection is unchanged.
+#define IVF_MQ 4
+struct IvfMqLds {                      // behind the interleaved tables (which start at LDS address 0)
+    float zres[IVF_MQ][128];
+    float pmin[IVF_MQ][16];
+    uint16_t qt[IVF_MQ][256];
+    double sc[IVF_MQ][2];              // d_min, delta
+    unsigned long long slot[IVF_MQ];   // slot list of the pair
+    float thr[IVF_MQ];                 // pruning bound; -inf: nothing passes (no pair, or list skipped)
+    uint32_t count[IVF_MQ];
+    uint32_t *counts_out[IVF_MQ];
+    int flag[IVF_MQ];
+};
+#define IVF_MQ_TAB_BYTES (8 * 256 * 8)
+
+// the four packed sums of one 64-bit code: lo = {q0, q1}, hi = {q2, q3} (16 bits each; eight
+// addends of at most 510 cannot carry)
+__device__ __forceinline__ void ivf_mq_sums(uint32_t w0, uint32_t w1, uint32_t three, uint32_t &lo, uint32_t &hi) {
+    const uint2 e0 = mq_entry<0>(0, w0, three), e1 = mq_entry<1>(1, w0, three);
+    const uint2 e2 = mq_entry<2>(2, w0, three), e3 = mq_entry<3>(3, w0, three);
+    const uint2 e4 = mq_entry<0>(4, w1, three), e5 = mq_entry<1>(5, w1, three);
+    const uint2 e6 = mq_entry<2>(6, w1, three), e7 = mq_entry<3>(7, w1, three);
+    lo = e0.x + e1.x + e2.x + e3.x + e4.x + e5.x + e6.x + e7.x;
+    hi = e0.y + e1.y + e2.y + e3.y + e4.y + e5.y + e6.y + e7.y;
+}
+
+template <int DS>
+__global__ void __launch_bounds__(256)
+k_ivf_scan_mq(const float *__restrict__ cb, const float *__restrict__ coarse,
+              const int64_t *__restrict__ list_offsets, const uint8_t *__restrict__ list_codes,
+              const int32_t *__restrict__ list_ids, const float *__restrict__ queries,
+              const int32_t *__restrict__ probe_ids, int nprobe, char *__restrict__ ws, size_t per_query,
+              size_t counts_off, size_t slots_off, int cap_b, const uint32_t *__restrict__ order,
+              const uint2 *__restrict__ gdesc, const uint32_t *__restrict__ ngroups) {
+    extern __shared__ __align__(16) unsigned char smem[];  // tables at LDS address 0 (no static LDS here)
+    IvfMqLds &S = *(IvfMqLds *)(smem + IVF_MQ_TAB_BYTES);
+    if (blockIdx.x >= *ngroups) return;
+    constexpr int d = 16 * DS;
+    constexpr uint32_t qmax = 255;
+    const uint2 gdv = gdesc[blockIdx.x];
+    const uint32_t first = gdv.x >> 3;
+    const int k = (int)(gdv.x & 7u);  // 1..4 pairs, all of cell c, whose list is not empty
+    const int c = (int)gdv.y;
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const bool act = w < k;
+    const uint32_t pair = order[first + (act ? (uint32_t)w : 0u)];  // (idle waves mirror pair 0, store nothing)
+    const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
+    const size_t q = pair / (uint32_t)nprobe;
+    const int a = (int)(pair % (uint32_t)nprobe);
+    char *wq = ws + q * per_query;
+    const IvfState *st = (const IvfState *)wq;
+    const float dmax = st->dmax, thr0 = st->thr0;
+    // the first codes of the list, requested now and used after the set-up
+    constexpr int PF = 2;
+    const int64_t lo2 = (lo + 1) & ~(int64_t)1;
+    const int64_t npair = hi > lo2 ? (hi - lo2) >> 1 : 0;
+    const uint4 *__restrict__ pairs = (const uint4 *)(list_codes + lo2 * 8);
+    uint4 pp[PF];
+    if (npair > 0) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            int64_t pi = (int64_t)u * 256 + threadIdx.x;
+            pi = pi < npair ? pi : npair - 1;
+            pp[u] = pairs[pi];
+        }
+    }
+    // codebook values of this lane's four table entries e = lane + 64 i
+    float cv[4][DS];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int t = 0; t < DS; ++t) cv[i][t] = cb[(lane + 64 * i) * DS + t];
+    for (int i = lane; i < d; i += 64) S.zres[w][i] = __fsub_rn(queries[q * d + i], coarse[(size_t)c * d + i]);
+    if (lane == 0) {
+        S.count[w] = 0;
+        S.slot[w] = (unsigned long long)((uint64_t *)(wq + slots_off) + (size_t)a * cap_b);
+        S.counts_out[w] = (uint32_t *)(wq + counts_off) + a;
+    }
+    __syncthreads();
+    // eq. (1), terms in ascending dimension order; 16 adjacent lanes hold one sub-quantizer
+    float tv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = lane + 64 * i;
+        const float *zz = S.zres[w] + (e >> 4) * DS;
+        float acc = 0.0f;
+#pragma unroll
+        for (int t = 0; t < DS; ++t) {
+            const float diff = __fsub_rn(zz[t], cv[i][t]);
+            acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+        }
+        tv[i] = acc;
+        float mn = acc;
+#pragma unroll
+        for (int sft = 1; sft < 16; sft <<= 1) {
+            const float o = __shfl_xor(mn, sft, QADC_WAVE);
+            mn = o < mn ? o : mn;
+        }
+        if ((lane & 15) == 0) S.pmin[w][e >> 4] = mn;
+    }
+    __syncthreads();
+    if (lane == 0) {
+        double dm = 0.0;
+        for (int j = 0; j < 16; ++j) dm = dm + (double)S.pmin[w][j];
+        double delta = ((double)dmax - dm) / (double)qmax;
+        if (!((delta > 0.0) && isfinite(delta))) delta = 0.0;
+        const int skip = dm >= (double)dmax;  // Section 3.4: nothing in this list is closer than d_max
+        S.sc[w][0] = dm;
+        S.sc[w][1] = delta;
+        S.flag[w] = skip;
+        S.thr[w] = (act && !skip) ? thr0 : -INFINITY;
+    }
+    __syncthreads();
+    {
+        const double delta = S.sc[w][1];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = lane + 64 * i;
+            uint32_t qv = 0;
+            if (delta > 0.0) {
+                const double x = floor(((double)tv[i] - (double)S.pmin[w][e >> 4]) / delta);
+                qv = (x >= (double)qmax) ? qmax : (uint32_t)x;
+            }
+            S.qt[w][e] = (uint16_t)qv;
+        }
+    }
+    __syncthreads();
+    // field w of the interleaved tables: entry (g, byte) = low-nibble entry + high-nibble entry
+    {
+        uint16_t *tf = (uint16_t *)smem + w;
+        for (int x = lane; x < 8 * 256; x += 64) {
+            const int g = x >> 8, byte = x & 255;
+            tf[4 * x] = (uint16_t)(S.qt[w][32 * g + (byte & 15)] + S.qt[w][32 * g + 16 + (byte >> 4)]);
+        }
+    }
+    __syncthreads();
+    // ---- one pass over the list for the four pairs
+    float fdelta[IVF_MQ], fdmin[IVF_MQ], thr[IVF_MQ];
+#pragma unroll
+    for (int j = 0; j < IVF_MQ; ++j) {
+        fdelta[j] = (float)S.sc[j][1];
+        fdmin[j] = (float)S.sc[j][0];
+        thr[j] = S.thr[j];
+    }
+    const uint32_t three = 3;
+    for (int64_t pb = 0; pb < npair; pb += (int64_t)PF * 256) {
+        if (pb != 0) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                int64_t pi = pb + (int64_t)u * 256 + threadIdx.x;
+                pi = pi < npair ? pi : npair - 1;
+                pp[u] = pairs[pi];
+            }
+        }
+        uint32_t slo[2 * PF], shi[2 * PF];
+        bool valid[PF];
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            valid[u] = pb + (int64_t)u * 256 + threadIdx.x < npair;
+            ivf_mq_sums(pp[u].x, pp[u].y, three, slo[2 * u], shi[2 * u]);
+            ivf_mq_sums(pp[u].z, pp[u].w, three, slo[2 * u + 1], shi[2 * u + 1]);
+        }
+        uint32_t ord[IVF_MQ][2 * PF];
+        bool pass[IVF_MQ][2 * PF], any = false;
+#pragma unroll
+        for (int j = 0; j < IVF_MQ; ++j)
+#pragma unroll
+            for (int u = 0; u < 2 * PF; ++u) {
+                const uint32_t sum = j == 0 ? (slo[u] & 0xffffu) : (j == 1 ? (slo[u] >> 16) : (j == 2 ? (shi[u] & 0xffffu) : (shi[u] >> 16)));
+                const float dist = fmaf((float)(sum > qmax ? qmax : sum), fdelta[j], fdmin[j]);
+                ord[j][u] = qadc_f2ord(dist);
+                pass[j][u] = valid[u >> 1] && dist <= thr[j];
+                any = any || pass[j][u];
+            }
+        if (__ballot(any) != 0) {
+            uint32_t id[2 * PF];
+#pragma unroll
+            for (int u = 0; u < 2 * PF; ++u) {
+                const int64_t pos = lo2 + 2 * (pb + (int64_t)(u >> 1) * 256 + threadIdx.x) + (u & 1);
+                bool need = false;
+#pragma unroll
+                for (int j = 0; j < IVF_MQ; ++j) need = need || pass[j][u];
+                id[u] = need ? (uint32_t)list_ids[pos] : 0u;
+            }
+#pragma unroll
+            for (int j = 0; j < IVF_MQ; ++j)
+                slot_append_multi<2 * PF>(pass[j], ord[j], id, (uint64_t *)S.slot[j], (uint32_t)cap_b, &S.count[j]);
+        }
+    }
+    // the codes outside the 16-byte pairs: position lo if it is odd, position hi-1 if one is left over
+    if (threadIdx.x < QADC_WAVE) {
+        int64_t pos = -1;
+        if (threadIdx.x == 0 && lo2 != lo) pos = lo;
+        if (threadIdx.x == 1 && lo2 + 2 * npair < hi) pos = hi - 1;
+        uint32_t l2 = 0, h2 = 0, idv = 0;
+        if (pos >= 0) {
+            const uint2 cw = *(const uint2 *)(list_codes + pos * 8);
+            ivf_mq_sums(cw.x, cw.y, three, l2, h2);
+            idv = (uint32_t)list_ids[pos];
+        }
+#pragma unroll
+        for (int j = 0; j < IVF_MQ; ++j) {
+            const uint32_t sum = j == 0 ? (l2 & 0xffffu) : (j == 1 ? (l2 >> 16) : (j == 2 ? (h2 & 0xffffu) : (h2 >> 16)));
+            const float dist = fmaf((float)(sum > qmax ? qmax : sum), fdelta[j], fdmin[j]);
+            slot_append(pos >= 0 && dist <= thr[j], qadc_f2ord(dist), idv, (uint64_t *)S.slot[j], (uint32_t)cap_b, &S.count[j]);
+        }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < k) *S.counts_out[threadIdx.x] = S.count[threadIdx.x];  // uncapped, as in k_ivf_scan
+}
+
+// Sorting the pairs by cell exactly, and cutting each cell's pairs into groups of IVF_MQ.
+// start[c] / gstart[c] = pairs / groups in cells before c (c = 0 .. nb, nb = K + 1 buckets: the
+// last holds the pairs without a list, which get no groups); cnt is cleared to serve as fill
+// cursors.  Two launches of nb / 1024 blocks: sums per block of 1024 buckets, then every block
+// adds up the sums before it and scans its own buckets.
+__device__ __forceinline__ uint32_t ivf_groups_of(uint32_t pairs, int bucket, int nb) {
+    return bucket < nb - 1 ? (pairs + IVF_MQ - 1) / IVF_MQ : 0u;
+}
+// block-wide sums of two values (1024 threads); the result reaches every thread
+__device__ __forceinline__ void ivf_block_sum2(uint32_t &a, uint32_t &b, uint32_t (*wsum)[16]) {
+    for (int sft = QADC_WAVE / 2; sft > 0; sft >>= 1) {
+        a += __shfl_xor(a, sft, QADC_WAVE);
+        b += __shfl_xor(b, sft, QADC_WAVE);
+    }
+    if (threadIdx.x % QADC_WAVE == 0) {
+        wsum[0][threadIdx.x / QADC_WAVE] = a;
+        wsum[1][threadIdx.x / QADC_WAVE] = b;
+    }
+    __syncthreads();
+    a = 0, b = 0;
+    for (int w = 0; w < 16; ++w) {
+        a += wsum[0][w];
+        b += wsum[1][w];
+    }
+    __syncthreads();
+}
+__global__ void __launch_bounds__(1024)
+k_pair_block_sums(const uint32_t *__restrict__ cnt, int nb, uint32_t *__restrict__ bsum) {
+    __shared__ uint32_t wsum[2][16];
+    const int i = blockIdx.x * 1024 + threadIdx.x;
+    uint32_t s = i < nb ? cnt[i] : 0u;
+    uint32_t g = i < nb ? ivf_groups_of(s, i, nb) : 0u;
+    ivf_block_sum2(s, g, wsum);
+    if (threadIdx.x == 0) {
+        bsum[2 * blockIdx.x] = s;
+        bsum[2 * blockIdx.x + 1] = g;
+    }
+}
+__global__ void __launch_bounds__(1024)
+k_pair_scan_groups(uint32_t *__restrict__ cnt, uint32_t *__restrict__ start, uint32_t *__restrict__ gstart, int nb,
+                   const uint32_t *__restrict__ bsum) {
+    __shared__ uint32_t wsum[2][16];
+    // pairs and groups in the blocks before this one (gridDim.x <= 1024 blocks: K < 2^20)
+    uint32_t ps = (int)threadIdx.x < (int)blockIdx.x ? bsum[2 * threadIdx.x] : 0u;
+    uint32_t pg = (int)threadIdx.x < (int)blockIdx.x ? bsum[2 * threadIdx.x + 1] : 0u;
+    ivf_block_sum2(ps, pg, wsum);
+    const int i = blockIdx.x * 1024 + threadIdx.x;
+    const uint32_t v = i < nb ? cnt[i] : 0u;
+    const uint32_t gv = i < nb ? ivf_groups_of(v, i, nb) : 0u;
+    const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
+    const uint32_t is = qadc_wave_incl_scan(v), ig = qadc_wave_incl_scan(gv);
+    if (lane == QADC_WAVE - 1) {
+        wsum[0][wave] = is;
+        wsum[1][wave] = ig;
+    }
+    __syncthreads();
+    uint32_t bs = ps + is - v, bg = pg + ig - gv;
+    for (int w = 0; w < wave; ++w) {
+        bs += wsum[0][w];
+        bg += wsum[1][w];
+    }
+    if (i < nb) {
+        start[i] = bs;
+        gstart[i] = bg;
+        cnt[i] = 0;
+    }
+    if (i == nb - 1) {
+        start[nb] = bs + v;
+        gstart[nb] = bg + gv;  // number of groups
+    }
+}
+
+// One thread per cell writes the cell's group descriptors {first pair << 3 | pairs, cell}; the pairs
+// without a list get their slot counts cleared (no block will visit them).  cnt holds the
+// cells' pair counts again after k_pair_fill.
+__global__ void __launch_bounds__(256)
+k_group_fill(const uint32_t *__restrict__ cnt, const uint32_t *__restrict__ start,
+             const uint32_t *__restrict__ gstart, const uint32_t *__restrict__ order, int K, int nprobe,
+             char *__restrict__ ws, size_t per_query, size_t counts_off, uint2 *__restrict__ gdesc) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c < K) {
+        const uint32_t n = cnt[c], s0 = start[c];
+        uint32_t g = gstart[c];
+        for (uint32_t i = 0; i < n; i += IVF_MQ, ++g)
+            gdesc[g] = make_uint2(((s0 + i) << 3) | (n - i < IVF_MQ ? n - i : (uint32_t)IVF_MQ), (uint32_t)c);
+    }
+    const uint32_t nodd = cnt[K], sodd = start[K];
+    for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < nodd; i += gridDim.x * 256) {
+        const uint32_t pair = order[sodd + i];
+        ((uint32_t *)(ws + (size_t)(pair / (uint32_t)nprobe) * per_query + counts_off))[pair % (uint32_t)nprobe] = 0;
+    }
+}
+
 // ------------------------------------------------------------ k_ivf_final ---
 // Rank candidates (ordered-float distance << 32 | id) and write the first R.
 __device__ inline void ivf_rank_and_write(const uint64_t *A, int na, int R, int32_t *ids,
@@ -901,16 +1214,60 @@ static int allow_lds(K kernel, size_t bytes) {
     return PQ_OK;
 }
 
+// 16 x 4 bits over equal sub-spaces of 4, 6 or 8 dimensions with 8-bit tables: that width, else 0
+static int ivf_fixed_shape(const pq_index *idx) {
+    const DevLayout &h = idx->h;
+    const bool ok = h.kind == SCAN_NIB8 && h.acc_bits == 8 && h.m == 16 && h.T == 256 && h.ds_uniform > 0 &&
+                    h.d == 16 * h.ds_uniform && (h.ds_uniform == 4 || h.ds_uniform == 6 || h.ds_uniform == 8);
+    return ok ? h.ds_uniform : 0;
+}
+
 template <int KIND, typename QT>
 static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *list_offsets,
                       const uint8_t *list_codes, const int32_t *list_ids, const float *queries,
                       int nq, const int32_t *probe_ids, int nprobe, int K, int want, int R,
                       int32_t *out_ids, float *out_dist, char *ws, const IvfPlan &p, uint32_t *sortws,
-                      bool tighten, hipStream_t s) {
+                      bool shared_lists, bool tighten, hipStream_t s) {
     // blocks in the order of the probed cells (see k_pair_count):
     // sortws = cnt[NB+1] | start[NB+1] | order[pairs]
     const uint32_t *order = nullptr;
-    if (sortws) {
+    // fixed shape of k_ivf_scan's fast set-up and of k_ivf_scan_mq: 16 x 4 bits over equal
+    // sub-spaces of 4, 6 or 8 dimensions, 8-bit tables
+    const int dsf = (KIND == SCAN_NIB8 && sizeof(QT) == 1) ? ivf_fixed_shape(idx) : 0;
+    const uint2 *gdesc = nullptr;
+    const uint32_t *ngroups = nullptr;
+    size_t max_groups = 0;
+    if (sortws && shared_lists && dsf != 0 && !tighten) {
+        // pairs sorted by cell exactly and cut into groups of four (see k_ivf_scan_mq):
+        // sortws = cnt[K+2] | start[K+2] | gstart[K+2] | bsum[2 * 1024] | order[pairs] | gdesc[pairs/4 + K + 1] (8 bytes each)
+        const int64_t npairs = (int64_t)nq * nprobe;
+        const size_t nbw = ((size_t)K + 3) & ~(size_t)1;  // K + 2 words, rounded up to even: gdesc is 8-byte aligned
+        uint32_t *cnt = sortws, *start = sortws + nbw, *gstart = sortws + 2 * nbw, *bsum = sortws + 3 * nbw;
+        uint32_t *ord = bsum + 2048;
+        uint2 *gd = (uint2 *)(ord + ((npairs + 1) & ~(int64_t)1));
+        max_groups = (size_t)(npairs / IVF_MQ) + (size_t)K + 1;
+        const unsigned scan_blocks = (unsigned)((K + 1 + 1023) / 1024);  // <= 1024: K < 2^20 is checked by the caller
+        hipLaunchKernelGGL(k_pair_zero, dim3((unsigned)((nbw + 255) / 256)), dim3(256), 0, s, cnt, (int)nbw);
+        QADC_LAUNCH_CHECK("k_pair_zero");
+        hipLaunchKernelGGL(k_pair_count, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, probe_ids,
+                           list_offsets, npairs, K, K, cnt);
+        QADC_LAUNCH_CHECK("k_pair_count");
+        hipLaunchKernelGGL(k_pair_block_sums, dim3(scan_blocks), dim3(1024), 0, s, (const uint32_t *)cnt, K + 1, bsum);
+        QADC_LAUNCH_CHECK("k_pair_block_sums");
+        hipLaunchKernelGGL(k_pair_scan_groups, dim3(scan_blocks), dim3(1024), 0, s, cnt, start, gstart, K + 1,
+                           (const uint32_t *)bsum);
+        QADC_LAUNCH_CHECK("k_pair_scan_groups");
+        hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, probe_ids,
+                           list_offsets, npairs, K, K, (const uint32_t *)start, cnt, ord);
+        QADC_LAUNCH_CHECK("k_pair_fill");
+        hipLaunchKernelGGL(k_group_fill, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s, (const uint32_t *)cnt,
+                           (const uint32_t *)start, (const uint32_t *)gstart, (const uint32_t *)ord, K, nprobe,
+                           ws, p.per_query, p.counts_off, gd);
+        QADC_LAUNCH_CHECK("k_group_fill");
+        order = ord;
+        gdesc = gd;
+        ngroups = gstart + (K + 1);
+    } else if (sortws) {
         const int64_t npairs = (int64_t)nq * nprobe;
         const int NB = K < IVF_SORT_BUCKETS ? K : IVF_SORT_BUCKETS;
         uint32_t *cnt = sortws, *start = sortws + (NB + 1), *ord = sortws + 2 * (size_t)(NB + 1);
@@ -970,6 +1327,32 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
         QADC_LAUNCH_CHECK("k_ivf_tight");
         return PQ_OK;
     }
+    if (gdesc) {
+        const size_t lds_mq = IVF_MQ_TAB_BYTES + sizeof(IvfMqLds);
+        static int mq_static_lds = -1;  // k_ivf_scan_mq addresses its tables from LDS address 0
+        if (mq_static_lds < 0) {
+            hipFuncAttributes a4, a6, a8;
+            if (hipFuncGetAttributes(&a4, (const void *)k_ivf_scan_mq<4>) != hipSuccess ||
+                hipFuncGetAttributes(&a6, (const void *)k_ivf_scan_mq<6>) != hipSuccess ||
+                hipFuncGetAttributes(&a8, (const void *)k_ivf_scan_mq<8>) != hipSuccess) {
+                qadc_set_error("k_ivf_scan_mq: hipFuncGetAttributes failed");
+                return PQ_EHIP;
+            }
+            mq_static_lds = (int)(a4.sharedSizeBytes + a6.sharedSizeBytes + a8.sharedSizeBytes);
+        }
+        if (mq_static_lds != 0) {
+            qadc_set_error("k_ivf_scan_mq: static LDS of %d bytes (its tables must start at LDS address 0)", mq_static_lds);
+            return PQ_EHIP;
+        }
+#define QADC_IVF_MQ(DSV)                                                                             \
+    hipLaunchKernelGGL((k_ivf_scan_mq<DSV>), dim3((unsigned)max_groups), dim3(256), lds_mq, s,       \
+                       idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,          \
+                       probe_ids, nprobe, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b, order, \
+                       gdesc, ngroups)
+        if (dsf == 4) QADC_IVF_MQ(4); else if (dsf == 6) QADC_IVF_MQ(6); else QADC_IVF_MQ(8);
+#undef QADC_IVF_MQ
+        QADC_LAUNCH_CHECK("k_ivf_scan_mq");
+    } else {
     const int scan_threads = (int)qadc_option(PQ_OPT_IVF_THREADS);
     // table entries per thread: the low-latency set-up holds up to four in registers
     const int ne = idx->h.T <= scan_threads ? 1 : (idx->h.T <= 2 * scan_threads ? 2 : (idx->h.T <= 4 * scan_threads ? 4 : 0));
@@ -980,22 +1363,21 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
                        p.slots_off, p.cap_b, order)
     // 16 x 4 bits over equal sub-spaces with 8-bit tables, at the default block size: the
     // fixed-shape set-up
-    const int dsf = (KIND == SCAN_NIB8 && sizeof(QT) == 1 && scan_threads == 128 && idx->h.m == 16 &&
-                     idx->h.T == 256 && idx->h.ds_uniform > 0 && idx->h.d == 16 * idx->h.ds_uniform)
-                        ? idx->h.ds_uniform : 0;
+    const int dsfix = scan_threads == 128 ? dsf : 0;
 #define QADC_IVF_SCAN_FIX(DSV)                                                                      \
     hipLaunchKernelGGL((k_ivf_scan<SCAN_NIB8, uint8_t, 2, DSV>), dim3(nprobe, nq), dim3(128), lds_scan, s, \
                        idx->dev, idx->edesc, idx->codebooks, coarse, list_offsets, list_codes,     \
                        list_ids, queries, probe_ids, nprobe, K, R, ws, p.per_query, p.counts_off,  \
                        p.slots_off, p.cap_b, order)
-    if (dsf == 4 || dsf == 6 || dsf == 8) {
+    if (dsfix != 0) {
         if (KIND == SCAN_NIB8 && sizeof(QT) == 1) {  // (the macro names the types itself)
-            if (dsf == 4) QADC_IVF_SCAN_FIX(4); else if (dsf == 6) QADC_IVF_SCAN_FIX(6); else QADC_IVF_SCAN_FIX(8);
+            if (dsfix == 4) QADC_IVF_SCAN_FIX(4); else if (dsfix == 6) QADC_IVF_SCAN_FIX(6); else QADC_IVF_SCAN_FIX(8);
         }
     } else if (ne == 1) QADC_IVF_SCAN(1); else if (ne == 2) QADC_IVF_SCAN(2); else if (ne == 4) QADC_IVF_SCAN(4); else QADC_IVF_SCAN(0);
 #undef QADC_IVF_SCAN_FIX
 #undef QADC_IVF_SCAN
     QADC_LAUNCH_CHECK("k_ivf_scan");
+    }
     if (small_final)
         hipLaunchKernelGGL((k_ivf_final<KIND, QT, true>), dim3(nq), dim3(256), lds_final, s, idx->dev,
                            idx->edesc, idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,
@@ -1014,11 +1396,20 @@ static size_t ivf_sort_bytes(int nq, int nprobe, int K) {
     const size_t nb = K < IVF_SORT_BUCKETS ? (size_t)K : (size_t)IVF_SORT_BUCKETS;
     return ((2 * (nb + 1) + (size_t)nq * (size_t)nprobe) * sizeof(uint32_t) + 255) & ~(size_t)255;
 }
+// the sort by cell and the groups of k_ivf_scan_mq
+static size_t ivf_group_bytes(int nq, int nprobe, int K) {
+    const size_t pairs = (size_t)nq * (size_t)nprobe;
+    return ((3 * ((size_t)K + 3) + 2048 + pairs + 2 + 2 * (pairs / IVF_MQ + (size_t)K + 1)) * sizeof(uint32_t) + 255) & ~(size_t)255;
+}
+// Half-pairs per cell from which one pass per list for four pairs beats a block per pair
+// (C4 shape, measured: 2 pairs per cell even, 3.9 pairs +13 %, 9.8 pairs +22 %; 1 pair -15 %)
+#define IVF_SHARED_MIN_HALF_PAIRS_PER_CELL 5
 
 extern "C" size_t ivf_sorted_workspace_bytes(const pq_index_t *idx, int nq, int nprobe, int R, int K) {
     if (!idx || nq < 0 || nprobe < 1 || R < 1 || K < 1) return 0;
     const size_t base = (qadc_ivf_plan(idx, nq, nprobe, R).total + 255) & ~(size_t)255;
-    return base + ivf_sort_bytes(nq, nprobe, K) + 256;
+    const size_t a = ivf_sort_bytes(nq, nprobe, K), b = ivf_group_bytes(nq, nprobe, K);
+    return base + (a > b ? a : b) + 256;
 }
 
 static int ivf_search(const char *name, bool tighten, const pq_index_t *idx, const float *coarse_centroids,
@@ -1067,10 +1458,16 @@ static int ivf_search(const char *name, bool tighten, const pq_index_t *idx, con
     if (!tighten && (int64_t)nq * nprobe * 4 >= (int64_t)K &&
         workspace_bytes >= base_bytes + ivf_sort_bytes(nq, nprobe, K))
         sortws = (uint32_t *)(ws + base_bytes);
+    // many pairs per cell (or the option says always): one pass over a list serves four pairs
+    const int64_t shared_opt = qadc_option(PQ_OPT_IVF_SHARED_LISTS);
+    const bool shared_lists = !tighten && shared_opt != 0 && ivf_fixed_shape(idx) != 0 && K < (1 << 20) &&
+                              workspace_bytes >= base_bytes + ivf_group_bytes(nq, nprobe, K) &&
+                              (shared_opt == 2 || 2 * (int64_t)nq * nprobe >= (int64_t)IVF_SHARED_MIN_HALF_PAIRS_PER_CELL * K);
+    if (shared_lists) sortws = (uint32_t *)(ws + base_bytes);
     const bool u8 = idx->h.acc_bits == 8;
 #define QADC_GO(KIND, QT)                                                                          \
     return launch_ivf<KIND, QT>(idx, coarse_centroids, list_offsets, list_codes, list_ids, queries, \
-                                nq, probe_ids, nprobe, K, (int)want, R, out_ids, out_dist, ws, p, sortws, tighten, s)
+                                nq, probe_ids, nprobe, K, (int)want, R, out_ids, out_dist, ws, p, sortws, shared_lists, tighten, s)
     switch (idx->h.kind) {
         case SCAN_NIB8:
             if (u8) QADC_GO(SCAN_NIB8, uint8_t); else QADC_GO(SCAN_NIB8, uint16_t);

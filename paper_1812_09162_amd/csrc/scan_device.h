@@ -289,6 +289,32 @@ __device__ __forceinline__ void keys_batch(const DevLayout *L, const QT *gtab,
     }
 }
 
+// ------------------------------------- interleaved tables of four queries ---
+// Byte N of w, times 8 (the byte offset of an 8-byte table entry), as one instruction: a shift
+// whose operand is selected by sub-dword addressing.
+template <int N>
+__device__ __forceinline__ uint32_t mq_byte_x8(uint32_t w, uint32_t three) {
+    uint32_t r;
+    if (N == 0)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(three), "v"(w));
+    else if (N == 1)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(three), "v"(w));
+    else if (N == 2)
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(three), "v"(w));
+    else
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(three), "v"(w));
+    return r;
+}
+// Entry `byte N of w` of group g of the interleaved tables, which start at LDS address 0 (the
+// kernel has no other LDS but what follows them): the read takes the shifted byte as its
+// address and g * 2048 as its immediate offset.
+typedef const unsigned long long __attribute__((address_space(3))) mq_lds_entry;
+template <int N>
+__device__ __forceinline__ uint2 mq_entry(int g, uint32_t w, uint32_t three) {
+    const unsigned long long e = *(mq_lds_entry *)(g * 2048u + mq_byte_x8<N>(w, three));
+    return make_uint2((uint32_t)e, (uint32_t)(e >> 32));
+}
+
 // ------------------------------------------------------------ slot lists ---
 #define MAX_G 4096                 // slot lists per query a final kernel can gather
 #define FINAL_LPT (MAX_G / 1024)   // slot lists per thread of a 1024-thread final kernel

@@ -60,6 +60,8 @@ def test_options_are_validated_and_kept():
     assert lib.pq_get_option(qb.PQ_OPT_SCAN_BLOCKS) == 2048
     assert lib.pq_set_option(qb.PQ_OPT_SCAN_BLOCKS, 0) == qb.PQ_EINVAL       # out of range: unchanged
     assert lib.pq_set_option(qb.PQ_OPT_IVF_THREADS, 100) == qb.PQ_EINVAL
+    assert lib.pq_set_option(qb.PQ_OPT_IVF_SHARED_LISTS, 3) == qb.PQ_EINVAL
+    assert lib.pq_get_option(qb.PQ_OPT_IVF_SHARED_LISTS) == 1
     assert lib.pq_set_option(99, 1) == qb.PQ_EINVAL and b"option 99" in lib.pq_last_error()
     assert lib.pq_get_option(99) == -1
     assert lib.pq_set_option(qb.PQ_OPT_SCAN_BLOCKS, 1024) == qb.PQ_OK

@@ -128,6 +128,16 @@ def run_ivf(qb, cfg, nq_oracle, R=100):
     torch.cuda.synchronize()
     assert torch.equal(gi, gi2) and torch.equal(gd, gd2)
     del small, gi2, gd2
+    # one pass per list for up to four of the queries that probe it, whatever the number of pairs per cell
+    qb.pq_set_option(qb.PQ_OPT_IVF_SHARED_LISTS, 2)
+    try:
+        gi3, gd3 = qb.ivf_adc_scan_topk(idx, ip.coarse, ip.list_offsets, ip.list_codes, ip.list_ids,
+                                        ip.queries, ip.probe_ids, T_CAL, R)
+        torch.cuda.synchronize()
+    finally:
+        qb.pq_set_option(qb.PQ_OPT_IVF_SHARED_LISTS, 1)
+    assert torch.equal(gi, gi3) and torch.equal(gd, gd3)
+    del gi3, gd3
     host = dict(cb=ip.codebooks.cpu().numpy(), coarse=ip.coarse.cpu().numpy(),
                 off=ip.list_offsets.cpu().numpy(), codes=ip.list_codes.cpu().numpy(),
                 ids=ip.list_ids.cpu().numpy(), q=ip.queries.cpu().numpy(),

@@ -384,8 +384,14 @@ def check_ivf(qb, ip, R, t=T_CAL, probe=None):
                         device=dev())
     gi2, gd2 = qb.ivf_adc_scan_topk(*args, workspace=small)   # minimal workspace: blocks in grid order
     ti, td = qb.ivf_adc_scan_topk_tightening(*args)           # the bound tightened list by list
-    torch.cuda.synchronize()
+    qb.pq_set_option(qb.PQ_OPT_IVF_SHARED_LISTS, 2)           # one pass per list for four pairs, always
+    try:
+        gi3, gd3 = qb.ivf_adc_scan_topk(*args)
+        torch.cuda.synchronize()
+    finally:
+        qb.pq_set_option(qb.PQ_OPT_IVF_SHARED_LISTS, 1)
     assert torch.equal(gi, gi2) and torch.equal(gd, gd2)
+    assert torch.equal(gi, gi3) and torch.equal(gd, gd3)
     host = (lay.d, lay.nbits, lay.dsub, lay.acc_bits, ip.codebooks.numpy(), ip.coarse.numpy(),
             ip.list_offsets.numpy(), ip.list_codes.numpy(), ip.list_ids.numpy())
     for q in range(ip.queries.shape[0]):
