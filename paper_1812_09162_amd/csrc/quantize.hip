@@ -32,6 +32,7 @@
 // them through the layout pointer would be a memory round trip ahead of every other load).
 struct QuantShape {
     int T, m, cs, qmax, d;
+    int ubits, uds;  // bits and dimensions of every sub-quantizer if they are all alike, else 0
 };
 // NIB8 pilot codes a thread holds in registers per batch
 #define PILOT_PER_THREAD 16
@@ -100,7 +101,31 @@ k_quantize(const DevLayout *__restrict__ L, const QuantShape shape, const EntryD
     EntryDesc ed0 = {0, 0, 0, 0};
     if ((int)threadIdx.x < T) ed0 = edesc[threadIdx.x];
 
-    if (queries) {
+    if (queries && shape.ubits > 0 && shape.uds > 0 && T > (int)blockDim.x) {
+        // long tables of sub-quantizers that are all alike (m x 8 bits): entry e is centroid
+        // e mod 2^bits of sub-quantizer e >> bits at codebook offset e * ds, so nothing has to
+        // be looked up before the codebook values are requested, and the loop over the
+        // dimensions has the same length in every lane
+        float *zs = (float *)ord;
+        for (int i = threadIdx.x; i < d; i += blockDim.x) zs[i] = queries[q * d + i];
+        __syncthreads();
+        const int ub = shape.ubits, ds = shape.uds;
+        for (int e = threadIdx.x; e < T; e += blockDim.x) {
+            const int j = e >> ub;
+            const float *c = cb + (size_t)e * ds;
+            const float *z = zs + j * ds;
+            float acc = 0.0f;
+            for (int l = 0; l < ds; ++l) {
+                float diff = __fsub_rn(z[l], c[l]);
+                acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+            }
+            tab[e] = acc;
+            esub[e] = (uint8_t)j;
+            atomicMin(&pmin_ord[j], qadc_f2ord(acc));
+            if (tables_out && first) tables_out[q * T + e] = acc;
+        }
+        __syncthreads();
+    } else if (queries) {
         float *zs = (float *)ord;  // the query lives where the ADC sums go later
         for (int i = threadIdx.x; i < d; i += blockDim.x) zs[i] = queries[q * d + i];
         for (int e = threadIdx.x; e < T; e += blockDim.x)
@@ -405,8 +430,13 @@ static int launch_quantize(const pq_index *idx, const float *queries, const floa
     if (lds > 48 * 1024)
         QADC_HIP_TRY(hipFuncSetAttribute((const void *)k_quantize<KIND, QT>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    int ubits = idx->h.nbits[0], uds = idx->h.dsub[0];
+    for (int j = 1; j < idx->h.m; ++j) {
+        if (idx->h.nbits[j] != ubits) ubits = 0;
+        if (idx->h.dsub[j] != uds) uds = 0;
+    }
     hipLaunchKernelGGL((k_quantize<KIND, QT>), dim3((unsigned)nq * (unsigned)pp.P), dim3(QUANT_THREADS), lds, s,
-                       idx->dev, QuantShape{idx->h.T, idx->h.m, idx->h.cs, idx->h.qmax, idx->h.d}, idx->edesc,
+                       idx->dev, QuantShape{idx->h.T, idx->h.m, idx->h.cs, idx->h.qmax, idx->h.d, ubits, uds}, idx->edesc,
                        idx->codebooks, queries, tables_in, tables_out, codes, t_eff, k,
                        pp.pilot, pp.slice, pp.P, qtables, qparams, gtab_out, gtab_stride, hdr_out, bound_rec);
     QADC_LAUNCH_CHECK("k_quantize");
