@@ -393,6 +393,24 @@ def main():
 
     extras = {}
     if not a.no_extras:
+        # a second denominator next to the published peak: what a plain copy kernel of this
+        # library moves on this GPU (1 GiB read + 1 GiB written, more than the last-level cache)
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        best = None
+        for _ in range(4):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            qb.pq_copy_bytes(dst, src)
+            e1.record()
+            e1.synchronize()
+            gbs = 2.0 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+            best = gbs if best is None or gbs > best else best
+        del src, dst
+        roofline["measured_copy_gbs"] = best
+        roofline["frac_of_measured_copy"] = achieved / best
+        if "achieved_cold" in roofline:
+            roofline["frac_cold_of_measured_copy"] = roofline["achieved_cold"] / best
         lat = Runner(qb, idx, pr.queries, pr.codes, a.batch, a.R, streams=1, fused=not a.unfused)
         med, mn = isolated_latency(lat)
         extras["isolated_latency_ms"] = {"median": med, "min": mn,
