@@ -507,6 +507,7 @@ def main():
             usable = os.cpu_count()
         out["cpu_baseline"] = {"value": a.cpu_queries * n / cdt / 1e9, "unit": "Gcodes/s",
                                "cores": threads, "kind": "oracle",
+                               "gcodes_per_s_per_core": a.cpu_queries * n / cdt / 1e9 / threads,
                                "nproc": os.cpu_count(), "usable_cpus": usable,
                                "sample": f"{a.cpu_queries} queries x {n} codes (the full list), "
                                          f"one query per thread on {threads} threads, {cdt:.1f} s wall"}
