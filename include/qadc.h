@@ -108,7 +108,7 @@ size_t ivf_workspace_bytes(const pq_index_t *idx, int nq, int nprobe, int R);
 /* The same plus room to order the (query, probe) pairs by probed cell (K cells): given that
  * much, and at least K/4 pairs, ivf_adc_scan_topk scans the pairs of one cell close together
  * in time, so that a list probed by several queries of the call is read from memory once;
- * with at least 2.5 pairs per cell, 16 x 4-bit codes over equal sub-spaces of 4, 6 or 8
+ * with at least 1.5 pairs per cell, 16 x 4-bit codes over equal sub-spaces of 4, 6 or 8
  * dimensions and 8-bit tables, one pass over a list then serves up to four of the queries that
  * probe it (PQ_OPT_IVF_SHARED_LISTS).  Results are the same. */
 size_t ivf_sorted_workspace_bytes(const pq_index_t *idx, int nq, int nprobe, int R, int K);
@@ -324,7 +324,7 @@ enum {
                                       0: it always writes the full score matrix (1) */
     PQ_OPT_IVF_SHARED_LISTS = 7,   /* inverted-list search, 16 x 4-bit codes with 8-bit tables: one pass
                                       over a list serves up to four of the queries that probe it.
-                                      0: never; 1: when the call has at least 2.5 (query, probe)
+                                      0: never; 1: when the call has at least 1.5 (query, probe)
                                       pairs per cell and the workspace is the larger one; 2: whenever
                                       the workspace is the larger one (1) */
     PQ_OPT_COUNT = 8

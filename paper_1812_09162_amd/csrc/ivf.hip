@@ -742,12 +742,17 @@ k_ivf_scan_mq(const float *__restrict__ cb, const float *__restrict__ coarse,
         }
     }
     __syncthreads();
-    // field w of the interleaved tables: entry (g, byte) = low-nibble entry + high-nibble entry
+    // the interleaved tables: entry (g, byte) holds, for each of the four pairs, low-nibble entry +
+    // high-nibble entry; a thread writes whole 8-byte entries
     {
-        uint16_t *tf = (uint16_t *)smem + w;
-        for (int x = lane; x < 8 * 256; x += 64) {
+        uint2 *tab = (uint2 *)smem;
+        for (int x = threadIdx.x; x < 8 * 256; x += 256) {
             const int g = x >> 8, byte = x & 255;
-            tf[4 * x] = (uint16_t)(S.qt[w][32 * g + (byte & 15)] + S.qt[w][32 * g + 16 + (byte >> 4)]);
+            const int il = 32 * g + (byte & 15), ih = 32 * g + 16 + (byte >> 4);
+            uint32_t v[IVF_MQ];
+#pragma unroll
+            for (int j = 0; j < IVF_MQ; ++j) v[j] = (uint32_t)S.qt[j][il] + (uint32_t)S.qt[j][ih];
+            tab[x] = make_uint2(v[0] | (v[1] << 16), v[2] | (v[3] << 16));
         }
     }
     __syncthreads();
@@ -1402,8 +1407,8 @@ static size_t ivf_group_bytes(int nq, int nprobe, int K) {
     return ((3 * ((size_t)K + 3) + 2048 + pairs + 2 + 2 * (pairs / IVF_MQ + (size_t)K + 1)) * sizeof(uint32_t) + 255) & ~(size_t)255;
 }
 // Half-pairs per cell from which one pass per list for four pairs beats a block per pair
-// (C4 shape, measured: 2 pairs per cell even, 3.9 pairs +13 %, 9.8 pairs +22 %; 1 pair -15 %)
-#define IVF_SHARED_MIN_HALF_PAIRS_PER_CELL 5
+// (C4 shape, measured: 1 pair per cell -7 %, 2 pairs +9 %, 3.9 pairs +22 %, 9.8 pairs +32 %)
+#define IVF_SHARED_MIN_HALF_PAIRS_PER_CELL 3
 
 extern "C" size_t ivf_sorted_workspace_bytes(const pq_index_t *idx, int nq, int nprobe, int R, int K) {
     if (!idx || nq < 0 || nprobe < 1 || R < 1 || K < 1) return 0;
