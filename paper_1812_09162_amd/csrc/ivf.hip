@@ -766,10 +766,14 @@ k_ivf_scan_mq(const float *__restrict__ cb, const float *__restrict__ coarse,
     }
     const uint32_t three = 3;
     for (int64_t pb = 0; pb < npair; pb += (int64_t)PF * 256) {
-        if (pb != 0) {
+        // the next round of codes is requested before this one is looked up
+        uint4 cur[PF];
+#pragma unroll
+        for (int u = 0; u < PF; ++u) cur[u] = pp[u];
+        if (pb + (int64_t)PF * 256 < npair) {
 #pragma unroll
             for (int u = 0; u < PF; ++u) {
-                int64_t pi = pb + (int64_t)u * 256 + threadIdx.x;
+                int64_t pi = pb + (int64_t)(PF + u) * 256 + threadIdx.x;
                 pi = pi < npair ? pi : npair - 1;
                 pp[u] = pairs[pi];
             }
@@ -779,8 +783,8 @@ k_ivf_scan_mq(const float *__restrict__ cb, const float *__restrict__ coarse,
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             valid[u] = pb + (int64_t)u * 256 + threadIdx.x < npair;
-            ivf_mq_sums(pp[u].x, pp[u].y, three, slo[2 * u], shi[2 * u]);
-            ivf_mq_sums(pp[u].z, pp[u].w, three, slo[2 * u + 1], shi[2 * u + 1]);
+            ivf_mq_sums(cur[u].x, cur[u].y, three, slo[2 * u], shi[2 * u]);
+            ivf_mq_sums(cur[u].z, cur[u].w, three, slo[2 * u + 1], shi[2 * u + 1]);
         }
         uint32_t ord[IVF_MQ][2 * PF];
         bool pass[IVF_MQ][2 * PF], any = false;
