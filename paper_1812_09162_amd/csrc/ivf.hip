@@ -617,6 +617,14 @@ k_ivf_scan(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
 // and then all four waves scan the list once: one 8-byte read per code byte serves the four
 // pairs.  Every pair keeps its own slot list and count, so the selection is unchanged.
 #define IVF_MQ 4
+// A group: up to four (query, probe) pairs of one cell, in one 32-byte record so that a block's
+// loads depend on one another two deep (record; then queries, list bounds and so on).
+struct __align__(16) IvfGroup {
+    uint32_t pair[IVF_MQ];  // q * nprobe + a; entries beyond k repeat the first
+    int32_t cell;
+    int32_t k;
+    int32_t pad[2];
+};
 struct IvfMqLds {                      // behind the interleaved tables (which start at LDS address 0)
     float zres[IVF_MQ][128];
     float pmin[IVF_MQ][16];
@@ -648,19 +656,18 @@ k_ivf_scan_mq(const float *__restrict__ cb, const float *__restrict__ coarse,
               const int32_t *__restrict__ list_ids, const float *__restrict__ queries,
               const int32_t *__restrict__ probe_ids, int nprobe, char *__restrict__ ws, size_t per_query,
               size_t counts_off, size_t slots_off, int cap_b, const uint32_t *__restrict__ order,
-              const uint2 *__restrict__ gdesc, const uint32_t *__restrict__ ngroups) {
+              const IvfGroup *__restrict__ gdesc, const uint32_t *__restrict__ ngroups) {
     extern __shared__ __align__(16) unsigned char smem[];  // tables at LDS address 0 (no static LDS here)
     IvfMqLds &S = *(IvfMqLds *)(smem + IVF_MQ_TAB_BYTES);
     if (blockIdx.x >= *ngroups) return;
     constexpr int d = 16 * DS;
     constexpr uint32_t qmax = 255;
-    const uint2 gdv = gdesc[blockIdx.x];
-    const uint32_t first = gdv.x >> 3;
-    const int k = (int)(gdv.x & 7u);  // 1..4 pairs, all of cell c, whose list is not empty
-    const int c = (int)gdv.y;
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const IvfGroup *gp = gdesc + blockIdx.x;
+    const int k = gp->k;  // 1..4 pairs, all of cell c, whose list is not empty
+    const int c = gp->cell;
     const bool act = w < k;
-    const uint32_t pair = order[first + (act ? (uint32_t)w : 0u)];  // (idle waves mirror pair 0, store nothing)
+    const uint32_t pair = gp->pair[w];  // (idle waves mirror pair 0, store nothing)
     const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
     const size_t q = pair / (uint32_t)nprobe;
     const int a = (int)(pair % (uint32_t)nprobe);
@@ -907,19 +914,26 @@ k_pair_scan_groups(uint32_t *__restrict__ cnt, uint32_t *__restrict__ start, uin
     }
 }
 
-// One thread per cell writes the cell's group descriptors {first pair << 3 | pairs, cell}; the pairs
+// One thread per cell writes the cell's group records; the pairs
 // without a list get their slot counts cleared (no block will visit them).  cnt holds the
 // cells' pair counts again after k_pair_fill.
 __global__ void __launch_bounds__(256)
 k_group_fill(const uint32_t *__restrict__ cnt, const uint32_t *__restrict__ start,
              const uint32_t *__restrict__ gstart, const uint32_t *__restrict__ order, int K, int nprobe,
-             char *__restrict__ ws, size_t per_query, size_t counts_off, uint2 *__restrict__ gdesc) {
+             char *__restrict__ ws, size_t per_query, size_t counts_off, IvfGroup *__restrict__ gdesc) {
     const int c = blockIdx.x * 256 + threadIdx.x;
     if (c < K) {
         const uint32_t n = cnt[c], s0 = start[c];
         uint32_t g = gstart[c];
-        for (uint32_t i = 0; i < n; i += IVF_MQ, ++g)
-            gdesc[g] = make_uint2(((s0 + i) << 3) | (n - i < IVF_MQ ? n - i : (uint32_t)IVF_MQ), (uint32_t)c);
+        for (uint32_t i = 0; i < n; i += IVF_MQ, ++g) {
+            IvfGroup gr;
+            gr.k = (int32_t)(n - i < IVF_MQ ? n - i : (uint32_t)IVF_MQ);
+            gr.cell = c;
+            gr.pad[0] = gr.pad[1] = 0;
+#pragma unroll
+            for (int j = 0; j < IVF_MQ; ++j) gr.pair[j] = order[s0 + i + (j < gr.k ? (uint32_t)j : 0u)];
+            gdesc[g] = gr;
+        }
     }
     const uint32_t nodd = cnt[K], sodd = start[K];
     for (uint32_t i = blockIdx.x * 256 + threadIdx.x; i < nodd; i += gridDim.x * 256) {
@@ -1243,17 +1257,17 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     // fixed shape of k_ivf_scan's fast set-up and of k_ivf_scan_mq: 16 x 4 bits over equal
     // sub-spaces of 4, 6 or 8 dimensions, 8-bit tables
     const int dsf = (KIND == SCAN_NIB8 && sizeof(QT) == 1) ? ivf_fixed_shape(idx) : 0;
-    const uint2 *gdesc = nullptr;
+    const IvfGroup *gdesc = nullptr;
     const uint32_t *ngroups = nullptr;
     size_t max_groups = 0;
     if (sortws && shared_lists && dsf != 0 && !tighten) {
         // pairs sorted by cell exactly and cut into groups of four (see k_ivf_scan_mq):
-        // sortws = cnt[K+2] | start[K+2] | gstart[K+2] | bsum[2 * 1024] | order[pairs] | gdesc[pairs/4 + K + 1] (8 bytes each)
+        // sortws = cnt[K+2] | start[K+2] | gstart[K+2] | bsum[2 * 1024] | order[pairs] | (16-byte aligned) gdesc[pairs/4 + K + 1]
         const int64_t npairs = (int64_t)nq * nprobe;
-        const size_t nbw = ((size_t)K + 3) & ~(size_t)1;  // K + 2 words, rounded up to even: gdesc is 8-byte aligned
+        const size_t nbw = (size_t)K + 2;
         uint32_t *cnt = sortws, *start = sortws + nbw, *gstart = sortws + 2 * nbw, *bsum = sortws + 3 * nbw;
         uint32_t *ord = bsum + 2048;
-        uint2 *gd = (uint2 *)(ord + ((npairs + 1) & ~(int64_t)1));
+        IvfGroup *gd = (IvfGroup *)(((uintptr_t)(ord + npairs) + 15) & ~(uintptr_t)15);
         max_groups = (size_t)(npairs / IVF_MQ) + (size_t)K + 1;
         const unsigned scan_blocks = (unsigned)((K + 1 + 1023) / 1024);  // <= 1024: K < 2^20 is checked by the caller
         hipLaunchKernelGGL(k_pair_zero, dim3((unsigned)((nbw + 255) / 256)), dim3(256), 0, s, cnt, (int)nbw);
@@ -1408,7 +1422,8 @@ static size_t ivf_sort_bytes(int nq, int nprobe, int K) {
 // the sort by cell and the groups of k_ivf_scan_mq
 static size_t ivf_group_bytes(int nq, int nprobe, int K) {
     const size_t pairs = (size_t)nq * (size_t)nprobe;
-    return ((3 * ((size_t)K + 3) + 2048 + pairs + 2 + 2 * (pairs / IVF_MQ + (size_t)K + 1)) * sizeof(uint32_t) + 255) & ~(size_t)255;
+    return ((3 * ((size_t)K + 2) + 2048 + pairs) * sizeof(uint32_t) + 16 +
+            (pairs / IVF_MQ + (size_t)K + 1) * sizeof(IvfGroup) + 255) & ~(size_t)255;
 }
 // Half-pairs per cell from which one pass per list for four pairs beats a block per pair
 // (C4 shape, measured: 1 pair per cell -7 %, 2 pairs +9 %, 3.9 pairs +22 %, 9.8 pairs +32 %)
