@@ -117,6 +117,65 @@ __device__ inline bool ivf_setup(const DevLayout *L, const EntryDesc *__restrict
     return true;
 }
 
+// The same for the fixed shape 16 x 4 bits over sub-spaces of DS dimensions each (T = 256,
+// d = 16 DS) by a block of 256 threads: thread e holds table entry e = centroid e % 16 of
+// sub-quantizer e / 16 at codebook offset e * DS, so nothing is looked up, the minima come
+// from lane exchanges, and the codebook values travel while the residual settles in LDS.
+template <int DS>
+__device__ inline bool ivf_setup_fix(const float *__restrict__ cb, const float *__restrict__ z,
+                                     const float *__restrict__ cen, float dmax, bool quantize,
+                                     uint32_t qmax, const IvfLds &l) {
+    constexpr int d = 16 * DS;
+    const int e = threadIdx.x;
+    float cv[DS];
+#pragma unroll
+    for (int t = 0; t < DS; ++t) cv[t] = cb[e * DS + t];
+    if (e < d) l.zres[e] = __fsub_rn(z[e], cen[e]);
+    __syncthreads();
+    const float *zz = l.zres + (e >> 4) * DS;
+    float acc = 0.0f;
+#pragma unroll
+    for (int t = 0; t < DS; ++t) {
+        const float diff = __fsub_rn(zz[t], cv[t]);
+        acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+    }
+    l.tab[e] = acc;
+    float mn = acc;
+#pragma unroll
+    for (int sft = 1; sft < 16; sft <<= 1) {
+        const float o = __shfl_xor(mn, sft, QADC_WAVE);
+        mn = o < mn ? o : mn;
+    }
+    if ((e & 15) == 0) l.pmin[e >> 4] = mn;
+    __syncthreads();
+    if (e == 0) {
+        double dm = 0.0;
+        for (int j = 0; j < 16; ++j) dm = dm + (double)l.pmin[j];
+        l.sc[0] = dm;
+        int skip = 0;
+        double delta = 0.0;
+        if (quantize) {
+            skip = dm >= (double)dmax;
+            delta = ((double)dmax - dm) / (double)qmax;
+            if (!((delta > 0.0) && isfinite(delta))) delta = 0.0;
+        }
+        l.sc[1] = delta;
+        *l.flag = skip;
+    }
+    __syncthreads();
+    if (!quantize) return true;
+    if (*l.flag) return false;
+    const double delta = l.sc[1];
+    uint32_t qv = 0;
+    if (delta > 0.0) {
+        const double x = floor(((double)acc - (double)l.pmin[e >> 4]) / delta);
+        qv = (x >= (double)qmax) ? qmax : (uint32_t)x;
+    }
+    l.qt[e] = (uint16_t)qv;
+    __syncthreads();
+    return true;
+}
+
 __device__ __forceinline__ uint32_t dist_bin(float dist, float lo, float scale) {
     float x = (dist - lo) * scale;
     return x <= 0.0f ? 0u : (x >= 255.0f ? 255u : (uint32_t)x);
@@ -125,7 +184,7 @@ __device__ __forceinline__ uint32_t dist_bin(float dist, float lo, float scale) 
 // ------------------------------------------------------------ k_ivf_calib ---
 // NIB: 64-bit m x 4 codes (sub-code j is nibble j of the code).  Other layouts take the
 // sub-quantizers' table offset, bit offset and width from a small LDS array.
-template <bool NIB>
+template <bool NIB, int DS = 0>
 __global__ void __launch_bounds__(256)
 k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
             const float *__restrict__ cb,
@@ -184,7 +243,10 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
         if (c < 0 || c >= K) continue;
         const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
         if (hi == lo) continue;
-        ivf_setup<SCAN_GENERIC, uint16_t>(L, edesc, cb, z, coarse + (size_t)c * L->d, 0.f, false, false, l);
+        if constexpr (DS > 0)
+            ivf_setup_fix<DS>(cb, z, coarse + (size_t)c * (16 * DS), 0.f, false, (uint32_t)qmax, l);
+        else
+            ivf_setup<SCAN_GENERIC, uint16_t>(L, edesc, cb, z, coarse + (size_t)c * L->d, 0.f, false, false, l);
         const int take = (int)((hi - lo) < (int64_t)(t_eff - seen) ? (hi - lo) : (int64_t)(t_eff - seen));
         for (int p = threadIdx.x; p < take; p += blockDim.x) {
             const uint8_t *code = list_codes + (size_t)(lo + p) * cs;
@@ -218,7 +280,11 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
         if (c < 0 || c >= K) continue;
         const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
         if (hi == lo) continue;
-        const bool ok = ivf_setup<SCAN_GENERIC, uint16_t>(L, edesc, cb, z, coarse + (size_t)c * L->d, dmax, true, false, l);
+        bool ok;
+        if constexpr (DS > 0)
+            ok = ivf_setup_fix<DS>(cb, z, coarse + (size_t)c * (16 * DS), dmax, true, (uint32_t)qmax, l);
+        else
+            ok = ivf_setup<SCAN_GENERIC, uint16_t>(L, edesc, cb, z, coarse + (size_t)c * L->d, dmax, true, false, l);
         const int take = (int)((hi - lo) < (int64_t)(pilot - seen) ? (hi - lo) : (int64_t)(pilot - seen));
         const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
         for (int p = threadIdx.x; p < take; p += blockDim.x) {
@@ -1154,7 +1220,7 @@ __device__ inline uint64_t tight_keep(uint64_t *A, int na, int R, uint32_t *hist
     return thr;
 }
 
-template <int KIND, typename QT>
+template <int KIND, typename QT, int DS = 0>
 __global__ void __launch_bounds__(256)
 k_ivf_tight(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
             const float *__restrict__ cb, const float *__restrict__ coarse,
@@ -1185,9 +1251,14 @@ k_ivf_tight(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
         if (c < 0 || c >= K) continue;
         const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
         if (hi == lo) continue;
-        if (!ivf_setup<KIND, QT>(L, edesc, cb, queries + q * L->d, coarse + (size_t)c * L->d, cur, true,
-                                 true, l))
-            continue;
+        bool ok;
+        if constexpr (DS > 0) {
+            ok = ivf_setup_fix<DS>(cb, queries + q * (16 * DS), coarse + (size_t)c * (16 * DS), cur, true, qmax, l);
+            if (ok) build_gtab<KIND, QT>(L, l.qt, (QT *)l.gtab);
+        } else {
+            ok = ivf_setup<KIND, QT>(L, edesc, cb, queries + q * L->d, coarse + (size_t)c * L->d, cur, true, true, l);
+        }
+        if (!ok) continue;
         const QT *gtab = (const QT *)l.gtab;
         const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
         const int na_before = na;
@@ -1326,7 +1397,6 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     const size_t lds_final = (small_final ? IVF_SMALL_CAP : FINAL_CAP) * 8 + lds_scan;
     int rc;
     constexpr bool NIB = KIND == SCAN_NIB8;
-    if ((rc = allow_lds(k_ivf_calib<NIB>, lds_calib)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_scan<KIND, QT, 0>, lds_scan)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_scan<KIND, QT, 1>, lds_scan)) != PQ_OK) return rc;
     if ((rc = allow_lds(k_ivf_scan<KIND, QT, 2>, lds_scan)) != PQ_OK) return rc;
@@ -1336,17 +1406,39 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     } else {
         if ((rc = allow_lds(k_ivf_final<KIND, QT, false>, lds_final)) != PQ_OK) return rc;
     }
-    hipLaunchKernelGGL(k_ivf_calib<NIB>, dim3(nq), dim3(256), lds_calib, s, idx->dev, idx->edesc,
-                       idx->codebooks, coarse, list_offsets, list_codes, queries, probe_ids, nprobe, K, want, pilot_want, R, ws,
-                       p.per_query);
+#define QADC_IVF_CALIB(...)                                                                          \
+    do {                                                                                             \
+        if ((rc = allow_lds(k_ivf_calib<__VA_ARGS__>, lds_calib)) != PQ_OK) return rc;               \
+        hipLaunchKernelGGL((k_ivf_calib<__VA_ARGS__>), dim3(nq), dim3(256), lds_calib, s, idx->dev,  \
+                           idx->edesc, idx->codebooks, coarse, list_offsets, list_codes, queries,    \
+                           probe_ids, nprobe, K, want, pilot_want, R, ws, p.per_query);              \
+    } while (0)
+    // (the fixed 16 x 4-bit shape has a set-up of its own)
+    if (dsf == 4) QADC_IVF_CALIB(true, 4);
+    else if (dsf == 6) QADC_IVF_CALIB(true, 6);
+    else if (dsf == 8) QADC_IVF_CALIB(true, 8);
+    else QADC_IVF_CALIB(NIB);
+#undef QADC_IVF_CALIB
     QADC_LAUNCH_CHECK("k_ivf_calib");
     if (tighten) {
         static_assert(PQ_MAX_R + TIGHT_U * 256 <= TIGHT_CAP, "room for one batch above R candidates");
         const size_t lds_tight = (size_t)TIGHT_CAP * 8 + lds_scan;
-        if ((rc = allow_lds(k_ivf_tight<KIND, QT>, lds_tight)) != PQ_OK) return rc;
-        hipLaunchKernelGGL((k_ivf_tight<KIND, QT>), dim3(nq), dim3(256), lds_tight, s, idx->dev, idx->edesc,
-                           idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries, probe_ids,
-                           nprobe, K, R, (const char *)ws, p.per_query, out_ids, out_dist);
+#define QADC_IVF_TIGHT(...)                                                                          \
+    do {                                                                                             \
+        if ((rc = allow_lds(k_ivf_tight<__VA_ARGS__>, lds_tight)) != PQ_OK) return rc;               \
+        hipLaunchKernelGGL((k_ivf_tight<__VA_ARGS__>), dim3(nq), dim3(256), lds_tight, s, idx->dev,  \
+                           idx->edesc, idx->codebooks, coarse, list_offsets, list_codes, list_ids,   \
+                           queries, probe_ids, nprobe, K, R, (const char *)ws, p.per_query, out_ids, \
+                           out_dist);                                                                \
+    } while (0)
+        if (KIND == SCAN_NIB8 && sizeof(QT) == 1 && dsf != 0) {
+            if (dsf == 4) QADC_IVF_TIGHT(SCAN_NIB8, uint8_t, 4);
+            else if (dsf == 6) QADC_IVF_TIGHT(SCAN_NIB8, uint8_t, 6);
+            else QADC_IVF_TIGHT(SCAN_NIB8, uint8_t, 8);
+        } else {
+            QADC_IVF_TIGHT(KIND, QT);
+        }
+#undef QADC_IVF_TIGHT
         QADC_LAUNCH_CHECK("k_ivf_tight");
         return PQ_OK;
     }
