@@ -474,9 +474,13 @@ k_select_cand(const uint32_t *__restrict__ counts, const uint64_t *__restrict__ 
 static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // queries per pass: the score matrix of a pass stays within 256 MB
+// Queries per pass: as many as a 1 GiB score matrix (the fallback's) holds.  Larger passes give the
+// pilot, the selections and the guarded fallback launches more blocks each (10,000 queries over
+// 65,536 cells: 2.70 ms per call with 256 MiB, 2.42 with 512 MiB, 2.29 with 1 GiB).
+#define QADC_COARSE_MATRIX_BYTES ((size_t)1 << 30)
 static int coarse_chunk(int nq, int K) {
     const size_t ld = ((size_t)K + 31) & ~(size_t)31;
-    size_t qc = ((size_t)256 << 20) / (ld * sizeof(float));
+    size_t qc = ((size_t)QADC_COARSE_MATRIX_BYTES) / (ld * sizeof(float));
     qc = qc / CS_TQ * CS_TQ;
     if (qc < CS_TQ) qc = CS_TQ;
     const size_t nqr = ((size_t)(nq > 0 ? nq : 1) + CS_TQ - 1) / CS_TQ * CS_TQ;
