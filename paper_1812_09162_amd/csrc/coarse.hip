@@ -201,7 +201,7 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
 // One block of 1024 threads per query; keys = order-preserving integers of the scores; the
 // result is the k = min(nprobe, K) smallest (key, id), ascending.
 //
-// Fast path: the keys are binned by (key - min) >> shift into 256 bins spanning [min, max]; the
+// Fast path: the scores are binned into 256 equal steps between the smallest and the largest; the
 // nearest cells sit in the sparse low tail, so the bin that holds the k-th key and the bins
 // below it hold only a few cells more than k.  They are gathered into LDS and ranked by
 // counting.  Three passes over the query's scores (range, histogram, gather), which stay in L2.
@@ -311,8 +311,15 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
         lo = s_lo[w2] < lo ? s_lo[w2] : lo;
         hi = s_hi[w2] > hi ? s_hi[w2] : hi;
     }
-    const uint32_t span = hi - lo;
-    const int shift = span < 256u ? 0 : 24 - __clz(span);  // (span >> shift) < 256
+    // 256 equal steps of the score itself between the smallest and the largest (equal steps of the
+    // ordered integer would put nearly every score into the top bins whenever the smallest score
+    // is negative and the others are not: the integers of floats near zero are far apart)
+    const float flo = qadc_ord2f(lo), fspan = qadc_ord2f(hi) - qadc_ord2f(lo);
+    const float fscale = (fspan > 0.0f && isfinite(fspan)) ? 255.0f / fspan : 0.0f;
+    auto bin_of = [flo, fscale](uint32_t key) -> uint32_t {
+        const float x = (qadc_ord2f(key) - flo) * fscale;  // >= 0, monotone in the key
+        return x >= 255.0f ? 255u : (uint32_t)x;
+    };
     for (int j0 = 0; j0 < nj; j0 += UB) {
         uint32_t v[UB][4];
         load_keys(j0, v);
@@ -321,7 +328,7 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const bool in = ((j0 + u) * BD + (int)threadIdx.x) * 4 + c < K;
-                cs_hist_add(hist, in ? (v[u][c] - lo) >> shift : 0u, in);
+                cs_hist_add(hist, in ? bin_of(v[u][c]) : 0u, in);
             }
     }
     __syncthreads();
@@ -338,7 +345,7 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const int i = ((j0 + u) * BD + (int)threadIdx.x) * 4 + c;
-                    const bool take = i < K && ((v[u][c] - lo) >> shift) <= kbin;
+                    const bool take = i < K && bin_of(v[u][c]) <= kbin;
                     const uint64_t m = __ballot(take);
                     if (m != 0) {
                         uint32_t base = 0;
