@@ -480,7 +480,6 @@ k_select_cand(const uint32_t *__restrict__ counts, const uint64_t *__restrict__ 
 // ------------------------------------------------------------------------ host ---
 static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// queries per pass: the score matrix of a pass stays within 256 MB
 // Queries per pass: as many as a 1 GiB score matrix (the fallback's) holds.  Larger passes give the
 // pilot, the selections and the guarded fallback launches more blocks each (10,000 queries over
 // 65,536 cells: 2.70 ms per call with 256 MiB, 2.42 with 512 MiB, 2.29 with 1 GiB).
