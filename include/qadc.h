@@ -315,7 +315,7 @@ enum {
     PQ_OPT_PILOT_CODES = 1,        /* codes the fused search samples for its pruning bound when
                                       several blocks share them: 0..2^24 (262144) */
     PQ_OPT_PILOT_CODES_SINGLE = 2, /* ... when one block per query counts them: 0..2^24 (65536) */
-    PQ_OPT_PILOT_BLOCKS = 3,       /* most blocks per query that share that sample: 1..64 (64) */
+    PQ_OPT_PILOT_BLOCKS = 3,       /* most blocks per query that share that sample: 1..128 (128) */
     PQ_OPT_IVF_THREADS = 4,        /* threads per (query, list) block of the inverted-list scan:
                                       64, 128 or 256 (128) */
     PQ_OPT_SHARED_PASSES = 5,      /* 1: four queries of a batch share each pass over the codes;

@@ -26,7 +26,7 @@ static std::atomic<int64_t> g_opt[PQ_OPT_COUNT] = {
     {2048},    // PQ_OPT_SCAN_BLOCKS
     {262144},  // PQ_OPT_PILOT_CODES
     {65536},   // PQ_OPT_PILOT_CODES_SINGLE
-    {64},      // PQ_OPT_PILOT_BLOCKS
+    {128},     // PQ_OPT_PILOT_BLOCKS
     {128},     // PQ_OPT_IVF_THREADS
     {1},       // PQ_OPT_SHARED_PASSES
     {1},       // PQ_OPT_COARSE_FILTER
@@ -41,7 +41,7 @@ extern "C" int pq_set_option(int option, int64_t value) {
         case PQ_OPT_SCAN_BLOCKS: ok = value >= 1 && value <= 4096; break;
         case PQ_OPT_PILOT_CODES: ok = value >= 0 && value <= ((int64_t)1 << 24); break;
         case PQ_OPT_PILOT_CODES_SINGLE: ok = value >= 0 && value <= ((int64_t)1 << 24); break;
-        case PQ_OPT_PILOT_BLOCKS: ok = value >= 1 && value <= 64; break;
+        case PQ_OPT_PILOT_BLOCKS: ok = value >= 1 && value <= 128; break;
         case PQ_OPT_IVF_THREADS: ok = value == 64 || value == 128 || value == 256; break;
         case PQ_OPT_IVF_SHARED_LISTS: ok = value >= 0 && value <= 2; break;
         default: ok = value == 0 || value == 1; break;

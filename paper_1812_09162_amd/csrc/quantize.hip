@@ -35,7 +35,7 @@ struct QuantShape {
     int ubits, uds;  // bits and dimensions of every sub-quantizer if they are all alike, else 0
 };
 // NIB8 pilot codes a thread holds in registers per batch
-#define PILOT_PER_THREAD 16
+#define PILOT_PER_THREAD 8
 template <int KIND, typename QT>
 __global__ void __launch_bounds__(QUANT_THREADS)
 k_quantize(const DevLayout *__restrict__ L, const QuantShape shape, const EntryDesc *__restrict__ edesc,

@@ -481,7 +481,7 @@ __device__ __forceinline__ void stage_append(bool pass, uint32_t key, uint32_t i
 // bin t; the first bin where it reaches k (the k-th smallest pilot key lies in it) gives an
 // upper bound on the k-th smallest key of the whole list: the bin's largest key.
 #define QADC_REC_BINS 64
-#define QADC_REC_SLOTS 64
+#define QADC_REC_SLOTS 128
 // Sum of the first P 16-bit slots of a record row, chunks [c0, c1) of 8 slots (16 bytes) each.
 __device__ __forceinline__ uint32_t scan_rec_row_sum(const uint16_t *__restrict__ row, int P, int c0, int c1) {
     uint32_t s = 0;
@@ -522,7 +522,8 @@ __device__ __forceinline__ void scan_bound_bins_256(const uint16_t *__restrict__
                                                     uint32_t *first_bin) {
     const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
     const int bin = wave * 16 + lane / 4, part = lane % 4;
-    uint32_t s = scan_rec_row_sum(rec + (size_t)bin * QADC_REC_SLOTS, P, 2 * part, 2 * part + 2);
+    constexpr int CPL = QADC_REC_SLOTS / 8 / 4;  // 16-byte chunks per lane
+    uint32_t s = scan_rec_row_sum(rec + (size_t)bin * QADC_REC_SLOTS, P, CPL * part, CPL * part + CPL);
     s += QADC_DPP_STEP(0u, s, 0xB1, 0xf);  // quad_perm [1,0,3,2]
     s += QADC_DPP_STEP(0u, s, 0x4E, 0xf);  // quad_perm [2,3,0,1]
     const uint64_t reached = __ballot(s >= k);
