@@ -719,9 +719,8 @@ template <int DS>
 __global__ void __launch_bounds__(256)
 k_ivf_scan_mq(const float *__restrict__ cb, const float *__restrict__ coarse,
               const int64_t *__restrict__ list_offsets, const uint8_t *__restrict__ list_codes,
-              const int32_t *__restrict__ list_ids, const float *__restrict__ queries,
-              const int32_t *__restrict__ probe_ids, int nprobe, char *__restrict__ ws, size_t per_query,
-              size_t counts_off, size_t slots_off, int cap_b, const uint32_t *__restrict__ order,
+              const int32_t *__restrict__ list_ids, const float *__restrict__ queries, int nprobe,
+              char *__restrict__ ws, size_t per_query, size_t counts_off, size_t slots_off, int cap_b,
               const IvfGroup *__restrict__ gdesc, const uint32_t *__restrict__ ngroups) {
     extern __shared__ __align__(16) unsigned char smem[];  // tables at LDS address 0 (no static LDS here)
     IvfMqLds &S = *(IvfMqLds *)(smem + IVF_MQ_TAB_BYTES);
@@ -1461,9 +1460,8 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
         }
 #define QADC_IVF_MQ(DSV)                                                                             \
     hipLaunchKernelGGL((k_ivf_scan_mq<DSV>), dim3((unsigned)max_groups), dim3(256), lds_mq, s,       \
-                       idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries,          \
-                       probe_ids, nprobe, ws, p.per_query, p.counts_off, p.slots_off, p.cap_b, order, \
-                       gdesc, ngroups)
+                       idx->codebooks, coarse, list_offsets, list_codes, list_ids, queries, nprobe,  \
+                       ws, p.per_query, p.counts_off, p.slots_off, p.cap_b, gdesc, ngroups)
         if (dsf == 4) QADC_IVF_MQ(4); else if (dsf == 6) QADC_IVF_MQ(6); else QADC_IVF_MQ(8);
 #undef QADC_IVF_MQ
         QADC_LAUNCH_CHECK("k_ivf_scan_mq");
