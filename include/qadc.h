@@ -313,7 +313,7 @@ const char *pq_last_error(void);
 enum {
     PQ_OPT_SCAN_BLOCKS = 0,        /* scan blocks per query for one or a few queries: 1..4096 (2048) */
     PQ_OPT_PILOT_CODES = 1,        /* codes the fused search samples for its pruning bound when
-                                      several blocks share them: 0..2^24 (262144) */
+                                      several blocks share them: 0..2^24 (524288) */
     PQ_OPT_PILOT_CODES_SINGLE = 2, /* ... when one block per query counts them: 0..2^24 (65536) */
     PQ_OPT_PILOT_BLOCKS = 3,       /* most blocks per query that share that sample: 1..128 (128) */
     PQ_OPT_IVF_THREADS = 4,        /* threads per (query, list) block of the inverted-list scan:

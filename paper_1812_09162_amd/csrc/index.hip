@@ -24,7 +24,7 @@ extern "C" const char *pq_last_error(void) { return g_err; }
 #include <atomic>
 static std::atomic<int64_t> g_opt[PQ_OPT_COUNT] = {
     {2048},    // PQ_OPT_SCAN_BLOCKS
-    {262144},  // PQ_OPT_PILOT_CODES
+    {524288},  // PQ_OPT_PILOT_CODES
     {65536},   // PQ_OPT_PILOT_CODES_SINGLE
     {128},     // PQ_OPT_PILOT_BLOCKS
     {128},     // PQ_OPT_IVF_THREADS

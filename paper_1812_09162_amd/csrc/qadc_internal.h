@@ -93,7 +93,7 @@ struct PilotPlan {
 };
 int qadc_pilot_blocks_max(int nq);
 size_t qadc_pilot_scratch_bytes(int nq);
-PilotPlan qadc_pilot_plan(int nq, int64_t n, int t_eff, int R, bool have_scratch);
+PilotPlan qadc_pilot_plan(int nq, int64_t n, int t_eff, int R, bool have_scratch, bool cheap_lookups);
 
 // gtab_out: if non-null, query q's group tables are also written to gtab_out + q*gtab_stride bytes.
 // hdr_out: if non-null, the scan header at hdr_out + q*gtab_stride is cleared (an empty candidate list).

@@ -391,11 +391,17 @@ size_t qadc_pilot_scratch_bytes(int nq) {
 // The pilot of a call: how many codes, split over how many blocks per query.  With scratch
 // memory (the fused search) a small batch of queries spreads a large pilot over many
 // blocks; without it every query has one block and the pilot stays small.
-PilotPlan qadc_pilot_plan(int nq, int64_t n, int t_eff, int R, bool have_scratch) {
-    const int64_t multi = qadc_option(PQ_OPT_PILOT_CODES);
+PilotPlan qadc_pilot_plan(int nq, int64_t n, int t_eff, int R, bool have_scratch, bool cheap_lookups) {
+    int64_t multi = qadc_option(PQ_OPT_PILOT_CODES);
     const int64_t single = qadc_option(PQ_OPT_PILOT_CODES_SINGLE);
     PilotPlan pp;
     const int pmax = have_scratch ? qadc_pilot_blocks_max(nq) : 1;
+    // The whole sample pays when many blocks share it and a look-up is cheap (m x 4 codes, one
+    // query per call: 4096 codes per block; fewer candidates then shorten the scan's appends and
+    // the selection by more than the sample costs).  Otherwise half of it, as long as that is
+    // not below 262144.
+    const int64_t per_block = cheap_lookups ? 4096 : 2048;
+    if (multi > 262144 && multi > per_block * pmax) multi = per_block * pmax > 262144 ? per_block * pmax : 262144;
     int64_t want = pmax > 1 ? multi : single;
     // the candidates the scan keeps grow with R / pilot: long result lists get a longer pilot
     if (pmax > 1 && want < 512 * (int64_t)R) want = 512 * (int64_t)R;
@@ -453,7 +459,8 @@ int qadc_quantize_launch(const pq_index *idx, const float *queries, const float 
     const int64_t want = t > 4 * (int64_t)R ? t : 4 * (int64_t)R;
     const int t_eff = (int)(n < want ? n : want);
     const int k = R < t_eff ? R : t_eff;
-    const PilotPlan pp = qadc_pilot_plan(nq, n, t_eff, R, scratch != nullptr);
+    const PilotPlan pp = qadc_pilot_plan(nq, n, t_eff, R, scratch != nullptr,
+                                         idx->h.kind == SCAN_NIB8 || idx->h.kind == SCAN_NIB16);
     if (plan_used) *plan_used = pp;
     uint16_t *bound_rec = (uint16_t *)scratch;
     const bool u8 = idx->h.acc_bits == 8;
