@@ -209,6 +209,7 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
 // radix passes give the k-th key and how many keys lie below it; the keys below it and the
 // lowest ids among its equals are collected and ranked.
 #define CS_CAND 2048
+#define CS_SMALL_CAP 1024  // candidates a 256-thread k_select_cand block ranks
 
 // histogram increment: one LDS atomic per wave when all its active lanes hit the same bin
 // (crowded keys), else one per lane
@@ -427,48 +428,48 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
 }
 
 // ---------------------------------------------------------------- k_select_cand ---
-// One block of 1024 threads per query: gather the query's candidate lists (one per block of 256
-// cells), keep those up to the bin of the k-th, rank by (score, id).  Bins: 256 equal steps of
-// the ordered score between the pilot's best score and the bound.  An overflowing list, or more
-// candidates than fit, raises *flag.
-__global__ void __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4)))
+// One block of NT threads per query: gather the query's candidate lists (one per block of 256
+// cells), keep those up to the bin of the k-th (at most ACAP), rank by (score, id).  256 threads
+// take the lists of up to 65,536 cells in one batch and leave room for eight blocks per CU.  An
+// overflowing list, or more candidates than fit, raises *flag.
+template <int NT, int ACAP>
+__global__ void __launch_bounds__(NT)
 k_select_cand(const uint32_t *__restrict__ counts, const uint64_t *__restrict__ slots, int ncb,
               const float *__restrict__ pilot, int pstride, int koff, int K, int nprobe, int logw,
               int32_t *__restrict__ probe_ids, float *__restrict__ probe_scores, int *__restrict__ flag) {
     extern __shared__ __align__(16) unsigned char smem[];
-    uint64_t *A = (uint64_t *)smem;  // FINAL_CAP entries
+    uint64_t *A = (uint64_t *)smem;  // ACAP entries
     __shared__ uint32_t hist[256];
-    __shared__ uint32_t whist[16][256];
+    __shared__ uint32_t whist[NT / QADC_WAVE][256];
     __shared__ uint32_t sh[32];
     __shared__ uint32_t wsum[16];
     const size_t q = blockIdx.x;
     const int k = nprobe < K ? nprobe : K;
-    const uint32_t lo = qadc_f2ord(pilot[q * pstride]);
-    const uint32_t hi = qadc_f2ord(pilot[q * pstride + koff]);
-    const uint32_t span = hi - lo;
-    const int shift = span < 256u ? 0 : 24 - __clz(span);
+    // 256 equal steps of the score itself between the pilot's best score and the bound (not of
+    // the ordered integer: see k_select); better scores than the pilot's best go to bin 0
+    const float flo = pilot[q * pstride], fspan = pilot[q * pstride + koff] - flo;
+    const float fscale = (fspan > 0.0f && isfinite(fspan)) ? 255.0f / fspan : 0.0f;
     FinalShared S;
     S.hist = hist;
     S.whist = whist;
     S.sh = sh;
     S.wsum = wsum;
     S.off = nullptr;
-    auto binf = [lo, shift](uint64_t c) {
-        const uint32_t key = (uint32_t)(c >> 32);
-        const uint32_t b = key <= lo ? 0u : (key - lo) >> shift;
-        return b > 255u ? 255u : b;
+    auto binf = [flo, fscale](uint64_t c) -> uint32_t {
+        const float x = (qadc_ord2f((uint32_t)(c >> 32)) - flo) * fscale;  // monotone in the key
+        return x >= 255.0f ? 255u : (x > 0.0f ? (uint32_t)x : 0u);
     };
     int na = 0;
-    const int per_batch = (ncb + (1024 >> logw) - 1) / (1024 >> logw);
+    const int per_batch = (ncb + (NT >> logw) - 1) / (NT >> logw);
     bool slow;
     const uint32_t *cq = counts + q * ncb;
     const uint64_t *sq = slots + q * ncb * CS_SLOT;
     if (per_batch <= 8)
-        slow = gather_select_rows<8>(cq, sq, ncb, CS_SLOT, k, logw, binf, A, S, na);
+        slow = gather_select_rows<8, NT, ACAP>(cq, sq, ncb, CS_SLOT, k, logw, binf, A, S, na);
     else if (per_batch <= 16)
-        slow = gather_select_rows<16>(cq, sq, ncb, CS_SLOT, k, logw, binf, A, S, na);
+        slow = gather_select_rows<16, NT, ACAP>(cq, sq, ncb, CS_SLOT, k, logw, binf, A, S, na);
     else
-        slow = gather_select_rows<32>(cq, sq, ncb, CS_SLOT, k, logw, binf, A, S, na);
+        slow = gather_select_rows<32, NT, ACAP>(cq, sq, ncb, CS_SLOT, k, logw, binf, A, S, na);
     if (slow) {
         if (threadIdx.x == 0) atomicOr(flag, 1);
         return;
@@ -582,9 +583,16 @@ extern "C" int ivf_coarse_search(const float *queries, int nq, const float *cent
                                d, cnorm, (float *)nullptr, ld, vec, (const float *)pilot_sc, nprobe, nprobe - 1,
                                slots, counts, (const int *)nullptr, (int)gq.x, (int)gq.y);
             QADC_LAUNCH_CHECK("k_scores (filter)");
-            hipLaunchKernelGGL(k_select_cand, dim3(nqc), dim3(1024), FINAL_CAP * sizeof(uint64_t), s,
-                               (const uint32_t *)counts, (const uint64_t *)slots, ncb, (const float *)pilot_sc,
-                               nprobe, nprobe - 1, K, nprobe, logw, pid, psc, flag);
+            if (ncb <= (256 >> logw) * 8 && nprobe <= CS_SMALL_CAP / 8)
+                hipLaunchKernelGGL((k_select_cand<256, CS_SMALL_CAP>), dim3(nqc), dim3(256),
+                                   CS_SMALL_CAP * sizeof(uint64_t), s, (const uint32_t *)counts,
+                                   (const uint64_t *)slots, ncb, (const float *)pilot_sc, nprobe, nprobe - 1, K,
+                                   nprobe, logw, pid, psc, flag);
+            else
+                hipLaunchKernelGGL((k_select_cand<1024, FINAL_CAP>), dim3(nqc), dim3(1024),
+                                   FINAL_CAP * sizeof(uint64_t), s, (const uint32_t *)counts,
+                                   (const uint64_t *)slots, ncb, (const float *)pilot_sc, nprobe, nprobe - 1, K,
+                                   nprobe, logw, pid, psc, flag);
             QADC_LAUNCH_CHECK("k_select_cand");
             guard = flag;  // the matrix form below only runs if a list overflowed
         }

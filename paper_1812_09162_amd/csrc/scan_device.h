@@ -780,16 +780,16 @@ __device__ inline bool gather_select(const uint32_t *__restrict__ counts,
 // per batch, so that all loads of the common case, the list lengths included, are
 // independent and in flight together; longer lists take extra rounds.  Entries beyond a
 // list's length are loaded and ignored, which needs cap_b >= W.  NU is 8, 16 or 32.
-template <int NU, class BinF>
+template <int NU, int NT, int ACAP, class BinF>  // NT threads per block, A holds ACAP entries
 __device__ inline bool gather_select_rows(const uint32_t *__restrict__ counts,
                                           const uint64_t *__restrict__ slots, int G, int cap_b,
                                           int R, int logw, BinF binf, uint64_t *A,
                                           const FinalShared &S, int &na) {
     const int W = 1 << logw;
-    const int LP = 1024 >> logw;  // lists per batch row
+    const int LP = NT >> logw;  // lists per batch row
     const int wave = threadIdx.x / QADC_WAVE, lane = threadIdx.x % QADC_WAVE;
     const int sub = threadIdx.x & (W - 1), row = threadIdx.x >> logw;
-    for (int i = threadIdx.x; i < 16 * 256; i += blockDim.x) (&S.whist[0][0])[i] = 0;
+    for (int i = threadIdx.x; i < NT / QADC_WAVE * 256; i += NT) (&S.whist[0][0])[i] = 0;
     if (threadIdx.x < 8) S.sh[threadIdx.x] = 0;  // 0: entries in A, 1: slow flag, 2: candidates
     __syncthreads();
     const bool single = G <= LP * NU;  // one batch: pass 1 reuses the registers of pass 0
@@ -838,12 +838,12 @@ __device__ inline bool gather_select_rows(const uint32_t *__restrict__ counts,
                     uint32_t base = 0;
                     if (lane == 0) base = atomicAdd(&S.sh[0], total);
                     base = __builtin_amdgcn_readfirstlane(base);
-                    if (base + total > FINAL_CAP && lane == 0) S.sh[1] = 1u;
+                    if (base + total > ACAP && lane == 0) S.sh[1] = 1u;
 #pragma unroll
                     for (int u = 0; u < NU; ++u) {
                         const uint64_t m = __ballot((keep >> u) & 1u);
                         const uint32_t pos = base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
-                        if (((keep >> u) & 1u) && pos < FINAL_CAP) A[pos] = c[u];
+                        if (((keep >> u) & 1u) && pos < ACAP) A[pos] = c[u];
                         base += (uint32_t)__popcll(m);
                     }
                 }
@@ -861,7 +861,7 @@ __device__ inline bool gather_select_rows(const uint32_t *__restrict__ counts,
                         atomicAdd(&S.whist[wave][bin], 1u);
                     } else if (bin <= kbin) {
                         const uint32_t pos = atomicAdd(&S.sh[0], 1u);
-                        if (pos < FINAL_CAP) A[pos] = e; else S.sh[1] = 1u;
+                        if (pos < ACAP) A[pos] = e; else S.sh[1] = 1u;
                     }
                 }
             }
@@ -876,7 +876,7 @@ __device__ inline bool gather_select_rows(const uint32_t *__restrict__ counts,
             if (threadIdx.x < 256) {
                 uint32_t t = 0;
 #pragma unroll
-                for (int w = 0; w < 16; ++w) t += S.whist[w][threadIdx.x];
+                for (int w = 0; w < NT / QADC_WAVE; ++w) t += S.whist[w][threadIdx.x];
                 S.hist[threadIdx.x] = t;
             }
             __syncthreads();

@@ -103,6 +103,7 @@ def test_coarse_search_full_k_sampled(qb):
 
 @pytest.mark.parametrize("K,d,nq,nprobe,seed", [
     (20_000, 96, 70, 64, 31), (16_511, 40, 130, 1, 32), (30_001, 128, 9, 20, 33), (17_000, 17, 257, 64, 34),
+    (70_001, 24, 33, 64, 35), (60_000, 16, 20, 200, 36),   # the 1024-thread candidate selection
 ])
 def test_coarse_search_filtering_form_bit_exact(qb, K, d, nq, nprobe, seed):
     """K large enough for the form that never writes the score matrix (pilot bound, candidate
