@@ -106,7 +106,7 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
     if (guard && *guard == 0) return;
     constexpr int LDA = CS_TQ + 1, LDB = CS_TC + 1;
     __shared__ float As[CS_KC * LDA];
-    __shared__ float Bs[CS_KC * LDB];
+    __shared__ __align__(16) float Bs[CS_KC * LDB];
     __shared__ __align__(16) float s_bound[FILTER ? CS_TQ : 4];
     __shared__ uint32_t s_cnt[FILTER ? CS_TQ : 1];
     const int w = threadIdx.x / QADC_WAVE, l = threadIdx.x % QADC_WAVE;
@@ -124,6 +124,12 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
                                       kc * CS_KC, vec != 0, rb);
         };
         load(0);
+        float cnv[4];  // the norms of this lane's four columns, in flight during the multiplications
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = c0 + wc * 128 + j * 32 + (l & 31);
+            cnv[j] = col < K ? cnorm[col] : 0.0f;
+        }
         f32x16 acc[2][4];
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -158,11 +164,38 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
             }
         }
         // element r of a 32 x 32 result: row (r/4)*8 + (lane/32)*4 + r%4, column lane%32
+        //
+        // FILTER: 1.6 % of the results survive, about one lane in two of the wave's 128 compares.
+        // A survivor is only pushed, as (score bits, local row << 16 | local column), onto a queue
+        // of its wave in the operand buffers (position: a wave-uniform count plus the lane's rank
+        // among the survivors, no atomic); the queue is emptied densely afterwards, one entry per
+        // lane: position in the (query, cell block) list by an LDS atomic, then the 8-byte store.
+        constexpr uint32_t QCAP = CS_KC * LDB / 2 / 4;  // entries per wave: a quarter of Bs
+        uint2 *queue = (uint2 *)Bs + w * QCAP;
+        uint32_t nqueued = 0;  // wave-uniform
+        auto flush = [&]() {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            for (uint32_t e = (uint32_t)l; e < nqueued; e += QADC_WAVE) {
+                const uint2 v = queue[e];
+                const int rl = (int)(v.y >> 16), cl = (int)(v.y & 0xffffu);
+                const uint32_t pos = atomicAdd(&s_cnt[rl], 1u);
+                if (pos < CS_SLOT)
+                    slots[((size_t)(q0 + rl) * ncb + cbx) * CS_SLOT + pos] =
+                        ((uint64_t)qadc_f2ord(__uint_as_float(v.x)) << 32) | (uint32_t)(c0 + cl);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            nqueued = 0;
+        };
+        if (FILTER) __syncthreads();  // every wave has read its last operands: Bs is free
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int col = c0 + wc * 128 + j * 32 + (l & 31);
-            if (col >= K) continue;
-            const float cn = cnorm[col];
+            const int cl = wc * 128 + j * 32 + (l & 31), col = c0 + cl;
+            const bool colok = col < K;
+            if (!FILTER && !colok) continue;
+            const float cn = cnv[j];
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -180,15 +213,23 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
                         const float sc = __fmaf_rn(-2.0f, acc[i][j][4 * r4 + rr], cn);
                         if (!FILTER) {
                             if (row < nqc) scores[(size_t)row * ld + col] = sc;
-                        } else if (sc <= bnd[rr]) {  // rows past the end have bound -inf
-                            const uint32_t pos = atomicAdd(&s_cnt[rl], 1u);
-                            if (pos < CS_SLOT)
-                                slots[((size_t)row * ncb + cbx) * CS_SLOT + pos] =
-                                    ((uint64_t)qadc_f2ord(sc) << 32) | (uint32_t)col;
+                        } else {
+                            const bool pass = colok && sc <= bnd[rr];  // rows past the end: bound -inf
+                            const uint64_t m = __ballot(pass);
+                            if (m != 0) {
+                                if (nqueued + QADC_WAVE > QCAP) flush();
+                                if (pass) {
+                                    const uint32_t at = nqueued + __builtin_amdgcn_mbcnt_hi(
+                                        (uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                                    queue[at] = make_uint2(__float_as_uint(sc), ((uint32_t)rl << 16) | (uint32_t)cl);
+                                }
+                                nqueued += (uint32_t)__popcll(m);
+                            }
                         }
                     }
                 }
         }
+        if (FILTER) flush();
         if (FILTER) {
             __syncthreads();
             if (threadIdx.x < CS_TQ && q0 + (int)threadIdx.x < nqc)
