@@ -1154,6 +1154,7 @@ k_ivf_final(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
 // neither be a result nor move a later R-th smallest.
 #define TIGHT_CAP 4096
 #define TIGHT_U 4  // codes per thread between two looks at the fill level
+#define TIGHT_PC 64  // probes whose cells and list bounds are fetched together
 
 // k-th smallest (k = 1..na) of the different 64-bit words A[0..na), byte by byte from the top.
 __device__ inline uint64_t tight_kth(const uint64_t *A, int na, int k, uint32_t *hist, uint32_t *sh) {
@@ -1219,6 +1220,60 @@ __device__ inline uint64_t tight_keep(uint64_t *A, int na, int R, uint32_t *hist
     return thr;
 }
 
+// The same for na <= 256 (one word per thread), R <= na: every thread counts the words below its
+// own (equal words, which only repeated stored ids give, count by position: the counts are
+// the ranks), the R smallest go to A[rank], in order, and the word of rank R - 1 is returned.
+// nsorted: A[0..nsorted) are in order already (the R words this function left), so that only
+// the words added since are compared one by one: an old word's rank is its position plus the
+// new words below it, a new word's the old words not above it (binary search) plus the new
+// words below it.  With R = 100 nearly every list adds a few candidates to the R held.
+__device__ inline uint64_t tight_keep_small(uint64_t *A, int na, int R, int nsorted, uint32_t *sh,
+                                            uint32_t *count) {
+    const bool have = (int)threadIdx.x < na;
+    const uint64_t mine = have ? A[threadIdx.x] : ~0ull;
+    int rank = 0;
+    if (nsorted > 0) {
+        if ((int)threadIdx.x < nsorted) {
+            rank = (int)threadIdx.x;
+        } else if (have) {
+            int lo = 0, hi = nsorted;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (A[mid] <= mine) lo = mid + 1; else hi = mid;
+            }
+            rank = lo;
+        }
+#pragma unroll 4
+        for (int j = nsorted; j < na; ++j) {
+            const uint64_t o = A[j];
+            rank += (o < mine || (o == mine && j < (int)threadIdx.x)) ? 1 : 0;
+        }
+    } else {
+        // four words per step as two 16-byte reads (every lane reads the same address), two steps
+        // in flight; words past na (stale, inside the buffer) count as the largest value
+#pragma unroll 2
+        for (int j = 0; j < na; j += 4) {
+            const uint4 p0 = *(const uint4 *)&A[j], p1 = *(const uint4 *)&A[j + 2];
+            const uint64_t other[4] = {((uint64_t)p0.y << 32) | p0.x, ((uint64_t)p0.w << 32) | p0.z,
+                                       ((uint64_t)p1.y << 32) | p1.x, ((uint64_t)p1.w << 32) | p1.z};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint64_t o = j + k < na ? other[k] : ~0ull;
+                rank += (o < mine || (o == mine && j + k < (int)threadIdx.x)) ? 1 : 0;
+            }
+        }
+    }
+    __syncthreads();  // every thread has read A
+    if (have && rank < R) A[rank] = mine;
+    if (have && rank == R - 1) {
+        sh[2] = (uint32_t)mine;
+        sh[3] = (uint32_t)(mine >> 32);
+    }
+    if (threadIdx.x == 0) *count = (uint32_t)R;
+    __syncthreads();
+    return ((uint64_t)sh[3] << 32) | sh[2];
+}
+
 template <int KIND, typename QT, int DS = 0>
 __global__ void __launch_bounds__(256)
 k_ivf_tight(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
@@ -1232,6 +1287,8 @@ k_ivf_tight(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
     __shared__ __align__(16) uint32_t hist[256];
     __shared__ uint32_t sh[8];
     __shared__ uint32_t s_na;
+    __shared__ int64_t s_plo[TIGHT_PC];
+    __shared__ int32_t s_plen[TIGHT_PC], s_pcell[TIGHT_PC];
     uint64_t *A = (uint64_t *)smem;  // TIGHT_CAP words
     IvfLds l;
     ivf_carve(L, smem + TIGHT_CAP * 8, sizeof(QT), l);
@@ -1243,56 +1300,102 @@ k_ivf_tight(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
     float cur = st->dmax;
     uint64_t pthr = ~0ull;  // words above it are beyond R held candidates
     int na = 0;
+    int nsorted = 0;  // A[0..nsorted) are in ascending order
     if (threadIdx.x == 0) s_na = 0;
     __syncthreads();
-    for (int a = 0; a < nprobe; ++a) {
-        const int c = probes[a];
-        if (c < 0 || c >= K) continue;
-        const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
-        if (hi == lo) continue;
-        bool ok;
-        if constexpr (DS > 0) {
-            ok = ivf_setup_fix<DS>(cb, queries + q * (16 * DS), coarse + (size_t)c * (16 * DS), cur, true, qmax, l);
-            if (ok) build_gtab<KIND, QT>(L, l.qt, (QT *)l.gtab);
-        } else {
-            ok = ivf_setup<KIND, QT>(L, edesc, cb, queries + q * L->d, coarse + (size_t)c * L->d, cur, true, true, l);
+    // The block's time is a chain of memory round trips, so as few as possible are left in it:
+    // cells and list bounds of TIGHT_PC probes are fetched at once, and (64-bit codes of
+    // nibbles) a list's first codes are requested before its set-up and every further batch
+    // before the previous one is looked up.
+    for (int a0 = 0; a0 < nprobe; a0 += TIGHT_PC) {
+        __syncthreads();  // the previous chunk's entries have been used
+        if (threadIdx.x < TIGHT_PC) {
+            const int a = a0 + (int)threadIdx.x;
+            const int c = a < nprobe ? probes[a] : -1;
+            const bool valid = c >= 0 && c < K;
+            const int64_t lo = valid ? list_offsets[c] : 0, hi = valid ? list_offsets[c + 1] : 0;
+            s_pcell[threadIdx.x] = c;
+            s_plo[threadIdx.x] = lo;
+            s_plen[threadIdx.x] = (int32_t)(hi - lo);  // a list is shorter than 2^31 codes
         }
-        if (!ok) continue;
-        const QT *gtab = (const QT *)l.gtab;
-        const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
-        const int na_before = na;
-        for (int64_t base = lo; base < hi; base += TIGHT_U * bd) {
-            if (na + TIGHT_U * bd > TIGHT_CAP) {  // na > R here: R <= TIGHT_CAP - TIGHT_U * 256
-                pthr = tight_keep(A, na, R, hist, sh, &s_na);
-                na = R;
-            }
-            uint32_t key[TIGHT_U];
-            keys_batch<KIND, QT, TIGHT_U>(L, gtab, list_codes, base + threadIdx.x, bd, hi, key);
+        __syncthreads();
+        const int a1 = nprobe - a0 < TIGHT_PC ? nprobe - a0 : TIGHT_PC;
+        for (int ai = 0; ai < a1; ++ai) {
+            if (s_plen[ai] <= 0) continue;
+            const int c = s_pcell[ai];
+            const int64_t lo = s_plo[ai], hi = lo + s_plen[ai];
+            uint2 wnext[TIGHT_U];
+            auto request = [&](int64_t base) {  // codes past the end: the last one again
 #pragma unroll
-            for (int u = 0; u < TIGHT_U; ++u) {
-                if (key[u] == 0xffffffffu || key[u] >= qmax) continue;  // past the end, or saturated
-                const uint32_t o = qadc_f2ord(fmaf((float)key[u], fdelta, fdmin));
-                if (o > (uint32_t)(pthr >> 32)) continue;
-                const int64_t p = base + (int64_t)u * bd + threadIdx.x;
-                const uint64_t w = ((uint64_t)o << 32) | (uint64_t)(uint32_t)list_ids[p];
-                if (w <= pthr) {
-                    const uint32_t pos = atomicAdd(&s_na, 1u);
-                    if (pos < TIGHT_CAP) A[pos] = w;  // always, unless stored ids repeat
+                for (int u = 0; u < TIGHT_U; ++u) {
+                    int64_t id = base + (int64_t)u * bd + threadIdx.x;
+                    id = id < hi ? id : hi - 1;
+                    wnext[u] = *(const uint2 *)(list_codes + id * 8);
                 }
-            }
-            __syncthreads();
-            na = (int)(s_na < TIGHT_CAP ? s_na : TIGHT_CAP);
-            __syncthreads();  // every thread has read the fill level before the next batch adds to it
-        }
-        if (na != na_before && na >= R) {
-            if (na > R) {
-                pthr = tight_keep(A, na, R, hist, sh, &s_na);
-                na = R;
+            };
+            if constexpr (KIND == SCAN_NIB8) request(lo);
+            bool ok;
+            if constexpr (DS > 0) {
+                ok = ivf_setup_fix<DS>(cb, queries + q * (16 * DS), coarse + (size_t)c * (16 * DS), cur, true, qmax, l);
+                if (ok) build_gtab<KIND, QT>(L, l.qt, (QT *)l.gtab);
             } else {
-                pthr = tight_kth(A, na, R, hist, sh);
+                ok = ivf_setup<KIND, QT>(L, edesc, cb, queries + q * L->d, coarse + (size_t)c * L->d, cur, true, true, l);
             }
-            const float worst = qadc_ord2f((uint32_t)(pthr >> 32));
-            cur = worst < cur ? worst : cur;
+            if (!ok) continue;
+            const QT *gtab = (const QT *)l.gtab;
+            const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
+            const int na_before = na;
+            for (int64_t base = lo; base < hi; base += TIGHT_U * bd) {
+                if (na + TIGHT_U * bd > TIGHT_CAP) {  // na > R here: R <= TIGHT_CAP - TIGHT_U * 256
+                    pthr = tight_keep(A, na, R, hist, sh, &s_na);
+                    na = R;
+                    nsorted = 0;
+                }
+                uint32_t key[TIGHT_U];
+                if constexpr (KIND == SCAN_NIB8) {
+                    uint2 w[TIGHT_U];
+#pragma unroll
+                    for (int u = 0; u < TIGHT_U; ++u) w[u] = wnext[u];
+                    if (base + TIGHT_U * bd < hi) request(base + TIGHT_U * bd);
+#pragma unroll
+                    for (int u = 0; u < TIGHT_U; ++u) {
+                        const uint32_t sum = sum8(gtab, w[u].x, w[u].y);
+                        key[u] = base + (int64_t)u * bd + threadIdx.x < hi ? (sum > qmax ? qmax : sum) : 0xffffffffu;
+                    }
+                } else {
+                    keys_batch<KIND, QT, TIGHT_U>(L, gtab, list_codes, base + threadIdx.x, bd, hi, key);
+                }
+#pragma unroll
+                for (int u = 0; u < TIGHT_U; ++u) {
+                    if (key[u] == 0xffffffffu || key[u] >= qmax) continue;  // past the end, or saturated
+                    const uint32_t o = qadc_f2ord(fmaf((float)key[u], fdelta, fdmin));
+                    if (o > (uint32_t)(pthr >> 32)) continue;
+                    const int64_t p = base + (int64_t)u * bd + threadIdx.x;
+                    const uint64_t w = ((uint64_t)o << 32) | (uint64_t)(uint32_t)list_ids[p];
+                    if (w <= pthr) {
+                        const uint32_t pos = atomicAdd(&s_na, 1u);
+                        if (pos < TIGHT_CAP) A[pos] = w;  // always, unless stored ids repeat
+                    }
+                }
+                __syncthreads();
+                na = (int)(s_na < TIGHT_CAP ? s_na : TIGHT_CAP);
+                __syncthreads();  // every thread has read the fill level before the next batch adds to it
+            }
+            if (na != na_before && na >= R) {
+                if (na <= 256) {
+                    pthr = tight_keep_small(A, na, R, nsorted, sh, &s_na);
+                    na = R;
+                    nsorted = R;
+                } else if (na > R) {
+                    pthr = tight_keep(A, na, R, hist, sh, &s_na);
+                    na = R;
+                    nsorted = 0;
+                } else {
+                    pthr = tight_kth(A, na, R, hist, sh);
+                }
+                const float worst = qadc_ord2f((uint32_t)(pthr >> 32));
+                cur = worst < cur ? worst : cur;
+            }
         }
     }
     ivf_rank_and_write(A, na, R, out_ids + q * R, out_dist + q * R);
