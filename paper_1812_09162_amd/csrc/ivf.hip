@@ -182,6 +182,27 @@ __device__ __forceinline__ uint32_t dist_bin(float dist, float lo, float scale) 
 }
 
 // ------------------------------------------------------------ k_ivf_calib ---
+#define CALIB_PC 64      // probes whose cell and list bounds the block keeps in LDS
+#define CALIB_EARLY1 2   // codes per thread requested before the set-up, calibration pass
+#define CALIB_EARLY2 4   // the same, pilot pass
+
+// cell and list bounds of probe a: from the block's table, or from memory beyond it
+__device__ __forceinline__ void calib_list(int a, const int32_t *__restrict__ probes,
+                                           const int64_t *__restrict__ list_offsets, int K,
+                                           const int32_t *s_pcell, const int64_t *s_plo, const int32_t *s_plen,
+                                           int &c, int64_t &lo, int64_t &hi) {
+    if (a < CALIB_PC) {
+        c = s_pcell[a];
+        lo = s_plo[a];
+        hi = lo + s_plen[a];
+    } else {
+        c = probes[a];
+        const bool valid = c >= 0 && c < K;
+        lo = valid ? list_offsets[c] : 0;
+        hi = valid ? list_offsets[c + 1] : 0;
+    }
+}
+
 // NIB: 64-bit m x 4 codes (sub-code j is nibble j of the code).  Other layouts take the
 // sub-quantizers' table offset, bit offset and width from a small LDS array.
 template <bool NIB, int DS = 0>
@@ -198,6 +219,11 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
     __shared__ uint32_t kmem[QADC_KTH_MEM];
     __shared__ unsigned long long s_np;
     __shared__ uint32_t sdesc[PQ_MAX_M];  // table offset | bit offset << 12 | bits << 24
+    // cell, first code and length of the lists of the first CALIB_PC probes (length 0: no list):
+    // the loops below walk a few lists one after the other and would otherwise wait for the
+    // probe id and then the bounds of each
+    __shared__ int64_t s_plo[CALIB_PC];
+    __shared__ int32_t s_plen[CALIB_PC], s_pcell[CALIB_PC];
     IvfLds l;
     unsigned char *rest = ivf_carve(L, smem, 2, l);
     uint32_t *ord = (uint32_t *)rest;  // [max(want, pilot_want)]
@@ -217,7 +243,14 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
         long long np = 0;
         for (int a = threadIdx.x; a < nprobe; a += blockDim.x) {
             const int c = probes[a];
-            if (c >= 0 && c < K) np += list_offsets[c + 1] - list_offsets[c];
+            const bool valid = c >= 0 && c < K;
+            const int64_t lo = valid ? list_offsets[c] : 0, hi = valid ? list_offsets[c + 1] : 0;
+            np += hi - lo;
+            if (a < CALIB_PC) {
+                s_pcell[a] = c;
+                s_plo[a] = lo;
+                s_plen[a] = (int32_t)(hi - lo);  // a list is shorter than 2^31 codes
+            }
         }
         for (int sft = QADC_WAVE / 2; sft > 0; sft >>= 1) np += __shfl_xor(np, sft, QADC_WAVE);
         if (threadIdx.x % QADC_WAVE == 0 && np != 0)
@@ -239,20 +272,29 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
     // pass 1: float ADC of the calibration codes
     int seen = 0;
     for (int a = 0; a < nprobe && seen < t_eff; ++a) {
-        const int c = probes[a];
-        if (c < 0 || c >= K) continue;
-        const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
+        int c;
+        int64_t lo, hi;
+        calib_list(a, probes, list_offsets, K, s_pcell, s_plo, s_plen, c, lo, hi);
         if (hi == lo) continue;
+        const int take = (int)((hi - lo) < (int64_t)(t_eff - seen) ? (hi - lo) : (int64_t)(t_eff - seen));
+        // the first codes are requested before the set-up (their sub-codes index its tables)
+        uint2 early[CALIB_EARLY1];
+        if (NIB) {
+#pragma unroll
+            for (int u = 0; u < CALIB_EARLY1; ++u) {
+                const int p = (int)threadIdx.x + u * 256;
+                early[u] = *(const uint2 *)(list_codes + (size_t)(lo + (p < take ? p : take - 1)) * 8);
+            }
+        }
         if constexpr (DS > 0)
             ivf_setup_fix<DS>(cb, z, coarse + (size_t)c * (16 * DS), 0.f, false, (uint32_t)qmax, l);
         else
             ivf_setup<SCAN_GENERIC, uint16_t>(L, edesc, cb, z, coarse + (size_t)c * L->d, 0.f, false, false, l);
-        const int take = (int)((hi - lo) < (int64_t)(t_eff - seen) ? (hi - lo) : (int64_t)(t_eff - seen));
-        for (int p = threadIdx.x; p < take; p += blockDim.x) {
+        auto adc = [&](int p, bool have, uint2 v) {  // have: v holds the code already (NIB)
             const uint8_t *code = list_codes + (size_t)(lo + p) * cs;
             float s = 0.0f;
             if (NIB) {
-                const uint2 v = *(const uint2 *)code;
+                if (!have) v = *(const uint2 *)code;
 #pragma unroll
                 for (int j = 0; j < 16; ++j)
                     s = __fadd_rn(s, l.tab[16 * j + (((j < 8 ? v.x : v.y) >> (4 * (j & 7))) & 15u)]);
@@ -268,7 +310,14 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
                     s = __fadd_rn(s, l.tab[L->toff[j] + qadc_extract_sub(code, L->bitoff[j], L->nbits[j])]);
             }
             ord[seen + p] = qadc_f2ord(s);
+        };
+        int p = threadIdx.x;
+        if (NIB) {
+#pragma unroll
+            for (int u = 0; u < CALIB_EARLY1; ++u, p += 256)
+                if (p < take) adc(p, true, early[u]);
         }
+        for (; p < take; p += blockDim.x) adc(p, false, make_uint2(0u, 0u));
         seen += take;
         __syncthreads();
     }
@@ -276,24 +325,32 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
     // pass 2: quantized distances of the first `pilot` probed codes -> thr0 and the binning
     seen = 0;
     for (int a = 0; a < nprobe && seen < pilot; ++a) {
-        const int c = probes[a];
-        if (c < 0 || c >= K) continue;
-        const int64_t lo = list_offsets[c], hi = list_offsets[c + 1];
+        int c;
+        int64_t lo, hi;
+        calib_list(a, probes, list_offsets, K, s_pcell, s_plo, s_plen, c, lo, hi);
         if (hi == lo) continue;
+        const int take = (int)((hi - lo) < (int64_t)(pilot - seen) ? (hi - lo) : (int64_t)(pilot - seen));
+        uint2 early[CALIB_EARLY2];
+        if (NIB) {
+#pragma unroll
+            for (int u = 0; u < CALIB_EARLY2; ++u) {
+                const int p = (int)threadIdx.x + u * 256;
+                early[u] = *(const uint2 *)(list_codes + (size_t)(lo + (p < take ? p : take - 1)) * 8);
+            }
+        }
         bool ok;
         if constexpr (DS > 0)
             ok = ivf_setup_fix<DS>(cb, z, coarse + (size_t)c * (16 * DS), dmax, true, (uint32_t)qmax, l);
         else
             ok = ivf_setup<SCAN_GENERIC, uint16_t>(L, edesc, cb, z, coarse + (size_t)c * L->d, dmax, true, false, l);
-        const int take = (int)((hi - lo) < (int64_t)(pilot - seen) ? (hi - lo) : (int64_t)(pilot - seen));
         const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
-        for (int p = threadIdx.x; p < take; p += blockDim.x) {
+        auto qadc_of = [&](int p, bool have, uint2 v) {
             uint32_t o = 0xffffffffu;
             if (ok) {
                 const uint8_t *code = list_codes + (size_t)(lo + p) * cs;
                 uint32_t acc = 0;
                 if (NIB) {
-                    const uint2 v = *(const uint2 *)code;
+                    if (!have) v = *(const uint2 *)code;
 #pragma unroll
                     for (int j = 0; j < 16; ++j)
                         acc += l.qt[16 * j + (((j < 8 ? v.x : v.y) >> (4 * (j & 7))) & 15u)];
@@ -312,7 +369,30 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
                 o = qadc_f2ord(fmaf((float)acc, fdelta, fdmin));
             }
             ord[seen + p] = o;
+        };
+        int p = threadIdx.x;
+        if (NIB) {
+            // rounds of CALIB_EARLY2 codes per thread; the next round is requested before the
+            // current one is looked up
+            while (p < take) {
+                uint2 cur[CALIB_EARLY2];
+#pragma unroll
+                for (int u = 0; u < CALIB_EARLY2; ++u) cur[u] = early[u];
+                const int pn = p + CALIB_EARLY2 * 256;
+                if (pn < take) {
+#pragma unroll
+                    for (int u = 0; u < CALIB_EARLY2; ++u) {
+                        const int pp = pn + u * 256;
+                        early[u] = *(const uint2 *)(list_codes + (size_t)(lo + (pp < take ? pp : take - 1)) * 8);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < CALIB_EARLY2; ++u)
+                    if (p + u * 256 < take) qadc_of(p + u * 256, true, cur[u]);
+                p = pn;
+            }
         }
+        for (; p < take; p += blockDim.x) qadc_of(p, false, make_uint2(0u, 0u));
         seen += take;
         __syncthreads();
     }
