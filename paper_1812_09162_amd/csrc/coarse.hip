@@ -197,7 +197,11 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
             if (!FILTER && !colok) continue;
             const float cn = cnv[j];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 2; ++i) {
+                // room for the 16 results per lane of this 32 x 32 tile (checked here, not at
+                // every result: the flush code exists eight times instead of 128)
+                static_assert(16 * QADC_WAVE <= QCAP, "a 32 x 32 tile's survivors fit the queue");
+                if (FILTER && nqueued + 16 * QADC_WAVE > QCAP) flush();
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     // four consecutive rows: their bounds come as one 16-byte LDS read
@@ -217,17 +221,17 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
                             const bool pass = colok && sc <= bnd[rr];  // rows past the end: bound -inf
                             const uint64_t m = __ballot(pass);
                             if (m != 0) {
-                                if (nqueued + QADC_WAVE > QCAP) flush();
                                 if (pass) {
                                     const uint32_t at = nqueued + __builtin_amdgcn_mbcnt_hi(
                                         (uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
                                     queue[at] = make_uint2(__float_as_uint(sc), ((uint32_t)rl << 16) | (uint32_t)cl);
                                 }
-                                nqueued += (uint32_t)__popcll(m);
+                                nqueued = __builtin_amdgcn_readfirstlane(nqueued + (uint32_t)__popcll(m));
                             }
                         }
                     }
                 }
+            }
         }
         if (FILTER) flush();
         if (FILTER) {
