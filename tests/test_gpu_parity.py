@@ -406,7 +406,9 @@ def check_ivf(qb, ip, R, t=T_CAL, probe=None):
 
 @pytest.mark.parametrize("n,K,nprobe,R", [(120_000, 256, 16, 100), (30_011, 64, 8, 10),
                                           (60_000, 128, 64, 1000), (9_001, 37, 5, 10),
-                                          (70_000, 1_031, 33, 100)])
+                                          (70_000, 1_031, 33, 100),
+                                          # short lists: calibration and pilot walk more than 64 probes
+                                          (20_000, 1_024, 300, 50)])
 def test_ivf_scaled_c4_bit_exact(qb, n, K, nprobe, R):
     ip = synth.build(synth.scaled("C4", n=n, nq=8, K=K, nprobe=nprobe))
     check_ivf(qb, ip, R)
