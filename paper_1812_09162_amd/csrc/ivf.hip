@@ -205,6 +205,8 @@ __device__ __forceinline__ void calib_list(int a, const int32_t *__restrict__ pr
 
 // NIB: 64-bit m x 4 codes (sub-code j is nibble j of the code).  Other layouts take the
 // sub-quantizers' table offset, bit offset and width from a small LDS array.
+// pair_cnt (or null): bucket counts of the pairs' sort by cell, pair_nb buckets and one more
+// for pairs without a list, zero on entry; the block adds its query's pairs.
 template <bool NIB, int DS = 0>
 __global__ void __launch_bounds__(256)
 k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
@@ -212,7 +214,7 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
             const float *__restrict__ coarse, const int64_t *__restrict__ list_offsets,
             const uint8_t *__restrict__ list_codes, const float *__restrict__ queries,
             const int32_t *__restrict__ probe_ids, int nprobe, int K, int want, int pilot_want,
-            int R, char *__restrict__ ws, size_t per_query) {
+            int R, char *__restrict__ ws, size_t per_query, uint32_t *__restrict__ pair_cnt, int pair_nb) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t sel[8];
@@ -246,6 +248,9 @@ k_ivf_calib(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
             const bool valid = c >= 0 && c < K;
             const int64_t lo = valid ? list_offsets[c] : 0, hi = valid ? list_offsets[c + 1] : 0;
             np += hi - lo;
+            // the count of the sort of the (query, probe) pairs by cell (ivf_pair_bucket), for
+            // which this loop has the cell and the bounds at hand
+            if (pair_cnt) atomicAdd(&pair_cnt[hi > lo ? (int)(((int64_t)c * pair_nb) / K) : pair_nb], 1u);
             if (a < CALIB_PC) {
                 s_pcell[a] = c;
                 s_plo[a] = lo;
@@ -440,13 +445,6 @@ __device__ __forceinline__ int ivf_pair_bucket(const int32_t *__restrict__ probe
     const int c = probe_ids[p];
     if (c < 0 || c >= K) return NB;
     return list_offsets[c + 1] > list_offsets[c] ? (int)(((int64_t)c * NB) / K) : NB;
-}
-
-__global__ void __launch_bounds__(256)
-k_pair_count(const int32_t *__restrict__ probe_ids, const int64_t *__restrict__ list_offsets,
-             int64_t npairs, int K, int NB, uint32_t *__restrict__ cnt) {
-    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (p < npairs) atomicAdd(&cnt[ivf_pair_bucket(probe_ids, list_offsets, p, K, NB)], 1u);
 }
 
 // one block: start[b] = number of pairs in buckets before b (b = 0 .. NB), and cnt cleared to
@@ -1504,7 +1502,7 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
                       int nq, const int32_t *probe_ids, int nprobe, int K, int want, int R,
                       int32_t *out_ids, float *out_dist, char *ws, const IvfPlan &p, uint32_t *sortws,
                       bool shared_lists, bool tighten, hipStream_t s) {
-    // blocks in the order of the probed cells (see k_pair_count):
+    // blocks in the order of the probed cells (see ivf_pair_bucket):
     // sortws = cnt[NB+1] | start[NB+1] | order[pairs]
     const uint32_t *order = nullptr;
     // fixed shape of k_ivf_scan's fast set-up and of k_ivf_scan_mq: 16 x 4 bits over equal
@@ -1513,51 +1511,26 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     const IvfGroup *gdesc = nullptr;
     const uint32_t *ngroups = nullptr;
     size_t max_groups = 0;
-    if (sortws && shared_lists && dsf != 0 && !tighten) {
+    // The sort's bucket counts are taken by k_ivf_calib (its blocks walk their probes anyway);
+    // the counters are cleared before it and the rest of the sort follows it.
+    uint32_t *pair_cnt = nullptr;
+    int pair_nb = 0;
+    const int64_t npairs = (int64_t)nq * nprobe;
+    const int sort_kind = tighten || !sortws ? 0 : (shared_lists && dsf != 0 ? 2 : 1);
+    if (sort_kind == 2) {
         // pairs sorted by cell exactly and cut into groups of four (see k_ivf_scan_mq):
         // sortws = cnt[K+2] | start[K+2] | gstart[K+2] | bsum[2 * 1024] | order[pairs] | (16-byte aligned) gdesc[pairs/4 + K + 1]
-        const int64_t npairs = (int64_t)nq * nprobe;
         const size_t nbw = (size_t)K + 2;
-        uint32_t *cnt = sortws, *start = sortws + nbw, *gstart = sortws + 2 * nbw, *bsum = sortws + 3 * nbw;
-        uint32_t *ord = bsum + 2048;
-        IvfGroup *gd = (IvfGroup *)(((uintptr_t)(ord + npairs) + 15) & ~(uintptr_t)15);
-        max_groups = (size_t)(npairs / IVF_MQ) + (size_t)K + 1;
-        const unsigned scan_blocks = (unsigned)((K + 1 + 1023) / 1024);  // <= 1024: K < 2^20 is checked by the caller
-        hipLaunchKernelGGL(k_pair_zero, dim3((unsigned)((nbw + 255) / 256)), dim3(256), 0, s, cnt, (int)nbw);
+        hipLaunchKernelGGL(k_pair_zero, dim3((unsigned)((nbw + 255) / 256)), dim3(256), 0, s, sortws, (int)nbw);
         QADC_LAUNCH_CHECK("k_pair_zero");
-        hipLaunchKernelGGL(k_pair_count, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, probe_ids,
-                           list_offsets, npairs, K, K, cnt);
-        QADC_LAUNCH_CHECK("k_pair_count");
-        hipLaunchKernelGGL(k_pair_block_sums, dim3(scan_blocks), dim3(1024), 0, s, (const uint32_t *)cnt, K + 1, bsum);
-        QADC_LAUNCH_CHECK("k_pair_block_sums");
-        hipLaunchKernelGGL(k_pair_scan_groups, dim3(scan_blocks), dim3(1024), 0, s, cnt, start, gstart, K + 1,
-                           (const uint32_t *)bsum);
-        QADC_LAUNCH_CHECK("k_pair_scan_groups");
-        hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, probe_ids,
-                           list_offsets, npairs, K, K, (const uint32_t *)start, cnt, ord);
-        QADC_LAUNCH_CHECK("k_pair_fill");
-        hipLaunchKernelGGL(k_group_fill, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s, (const uint32_t *)cnt,
-                           (const uint32_t *)start, (const uint32_t *)gstart, (const uint32_t *)ord, K, nprobe,
-                           ws, p.per_query, p.counts_off, gd);
-        QADC_LAUNCH_CHECK("k_group_fill");
-        order = ord;
-        gdesc = gd;
-        ngroups = gstart + (K + 1);
-    } else if (sortws) {
-        const int64_t npairs = (int64_t)nq * nprobe;
+        pair_cnt = sortws;
+        pair_nb = K;
+    } else if (sort_kind == 1) {
         const int NB = K < IVF_SORT_BUCKETS ? K : IVF_SORT_BUCKETS;
-        uint32_t *cnt = sortws, *start = sortws + (NB + 1), *ord = sortws + 2 * (size_t)(NB + 1);
-        hipLaunchKernelGGL(k_pair_zero, dim3((NB + 1 + 255) / 256), dim3(256), 0, s, cnt, NB + 1);
+        hipLaunchKernelGGL(k_pair_zero, dim3((NB + 1 + 255) / 256), dim3(256), 0, s, sortws, NB + 1);
         QADC_LAUNCH_CHECK("k_pair_zero");
-        hipLaunchKernelGGL(k_pair_count, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, probe_ids,
-                           list_offsets, npairs, K, NB, cnt);
-        QADC_LAUNCH_CHECK("k_pair_count");
-        hipLaunchKernelGGL(k_pair_scan, dim3(1), dim3(1024), 0, s, cnt, start, NB + 1);
-        QADC_LAUNCH_CHECK("k_pair_scan");
-        hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, probe_ids,
-                           list_offsets, npairs, K, NB, (const uint32_t *)start, cnt, ord);
-        QADC_LAUNCH_CHECK("k_pair_fill");
-        order = ord;
+        pair_cnt = sortws;
+        pair_nb = NB;
     }
     // pilot: as many codes as fit the calibration block's LDS next to its tables (the kernel's
     // own static arrays stay under 12 KB of the 160 KB), never fewer than the calibration codes;
@@ -1593,7 +1566,8 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
         if ((rc = allow_lds(k_ivf_calib<__VA_ARGS__>, lds_calib)) != PQ_OK) return rc;               \
         hipLaunchKernelGGL((k_ivf_calib<__VA_ARGS__>), dim3(nq), dim3(256), lds_calib, s, idx->dev,  \
                            idx->edesc, idx->codebooks, coarse, list_offsets, list_codes, queries,    \
-                           probe_ids, nprobe, K, want, pilot_want, R, ws, p.per_query);              \
+                           probe_ids, nprobe, K, want, pilot_want, R, ws, p.per_query, pair_cnt,     \
+                           pair_nb);                                                                 \
     } while (0)
     // (the fixed 16 x 4-bit shape has a set-up of its own)
     if (dsf == 4) QADC_IVF_CALIB(true, 4);
@@ -1623,6 +1597,38 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
 #undef QADC_IVF_TIGHT
         QADC_LAUNCH_CHECK("k_ivf_tight");
         return PQ_OK;
+    }
+    if (sort_kind == 2) {
+        const size_t nbw = (size_t)K + 2;
+        uint32_t *cnt = sortws, *start = sortws + nbw, *gstart = sortws + 2 * nbw, *bsum = sortws + 3 * nbw;
+        uint32_t *ord = bsum + 2048;
+        IvfGroup *gd = (IvfGroup *)(((uintptr_t)(ord + npairs) + 15) & ~(uintptr_t)15);
+        max_groups = (size_t)(npairs / IVF_MQ) + (size_t)K + 1;
+        const unsigned scan_blocks = (unsigned)((K + 1 + 1023) / 1024);  // <= 1024: K < 2^20 is checked by the caller
+        hipLaunchKernelGGL(k_pair_block_sums, dim3(scan_blocks), dim3(1024), 0, s, (const uint32_t *)cnt, K + 1, bsum);
+        QADC_LAUNCH_CHECK("k_pair_block_sums");
+        hipLaunchKernelGGL(k_pair_scan_groups, dim3(scan_blocks), dim3(1024), 0, s, cnt, start, gstart, K + 1,
+                           (const uint32_t *)bsum);
+        QADC_LAUNCH_CHECK("k_pair_scan_groups");
+        hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, probe_ids,
+                           list_offsets, npairs, K, K, (const uint32_t *)start, cnt, ord);
+        QADC_LAUNCH_CHECK("k_pair_fill");
+        hipLaunchKernelGGL(k_group_fill, dim3((unsigned)((K + 255) / 256)), dim3(256), 0, s, (const uint32_t *)cnt,
+                           (const uint32_t *)start, (const uint32_t *)gstart, (const uint32_t *)ord, K, nprobe,
+                           ws, p.per_query, p.counts_off, gd);
+        QADC_LAUNCH_CHECK("k_group_fill");
+        order = ord;
+        gdesc = gd;
+        ngroups = gstart + (K + 1);
+    } else if (sort_kind == 1) {
+        const int NB = pair_nb;
+        uint32_t *cnt = sortws, *start = sortws + (NB + 1), *ord = sortws + 2 * (size_t)(NB + 1);
+        hipLaunchKernelGGL(k_pair_scan, dim3(1), dim3(1024), 0, s, cnt, start, NB + 1);
+        QADC_LAUNCH_CHECK("k_pair_scan");
+        hipLaunchKernelGGL(k_pair_fill, dim3((unsigned)((npairs + 255) / 256)), dim3(256), 0, s, probe_ids,
+                           list_offsets, npairs, K, NB, (const uint32_t *)start, cnt, ord);
+        QADC_LAUNCH_CHECK("k_pair_fill");
+        order = ord;
     }
     if (gdesc) {
         const size_t lds_mq = IVF_MQ_TAB_BYTES + sizeof(IvfMqLds);
