@@ -190,6 +190,16 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
             nqueued = 0;
         };
         if (FILTER) __syncthreads();  // every wave has read its last operands: Bs is free
+        // the bounds of this lane's 32 rows (four consecutive rows per 16-byte LDS read), all
+        // requested together and kept for the four column blocks
+        float4 bq[2][4];
+        if (FILTER) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4)
+                    bq[i][r4] = *(const float4 *)&s_bound[wr * 64 + i * 32 + r4 * 8 + (l >> 5) * 4];
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int cl = wc * 128 + j * 32 + (l & 31), col = c0 + cl;
@@ -204,12 +214,10 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
                 if (FILTER && nqueued + 16 * QADC_WAVE > QCAP) flush();
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    // four consecutive rows: their bounds come as one 16-byte LDS read
                     const int rl0 = wr * 64 + i * 32 + r4 * 8 + (l >> 5) * 4;
                     float bnd[4] = {0.f, 0.f, 0.f, 0.f};
                     if (FILTER) {
-                        const float4 b4 = *(const float4 *)&s_bound[rl0];
-                        bnd[0] = b4.x; bnd[1] = b4.y; bnd[2] = b4.z; bnd[3] = b4.w;
+                        bnd[0] = bq[i][r4].x; bnd[1] = bq[i][r4].y; bnd[2] = bq[i][r4].z; bnd[3] = bq[i][r4].w;
                     }
 #pragma unroll
                     for (int rr = 0; rr < 4; ++rr) {
