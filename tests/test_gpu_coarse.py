@@ -171,6 +171,41 @@ def test_coarse_search_against_the_plain_definition_in_fp64(qb, K, d, nq, nprobe
         assert np.all(np.abs(sc[q, :k] + (q64[q] ** 2).sum() - true[got]) <= tol)   # the scores themselves
 
 
+def _random_coarse_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        big = rng.random() < 0.7   # large enough for the form that writes no score matrix
+        out.append((int(rng.integers(16_500, 90_000)) if big else int(rng.integers(1, 16_500)),
+                    int(rng.choice([4, 7, 16, 33, 64, 96, 128])), int(rng.integers(1, 300)),
+                    int(rng.choice([1, 3, 16, 64, 100, 128, 129, 200, 256])), int(rng.integers(0, 4)),
+                    int(rng.integers(1, 1 << 30))))
+    return out
+
+
+@pytest.mark.parametrize("K,d,nq,nprobe,mode,seed", _random_coarse_cases(16, seed=20240612))
+def test_coarse_search_random_cases(qb, K, d, nq, nprobe, mode, seed):
+    """Drawn shapes over both forms and both candidate-selection kernels; mode 0: small integers
+    (many exact ties), 1: unit-norm centroids, 2: scores of both signs with fifty equal cells,
+    3: plain normal data."""
+    r = np.random.default_rng(seed)
+    if mode == 0:
+        cen = r.integers(0, 6, (K, d)).astype(np.float32)
+        qs = r.integers(0, 6, (nq, d)).astype(np.float32)
+    elif mode == 1:
+        cen = r.normal(size=(K, d)).astype(np.float32)
+        cen /= np.linalg.norm(cen, axis=1, keepdims=True)
+        qs = r.normal(size=(nq, d)).astype(np.float32)
+    elif mode == 2:
+        cen = (r.normal(size=(K, d)) * 0.3).astype(np.float32)
+        cen[K // 2: K // 2 + min(50, K - K // 2)] = cen[K // 2]
+        qs = (r.normal(size=(nq, d)) * 3).astype(np.float32)
+    else:
+        cen = r.normal(size=(K, d)).astype(np.float32)
+        qs = r.normal(size=(nq, d)).astype(np.float32)
+    check(qb, cen, qs, nprobe, nq_oracle=min(nq, 10))
+
+
 def test_coarse_search_errors(qb):
     cen = torch.zeros((10, 4), dtype=torch.float32, device=dev())
     qs = torch.zeros((2, 4), dtype=torch.float32, device=dev())

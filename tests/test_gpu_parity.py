@@ -432,6 +432,33 @@ def test_ivf_16x4_subspace_widths(qb, d, acc):
     check_ivf(qb, ip, 100)
 
 
+def _random_ivf_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        kind = int(rng.integers(0, 5))
+        if kind <= 2:
+            d, nbits, acc = int(rng.choice([64, 96, 128])), [4] * 16, 8
+        elif kind == 3:
+            d, nbits, acc = 80, [4] * 16, int(rng.choice([8, 16]))
+        else:
+            d, nbits, acc = 128, list(synth.C3_BITS), 16
+        K = int(rng.integers(8, 600))
+        out.append((int(rng.integers(2_000, 60_000)), K, int(rng.integers(1, min(K, 200) + 1)),
+                    int(rng.choice([1, 7, 50, 100, 256, 300, 1000])), d, nbits, acc,
+                    str(rng.choice(["gamma_ints", "aniso_gauss"])), int(rng.integers(1, 1 << 30))))
+    return out
+
+
+@pytest.mark.parametrize("n,K,nprobe,R,d,nbits,acc,dist,seed", _random_ivf_cases(16, seed=20240611))
+def test_ivf_random_cases(qb, n, K, nprobe, R, d, nbits, acc, dist, seed):
+    """Drawn sizes, probe counts, result lengths, layouts and distributions (integer-valued data
+    gives many equal distances): both modes and every workspace variant against the oracle."""
+    ip = synth.make_ivf_problem(n=n, nq=3, d=d, nbits=nbits, acc_bits=acc, dist=dist, K=K, nprobe=nprobe,
+                                seed=seed, train_n=min(n, 6000), kmeans_iters=2)
+    check_ivf(qb, ip, R)
+
+
 def test_ivf_largest_nprobe(qb):
     """nprobe = 1024, the most the call accepts: one slot list per probed cell in the selection."""
     ip = synth.build(synth.scaled("C4", n=300_000, nq=3, K=2048, nprobe=1024, train_n=40_000, kmeans_iters=2))
