@@ -35,6 +35,15 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 #define CS_TQ 128     // queries per block tile
 #define CS_TC 256     // cells per block tile
 #define CS_KC 32      // dimensions per LDS chunk
+#ifndef CS_NT
+#define CS_NT 512     // threads per k_scores block: 8 waves as 2 x 4, 64 x 64 results each
+#endif
+#ifndef CS_KK_UNROLL
+#define CS_KK_UNROLL 5  // steps of two dimensions unrolled together (all 16: operand reads hoisted until registers spill)
+#endif
+#define CS_NW (CS_NT / 64)
+#define CS_WC (CS_NW / 2)            // waves side by side over the tile's cells
+#define CS_NJ (CS_TC / CS_WC / 32)   // 32 x 32 MFMA tiles side by side per wave
 #define CS_MAX_NPROBE 1024
 #define CS_SLOT 32    // candidate slots per (query, block of CS_TC cells) in the filtering form
 
@@ -55,14 +64,14 @@ k_cnorm(const float *__restrict__ centroids, int K, int d, float *__restrict__ c
 // consecutive floats; rows of an odd number of floats ( so that the transposing stores spread over
 // the banks).  Global loads: eight adjacent lanes fetch the 128 contiguous bytes that one row
 // contributes to a chunk, so every cache line is requested once.
-template <int NI>  // rows rowb + 32 i, i < NI: a tile of 32 NI rows
+template <int NI>  // rows rowb + (CS_NT / 8) i, i < NI: a tile of (CS_NT / 8) NI rows
 __device__ __forceinline__ void cs_load_chunk(const float *__restrict__ base, int rows_valid, int d,
                                               int k0, bool vec, float4 (&r)[NI]) {
     const int piece = threadIdx.x & 7, rowb = threadIdx.x >> 3;
     const int k = k0 + piece * 4;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-        const int row = rowb + 32 * i;
+        const int row = rowb + (CS_NT / 8) * i;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
         if (row < rows_valid) {
             const float *p = base + (size_t)row * d + k;
@@ -79,14 +88,25 @@ __device__ __forceinline__ void cs_load_chunk(const float *__restrict__ base, in
     }
 }
 
+// The same for a tile whose rows all exist and a chunk that lies inside the rows, 16-byte
+// loads allowed: no tests, one address per row.
+template <int NI>
+__device__ __forceinline__ void cs_load_chunk_full(const float *__restrict__ base, int d, int k0,
+                                                   float4 (&r)[NI]) {
+    const int piece = threadIdx.x & 7, rowb = threadIdx.x >> 3;
+    const float *p = base + (size_t)rowb * d + k0 + piece * 4;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) r[i] = *(const float4 *)(p + (size_t)((CS_NT / 8) * i) * d);
+}
+
 template <int NI>
 __device__ __forceinline__ void cs_store_chunk(float *S, const float4 (&r)[NI]) {
-    constexpr int LD = 32 * NI + 1;
+    constexpr int LD = (CS_NT / 8) * NI + 1;
     const int piece = threadIdx.x & 7, rowb = threadIdx.x >> 3;
     const int k = piece * 4;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-        const int row = rowb + 32 * i;
+        const int row = rowb + (CS_NT / 8) * i;
         S[(k + 0) * LD + row] = r[i].x;
         S[(k + 1) * LD + row] = r[i].y;
         S[(k + 2) * LD + row] = r[i].z;
@@ -98,7 +118,7 @@ __device__ __forceinline__ void cs_store_chunk(float *S, const float4 (&r)[NI]) 
 // appended to slots[(q * ncb + block) * CS_SLOT ...] and counted in counts[q * ncb + block].
 // guard: if non-null and *guard == 0 the kernel does nothing (the matrix form as a fallback).
 template <bool FILTER>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(CS_NT) __attribute__((amdgpu_waves_per_eu(CS_NT / 128, CS_NT / 128)))
 k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ centroids, int K,
          int d, const float *__restrict__ cnorm, float *__restrict__ scores, size_t ld, int vec,
          const float *__restrict__ pilot, int pstride, int koff, uint64_t *__restrict__ slots,
@@ -110,59 +130,72 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
     __shared__ __align__(16) float s_bound[FILTER ? CS_TQ : 4];
     __shared__ uint32_t s_cnt[FILTER ? CS_TQ : 1];
     const int w = threadIdx.x / QADC_WAVE, l = threadIdx.x % QADC_WAVE;
-    const int wr = w >> 1, wc = w & 1;  // this wave's 64 x 128 part: 2 x 4 MFMA tiles
+    const int wr = w / CS_WC, wc = w % CS_WC;  // this wave's 64 x (32 CS_NJ) part: 2 x CS_NJ MFMA tiles
     const int ncb = gx;
     const int nch = (d + CS_KC - 1) / CS_KC;
-    float4 ra[CS_TQ / 32], rb[CS_TC / 32];
+    constexpr int RPP = CS_NT / 8;  // rows per pass of the loads
+    float4 ra[CS_TQ / RPP], rb[CS_TC / RPP];
     {
         const int tile = blockIdx.x;  // cell block tile % gx, query block tile / gx
         const int c0 = (tile % gx) * CS_TC, q0 = (tile / gx) * CS_TQ, cbx = tile % gx;
+        const bool full_a = vec != 0 && nqc - q0 >= CS_TQ, full_b = vec != 0 && K - c0 >= CS_TC;  // (block-uniform)
         auto load = [&](int kc) {
-            cs_load_chunk<CS_TQ / 32>(queries + (size_t)q0 * d, nqc - q0 < CS_TQ ? nqc - q0 : CS_TQ, d,
-                                      kc * CS_KC, vec != 0, ra);
-            cs_load_chunk<CS_TC / 32>(centroids + (size_t)c0 * d, K - c0 < CS_TC ? K - c0 : CS_TC, d,
-                                      kc * CS_KC, vec != 0, rb);
+            const bool inside = (kc + 1) * CS_KC <= d;
+            if (full_a && inside)
+                cs_load_chunk_full<CS_TQ / RPP>(queries + (size_t)q0 * d, d, kc * CS_KC, ra);
+            else
+                cs_load_chunk<CS_TQ / RPP>(queries + (size_t)q0 * d, nqc - q0 < CS_TQ ? nqc - q0 : CS_TQ, d,
+                                           kc * CS_KC, vec != 0, ra);
+            if (full_b && inside)
+                cs_load_chunk_full<CS_TC / RPP>(centroids + (size_t)c0 * d, d, kc * CS_KC, rb);
+            else
+                cs_load_chunk<CS_TC / RPP>(centroids + (size_t)c0 * d, K - c0 < CS_TC ? K - c0 : CS_TC, d,
+                                           kc * CS_KC, vec != 0, rb);
         };
         load(0);
-        float cnv[4];  // the norms of this lane's four columns, in flight during the multiplications
+        float cnv[CS_NJ];  // the norms of this lane's columns, in flight during the multiplications
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int col = c0 + wc * 128 + j * 32 + (l & 31);
+        for (int j = 0; j < CS_NJ; ++j) {
+            const int col = c0 + wc * (32 * CS_NJ) + j * 32 + (l & 31);
             cnv[j] = col < K ? cnorm[col] : 0.0f;
         }
-        f32x16 acc[2][4];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+        f32x16 acc[2][CS_NJ];  // set by the first multiplications (zero as their addend)
         if (FILTER && threadIdx.x < CS_TQ) {  // visible after the barriers of the first chunk
             const int row = q0 + (int)threadIdx.x;
             s_bound[threadIdx.x] = row < nqc ? pilot[(size_t)row * pstride + koff] : -INFINITY;
             s_cnt[threadIdx.x] = 0;
         }
-        for (int kc = 0; kc < nch; ++kc) {
+        auto chunk = [&](int kc, bool first) {
             __syncthreads();  // the previous chunk has been consumed
-            cs_store_chunk<CS_TQ / 32>(As, ra);
-            cs_store_chunk<CS_TC / 32>(Bs, rb);
+            cs_store_chunk<CS_TQ / RPP>(As, ra);
+            cs_store_chunk<CS_TC / RPP>(Bs, rb);
             __syncthreads();
             if (kc + 1 < nch) load(kc + 1);  // in flight during the multiplications
-#pragma unroll
-            for (int kk = 0; kk < CS_KC; kk += 2) {
+            auto step = [&](int kk, bool zero_addend) {
                 const int ka = (kk + (l >> 5)) * LDA + (l & 31) + wr * 64;
-                const int kb = (kk + (l >> 5)) * LDB + (l & 31) + wc * 128;
+                const int kb = (kk + (l >> 5)) * LDB + (l & 31) + wc * (32 * CS_NJ);
                 const float a0 = As[ka], a1 = As[ka + 32];
-                float bv[4];
+                float bv[CS_NJ];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) bv[j] = Bs[kb + 32 * j];
+                for (int j = 0; j < CS_NJ; ++j) bv[j] = Bs[kb + 32 * j];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, bv[j], acc[0][j], 0, 0, 0);
-                    acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, bv[j], acc[1][j], 0, 0, 0);
+                for (int j = 0; j < CS_NJ; ++j) {
+                    if (zero_addend) {
+                        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, bv[j], zero, 0, 0, 0);
+                        acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, bv[j], zero, 0, 0, 0);
+                    } else {
+                        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, bv[j], acc[0][j], 0, 0, 0);
+                        acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, bv[j], acc[1][j], 0, 0, 0);
+                    }
                 }
-            }
-        }
+            };
+            step(0, first);
+#pragma unroll CS_KK_UNROLL
+            for (int kk = 2; kk < CS_KC; kk += 2) step(kk, false);
+        };
+        chunk(0, true);
+        for (int kc = 1; kc < nch; ++kc) chunk(kc, false);
         // element r of a 32 x 32 result: row (r/4)*8 + (lane/32)*4 + r%4, column lane%32
         //
         // FILTER: 1.6 % of the results survive, about one lane in two of the wave's 128 compares.
@@ -170,7 +203,8 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
         // of its wave in the operand buffers (position: a wave-uniform count plus the lane's rank
         // among the survivors, no atomic); the queue is emptied densely afterwards, one entry per
         // lane: position in the (query, cell block) list by an LDS atomic, then the 8-byte store.
-        constexpr uint32_t QCAP = CS_KC * LDB / 2 / 4;  // entries per wave: a quarter of Bs
+        constexpr uint32_t QCAP = CS_KC * LDB / 2 / CS_NW;  // entries per wave: its share of Bs
+        constexpr int RG = QCAP >= 16 * QADC_WAVE ? 4 : 2;  // groups of four rows between two looks at the room
         uint2 *queue = (uint2 *)Bs + w * QCAP;
         uint32_t nqueued = 0;  // wave-uniform
         auto flush = [&]() {
@@ -190,34 +224,27 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
             nqueued = 0;
         };
         if (FILTER) __syncthreads();  // every wave has read its last operands: Bs is free
-        // the bounds of this lane's 32 rows (four consecutive rows per 16-byte LDS read), all
-        // requested together and kept for the four column blocks
-        float4 bq[2][4];
-        if (FILTER) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4)
-                    bq[i][r4] = *(const float4 *)&s_bound[wr * 64 + i * 32 + r4 * 8 + (l >> 5) * 4];
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int cl = wc * 128 + j * 32 + (l & 31), col = c0 + cl;
+        for (int j = 0; j < CS_NJ; ++j) {
+            const int cl = wc * (32 * CS_NJ) + j * 32 + (l & 31), col = c0 + cl;
             const bool colok = col < K;
+            const uint64_t colmask = __ballot(colok);
+            const uint32_t pl = ((uint32_t)(wr * 64 + (l >> 5) * 4) << 16) | (uint32_t)cl;  // first row | column
             if (!FILTER && !colok) continue;
             const float cn = cnv[j];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                // room for the 16 results per lane of this 32 x 32 tile (checked here, not at
-                // every result: the flush code exists eight times instead of 128)
-                static_assert(16 * QADC_WAVE <= QCAP, "a 32 x 32 tile's survivors fit the queue");
-                if (FILTER && nqueued + 16 * QADC_WAVE > QCAP) flush();
+                // room for the next 4 RG results per lane (looked at here, not at every result:
+                // the flush code exists a few times instead of 128)
+                static_assert(4 * RG * QADC_WAVE <= QCAP, "the survivors between two looks fit the queue");
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
+                    if (FILTER && r4 % RG == 0 && nqueued + 4 * RG * QADC_WAVE > QCAP) flush();
                     const int rl0 = wr * 64 + i * 32 + r4 * 8 + (l >> 5) * 4;
                     float bnd[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (FILTER) {
-                        bnd[0] = bq[i][r4].x; bnd[1] = bq[i][r4].y; bnd[2] = bq[i][r4].z; bnd[3] = bq[i][r4].w;
+                    if (FILTER) {  // four consecutive rows: their bounds come as one 16-byte LDS read
+                        const float4 b4 = *(const float4 *)&s_bound[rl0];
+                        bnd[0] = b4.x; bnd[1] = b4.y; bnd[2] = b4.z; bnd[3] = b4.w;
                     }
 #pragma unroll
                     for (int rr = 0; rr < 4; ++rr) {
@@ -226,13 +253,15 @@ k_scores(const float *__restrict__ queries, int nqc, const float *__restrict__ c
                         if (!FILTER) {
                             if (row < nqc) scores[(size_t)row * ld + col] = sc;
                         } else {
-                            const bool pass = colok && sc <= bnd[rr];  // rows past the end: bound -inf
-                            const uint64_t m = __ballot(pass);
+                            // (the compare's lane mask taken as it is: a ballot of the combined
+                            // condition costs two more vector instructions per result)
+                            const uint64_t m = __builtin_amdgcn_fcmpf(sc, bnd[rr], 5 /* ordered <= */) & colmask;
                             if (m != 0) {
+                                const bool pass = colok && sc <= bnd[rr];  // rows past the end: bound -inf
                                 if (pass) {
                                     const uint32_t at = nqueued + __builtin_amdgcn_mbcnt_hi(
                                         (uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                                    queue[at] = make_uint2(__float_as_uint(sc), ((uint32_t)rl << 16) | (uint32_t)cl);
+                                    queue[at] = make_uint2(__float_as_uint(sc), pl + ((uint32_t)(i * 32 + r4 * 8 + rr) << 16));
                                 }
                                 nqueued = __builtin_amdgcn_readfirstlane(nqueued + (uint32_t)__popcll(m));
                             }
@@ -624,7 +653,7 @@ extern "C" int ivf_coarse_search(const float *queries, int nq, const float *cent
         const int *guard = nullptr;
         if (P > 0) {
             // pilot: matrix form over the first P cells -> bound and best score per query
-            hipLaunchKernelGGL(k_scores<false>, dim3(cs_grid(P / CS_TC, gq.y)), dim3(256), 0, s, qp, nqc,
+            hipLaunchKernelGGL(k_scores<false>, dim3(cs_grid(P / CS_TC, gq.y)), dim3(CS_NT), 0, s, qp, nqc,
                                centroids, P, d, cnorm, scores, (size_t)P, vec, (const float *)nullptr, 0, 0,
                                (uint64_t *)nullptr, (uint32_t *)nullptr, (const int *)nullptr, P / CS_TC,
                                (int)gq.y);
@@ -632,7 +661,7 @@ extern "C" int ivf_coarse_search(const float *queries, int nq, const float *cent
             hipLaunchKernelGGL(k_select<256>, dim3(nqc), dim3(256), 0, s, scores, (size_t)P, P, nprobe, pilot_ids,
                                pilot_sc, (const int *)nullptr, flag);
             QADC_LAUNCH_CHECK("k_select (pilot)");
-            hipLaunchKernelGGL(k_scores<true>, dim3(cs_grid(gq.x, gq.y)), dim3(256), 0, s, qp, nqc, centroids, K,
+            hipLaunchKernelGGL(k_scores<true>, dim3(cs_grid(gq.x, gq.y)), dim3(CS_NT), 0, s, qp, nqc, centroids, K,
                                d, cnorm, (float *)nullptr, ld, vec, (const float *)pilot_sc, nprobe, nprobe - 1,
                                slots, counts, (const int *)nullptr, (int)gq.x, (int)gq.y);
             QADC_LAUNCH_CHECK("k_scores (filter)");
@@ -649,7 +678,7 @@ extern "C" int ivf_coarse_search(const float *queries, int nq, const float *cent
             QADC_LAUNCH_CHECK("k_select_cand");
             guard = flag;  // the matrix form below only runs if a list overflowed
         }
-        hipLaunchKernelGGL(k_scores<false>, dim3(cs_grid(gq.x, gq.y)), dim3(256), 0, s, qp, nqc, centroids, K, d,
+        hipLaunchKernelGGL(k_scores<false>, dim3(cs_grid(gq.x, gq.y)), dim3(CS_NT), 0, s, qp, nqc, centroids, K, d,
                            cnorm, scores, ld, vec, (const float *)nullptr, 0, 0, (uint64_t *)nullptr,
                            (uint32_t *)nullptr, guard, (int)gq.x, (int)gq.y);
         QADC_LAUNCH_CHECK("k_scores");
