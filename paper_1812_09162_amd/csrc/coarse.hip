@@ -362,11 +362,32 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
         }
     };
 
+    // Up to RC rounds of keys (the pilot's few thousand scores) stay in registers after the first
+    // pass: the three passes are bound by the memory system, not by their arithmetic.
+    constexpr int RC = 4;
+    const bool cached = nj <= RC;  // (block-uniform)
+    uint32_t kc[RC][4];
+    auto keys = [&](int j0, uint32_t (&v)[UB][4]) {
+        if (cached) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[u][c] = u < RC ? kc[u < RC ? u : 0][c] : 0xffffffffu;
+        } else {
+            load_keys(j0, v);
+        }
+    };
     // range of the keys
     uint32_t lo = 0xffffffffu, hi = 0u;
     for (int j0 = 0; j0 < nj; j0 += UB) {
         uint32_t v[UB][4];
         load_keys(j0, v);
+        if (cached) {
+#pragma unroll
+            for (int u = 0; u < RC; ++u)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) kc[u][c] = v[u][c];
+        }
 #pragma unroll
         for (int u = 0; u < UB; ++u)
 #pragma unroll
@@ -405,7 +426,7 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
     };
     for (int j0 = 0; j0 < nj; j0 += UB) {
         uint32_t v[UB][4];
-        load_keys(j0, v);
+        keys(j0, v);
 #pragma unroll
         for (int u = 0; u < UB; ++u)
 #pragma unroll
@@ -422,7 +443,7 @@ k_select(const float *__restrict__ scores, size_t ld, int K, int nprobe,
     if (cand <= CS_CAND) {
         for (int j0 = 0; j0 < nj; j0 += UB) {
             uint32_t v[UB][4];
-            load_keys(j0, v);
+            keys(j0, v);
 #pragma unroll
             for (int u = 0; u < UB; ++u)
 #pragma unroll
