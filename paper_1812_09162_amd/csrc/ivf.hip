@@ -1230,7 +1230,8 @@ k_ivf_final(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
 // LDS; whenever the buffer runs full, and at the end of every list that added to it, the R
 // smallest are kept and the rest dropped: a dropped word is above R held ones, so it can
 // neither be a result nor move a later R-th smallest.
-#define TIGHT_CAP 4096
+#define TIGHT_CAP 4096       // words of the candidate buffer ...
+#define TIGHT_CAP_SMALL 2048 // ... and for R <= TIGHT_CAP_SMALL - TIGHT_U * 256: half the LDS, more blocks per CU
 #define TIGHT_U 4  // codes per thread between two looks at the fill level
 #define TIGHT_PC 64  // probes whose cells and list bounds are fetched together
 
@@ -1276,10 +1277,11 @@ __device__ inline uint64_t tight_kth(const uint64_t *A, int na, int k, uint32_t 
 }
 
 // Keep the R smallest of A[0..na), na > R; returns the R-th smallest.  *count becomes R.
+template <int CAP>
 __device__ inline uint64_t tight_keep(uint64_t *A, int na, int R, uint32_t *hist, uint32_t *sh,
                                       uint32_t *count) {
     const uint64_t thr = tight_kth(A, na, R, hist, sh);
-    constexpr int PER = TIGHT_CAP / 256;
+    constexpr int PER = CAP / 256;
     uint64_t mine[PER];
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
@@ -1292,7 +1294,7 @@ __device__ inline uint64_t tight_keep(uint64_t *A, int na, int R, uint32_t *hist
     for (int u = 0; u < PER; ++u)
         if (mine[u] <= thr) {
             const uint32_t pos = atomicAdd(count, 1u);
-            if (pos < TIGHT_CAP) A[pos] = mine[u];
+            if (pos < CAP) A[pos] = mine[u];
         }
     __syncthreads();
     return thr;
@@ -1352,7 +1354,7 @@ __device__ inline uint64_t tight_keep_small(uint64_t *A, int na, int R, int nsor
     return ((uint64_t)sh[3] << 32) | sh[2];
 }
 
-template <int KIND, typename QT, int DS = 0>
+template <int KIND, typename QT, int CAP, int DS = 0>
 __global__ void __launch_bounds__(256)
 k_ivf_tight(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc,
             const float *__restrict__ cb, const float *__restrict__ coarse,
@@ -1367,9 +1369,9 @@ k_ivf_tight(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
     __shared__ uint32_t s_na;
     __shared__ int64_t s_plo[TIGHT_PC];
     __shared__ int32_t s_plen[TIGHT_PC], s_pcell[TIGHT_PC];
-    uint64_t *A = (uint64_t *)smem;  // TIGHT_CAP words
+    uint64_t *A = (uint64_t *)smem;  // CAP words
     IvfLds l;
-    ivf_carve(L, smem + TIGHT_CAP * 8, sizeof(QT), l);
+    ivf_carve(L, smem + CAP * 8, sizeof(QT), l);
     const size_t q = blockIdx.x;
     const IvfState *st = (const IvfState *)(ws + q * per_query);
     const int32_t *probes = probe_ids + q * nprobe;
@@ -1422,13 +1424,14 @@ k_ivf_tight(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
             if (!ok) continue;
             const QT *gtab = (const QT *)l.gtab;
             const float fdelta = (float)l.sc[1], fdmin = (float)l.sc[0];
-            const int na_before = na;
+            bool added = false;  // the list has added to the buffer (also if a full buffer was cut back since)
             for (int64_t base = lo; base < hi; base += TIGHT_U * bd) {
-                if (na + TIGHT_U * bd > TIGHT_CAP) {  // na > R here: R <= TIGHT_CAP - TIGHT_U * 256
-                    pthr = tight_keep(A, na, R, hist, sh, &s_na);
+                if (na + TIGHT_U * bd > CAP) {  // na > R here: R <= CAP - TIGHT_U * 256
+                    pthr = tight_keep<CAP>(A, na, R, hist, sh, &s_na);
                     na = R;
                     nsorted = 0;
                 }
+                const int na_old = na;
                 uint32_t key[TIGHT_U];
                 if constexpr (KIND == SCAN_NIB8) {
                     uint2 w[TIGHT_U];
@@ -1452,20 +1455,21 @@ k_ivf_tight(const DevLayout *__restrict__ L, const EntryDesc *__restrict__ edesc
                     const uint64_t w = ((uint64_t)o << 32) | (uint64_t)(uint32_t)list_ids[p];
                     if (w <= pthr) {
                         const uint32_t pos = atomicAdd(&s_na, 1u);
-                        if (pos < TIGHT_CAP) A[pos] = w;  // always, unless stored ids repeat
+                        if (pos < CAP) A[pos] = w;  // always, unless stored ids repeat
                     }
                 }
                 __syncthreads();
-                na = (int)(s_na < TIGHT_CAP ? s_na : TIGHT_CAP);
+                na = (int)(s_na < CAP ? s_na : CAP);
+                added = added || na != na_old;
                 __syncthreads();  // every thread has read the fill level before the next batch adds to it
             }
-            if (na != na_before && na >= R) {
+            if (added && na >= R) {
                 if (na <= 256) {
                     pthr = tight_keep_small(A, na, R, nsorted, sh, &s_na);
                     na = R;
                     nsorted = R;
                 } else if (na > R) {
-                    pthr = tight_keep(A, na, R, hist, sh, &s_na);
+                    pthr = tight_keep<CAP>(A, na, R, hist, sh, &s_na);
                     na = R;
                     nsorted = 0;
                 } else {
@@ -1578,8 +1582,9 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
     QADC_LAUNCH_CHECK("k_ivf_calib");
     if (tighten) {
         static_assert(PQ_MAX_R + TIGHT_U * 256 <= TIGHT_CAP, "room for one batch above R candidates");
-        const size_t lds_tight = (size_t)TIGHT_CAP * 8 + lds_scan;
-#define QADC_IVF_TIGHT(...)                                                                          \
+        const bool small_cap = R + TIGHT_U * 256 <= TIGHT_CAP_SMALL;
+        const size_t lds_tight = (size_t)(small_cap ? TIGHT_CAP_SMALL : TIGHT_CAP) * 8 + lds_scan;
+#define QADC_IVF_TIGHT1(...)                                                                         \
     do {                                                                                             \
         if ((rc = allow_lds(k_ivf_tight<__VA_ARGS__>, lds_tight)) != PQ_OK) return rc;               \
         hipLaunchKernelGGL((k_ivf_tight<__VA_ARGS__>), dim3(nq), dim3(256), lds_tight, s, idx->dev,  \
@@ -1587,13 +1592,19 @@ static int launch_ivf(const pq_index *idx, const float *coarse, const int64_t *l
                            queries, probe_ids, nprobe, K, R, (const char *)ws, p.per_query, out_ids, \
                            out_dist);                                                                \
     } while (0)
+#define QADC_IVF_TIGHT(KINDV, QTV, DSV)                                                              \
+    do {                                                                                             \
+        if (small_cap) QADC_IVF_TIGHT1(KINDV, QTV, TIGHT_CAP_SMALL, DSV);                            \
+        else QADC_IVF_TIGHT1(KINDV, QTV, TIGHT_CAP, DSV);                                            \
+    } while (0)
         if (KIND == SCAN_NIB8 && sizeof(QT) == 1 && dsf != 0) {
             if (dsf == 4) QADC_IVF_TIGHT(SCAN_NIB8, uint8_t, 4);
             else if (dsf == 6) QADC_IVF_TIGHT(SCAN_NIB8, uint8_t, 6);
             else QADC_IVF_TIGHT(SCAN_NIB8, uint8_t, 8);
         } else {
-            QADC_IVF_TIGHT(KIND, QT);
+            QADC_IVF_TIGHT(KIND, QT, 0);
         }
+#undef QADC_IVF_TIGHT1
 #undef QADC_IVF_TIGHT
         QADC_LAUNCH_CHECK("k_ivf_tight");
         return PQ_OK;

@@ -408,7 +408,10 @@ def check_ivf(qb, ip, R, t=T_CAL, probe=None):
                                           (60_000, 128, 64, 1000), (9_001, 37, 5, 10),
                                           (70_000, 1_031, 33, 100),
                                           # short lists: calibration and pilot walk more than 64 probes
-                                          (20_000, 1_024, 300, 50)])
+                                          (20_000, 1_024, 300, 50),
+                                          # either side of the result length at which the tightening
+                                          # mode's candidate buffer doubles
+                                          (40_000, 100, 50, 1_024), (40_000, 100, 50, 1_025)])
 def test_ivf_scaled_c4_bit_exact(qb, n, K, nprobe, R):
     ip = synth.build(synth.scaled("C4", n=n, nq=8, K=K, nprobe=nprobe))
     check_ivf(qb, ip, R)
@@ -457,6 +460,15 @@ def test_ivf_random_cases(qb, n, K, nprobe, R, d, nbits, acc, dist, seed):
     ip = synth.make_ivf_problem(n=n, nq=3, d=d, nbits=nbits, acc_bits=acc, dist=dist, K=K, nprobe=nprobe,
                                 seed=seed, train_n=min(n, 6000), kmeans_iters=2)
     check_ivf(qb, ip, R)
+
+
+def test_ivf_tightening_bound_after_a_cut_of_the_full_buffer(qb):
+    """A list that fills the tightening mode's candidate buffer, has it cut back to the R best
+    and then adds nothing more still moves the bound for the lists after it (the oracle's
+    R-th smallest distance so far): long result list, lists of up to 1200 codes."""
+    ip = synth.make_ivf_problem(n=52_320, nq=3, d=128, nbits=[4] * 16, acc_bits=8, dist="aniso_gauss", K=74,
+                                nprobe=64, seed=116031117, train_n=6000, kmeans_iters=2)
+    check_ivf(qb, ip, 1000)
 
 
 def test_ivf_largest_nprobe(qb):
