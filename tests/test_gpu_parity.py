@@ -372,6 +372,48 @@ def test_error_paths_on_device(qb):
     idx.close()
 
 
+def _random_big_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    lays = [([4] * 16, 96, 8), ([4] * 16, 128, 8), ([4] * 32, 128, 8), (list(synth.C3_BITS), 128, 16),
+            ([8] * 8, 64, 16), ([6, 6, 4] * 4, 128, 16), ([6, 5, 5] * 4, 128, 16), ([8] * 16, 128, 16),
+            ([4] * 16, 96, 16), ([5, 3, 7, 2, 6], 40, 8)]
+    out = []
+    for _ in range(count):
+        nbits, d, acc = lays[int(rng.integers(0, len(lays)))]
+        out.append((nbits, d, acc, int(rng.integers(100_000, 1_200_000)), int(rng.choice([1, 10, 100, 128, 129, 1000])),
+                    int(rng.choice([1, 2, 5, 9])), str(rng.choice(["gamma_ints", "aniso_gauss"])),
+                    int(rng.integers(1, 1 << 30))))
+    return out
+
+
+@pytest.mark.parametrize("nbits,d,acc,n,R,nq,dist,seed", _random_big_cases(10, seed=20240613))
+def test_random_cases_with_pilot_and_many_blocks(qb, nbits, d, acc, n, R, nq, dist, seed):
+    """Drawn layouts, sizes (hundreds of thousands of codes: the quantizer's pilot, every scan
+    block and the batched passes are in play), result lengths and batch sizes: staged calls,
+    the fused call and a single-query call agree, and the first two queries match the oracle."""
+    pr = synth.make_problem(n=n, nq=nq, d=d, nbits=nbits, acc_bits=acc, dist=dist, seed=seed, train_n=20000,
+                            kmeans_iters=2, device=dev())
+    lay = pr.layout
+    idx = qb.PqIndex(lay.d, lay.nbits, lay.dsub, pr.codebooks.to(dev()), lay.acc_bits)
+    codes_d, qd = pr.codes.to(dev()), pr.queries.to(dev())
+    three = gpu_search(qb, idx, qd, codes_d, R)
+    fused = qb.pq_search_topk(idx, qd, codes_d, T_CAL, R)
+    one = qb.pq_search_topk(idx, qd[:1].contiguous(), codes_d, T_CAL, R)
+    torch.cuda.synchronize()
+    for a, b in zip(three[3:], fused):
+        assert torch.equal(a, b)
+    for a, b in zip(fused, one):
+        assert torch.equal(a[:1], b)
+    codes, cb = pr.codes.cpu().numpy(), pr.codebooks.cpu().numpy()
+    for q in range(min(nq, 2)):
+        oi, ok, od = oracle.search(lay.d, lay.nbits, lay.dsub, lay.acc_bits, cb, pr.queries[q].cpu().numpy(), codes,
+                                   T_CAL, R)
+        assert np.array_equal(fused[0][q].cpu().numpy(), oi), (q, fused[0][q][:8], oi[:8])
+        assert np.array_equal(fused[1][q].cpu().numpy().astype(np.uint16), ok)
+        assert np.array_equal(fused[2][q].cpu().numpy(), od)
+    idx.close()
+
+
 # ------------------------------------------------------------------ IVF ------
 def check_ivf(qb, ip, R, t=T_CAL, probe=None):
     lay = ip.layout
